@@ -1,0 +1,167 @@
+/*
+ * msa.h -- C ABI of the routed-attention hot path of Memory Sparse Attention (MSA) on MI355X (gfx950).
+ *
+ * Three operations, in the order a query meets them (paper, Section 3.4.1 "Three-Stage Inference"):
+ *   msa_build_routing_keys  offline, once per bank version: chunk-wise mean pooling phi(.) of the
+ *                           keys (Section 3.2.1, text after Eq. 1) -> routing index
+ *   msa_score_topk          online routing: relevance scores (Eq. 2), document score s_i = max_j S_ij,
+ *                           top-k documents (Section 3.2.1)
+ *   msa_sparse_attend       context assembly (Eq. 3) with document-wise RoPE (Section 3.2.2) and
+ *                           attention (Eq. 4) over [selected documents ; local context]
+ *
+ * Notation: N documents, G tokens per document, P chunk size, C = G/P chunks per document,
+ * Hq query heads, Hkv key/value heads, r = Hq/Hkv, d head dimension, B sequences, M query tokens per
+ * sequence, k selected documents, Lloc local-context tokens.  Query head h uses KV head g = h / r.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers (HIP), 16-byte aligned, dense, row-major in the index
+ *     order written next to them; bf16 = bfloat16 bit patterns (uint16_t).  The config struct is a
+ *     HOST pointer and is read before the call returns.
+ *   - Ownership: the caller owns every buffer, workspace included.  The library allocates nothing,
+ *     frees nothing and keeps no state between calls.
+ *   - Asynchrony: work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream); no call synchronises.  Outputs are valid once the stream reaches that point.
+ *   - Errors: 0 on success, a negative msa_status otherwise.  Arguments are validated on the host
+ *     before anything is enqueued, so an error return (other than MSA_ERR_HIP) means no work was
+ *     launched and no GPU is needed to observe it.  No exceptions, no aborts, no printing.
+ *   - Inputs are finite by contract.  Out-of-range document ids in `idx` are the caller's bug.
+ */
+#ifndef MSA_H_
+#define MSA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void* msa_stream_t; /* hipStream_t */
+
+typedef enum msa_status {
+  MSA_OK = 0,
+  MSA_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, k out of range, G % P != 0, ... */
+  MSA_ERR_UNSUPPORTED = -2,   /* valid request outside what the kernels implement (see msa_config) */
+  MSA_ERR_WORKSPACE = -3,     /* workspace_bytes smaller than the matching *_workspace_bytes()   */
+  MSA_ERR_MISALIGNED = -4,    /* a tensor pointer is not 16-byte aligned                         */
+  MSA_ERR_HIP = -5            /* a kernel launch failed (hipGetLastError)                        */
+} msa_status;
+
+enum { MSA_SIM_DOT = 0, MSA_SIM_COS = 1 };
+enum { MSA_SCOPE_GROUP = 0, MSA_SCOPE_ALL = 1 };
+enum { MSA_MAX_TOPK = 64 };
+
+typedef struct msa_config {
+  int32_t n_docs;       /* N >= 1                                                                  */
+  int32_t doc_len;      /* G, tokens per document; G % P == 0; msa_sparse_attend needs G % 32 == 0 */
+  int32_t chunk;        /* P, pooling size (paper: 64); P % 8 == 0; C = G/P must be 1, 2, 4, 8 or 16 */
+  int32_t n_q_heads;    /* Hq, multiple of Hkv; r = Hq/Hkv <= 8                                    */
+  int32_t n_kv_heads;   /* Hkv                                                                     */
+  int32_t head_dim;     /* d, 64 or 128                                                            */
+  float rope_base;      /* RoPE base (theta_u = base^(-2u/d)), e.g. 1e4 or 1e6                      */
+  int32_t sim;          /* MSA_SIM_COS (paper, Eq. 2) or MSA_SIM_DOT                               */
+  int32_t select_scope; /* MSA_SCOPE_GROUP: head mean over the r heads of a KV group, one selection
+                           per KV head (S = Hkv).  MSA_SCOPE_ALL (literal Eq. 2, S = 1): UNSUPPORTED */
+  int32_t token_pool;   /* 0: one selection per query token.  1 (literal Eq. 2 max over tokens):
+                           UNSUPPORTED in this version                                             */
+} msa_config_t;
+
+/* Library version (major * 100 + minor). */
+int msa_version(void);
+
+/* Static, never-NULL description of a status code. */
+const char* msa_status_string(int status);
+
+/*
+ * Layout of the routing index (output of msa_build_routing_keys, input of msa_score_topk).
+ *
+ * Keys are numbered c = i*C + j (chunk j of document i) and stored in TILES of 16 keys so that one
+ * 64-lane wavefront reads a tile with four (d = 128) fully coalesced 1 KiB loads that are already in
+ * MFMA operand order:
+ *     KR[g][c / 16][dim / 8][c % 16][dim % 8]          bf16, g < Hkv, tiles = ceil(N*C / 16)
+ *     inv_norm[g][c]                                     fp32, padded to tiles*16 entries per head
+ * Slots past N*C in the last tile are zero.  A key in plain order [g][c][dim] is recovered by
+ * swapping the two middle axes of a tile.
+ */
+
+/* Bytes of KR for this config (Hkv * tiles * 16 * d * 2).  0 if cfg is NULL or invalid. */
+size_t msa_routing_keys_bytes(const msa_config_t* cfg);
+/* Bytes of inv_norm for this config (Hkv * tiles * 16 * 4).  0 if cfg is NULL or invalid. */
+size_t msa_inv_norm_bytes(const msa_config_t* cfg);
+
+/*
+ * Size of a POOLED bank in the paper's storage estimate (Section 3.4.2, "Tiered Memory Storage
+ * Strategy"): n_tensors * n_layers * (tokens / P) * heads * d * bytes_per_elem.  With 100*2^20 tokens,
+ * P = 64, 8 heads, d = 128, 18 layers, 2 bytes: 3 tensors -> 168.75 GiB, routing keys alone 56.25 GiB.
+ */
+uint64_t msa_pooled_bank_bytes(uint64_t tokens, uint32_t chunk, uint32_t heads, uint32_t head_dim,
+                               uint32_t n_layers, uint32_t bytes_per_elem, uint32_t n_tensors);
+
+/* Workspace requirements (bytes, multiple of 256).  0 if the arguments are invalid. */
+size_t msa_score_topk_workspace_bytes(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k);
+size_t msa_sparse_attend_workspace_bytes(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k,
+                                         int32_t Lloc);
+
+/*
+ * Chunk-wise mean pooling of un-rotated keys into the routing index (Section 3.2.1, phi(.)):
+ *     KR(g, i*C + j, :) = bf16_rne( (1/P) * sum_{t in chunk j} K[i][g][t][:] )      fp32 accumulate
+ *     inv_norm(g, i*C + j) = 1 / max(||KR(g, i*C + j, :)||, 1e-12)                   of the ROUNDED key
+ * for documents i in [doc_begin, doc_begin + doc_count), so a bank can be built or updated in pieces.
+ *   K         in   bf16 [N][Hkv][G][d]   (whole bank; only the addressed documents are read)
+ *   KR        out  bf16, tiled layout above (whole index; only the addressed keys are written)
+ *   inv_norm  out  fp32 [Hkv][tiles*16]; may be NULL iff cfg->sim == MSA_SIM_DOT
+ */
+int msa_build_routing_keys(const msa_config_t* cfg, const void* K, int32_t doc_begin,
+                           int32_t doc_count, void* KR, float* inv_norm, msa_stream_t stream);
+
+/*
+ * Routing (Section 3.2.1, Eq. 2 and the text after it), fused so chunk scores never reach memory:
+ *     Sc(b,m,g,c) = (1/r) * sum_{h in group g} sim(q_route[b][m][h][:], KR(g,c,:))
+ *     s(b,m,g,i)  = max_{j < C} Sc(b,m,g,i*C + j)
+ *     out_idx[b][m][g][0..k) = the k documents with the largest s, ordered by (s descending,
+ *                               document index ascending); out_score = their s.
+ * sim = cosine: x.y / (max(|x|,1e-12) * max(|y|,1e-12)), or the plain dot product.
+ *   q_route   in   bf16 [B][M][Hq][d]
+ *   KR, inv_norm   as written by msa_build_routing_keys (inv_norm may be NULL iff sim == DOT)
+ *   k              1 <= k <= min(N, MSA_MAX_TOPK)
+ *   out_idx   out  int32 [B][M][Hkv][k]
+ *   out_score out  fp32  [B][M][Hkv][k], may be NULL
+ *   workspace      >= msa_score_topk_workspace_bytes(cfg, B, M, k); contents undefined on entry/exit
+ * Scores are accumulated in fp32; each query is carried as a bf16 (hi, lo) pair, so a score differs
+ * from exact arithmetic by a few 1e-6 relative.
+ */
+int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
+                   const void* KR, const float* inv_norm, int32_t k, int32_t* out_idx,
+                   float* out_score, void* workspace, size_t workspace_bytes, msa_stream_t stream);
+
+/*
+ * Sparse attention (Eq. 3-4 with the position scheme of Section 3.2.2).  For query (b,m), head h of
+ * KV group g, the keys are, in order:
+ *     every token p < G of every document i = idx[b][m][g][j] >= 0:  RoPE(K[i][g][p][:], p)
+ *     every local token t < Lloc with local_pos0 + t <= q_pos[b][m]:  RoPE(Kloc[b][g][t][:], local_pos0 + t)
+ * with the matching un-rotated value rows, and
+ *     out[b][m][h][:] = softmax_j( RoPE(q[b][m][h][:], q_pos[b][m]) . key_j / sqrt(d) ) . value_j
+ *     lse[b][m][h]    = log sum_j exp( ... )          (natural log; -inf and out = 0 if no key is visible)
+ * RoPE pairs element u with u + d/2, angle p * base^(-2u/d).  Positions restart at 0 in every document;
+ * idx == -1 marks "no document"; a document listed twice is attended twice.
+ *   q         in   bf16 [B][M][Hq][d]
+ *   K, V      in   bf16 [N][Hkv][G][d]
+ *   idx       in   int32 [B][M][Hkv][k]
+ *   Kloc,Vloc in   bf16 [B][Hkv][Lloc][d]; may be NULL iff Lloc == 0
+ *   q_pos     in   int32 [B][M]
+ *   out       out  bf16 [B][M][Hq][d]
+ *   lse       out  fp32 [B][M][Hq], may be NULL
+ *   workspace      >= msa_sparse_attend_workspace_bytes(cfg, B, M, k, Lloc)
+ * Rotated keys are rounded to bf16 before the fp32-accumulated matrix products; queries and softmax
+ * weights are carried as bf16 (hi, lo) pairs.
+ */
+int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t M, const void* K,
+                      const void* V, const int32_t* idx, int32_t k, const void* Kloc,
+                      const void* Vloc, int32_t Lloc, int32_t local_pos0, const int32_t* q_pos,
+                      void* out, float* lse, void* workspace, size_t workspace_bytes,
+                      msa_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MSA_H_ */

@@ -63,12 +63,14 @@ def normal_bf16_bits(seed, start, count):
     count = int(count)
     if count == 0:
         return np.zeros(0, dtype=np.uint16)
-    e = np.arange(start, start + count, dtype=np.uint64)
+    w0, w1 = start >> 2, (start + count + 3) >> 2            # 64-bit words covering the range
     with np.errstate(over="ignore"):
         base = np.uint64(seed) * _GOLDEN
-        word = _mix64(base + (e >> np.uint64(2)))
-    sh = (e & np.uint64(3)) * np.uint64(16)
-    idx = ((word >> sh) & np.uint64(0xFFFF)).astype(np.int64)
+        word = _mix64(base + np.arange(w0, w1, dtype=np.uint64))
+    idx = np.empty((w1 - w0, 4), dtype=np.uint16)
+    for lane in range(4):
+        idx[:, lane] = (word >> np.uint64(16 * lane)).astype(np.uint16)   # truncation keeps 16 bits
+    idx = idx.reshape(-1)[start - 4 * w0: start - 4 * w0 + count]
     return quantile_table()[idx]
 
 

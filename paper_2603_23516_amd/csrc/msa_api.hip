@@ -1,0 +1,159 @@
+// C-ABI layer: argument validation (host only, before anything is enqueued), work plans, launches.
+#include "msa_host.h"
+
+namespace msa {
+
+static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// Returns MSA_OK and fills dm, or the status that describes what is wrong with cfg.
+static int make_dims(const msa_config_t* cfg, Dims* dm) {
+  if (cfg == nullptr) return MSA_ERR_INVALID_ARG;
+  if (cfg->n_docs < 1 || cfg->doc_len < 1 || cfg->chunk < 1 || cfg->n_q_heads < 1 ||
+      cfg->n_kv_heads < 1 || cfg->head_dim < 1)
+    return MSA_ERR_INVALID_ARG;
+  if (cfg->doc_len % cfg->chunk != 0) return MSA_ERR_INVALID_ARG;
+  if (cfg->n_q_heads % cfg->n_kv_heads != 0) return MSA_ERR_INVALID_ARG;
+  if (cfg->sim != MSA_SIM_DOT && cfg->sim != MSA_SIM_COS) return MSA_ERR_INVALID_ARG;
+  if (cfg->select_scope != MSA_SCOPE_GROUP && cfg->select_scope != MSA_SCOPE_ALL)
+    return MSA_ERR_INVALID_ARG;
+  if (cfg->token_pool != 0 && cfg->token_pool != 1) return MSA_ERR_INVALID_ARG;
+  if (!(cfg->rope_base > 1.0f)) return MSA_ERR_INVALID_ARG;
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return MSA_ERR_UNSUPPORTED;
+  if (cfg->chunk % 8 != 0) return MSA_ERR_UNSUPPORTED;
+  const int C = cfg->doc_len / cfg->chunk;
+  if (!pow2(C) || C > 16) return MSA_ERR_UNSUPPORTED;
+  if (cfg->n_q_heads / cfg->n_kv_heads > 8) return MSA_ERR_UNSUPPORTED;
+  if (cfg->select_scope != MSA_SCOPE_GROUP || cfg->token_pool != 0) return MSA_ERR_UNSUPPORTED;
+  dm->N = cfg->n_docs;
+  dm->G = cfg->doc_len;
+  dm->P = cfg->chunk;
+  dm->C = C;
+  dm->Hq = cfg->n_q_heads;
+  dm->Hkv = cfg->n_kv_heads;
+  dm->r = cfg->n_q_heads / cfg->n_kv_heads;
+  dm->d = cfg->head_dim;
+  dm->cos = cfg->sim == MSA_SIM_COS;
+  dm->base = cfg->rope_base;
+  dm->NC = (int64_t)dm->N * C;
+  dm->tiles = (dm->NC + 15) / 16;
+  return MSA_OK;
+}
+
+static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+}  // namespace msa
+
+using namespace msa;
+
+extern "C" {
+
+int msa_version(void) { return 100; }
+
+const char* msa_status_string(int status) {
+  switch (status) {
+    case MSA_OK: return "ok";
+    case MSA_ERR_INVALID_ARG: return "invalid argument";
+    case MSA_ERR_UNSUPPORTED: return "valid request not supported by this build";
+    case MSA_ERR_WORKSPACE: return "workspace too small";
+    case MSA_ERR_MISALIGNED: return "pointer not 16-byte aligned";
+    case MSA_ERR_HIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+size_t msa_routing_keys_bytes(const msa_config_t* cfg) {
+  Dims dm;
+  if (make_dims(cfg, &dm) != MSA_OK) return 0;
+  return (size_t)dm.Hkv * (size_t)dm.tiles * 16 * (size_t)dm.d * 2;
+}
+
+size_t msa_inv_norm_bytes(const msa_config_t* cfg) {
+  Dims dm;
+  if (make_dims(cfg, &dm) != MSA_OK) return 0;
+  return (size_t)dm.Hkv * (size_t)dm.tiles * 16 * sizeof(float);
+}
+
+uint64_t msa_pooled_bank_bytes(uint64_t tokens, uint32_t chunk, uint32_t heads, uint32_t head_dim,
+                               uint32_t n_layers, uint32_t bytes_per_elem, uint32_t n_tensors) {
+  if (chunk == 0 || tokens % chunk != 0) return 0;
+  return (uint64_t)n_tensors * n_layers * (tokens / chunk) * heads * head_dim * bytes_per_elem;
+}
+
+size_t msa_score_topk_workspace_bytes(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k) {
+  Dims dm;
+  if (make_dims(cfg, &dm) != MSA_OK) return 0;
+  if (B < 1 || M < 1 || k < 1 || k > MSA_MAX_TOPK || k > dm.N) return 0;
+  if ((int64_t)B * M > (1 << 20)) return 0;
+  return plan_score(dm, B * M, k).ws_bytes;
+}
+
+size_t msa_sparse_attend_workspace_bytes(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k,
+                                         int32_t Lloc) {
+  Dims dm;
+  if (make_dims(cfg, &dm) != MSA_OK) return 0;
+  if (B < 1 || M < 1 || k < 1 || k > MSA_MAX_TOPK || Lloc < 0) return 0;
+  if ((int64_t)B * M > 65535 || dm.G % 32 != 0) return 0;
+  return plan_attend(dm, B * M, k, Lloc).ws_bytes;
+}
+
+int msa_build_routing_keys(const msa_config_t* cfg, const void* K, int32_t doc_begin,
+                           int32_t doc_count, void* KR, float* inv_norm, msa_stream_t stream) {
+  Dims dm;
+  const int rc = make_dims(cfg, &dm);
+  if (rc != MSA_OK) return rc;
+  if (K == nullptr || KR == nullptr) return MSA_ERR_INVALID_ARG;
+  if (inv_norm == nullptr && dm.cos) return MSA_ERR_INVALID_ARG;
+  if (doc_begin < 0 || doc_count < 0 || (int64_t)doc_begin + doc_count > dm.N)
+    return MSA_ERR_INVALID_ARG;
+  if (misaligned(K) || misaligned(KR) || misaligned(inv_norm)) return MSA_ERR_MISALIGNED;
+  return launch_build(dm, K, doc_begin, doc_count, KR, inv_norm, (hipStream_t)stream);
+}
+
+int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
+                   const void* KR, const float* inv_norm, int32_t k, int32_t* out_idx,
+                   float* out_score, void* workspace, size_t workspace_bytes, msa_stream_t stream) {
+  Dims dm;
+  const int rc = make_dims(cfg, &dm);
+  if (rc != MSA_OK) return rc;
+  if (q_route == nullptr || KR == nullptr || out_idx == nullptr || workspace == nullptr)
+    return MSA_ERR_INVALID_ARG;
+  if (inv_norm == nullptr && dm.cos) return MSA_ERR_INVALID_ARG;
+  if (B < 1 || M < 1 || (int64_t)B * M > (1 << 20)) return MSA_ERR_INVALID_ARG;
+  if (k < 1 || k > dm.N) return MSA_ERR_INVALID_ARG;
+  if (k > MSA_MAX_TOPK) return MSA_ERR_UNSUPPORTED;
+  if (misaligned(q_route) || misaligned(KR) || misaligned(inv_norm) || misaligned(out_idx) ||
+      misaligned(out_score) || misaligned(workspace))
+    return MSA_ERR_MISALIGNED;
+  const ScorePlan pl = plan_score(dm, B * M, k);
+  if (workspace_bytes < pl.ws_bytes) return MSA_ERR_WORKSPACE;
+  return launch_score(dm, pl, q_route, B * M, KR, inv_norm, k, out_idx, out_score, workspace,
+                      (hipStream_t)stream);
+}
+
+int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t M, const void* K,
+                      const void* V, const int32_t* idx, int32_t k, const void* Kloc,
+                      const void* Vloc, int32_t Lloc, int32_t local_pos0, const int32_t* q_pos,
+                      void* out, float* lse, void* workspace, size_t workspace_bytes,
+                      msa_stream_t stream) {
+  Dims dm;
+  const int rc = make_dims(cfg, &dm);
+  if (rc != MSA_OK) return rc;
+  if (q == nullptr || K == nullptr || V == nullptr || idx == nullptr || q_pos == nullptr ||
+      out == nullptr || workspace == nullptr)
+    return MSA_ERR_INVALID_ARG;
+  if (B < 1 || M < 1 || Lloc < 0 || local_pos0 < 0) return MSA_ERR_INVALID_ARG;
+  if (Lloc > 0 && (Kloc == nullptr || Vloc == nullptr)) return MSA_ERR_INVALID_ARG;
+  if (k < 1) return MSA_ERR_INVALID_ARG;
+  if (k > MSA_MAX_TOPK || (int64_t)B * M > 65535 || dm.G % 32 != 0) return MSA_ERR_UNSUPPORTED;
+  if ((int64_t)local_pos0 + Lloc > (1 << 24)) return MSA_ERR_UNSUPPORTED;
+  if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(idx) || misaligned(Kloc) ||
+      misaligned(Vloc) || misaligned(q_pos) || misaligned(out) || misaligned(lse) ||
+      misaligned(workspace))
+    return MSA_ERR_MISALIGNED;
+  const AttendPlan pl = plan_attend(dm, B * M, k, Lloc);
+  if (workspace_bytes < pl.ws_bytes) return MSA_ERR_WORKSPACE;
+  return launch_attend(dm, pl, q, B, M, K, V, idx, k, Kloc, Vloc, Lloc, local_pos0, q_pos, out,
+                       lse, workspace, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,449 @@
+// msa_sparse_attend: context assembly (paper, Eq. 3) with document-wise RoPE (Section 3.2.2) and
+// attention (Eq. 4) over [selected documents ; local context], as a split-K flash-decode with a
+// log-sum-exp merge.  HBM-bound: every selected K and V row is read once per (query, KV head) and
+// shared by the r query heads of the group.
+//
+// Key sequence of one (query, KV head): k documents x G tokens, then Lloc local tokens, cut into
+// STEPS of 32 keys (G % 32 == 0, so a step never straddles two documents).  A block owns a
+// contiguous range of steps, each of its 4 waves a contiguous sub-range, so positions advance by 16
+// from one 16-key sub-tile to the next and the rotation angles follow a two-multiply recurrence.
+//
+// Per sub-tile (S^T = K~ Q~^T on 16x16x32 bf16 MFMA):
+//   A = rotated keys: lane (rr, n) loads 16-byte pieces of key row n (dims 32s + 8rr .. +8, s < d/32);
+//       element u is paired with u + d/2, which the same lane holds in slice s + d/64.
+//       Rotation in fp32 by the lane's running (cos, sin)(p * theta_u), then rounded to bf16.
+//   B = the r rotated, pre-scaled queries (log2(e)/sqrt(d) folded in) as bf16 (hi, lo) pairs in
+//       columns 2h, 2h+1; the two halves of a score are summed with one DPP exchange.
+//   D: lane (rr, n) holds column n (head slot) for keys 4rr .. 4rr+3.
+// Online softmax per head slot (exp2 domain), running max shared across the four row groups by
+// two shuffles; the weights go back as a bf16 (hi, lo) pair in the same two columns, which is exactly
+// the B-operand layout of the second product
+//   O^T[dd][slot] += V^T[dd][key] P^T[key][slot]       (8 MFMAs per 32 keys at d = 128)
+// whose A operand (V transposed) is read from an LDS copy of the 32 value rows with 16-bit reads.
+// Every accumulator of a lane belongs to its own head slot, so the rescale needs no cross-lane data.
+#include "msa_device.h"
+#include "msa_host.h"
+
+namespace msa {
+
+constexpr int kAttWaves = 4;
+constexpr int kMaxHalf = 64;  // d/2 <= 64
+
+struct RopeTheta {
+  double th[kMaxHalf];  // theta_u = base^(-2u/d), computed on the host in double
+};
+
+struct AttendArgs {
+  const uint16_t* q;     // [BM][Hq][D]
+  const uint16_t* K;     // [N][Hkv][G][D]
+  const uint16_t* V;
+  const int32_t* idx;    // [BM][Hkv][k]
+  const uint16_t* Kloc;  // [B][Hkv][Lloc][D]
+  const uint16_t* Vloc;
+  const int32_t* q_pos;  // [BM]
+  float* part_o;         // [BM][Hq][n_splits][D]   unnormalised partial outputs
+  float2* part_ml;       // [BM][Hq][n_splits]      (running max in log2 units, sum)
+  int M, Hq, Hkv, r, G, k, Lloc, pos0;
+  int steps_mem, steps_total, steps_per_split, n_splits;
+  float qscale;          // log2(e) / sqrt(d)
+};
+
+// (cos, sin)(p * theta): product and range reduction in double, sincos of the reduced angle in fp32.
+__device__ __forceinline__ float2 cis_pos(int p, double theta) {
+  const double x = (double)p * theta;
+  const double kk = rint(x * 0.15915494309189535);
+  double red = fma(-kk, 6.283185307179586, x);
+  red = fma(-kk, 2.4492935982947064e-16, red);
+  float s, c;
+  sincosf((float)red, &s, &c);
+  return make_float2(c, s);
+}
+
+__device__ __forceinline__ float2 cmul(float2 a, float2 b) {
+  return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeTheta th) {
+  constexpr int NS = D / 32;        // MFMA k-slices per key row
+  constexpr int HALF = D / 2;
+  constexpr int NU = (NS / 2) * 8;  // rotation pairs per lane
+  constexpr int NCB = D / 16;       // output column blocks
+  constexpr int VSTRIDE = D * 2 + 8;  // bytes per staged value row (+8: conflict-free 16-bit reads)
+  constexpr int VBYTES = 32 * VSTRIDE;
+  constexpr int OBYTES = 16 * D * 4;  // one wave's partial output in the merge
+  constexpr int STAGE = (VBYTES > OBYTES ? VBYTES : OBYTES);
+
+  __shared__ float2 base0[16][HALF];  // e^{i n theta_u}: positions 0..15
+  __shared__ float2 step16[HALF];     // e^{i 16 theta_u}
+  __shared__ float qrot[8][D];        // rotated, scaled queries of this group
+  __shared__ __attribute__((aligned(16))) unsigned char stage[kAttWaves][STAGE];
+  __shared__ float wm[kAttWaves][16], wl[kAttWaves][16];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int rr = lane >> 4;
+  const int n = lane & 15;
+  const int sp = blockIdx.x;
+  const int g = blockIdx.y;
+  const int bm = blockIdx.z;
+  const int b = bm / a.M;
+  const int qpos = a.q_pos[bm];
+  int n_vis = qpos - a.pos0 + 1;  // visible local tokens
+  n_vis = n_vis < 0 ? 0 : (n_vis > a.Lloc ? a.Lloc : n_vis);
+
+  // ---- block prologue: rotation tables and rotated queries ------------------------------------
+  for (int e = tid; e < 16 * HALF; e += 256) base0[e / HALF][e % HALF] = cis_pos(e / HALF, th.th[e % HALF]);
+  if (tid < HALF) step16[tid] = cis_pos(16, th.th[tid]);
+  for (int e = tid; e < a.r * HALF; e += 256) {
+    const int hh = e / HALF, u = e % HALF;
+    const uint16_t* qp = a.q + ((long long)bm * a.Hq + g * a.r + hh) * D;
+    const float x1 = __uint_as_float((uint32_t)qp[u] << 16);
+    const float x2 = __uint_as_float((uint32_t)qp[u + HALF] << 16);
+    const float2 cs = cis_pos(qpos, th.th[u]);
+    qrot[hh][u] = (x1 * cs.x - x2 * cs.y) * a.qscale;
+    qrot[hh][u + HALF] = (x2 * cs.x + x1 * cs.y) * a.qscale;
+  }
+  __syncthreads();
+
+  // B operand of the score product: column n = head slot (head n/2, hi or lo half)
+  bf16x8_t bq[NS];
+  {
+    const int hh = n >> 1;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      uint32_t w[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        float x0 = 0.f, x1 = 0.f;
+        if (hh < a.r) {
+          x0 = qrot[hh][32 * s + 8 * rr + 2 * jj];
+          x1 = qrot[hh][32 * s + 8 * rr + 2 * jj + 1];
+        }
+        float h0, l0, h1, l1;
+        split_bf16(x0, h0, l0);
+        split_bf16(x1, h1, l1);
+        w[jj] = (n & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
+      }
+      bq[s] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+    }
+  }
+
+  // ---- this wave's steps -----------------------------------------------------------------------
+  const int sb = sp * a.steps_per_split;
+  int se = sb + a.steps_per_split;
+  if (se > a.steps_total) se = a.steps_total;
+  const int spw = (se - sb + kAttWaves - 1) / kAttWaves;
+  const int wb = sb + wave * spw;
+  int we = wb + spw;
+  if (we > se) we = se;
+
+  float2 cs[NU];         // (cos, sin)((cur_p + n) * theta_u), u = 32s' + 8rr + j at index 8s' + j
+  int cur_p = -1;        // position of key 0 of the sub-tile the state is valid for; -1 = invalid
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4_t o[NCB];
+#pragma unroll
+  for (int c = 0; c < NCB; ++c) o[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  unsigned char* vst = stage[wave];
+
+  for (int st = wb; st < we; ++st) {
+    const uint16_t* Kb;
+    const uint16_t* Vb;
+    int rows_valid = 32;
+    int p_first;
+    if (st < a.steps_mem) {
+      const int tok = st * 32;
+      const int slot = tok / a.G;
+      const int pin = tok - slot * a.G;
+      const int doc = a.idx[((long long)bm * a.Hkv + g) * a.k + slot];
+      if (doc < 0) continue;  // wave-uniform
+      const long long off = (((long long)doc * a.Hkv + g) * a.G + pin) * D;
+      Kb = a.K + off;
+      Vb = a.V + off;
+      p_first = pin;
+    } else {
+      const int t0 = (st - a.steps_mem) * 32;
+      if (t0 >= n_vis) break;  // wave-uniform; later steps are further right
+      const long long off = (((long long)b * a.Hkv + g) * a.Lloc + t0) * D;
+      Kb = a.Kloc + off;
+      Vb = a.Vloc + off;
+      rows_valid = n_vis - t0 < 32 ? n_vis - t0 : 32;
+      p_first = a.pos0 + t0;
+    }
+
+    // ---- issue all global loads of the step --------------------------------------------------
+    uint4 kraw[2][NS];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      int row = 16 * h + n;
+      row = row < rows_valid ? row : rows_valid - 1;
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+        kraw[h][s] = *reinterpret_cast<const uint4*>(Kb + row * D + 32 * s + 8 * rr);
+    }
+    constexpr int NVL = 32 * D * 2 / 1024;  // wave-wide 16-byte loads covering 32 value rows
+    uint4 vraw[NVL];
+#pragma unroll
+    for (int i = 0; i < NVL; ++i) {
+      const int f = i * 64 + lane;
+      int row = f / (D / 8);
+      const int piece = f % (D / 8);
+      row = row < rows_valid ? row : rows_valid - 1;
+      vraw[i] = *reinterpret_cast<const uint4*>(Vb + row * D + piece * 8);
+    }
+
+    // ---- rotation state for this step ----------------------------------------------------------
+    if (cur_p != p_first) {
+      if (p_first == 0) {
+#pragma unroll
+        for (int s2 = 0; s2 < NS / 2; ++s2)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = base0[n][32 * s2 + 8 * rr + j];
+      } else {
+#pragma unroll
+        for (int s2 = 0; s2 < NS / 2; ++s2)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int u = 32 * s2 + 8 * rr + j;
+            cs[8 * s2 + j] = cmul(cis_pos(p_first, th.th[u]), base0[n][u]);
+          }
+      }
+      cur_p = p_first;
+    }
+
+    // ---- scores of the two 16-key sub-tiles ---------------------------------------------------
+    float sc[2][4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint32_t y1[NS / 2][4], y2[NS / 2][4];
+#pragma unroll
+      for (int s2 = 0; s2 < NS / 2; ++s2) {
+        const uint4 a1 = kraw[h][s2], a2 = kraw[h][s2 + NS / 2];
+        const uint32_t w1[4] = {a1.x, a1.y, a1.z, a1.w};
+        const uint32_t w2[4] = {a2.x, a2.y, a2.z, a2.w};
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const float2 c0 = cs[8 * s2 + 2 * jj], c1 = cs[8 * s2 + 2 * jj + 1];
+          const float p0 = bf16_lo(w1[jj]), p1 = bf16_hi(w1[jj]);
+          const float q0 = bf16_lo(w2[jj]), q1 = bf16_hi(w2[jj]);
+          y1[s2][jj] = pack_bf16(p0 * c0.x - q0 * c0.y, p1 * c1.x - q1 * c1.y);
+          y2[s2][jj] = pack_bf16(q0 * c0.x + p0 * c0.y, q1 * c1.x + p1 * c1.y);
+        }
+      }
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s2 = 0; s2 < NS / 2; ++s2) {
+        acc = mfma16(as_bf16x8(make_uint4(y1[s2][0], y1[s2][1], y1[s2][2], y1[s2][3])), bq[s2], acc);
+        acc = mfma16(as_bf16x8(make_uint4(y2[s2][0], y2[s2][1], y2[s2][2], y2[s2][3])),
+                     bq[s2 + NS / 2], acc);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float v = acc[i] + dpp_f<kDppXor1>(acc[i]);  // hi + lo column
+        sc[h][i] = (16 * h + 4 * rr + i < rows_valid) ? v : -INFINITY;
+      }
+      // advance the rotation state by 16 positions
+#pragma unroll
+      for (int s2 = 0; s2 < NS / 2; ++s2)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = cmul(cs[8 * s2 + j], step16[32 * s2 + 8 * rr + j]);
+    }
+    cur_p += 32;
+
+    // ---- online softmax (exp2 domain) ---------------------------------------------------------
+    float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                     fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+    m_run = m_new;
+    float psum = 0.f;
+    uint32_t pw[4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float pv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float p = __builtin_amdgcn_exp2f(sc[h][i] - m_use);
+        psum += p;
+        float hi, lo;
+        split_bf16(p, hi, lo);
+        pv[i] = (n & 1) ? lo : hi;
+      }
+      pw[2 * h] = pack_bf16(pv[0], pv[1]);
+      pw[2 * h + 1] = pack_bf16(pv[2], pv[3]);
+    }
+    l_run = l_run * alpha + psum;
+    const bf16x8_t pb = as_bf16x8(make_uint4(pw[0], pw[1], pw[2], pw[3]));
+
+    // ---- stage the 32 value rows in LDS, read them back transposed ----------------------------
+#pragma unroll
+    for (int i = 0; i < NVL; ++i) {
+      const int f = i * 64 + lane;
+      const int row = f / (D / 8);
+      const int piece = f % (D / 8);
+      uint2* dst = reinterpret_cast<uint2*>(vst + row * VSTRIDE + piece * 16);
+      dst[0] = make_uint2(vraw[i].x, vraw[i].y);
+      dst[1] = make_uint2(vraw[i].z, vraw[i].w);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int c = 0; c < NCB; ++c) {
+      uint32_t w[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        // k-slots 2jj, 2jj+1 of this lane: keys 4rr + j (j < 4, first sub-tile), 16 + 4rr + j - 4
+        const int j0 = 2 * jj, j1 = 2 * jj + 1;
+        const int r0 = (j0 < 4) ? 4 * rr + j0 : 16 + 4 * rr + (j0 - 4);
+        const int r1 = (j1 < 4) ? 4 * rr + j1 : 16 + 4 * rr + (j1 - 4);
+        const uint32_t lo = *reinterpret_cast<const volatile uint16_t*>(vst + r0 * VSTRIDE + (16 * c + n) * 2);
+        const uint32_t hi = *reinterpret_cast<const volatile uint16_t*>(vst + r1 * VSTRIDE + (16 * c + n) * 2);
+        w[jj] = lo | (hi << 16);
+      }
+      f32x4_t oc = o[c];
+      oc[0] *= alpha;
+      oc[1] *= alpha;
+      oc[2] *= alpha;
+      oc[3] *= alpha;
+      o[c] = mfma16(as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])), pb, oc);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+
+  // ---- merge the four waves ----------------------------------------------------------------------
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  __syncthreads();  // every wave is done with its value staging area
+  {
+    float* wo = reinterpret_cast<float*>(stage[wave]);  // [16 slots][D]
+#pragma unroll
+    for (int c = 0; c < NCB; ++c)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) wo[n * D + 16 * c + 4 * rr + i] = o[c][i];
+    if (rr == 0) {
+      wm[wave][n] = m_run;
+      wl[wave][n] = l_run;
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < a.r * D; e += 256) {
+    const int hh = e / D, dd = e % D;
+    const int s0 = 2 * hh;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kAttWaves; ++w) mx = fmaxf(mx, wm[w][s0]);
+    float osum = 0.f, lsum = 0.f;
+    if (mx != -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < kAttWaves; ++w) {
+        const float mw = wm[w][s0];
+        const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mx);
+        const float* wo = reinterpret_cast<const float*>(stage[w]);
+        osum += f * (wo[s0 * D + dd] + wo[(s0 + 1) * D + dd]);
+        lsum += f * wl[w][s0];
+      }
+    }
+    const long long ph = ((long long)bm * a.Hq + g * a.r + hh) * a.n_splits + sp;
+    a.part_o[ph * D + dd] = osum;
+    if (dd == 0) a.part_ml[ph] = make_float2(mx, lsum);
+  }
+}
+
+// Log-sum-exp merge of the split partials of one (query, head).
+template <int D>
+__global__ void attend_merge_kernel(const float* __restrict__ part_o, const float2* __restrict__ part_ml,
+                                    uint16_t* __restrict__ out, float* __restrict__ lse, int n_splits) {
+  const long long qh = blockIdx.x;
+  const int dd = threadIdx.x;
+  float mx = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, part_ml[qh * n_splits + s].x);
+  float osum = 0.f, lsum = 0.f;
+  if (mx != -INFINITY) {
+    for (int s = 0; s < n_splits; ++s) {
+      const float2 ml = part_ml[qh * n_splits + s];
+      const float f = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - mx);
+      lsum += f * ml.y;
+      osum += f * part_o[(qh * n_splits + s) * D + dd];
+    }
+  }
+  const float res = (lsum > 0.f) ? osum / lsum : 0.f;
+  const uint32_t pk = pack_bf16(res, 0.f);
+  out[qh * D + dd] = (uint16_t)(pk & 0xffffu);
+  if (lse != nullptr && dd == 0) {
+    lse[qh] = (lsum > 0.f) ? (mx + log2f(lsum)) * 0.6931471805599453f : -INFINITY;
+  }
+}
+
+AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc) {
+  AttendPlan p;
+  p.steps_mem = (int)(((long long)k * dm.G) / 32);
+  p.steps_total = p.steps_mem + (Lloc + 31) / 32;
+  const long long pairs = (long long)BM * dm.Hkv;
+  long long per = ((long long)p.steps_total * pairs + 1023) / 1024;  // aim at ~1024 blocks
+  if (per < kAttWaves) per = kAttWaves;
+  if (per > p.steps_total) per = p.steps_total;
+  if (per < 1) per = 1;
+  p.steps_per_split = (int)per;
+  p.n_splits = (p.steps_total + p.steps_per_split - 1) / p.steps_per_split;
+  if (p.n_splits < 1) p.n_splits = 1;
+  const size_t o_bytes = round_up256((size_t)BM * dm.Hq * p.n_splits * dm.d * sizeof(float));
+  p.off_ml = o_bytes;
+  p.ws_bytes = o_bytes + round_up256((size_t)BM * dm.Hq * p.n_splits * sizeof(float2));
+  return p;
+}
+
+int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, int M, const void* K,
+                  const void* V, const int32_t* idx, int k, const void* Kloc, const void* Vloc,
+                  int Lloc, int pos0, const int32_t* q_pos, void* out, float* lse, void* ws,
+                  hipStream_t st) {
+  AttendArgs a;
+  a.q = (const uint16_t*)q;
+  a.K = (const uint16_t*)K;
+  a.V = (const uint16_t*)V;
+  a.idx = idx;
+  a.Kloc = (const uint16_t*)Kloc;
+  a.Vloc = (const uint16_t*)Vloc;
+  a.q_pos = q_pos;
+  a.part_o = (float*)ws;
+  a.part_ml = (float2*)((char*)ws + pl.off_ml);
+  a.M = M;
+  a.Hq = dm.Hq;
+  a.Hkv = dm.Hkv;
+  a.r = dm.r;
+  a.G = dm.G;
+  a.k = k;
+  a.Lloc = Lloc;
+  a.pos0 = pos0;
+  a.steps_mem = pl.steps_mem;
+  a.steps_total = pl.steps_total;
+  a.steps_per_split = pl.steps_per_split;
+  a.n_splits = pl.n_splits;
+  a.qscale = (float)(1.4426950408889634 / sqrt((double)dm.d));
+  RopeTheta th;
+  for (int u = 0; u < kMaxHalf; ++u)
+    th.th[u] = (u < dm.d / 2) ? pow((double)dm.base, -2.0 * (double)u / (double)dm.d) : 0.0;
+  const int BM = B * M;
+  dim3 grid(pl.n_splits, dm.Hkv, BM), block(256);
+  if (dm.d == 128)
+    hipLaunchKernelGGL(attend_partial_kernel<128>, grid, block, 0, st, a, th);
+  else
+    hipLaunchKernelGGL(attend_partial_kernel<64>, grid, block, 0, st, a, th);
+  if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+  if (dm.d == 128)
+    hipLaunchKernelGGL(attend_merge_kernel<128>, dim3(BM * dm.Hq), dim3(128), 0, st,
+                       (const float*)a.part_o, (const float2*)a.part_ml, (uint16_t*)out, lse,
+                       pl.n_splits);
+  else
+    hipLaunchKernelGGL(attend_merge_kernel<64>, dim3(BM * dm.Hq), dim3(64), 0, st,
+                       (const float*)a.part_o, (const float2*)a.part_ml, (uint16_t*)out, lse,
+                       pl.n_splits);
+  if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+  return MSA_OK;
+}
+
+}  // namespace msa

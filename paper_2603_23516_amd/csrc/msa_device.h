@@ -1,0 +1,74 @@
+// Device-side helpers shared by the MSA kernels (gfx950 only, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace msa {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// ---- bf16 <-> fp32 ---------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Two floats -> packed bf16 pair (a in the low half), round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// x = hi + lo with hi = bf16(x), lo = bf16(x - hi): carries ~16 significant bits through bf16 MFMA.
+__device__ __forceinline__ void split_bf16(float x, float& hi, float& lo) {
+  hi = bf16_lo(pack_bf16(x, 0.f));
+  lo = x - hi;
+}
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
+
+// D(16x16, fp32) += A(16x32, bf16) * B(32x16, bf16).
+// Lane l = 16*q + n holds A[n][8q..8q+7], B[8q..8q+7][n], and D[4q..4q+3][n].
+__device__ __forceinline__ f32x4_t mfma16(bf16x8_t a, bf16x8_t b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// ---- cross-lane ----------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7 - i inside each group of 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15 - i inside each row of 16
+
+// Max over aligned groups of C consecutive lanes (C in {1,2,4,8,16}); every lane gets the result.
+template <int C>
+__device__ __forceinline__ float group_max(float x) {
+  if (C >= 2) x = fmaxf(x, dpp_f<kDppXor1>(x));
+  if (C >= 4) x = fmaxf(x, dpp_f<kDppXor2>(x));
+  if (C >= 8) x = fmaxf(x, dpp_f<kDppHalfMirror>(x));
+  if (C >= 16) x = fmaxf(x, dpp_f<kDppMirror>(x));
+  return x;
+}
+
+// ---- ordered 64-bit selection keys ---------------------------------------------------------------
+// Larger key = better candidate: score descending, then document index ascending.
+__device__ __forceinline__ uint32_t orderable(float s) {
+  uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float unorderable(uint32_t o) {
+  return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+}
+__device__ __forceinline__ uint64_t make_key(float score, uint32_t doc) {
+  return ((uint64_t)orderable(score) << 32) | (uint64_t)(0xffffffffu - doc);
+}
+__device__ __forceinline__ uint32_t key_doc(uint64_t key) { return 0xffffffffu - (uint32_t)key; }
+__device__ __forceinline__ float key_score(uint64_t key) { return unorderable((uint32_t)(key >> 32)); }
+
+}  // namespace msa

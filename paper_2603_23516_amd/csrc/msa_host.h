@@ -1,0 +1,53 @@
+// Host-side declarations shared by the C-ABI layer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/msa.h"
+
+namespace msa {
+
+// Validated, derived view of msa_config_t.
+struct Dims {
+  int N, G, P, C, Hq, Hkv, r, d;
+  int cos;        // 1 = cosine, 0 = dot
+  float base;
+  int64_t NC;     // N * C routing keys per KV head
+  int64_t tiles;  // ceil(NC / 16) tiles of 16 keys per KV head
+};
+
+// Work split of the routing scan (depends only on the problem size, so the workspace size is a
+// pure function of the arguments).
+struct ScorePlan {
+  int n_splits;          // blocks per KV head
+  int tiles_per_split;
+  int q_per_pass;        // queries scored per launch (8 or 16)
+  int n_pass;
+  size_t ws_bytes;
+};
+ScorePlan plan_score(const Dims& dm, int BM, int k);
+
+struct AttendPlan {
+  int steps_mem;         // 32-key steps over the selected documents (k * G / 32)
+  int steps_total;       // + ceil(Lloc / 32)
+  int steps_per_split;
+  int n_splits;
+  size_t off_ml;         // byte offset of the (m, l) pairs inside the workspace
+  size_t ws_bytes;
+};
+AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc);
+
+int launch_build(const Dims& dm, const void* K, int doc_begin, int doc_count, void* KR,
+                 float* inv_norm, hipStream_t st);
+int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int BM, const void* KR,
+                 const float* inv_norm, int k, int32_t* out_idx, float* out_score, void* ws,
+                 hipStream_t st);
+int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, int M, const void* K,
+                  const void* V, const int32_t* idx, int k, const void* Kloc, const void* Vloc,
+                  int Lloc, int pos0, const int32_t* q_pos, void* out, float* lse, void* ws,
+                  hipStream_t st);
+
+inline size_t round_up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace msa

@@ -1,0 +1,148 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads and exports every
+symbol the header declares, every argument-validation path returns its status before any launch,
+and the size helpers reproduce the closed forms (including the paper's printed memory estimate)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2603_23516_amd as msa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(msa.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return msa.load_library()
+
+
+def _cfg(**kw):
+    base = dict(n_docs=64, doc_len=512, chunk=64, n_q_heads=8, n_kv_heads=2, head_dim=64, rope_base=1e4)
+    base.update(kw)
+    return msa.MsaConfig(**base)
+
+
+def test_exports_match_header(lib):
+    text = open(os.path.join(ROOT, "include", "msa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(msa_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(msa.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.msa_version() == 100
+    for st in (0, -1, -2, -3, -4, -5, -99):
+        assert len(msa.status_string(st)) > 0
+
+
+def test_sizes_and_paper_estimate(lib):
+    c = _cfg()
+    assert msa.routing_keys_bytes(c) == 2 * (64 * 8) * 64 * 2             # Hkv * N*C * d * 2 B
+    assert msa.inv_norm_bytes(c) == 2 * (64 * 8) * 4
+    c5 = _cfg(n_docs=97656, n_q_heads=32, n_kv_heads=8, head_dim=128)
+    assert msa.routing_keys_bytes(c5) == 8 * 781248 * 128 * 2              # ~1.6 GB
+    odd = _cfg(n_docs=3, doc_len=64, chunk=32)                             # 6 keys -> one padded tile
+    assert msa.routing_keys_bytes(odd) == 2 * 16 * 64 * 2
+    # paper, Section 3.4.2: about 169 GB for K-bar, V-bar and routing keys, ~56 GB for routing keys
+    line = [l for l in open(os.path.join(ROOT, "tests", "golden", "paper_memory_estimate.txt"))
+            if not l.startswith("#")][0]
+    tokens, P, heads, d, layers, bpe, total_gb, routing_gb = (int(x) for x in line.split())
+    total = msa.pooled_bank_bytes(tokens, P, heads, d, layers, bpe, 3)
+    routing = msa.pooled_bank_bytes(tokens, P, heads, d, layers, bpe, 1)
+    assert total == int(168.75 * 2 ** 30) and routing == int(56.25 * 2 ** 30)
+    assert round(total / 2 ** 30) == total_gb and round(routing / 2 ** 30) == routing_gb
+    assert msa.pooled_bank_bytes(100, 64, 8, 128, 18, 2, 3) == 0           # tokens % P != 0
+
+
+def test_workspace_sizes(lib):
+    c = _cfg(n_docs=2048, n_q_heads=32, n_kv_heads=8, head_dim=128, rope_base=1e6)
+    w = msa.score_topk_workspace_bytes(c, 1, 1, 16)
+    assert w > 0 and w % 256 == 0
+    assert msa.score_topk_workspace_bytes(c, 1, 1, 0) == 0
+    assert msa.score_topk_workspace_bytes(c, 1, 1, 65) == 0
+    assert msa.score_topk_workspace_bytes(c, 1, 1, 4096) == 0
+    wa = msa.sparse_attend_workspace_bytes(c, 1, 1, 16, 2048)
+    assert wa > 0 and wa % 256 == 0
+    assert msa.sparse_attend_workspace_bytes(c, 1, 1, 16, -1) == 0
+    assert msa.sparse_attend_workspace_bytes(_cfg(doc_len=48, chunk=16), 1, 1, 4, 0) == 0   # G % 32
+
+
+def test_config_validation(lib):
+    bad = [
+        (dict(n_docs=0), msa.MSA_ERR_INVALID_ARG),
+        (dict(doc_len=500), msa.MSA_ERR_INVALID_ARG),                 # G % P != 0
+        (dict(n_q_heads=7), msa.MSA_ERR_INVALID_ARG),                 # Hq % Hkv != 0
+        (dict(sim=5), msa.MSA_ERR_INVALID_ARG),
+        (dict(rope_base=1.0), msa.MSA_ERR_INVALID_ARG),
+        (dict(head_dim=96), msa.MSA_ERR_UNSUPPORTED),
+        (dict(chunk=4, doc_len=32), msa.MSA_ERR_UNSUPPORTED),         # P % 8 != 0
+        (dict(doc_len=64 * 12), msa.MSA_ERR_UNSUPPORTED),             # C = 12
+        (dict(doc_len=64 * 32), msa.MSA_ERR_UNSUPPORTED),             # C = 32
+        (dict(n_q_heads=32, n_kv_heads=2), msa.MSA_ERR_UNSUPPORTED),  # r = 16
+        (dict(select_scope=msa.MSA_SCOPE_ALL), msa.MSA_ERR_UNSUPPORTED),
+        (dict(token_pool=1), msa.MSA_ERR_UNSUPPORTED),
+    ]
+    p = ctypes.c_void_p(0x10000)
+    for kw, want in bad:
+        c = _cfg(**kw)
+        assert lib.msa_build_routing_keys(ctypes.byref(c), p, 0, 1, p, p, None) == want, kw
+        assert msa.routing_keys_bytes(c) == 0
+    assert lib.msa_build_routing_keys(None, p, 0, 1, p, p, None) == msa.MSA_ERR_INVALID_ARG
+
+
+def test_argument_validation_before_launch(lib):
+    c = _cfg()
+    cb = ctypes.byref(c)
+    p = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x10008)
+    big = 1 << 30
+    E = msa
+    # build
+    assert lib.msa_build_routing_keys(cb, None, 0, 1, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_build_routing_keys(cb, p, 0, 1, None, p, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_build_routing_keys(cb, p, 0, 1, p, None, None) == E.MSA_ERR_INVALID_ARG   # cosine needs inv_norm
+    assert lib.msa_build_routing_keys(cb, p, -1, 1, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_build_routing_keys(cb, p, 60, 5, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_build_routing_keys(cb, odd, 0, 1, p, p, None) == E.MSA_ERR_MISALIGNED
+    # score
+    assert lib.msa_score_topk(cb, None, 1, 1, p, p, 4, p, p, p, big, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_score_topk(cb, p, 1, 1, p, None, 4, p, p, p, big, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_score_topk(cb, p, 0, 1, p, p, 4, p, p, p, big, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_score_topk(cb, p, 1, 1, p, p, 0, p, p, p, big, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_score_topk(cb, p, 1, 1, p, p, 65, p, p, p, big, None) == E.MSA_ERR_INVALID_ARG   # k > N = 64
+    c2 = _cfg(n_docs=1000)
+    assert lib.msa_score_topk(ctypes.byref(c2), p, 1, 1, p, p, 65, p, p, p, big, None) == E.MSA_ERR_UNSUPPORTED
+    assert lib.msa_score_topk(cb, p, 1, 1, odd, p, 4, p, p, p, big, None) == E.MSA_ERR_MISALIGNED
+    assert lib.msa_score_topk(cb, p, 1, 1, p, p, 4, p, p, p, 16, None) == E.MSA_ERR_WORKSPACE
+    assert lib.msa_score_topk(cb, p, 1, 1, p, p, 4, p, p, None, big, None) == E.MSA_ERR_INVALID_ARG
+    # attend
+    args = [cb, p, 1, 1, p, p, p, 4, p, p, 256, 512, p, p, p, p, big, None]
+
+    def call(**repl):
+        a = list(args)
+        for i, v in repl.items():
+            a[int(i[1:])] = v
+        return lib.msa_sparse_attend(*a)
+    assert call(a1=None) == E.MSA_ERR_INVALID_ARG           # q
+    assert call(a6=None) == E.MSA_ERR_INVALID_ARG           # idx
+    assert call(a8=None) == E.MSA_ERR_INVALID_ARG           # Kloc null with Lloc > 0
+    assert call(a12=None) == E.MSA_ERR_INVALID_ARG          # q_pos
+    assert call(a7=0) == E.MSA_ERR_INVALID_ARG              # k
+    assert call(a10=-1) == E.MSA_ERR_INVALID_ARG            # Lloc
+    assert call(a7=65) == E.MSA_ERR_UNSUPPORTED
+    assert call(a4=odd) == E.MSA_ERR_MISALIGNED
+    assert call(a16=64) == E.MSA_ERR_WORKSPACE
+    c3 = _cfg(doc_len=48, chunk=8 * 3)                      # C = 2, G % 32 != 0
+    a = list(args)
+    a[0] = ctypes.byref(c3)
+    assert lib.msa_sparse_attend(*a) == E.MSA_ERR_UNSUPPORTED
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    c = _cfg()
+    with pytest.raises(ValueError):
+        msa.msa_build_routing_keys(c, torch.zeros((64, 2, 512, 64), dtype=torch.bfloat16))

@@ -1,0 +1,393 @@
+"""GPU parity: the HIP path (through the C ABI) against the float64 oracle, element by element, on
+seeded inputs small enough for the oracle but spanning several tiles, splits and ragged tails.
+
+Tolerances (north star / design document):
+  routing keys   : equal to the oracle's bf16 value, or its bf16 neighbour when the exact mean lies
+                   within fp32 summation error of a rounding tie;  inv_norm rel 1e-6
+  top-k indices  : bit-exact wherever the k-th / (k+1)-th oracle gap exceeds 1e-3 relative; inside
+                   that band any document whose oracle score is within the band of s_k is accepted
+  top-k scores   : |gpu - oracle| <= 2e-5 (fp32 accumulation, bf16 hi/lo query split)
+  attention out  : max-abs <= 2e-2 and relative L2 <= 5e-3 (bf16 inputs, fp32 accumulation)
+"""
+import ctypes
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import msa_synth as S
+import paper_2603_23516_amd as msa
+from oracle import msa_oracle as O
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(bits):
+    from msa_synth import device as SD
+    return SD.bits_to_torch(bits)
+
+
+def host_bits(t):
+    from msa_synth import device as SD
+    return SD.torch_to_bits(t)
+
+
+def bf16_to_f64(t):
+    return S.bf16_bits_to_f64(host_bits(t))
+
+
+def upload_oracle_index(cfg, KRb, inv):
+    """Oracle routing keys [Hkv][NC][d] (float64, bf16-representable) -> the library's tiled
+    layout on the device (pure re-indexing), plus fp32 inv_norm padded to whole tiles."""
+    Hkv, NC, d = KRb.shape
+    tiles = cfg.n_tiles
+    bits = np.zeros((Hkv, tiles * 16, d), dtype=np.uint16)
+    bits[:, :NC] = S.f64_to_bf16_bits(KRb)
+    tiled = bits.reshape(Hkv, tiles, 16, d // 8, 8).transpose(0, 1, 3, 2, 4)
+    invp = np.zeros((Hkv, tiles * 16), dtype=np.float32)
+    invp[:, :NC] = inv.astype(np.float32)
+    return dev(np.ascontiguousarray(tiled)), torch.from_numpy(invp).cuda()
+
+
+class Case:
+    """Seeded inputs of one configuration, on the host (float64) and on the device (bf16)."""
+
+    def __init__(self, seed, N, Hkv, r, G, d, P, B, M, Lloc, base):
+        self.N, self.Hkv, self.r, self.G, self.d, self.P = N, Hkv, r, G, d, P
+        self.B, self.M, self.Lloc, self.base = B, M, Lloc, base
+        self.Hq = Hkv * r
+        self.C = G // P
+        self.Kb, self.K = S.normal_bf16(seed, (N, Hkv, G, d))
+        self.Vb, self.V = S.normal_bf16(seed + 1, (N, Hkv, G, d))
+        self.qb, self.q = S.normal_bf16(seed + 2, (B, M, self.Hq, d))
+        if Lloc > 0:
+            self.Klb, self.Kl = S.normal_bf16(seed + 3, (B, Hkv, Lloc, d))
+            self.Vlb, self.Vl = S.normal_bf16(seed + 4, (B, Hkv, Lloc, d))
+        else:
+            self.Klb = self.Kl = self.Vlb = self.Vl = None
+
+    def cfg(self, **kw):
+        return msa.MsaConfig(self.N, self.G, self.P, self.Hq, self.Hkv, self.d, self.base, **kw)
+
+    def to_device(self):
+        self.dK, self.dV, self.dq = dev(self.Kb), dev(self.Vb), dev(self.qb)
+        self.dKl = dev(self.Klb) if self.Lloc else None
+        self.dVl = dev(self.Vlb) if self.Lloc else None
+        return self
+
+
+# ------------------------------------------------------------------------------------------------
+# probes of the device helpers (layout assumptions everything else rests on)
+# ------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def probe():
+    return ctypes.CDLL(os.path.join(HERE, "libmsa_probe.so"))
+
+
+def test_probe_mfma_layout(probe):
+    say("probe: mfma 16x16x32 bf16 operand layout")
+    Ab, A = S.normal_bf16(901, (16, 32))
+    Bb, B = S.normal_bf16(902, (32, 16))
+    dA, dB = dev(Ab), dev(Bb)
+    D = torch.zeros((16, 16), dtype=torch.float32, device="cuda")
+    probe.probe_mfma(ctypes.c_void_p(dA.data_ptr()), ctypes.c_void_p(dB.data_ptr()), ctypes.c_void_p(D.data_ptr()))
+    torch.cuda.synchronize()
+    want = A @ B
+    got = D.cpu().numpy().astype(np.float64)
+    assert np.allclose(got, want, rtol=1e-5, atol=1e-5), np.abs(got - want).max()
+
+
+def test_probe_group_max_and_dpp(probe):
+    say("probe: DPP group max")
+    x = np.random.default_rng(3).standard_normal(64).astype(np.float32)
+    dx = torch.from_numpy(x).cuda()
+    for C in (1, 2, 4, 8, 16):
+        out = torch.zeros(128, dtype=torch.float32, device="cuda")
+        probe.probe_group_max(ctypes.c_void_p(dx.data_ptr()), ctypes.c_void_p(out.data_ptr()), C)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        want = np.repeat(x.reshape(64 // C, C).max(axis=1), C)
+        assert np.array_equal(got[:64], want), C
+        assert np.array_equal(got[64:], x.reshape(32, 2)[:, ::-1].reshape(64))
+
+
+def test_probe_pack_bf16_is_rne(probe):
+    say("probe: bf16 packing")
+    rng = np.random.default_rng(4)
+    x = np.concatenate([rng.standard_normal(5000), rng.standard_normal(1000) * 1e-4,
+                        np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, -1 - 2.0 ** -8, 0.0, 255.5])]).astype(np.float32)
+    n = x.size
+    dx = torch.from_numpy(x).cuda()
+    out = torch.zeros(n, dtype=torch.int16, device="cuda")
+    hi = torch.zeros(n, dtype=torch.float32, device="cuda")
+    lo = torch.zeros(n, dtype=torch.float32, device="cuda")
+    probe.probe_pack(ctypes.c_void_p(dx.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                     ctypes.c_void_p(hi.data_ptr()), ctypes.c_void_p(lo.data_ptr()), n)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint16)
+    assert np.array_equal(S.bf16_bits_to_f64(got), O.bf16_round(x.astype(np.float64)))
+    h, l = hi.cpu().numpy().astype(np.float64), lo.cpu().numpy().astype(np.float64)
+    assert np.array_equal(h, O.bf16_round(x.astype(np.float64)))
+    assert np.array_equal(h + l, x.astype(np.float64))          # the split is exact in fp32
+
+
+def test_probe_selection_keys(probe):
+    say("probe: ordered selection keys")
+    rng = np.random.default_rng(5)
+    s = np.concatenate([rng.standard_normal(500), [0.0, -0.0, 1.0, 1.0, -1.0, 1e-30, -1e-30]]).astype(np.float32)
+    d = rng.integers(0, 2 ** 31 - 1, size=s.size).astype(np.uint32)
+    d[-4], d[-5] = 7, 9                                           # equal scores 1.0: doc 9 vs doc 7
+    n = s.size
+    ds, dd = torch.from_numpy(s).cuda(), torch.from_numpy(d.view(np.int32)).cuda()
+    key = torch.zeros(n, dtype=torch.int64, device="cuda")
+    sb = torch.zeros(n, dtype=torch.float32, device="cuda")
+    db = torch.zeros(n, dtype=torch.int32, device="cuda")
+    probe.probe_keys(*(ctypes.c_void_p(t.data_ptr()) for t in (ds, dd, key, sb, db)), n)
+    torch.cuda.synchronize()
+    keys = key.cpu().numpy().view(np.uint64)
+    assert np.array_equal(sb.cpu().numpy().view(np.uint32), s.view(np.uint32))
+    assert np.array_equal(db.cpu().numpy().view(np.uint32), d)
+    order = np.argsort(keys)[::-1]
+    want = np.lexsort((d, -s.astype(np.float64)))
+    nz = s != 0                                                  # +0 / -0 compare equal as floats
+    assert np.array_equal(order[np.isin(order, np.nonzero(nz)[0])], want[np.isin(want, np.nonzero(nz)[0])])
+
+
+def test_synth_device_fill_matches_host():
+    say("synth: device fill == host bits")
+    from msa_synth import device as SD
+    for count, start in ((4096 + 3, 0), (1000, 4 * 12345), (8, 2 ** 33)):
+        t = torch.zeros(count, dtype=torch.bfloat16, device="cuda")
+        SD.fill_normal_(t, 77, start)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(t), S.normal_bf16_bits(77, start, count))
+
+
+# ------------------------------------------------------------------------------------------------
+# stage parity
+# ------------------------------------------------------------------------------------------------
+def check_routing_keys(case, cfg, KR, inv):
+    KRb, oinv = O.routing_keys(case.K, case.P)
+    exact = O.pool_chunks(case.K, case.P)
+    got = bf16_to_f64(msa.untile_routing_keys(cfg, KR))
+    diff = got != KRb
+    # a mismatch is allowed only next to a rounding tie: the exact mean must lie within fp32
+    # summation error of the midpoint between the two candidates
+    if diff.any():
+        mid = (got[diff] + KRb[diff]) / 2
+        ulp = np.abs(got[diff] - KRb[diff])
+        assert np.all(ulp <= np.abs(KRb[diff]) * 2.0 ** -7 + 1e-30), "more than one bf16 ulp off"
+        assert np.all(np.abs(exact[diff] - mid) <= 64 * 2.0 ** -24 * np.abs(exact[diff]) + 1e-12), "not a tie"
+    assert diff.mean() < 1e-3, diff.mean()
+    gi = inv.cpu().numpy().astype(np.float64)[:, :case.N * case.C]
+    gnorm = 1.0 / np.maximum(np.linalg.norm(got, axis=-1), O.EPS_NORM)
+    assert np.allclose(gi, gnorm, rtol=1e-6), np.abs(gi / gnorm - 1).max()
+    return diff.sum()
+
+
+def check_topk(case, idx, val, KRb, k, sim="cos", atol=2e-5):
+    """Compare GPU top-k with the oracle's, with the tie band of the design."""
+    oi, ov, s = O.score_topk(case.q, KRb, case.C, k, sim)
+    gi = idx.cpu().numpy().astype(np.int64)
+    gv = val.cpu().numpy().astype(np.float64)
+    assert gi.shape == oi.shape
+    n_band = 0
+    for b in range(case.B):
+        for m in range(case.M):
+            for g in range(case.Hkv):
+                srow = s[b, m, g]
+                got, want = gi[b, m, g], oi[b, m, g]
+                assert len(set(got.tolist())) == k and got.min() >= 0 and got.max() < case.N
+                # scores reported for the chosen documents are the oracle's scores of those documents
+                assert np.allclose(gv[b, m, g], srow[got], rtol=0, atol=atol), np.abs(gv[b, m, g] - srow[got]).max()
+                # sorted by (score desc, idx asc) in the GPU's own arithmetic
+                assert np.all(np.diff(gv[b, m, g]) <= 0)
+                if np.array_equal(got, want):
+                    continue
+                sk = ov[b, m, g, k - 1]
+                band = 1e-3 * abs(sk)
+                sure = want[srow[want] > sk + band]
+                assert set(sure.tolist()) <= set(got.tolist()), "a clear winner is missing"
+                assert np.all(srow[got] >= sk - band), "selected a document outside the tie band"
+                clear = np.all(np.abs(np.diff(srow[want])) > band) and \
+                    (k == case.N or srow[want[-1]] - np.sort(srow)[::-1][k] > band)
+                assert not clear, (got, want)
+                n_band += 1
+    return oi, n_band
+
+
+def check_attend(case, out, lse, idx_np, pos0, q_pos):
+    oo, ol = O.sparse_attend(case.q, case.K, case.V, idx_np, case.Kl, case.Vl, pos0, q_pos, case.base)
+    go = out.float().cpu().numpy().astype(np.float64)
+    gl = lse.cpu().numpy().astype(np.float64)
+    err = np.abs(go - oo)
+    rel = np.linalg.norm(err) / max(np.linalg.norm(oo), 1e-30)
+    say(f"   attend: max-abs {err.max():.3e}  rel-L2 {rel:.3e}")
+    assert err.max() <= 2e-2, err.max()
+    assert rel <= 5e-3, rel
+    fin = np.isfinite(ol)
+    assert np.array_equal(np.isfinite(gl), fin)
+    assert np.allclose(gl[fin], ol[fin], rtol=0, atol=5e-3), np.abs(gl[fin] - ol[fin]).max()
+    return err.max(), rel
+
+
+CASES = {
+    # name: (seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k)
+    "cfg1_tiny": (1000, 64, 2, 4, 512, 64, 64, 1, 1, 256, 1e4, 4),
+    "d128_ragged": (2000, 37, 2, 4, 512, 128, 64, 2, 1, 77, 1e6, 5),
+    "d128_batch16": (3000, 150, 1, 4, 128, 128, 16, 16, 1, 40, 1e6, 8),
+    "d64_c2_batch20": (4000, 301, 2, 2, 64, 64, 32, 5, 4, 33, 1e4, 3),
+    "c16_r8": (5000, 21, 1, 8, 256, 128, 16, 1, 2, 0, 1e4, 21),
+    "c1_r1": (6000, 90, 3, 1, 64, 64, 64, 1, 3, 64, 1e6, 7),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_stage_parity(name):
+    seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k = CASES[name]
+    say(f"case {name}: N={N} Hkv={Hkv} r={r} G={G} d={d} P={P} B={B} M={M} Lloc={Lloc} k={k}")
+    case = Case(seed, N, Hkv, r, G, d, P, B, M, Lloc, base).to_device()
+    cfg = case.cfg()
+    say("   build_routing_keys")
+    KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+    torch.cuda.synchronize()
+    nd = check_routing_keys(case, cfg, KR, inv)
+    say(f"   routing keys ok ({nd} tie-adjacent roundings)")
+
+    say("   score_topk on the oracle's index")
+    KRo, invo = O.routing_keys(case.K, P)
+    dKRo, dinvo = upload_oracle_index(cfg, KRo, invo)
+    idx_s, val_s = msa.msa_score_topk(cfg, case.dq, dKRo, dinvo, k)
+    torch.cuda.synchronize()
+    oi, n_band = check_topk(case, idx_s, val_s, KRo, k)
+    say(f"   top-k ok ({n_band} selections inside the tie band)")
+    say("   score_topk on the GPU's own index")
+    idx, val = msa.msa_score_topk(cfg, case.dq, KR, inv, k)
+    torch.cuda.synchronize()
+    _, n_band = check_topk(case, idx, val, KRo, k, atol=2e-4 if nd else 2e-5)
+    say(f"   chained top-k ok ({n_band} inside the tie band)")
+
+    say("   sparse_attend (oracle's indices)")
+    pos0 = G
+    if M == 1:
+        q_pos = np.full((B, M), pos0 + Lloc - 1 if Lloc else pos0)
+    else:                                                          # staggered causal masks
+        q_pos = np.array([[pos0 + min(Lloc - 1, (3 * m + b) % max(Lloc, 1)) if Lloc else pos0
+                           for m in range(M)] for b in range(B)])
+    dpos = torch.from_numpy(q_pos.astype(np.int32)).cuda()
+    didx = torch.from_numpy(oi.astype(np.int32)).cuda()
+    out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    check_attend(case, out, lse, oi, pos0, q_pos)
+
+    say("   chained on the GPU's own indices")
+    out2, lse2 = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    check_attend(case, out2, lse2, idx.cpu().numpy().astype(np.int64), pos0, q_pos)
+
+
+def test_dot_similarity_and_incremental_build():
+    say("case dot + incremental build")
+    case = Case(7000, 45, 2, 4, 128, 128, 32, 3, 1, 0, 1e6).to_device()
+    cfg = case.cfg(sim=msa.MSA_SIM_DOT)
+    KR, inv = msa.alloc_routing_index(cfg)
+    KR.zero_()
+    inv.zero_()
+    for a, n in ((30, 15), (0, 7), (7, 23)):                       # pieces, out of order
+        msa.msa_build_routing_keys(cfg, case.dK, a, n, KR, inv)
+    torch.cuda.synchronize()
+    KR1, inv1 = msa.msa_build_routing_keys(cfg, case.dK)
+    torch.cuda.synchronize()
+    assert torch.equal(KR.view(torch.int16), KR1.view(torch.int16)) and torch.equal(inv, inv1)
+    check_routing_keys(case, cfg, KR, inv)
+    idx, val = msa.msa_score_topk(cfg, case.dq, KR, None, 6)
+    torch.cuda.synchronize()
+    KRb = bf16_to_f64(msa.untile_routing_keys(cfg, KR))
+    oi, ov, s = O.score_topk(case.q, KRb, case.C, 6, "dot")
+    assert np.array_equal(idx.cpu().numpy(), oi)
+    assert np.allclose(val.cpu().numpy(), ov, rtol=1e-5, atol=1e-4)
+
+
+def test_ties_duplicates_and_pads():
+    say("case ties / duplicate documents / -1 pads")
+    case = Case(8000, 40, 2, 4, 64, 64, 32, 2, 1, 48, 1e4)
+    for a, b in ((3, 17), (5, 39), (0, 20)):                       # exact duplicates -> exact score ties
+        case.K[b], case.Kb[b] = case.K[a], case.Kb[a]
+    case.to_device()
+    cfg = case.cfg()
+    KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+    idx, val = msa.msa_score_topk(cfg, case.dq, KR, inv, 40)       # k = N: full ranking
+    torch.cuda.synchronize()
+    gi = idx.cpu().numpy()
+    gv = val.cpu().numpy()
+    for b in range(2):
+        for g in range(2):
+            order = gi[b, 0, g].tolist()
+            assert sorted(order) == list(range(40))
+            for lo, hi in ((3, 17), (5, 39), (0, 20)):
+                assert order.index(lo) + 1 == order.index(hi), "equal scores: lower index first, adjacent"
+            assert gv[b, 0, g, order.index(3)] == gv[b, 0, g, order.index(17)]
+    # all-zero keys -> every score 0 -> idx = 0..k-1
+    zK = torch.zeros_like(case.dK)
+    KRz, invz = msa.msa_build_routing_keys(cfg, zK)
+    iz, vz = msa.msa_score_topk(cfg, case.dq, KRz, invz, 9)
+    torch.cuda.synchronize()
+    assert np.array_equal(iz.cpu().numpy(), np.broadcast_to(np.arange(9), (2, 1, 2, 9)))
+    assert np.all(vz.cpu().numpy() == 0)
+    # -1 pads are skipped; a document listed twice is attended twice; all -1 and no local -> zeros
+    sel = np.array([[[[4, -1, 9, 4], [-1, -1, 2, -1]]], [[[-1, -1, -1, -1], [7, 7, 7, 7]]]])
+    pos0 = 64
+    q_pos = np.array([[pos0 + 47], [pos0 + 10]])
+    didx = torch.from_numpy(sel.astype(np.int32)).cuda()
+    dpos = torch.from_numpy(q_pos.astype(np.int32)).cuda()
+    out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    check_attend(case, out, lse, sel, pos0, q_pos)
+    case.Kl = case.Vl = None
+    out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, None, None, pos0, dpos)
+    torch.cuda.synchronize()
+    check_attend(case, out, lse, sel, pos0, q_pos)
+    assert torch.all(out[1, 0, :4] == 0) and torch.all(torch.isinf(lse[1, 0, :4]))
+
+
+def test_positions_paper_offset_and_determinism():
+    say("case local_pos0 = k (paper's offset) and run-to-run determinism")
+    case = Case(9000, 30, 2, 4, 128, 128, 64, 1, 1, 50, 1e6).to_device()
+    cfg = case.cfg()
+    KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+    idx, val = msa.msa_score_topk(cfg, case.dq, KR, inv, 4)
+    pos0 = 4                                                       # Section 3.2.2: query positions start at k
+    q_pos = np.array([[pos0 + 49]])
+    dpos = torch.from_numpy(q_pos.astype(np.int32)).cuda()
+    out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    check_attend(case, out, lse, idx.cpu().numpy().astype(np.int64), pos0, q_pos)
+    for _ in range(5):
+        i2, v2 = msa.msa_score_topk(cfg, case.dq, KR, inv, 4)
+        o2, l2 = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx, case.dKl, case.dVl, pos0, dpos)
+        torch.cuda.synchronize()
+        assert torch.equal(i2, idx) and torch.equal(v2, val)
+        assert torch.equal(o2.view(torch.int16), out.view(torch.int16)) and torch.equal(l2, lse)
+
+
+def test_single_document_bank():
+    say("case N = 1, k = 1")
+    case = Case(9500, 1, 2, 4, 64, 64, 64, 1, 1, 0, 1e4).to_device()
+    cfg = case.cfg()
+    KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+    idx, val = msa.msa_score_topk(cfg, case.dq, KR, inv, 1)
+    torch.cuda.synchronize()
+    assert torch.all(idx == 0)
+    q_pos = np.array([[64]])
+    out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx, None, None, 64,
+                                     torch.from_numpy(q_pos.astype(np.int32)).cuda())
+    torch.cuda.synchronize()
+    check_attend(case, out, lse, idx.cpu().numpy().astype(np.int64), 64, q_pos)
