@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the MSA routed-decode hot path on one MI355X.
+
+A "step" is one pass of the online path over one batch of synthetic queries: msa_score_topk
+(relevance scores, document max, top-k) followed by msa_sparse_attend (gather with document-wise
+RoPE + attention) with every input already resident in HBM.  The routing index is built once before
+the timed region by msa_build_routing_keys -- the paper's Stage 1 is offline, once per bank version
+(Section 3.4.1) -- and its own time and bandwidth are reported in the "build" object.
+
+Prints ONE JSON line: metric value = routed decode queries/s; "roofline" = achieved HBM GB/s of the
+dominant kernel family (the routing scan) from HIP events on the launch stream; "cpu_baseline" = the
+float64 oracle timed on this machine's host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg5_decode_50m",
+                    help="cfg5_decode_50m (default), cfg3_batch32_4m, cfg2_decode_1m, cfg1_tiny_32k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-docs", type=int, default=512)
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, sample_docs):
+    """Time the oracle, as it stands, on a bounded sample of the workload:
+      routing  : all B*M queries over the first `sample_docs` documents (regenerated on the host),
+                 scaled linearly to N documents -- the scan is O(N) (paper, Section 5.1);
+      attention: one query, one KV group (its r heads) over its k selected documents + the local
+                 context, scaled by Hkv -- independent of N."""
+    import numpy as np
+    import msa_synth as S
+    from msa_synth import workloads as W
+    from oracle import msa_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    n_s = min(sample_docs, wl.N)
+    Ks = np.stack([W.host_doc(wl, "K", i)[1] for i in range(n_s)])
+    q = wl.q_host
+    t0 = time.perf_counter()
+    KRb, _ = O.routing_keys(Ks, wl.P)
+    t_build = time.perf_counter() - t0
+    kk = min(wl.k, n_s)
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        idx, val, _ = O.score_topk(q, KRb, wl.C, kk)
+    t_score = (time.perf_counter() - t0) / reps
+    sel = idx[0, 0, 0]
+    K_sel = Ks[sel][:, :1]
+    V_sel = np.stack([W.host_doc(wl, "V", int(i))[1][:1] for i in sel])
+    Kl = S.normal_bf16(wl.seeds["Kloc"], (1, 1, wl.Lloc, wl.d))[1]
+    Vl = S.normal_bf16(wl.seeds["Vloc"], (1, 1, wl.Lloc, wl.d))[1]
+    t0 = time.perf_counter()
+    O.sparse_attend(q[:1, :1, :wl.r], K_sel, V_sel, np.arange(kk)[None, None, None], Kl, Vl, wl.pos0,
+                    wl.q_pos_host[:1, :1], wl.base)
+    t_att = time.perf_counter() - t0
+    nq = wl.B * wl.M
+    per_query = t_score * (wl.N / n_s) / nq + t_att * wl.Hkv * (wl.k / kk)
+    return {
+        "value": 1.0 / per_query, "unit": "queries/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"float64 NumPy oracle, {os.cpu_count()} host cpus visible: routing of {nq} queries over "
+                   f"{n_s} of {wl.N} documents {t_score:.3f}s (scaled x{wl.N / n_s:.1f}: extrapolated); attention "
+                   f"of 1 query, 1 of {wl.Hkv} KV groups over {kk} documents + {wl.Lloc} local tokens "
+                   f"{t_att:.3f}s (scaled x{wl.Hkv}); pooling {n_s} documents {t_build:.3f}s (offline, not in value)"),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2603_23516_amd as msa
+    from msa_synth import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    msa.load_library()
+    torch.cuda.set_device(0)
+    wl = W.make(args.workload)
+    cfg = msa.MsaConfig(wl.N, wl.G, wl.P, wl.Hq, wl.Hkv, wl.d, wl.base)
+    ab = W.algorithmic_bytes(wl)
+    stream = torch.cuda.current_stream()
+
+    # ---- offline stage: routing index (timed on its own, outside the metric) -------------------
+    KR, inv = msa.alloc_routing_index(cfg)
+    msa.msa_build_routing_keys(cfg, wl.K, KR=KR, inv_norm=inv)          # warm-up
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    msa.msa_build_routing_keys(cfg, wl.K, KR=KR, inv_norm=inv)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    build_ms = e0.elapsed_time(e1)
+
+    # ---- online path: everything preallocated, nothing allocated inside the timed region --------
+    B, M, k = wl.B, wl.M, wl.k
+    idx = torch.empty((B, M, wl.Hkv, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((B, M, wl.Hkv, k), dtype=torch.float32, device="cuda")
+    out = torch.empty_like(wl.q)
+    lse = torch.empty((B, M, wl.Hq), dtype=torch.float32, device="cuda")
+    ws_s = torch.empty(msa.score_topk_workspace_bytes(cfg, B, M, k), dtype=torch.uint8, device="cuda")
+    ws_a = torch.empty(msa.sparse_attend_workspace_bytes(cfg, B, M, k, wl.Lloc), dtype=torch.uint8, device="cuda")
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        msa.msa_score_topk(cfg, wl.q, KR, inv, k, idx, val, ws_s, stream=stream)
+        if ev:
+            ev[1].record(stream)
+        msa.msa_sparse_attend(cfg, wl.q, wl.K, wl.V, idx, wl.Kloc, wl.Vloc, wl.pos0, wl.q_pos, out, lse,
+                              ws_a, stream=stream)
+        if ev:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    score_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    attend_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    ms_per_step = wall * 1e3 / args.steps
+    nq = B * M
+    qps = nq / (ms_per_step * 1e-3)
+    score_gbs = ab["score"] / (score_ms * 1e-3) / 1e9
+    attend_gbs = ab["attend"] / (attend_ms * 1e-3) / 1e9
+    build_gbs = ab["build"] / (build_ms * 1e-3) / 1e9
+
+    res = {
+        "metric": "routed decode queries/sec (score+top-k then sparse attend, one MSA layer)",
+        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "memory_tokens": wl.N * wl.G, "docs": wl.N, "doc_len": wl.G,
+                   "chunk": wl.P, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.d, "batch": B,
+                   "query_tokens": M, "top_k": k, "local_tokens": wl.Lloc, "rope_base": wl.base},
+        "roofline": {"bound": "hbm", "kernel": "msa_score_topk (score_scan_kernel + merge)",
+                     "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": score_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": ab["score"], "avg_ms": score_ms},
+        "attend": {"bound": "hbm", "achieved": attend_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                   "frac": attend_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": ab["attend"],
+                   "avg_ms": attend_ms},
+        "build": {"bound": "hbm", "achieved": build_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                  "frac": build_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": ab["build"],
+                  "ms": build_ms, "note": "offline Stage 1, once per bank version; outside the timed steps"},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_docs)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
