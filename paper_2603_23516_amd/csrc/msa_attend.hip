@@ -354,27 +354,68 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
   }
 }
 
-// Log-sum-exp merge of the split partials of one (query, head).
+// Log-sum-exp merge of the split partials of one (query, head); one thread per output element.
+// The (max, sum) pairs are loaded split-parallel and reduced through LDS so that no thread walks a
+// chain of dependent loads.
+constexpr int kMaxAttSplits = 256;
+
 template <int D>
-__global__ void attend_merge_kernel(const float* __restrict__ part_o, const float2* __restrict__ part_ml,
-                                    uint16_t* __restrict__ out, float* __restrict__ lse, int n_splits) {
+__global__ __launch_bounds__(D) void attend_merge_kernel(const float* __restrict__ part_o,
+                                                         const float2* __restrict__ part_ml,
+                                                         uint16_t* __restrict__ out,
+                                                         float* __restrict__ lse, int n_splits) {
+  __shared__ float wgt[kMaxAttSplits];
+  __shared__ float red[4];
   const long long qh = blockIdx.x;
-  const int dd = threadIdx.x;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  constexpr int NW = D / 64;
+  float2 ml[kMaxAttSplits / D];
   float mx = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, part_ml[qh * n_splits + s].x);
-  float osum = 0.f, lsum = 0.f;
-  if (mx != -INFINITY) {
-    for (int s = 0; s < n_splits; ++s) {
-      const float2 ml = part_ml[qh * n_splits + s];
-      const float f = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - mx);
-      lsum += f * ml.y;
-      osum += f * part_o[(qh * n_splits + s) * D + dd];
-    }
+#pragma unroll
+  for (int i = 0; i < kMaxAttSplits / D; ++i) {
+    const int s = tid + i * D;
+    ml[i] = (s < n_splits) ? part_ml[qh * n_splits + s] : make_float2(-INFINITY, 0.f);
+    mx = fmaxf(mx, ml[i].x);
   }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  if ((tid & 63) == 0) red[wave] = mx;
+  __syncthreads();
+  mx = red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) mx = fmaxf(mx, red[w]);
+  __syncthreads();
+  float lsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < kMaxAttSplits / D; ++i) {
+    const int s = tid + i * D;
+    const float f = (ml[i].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[i].x - mx);
+    if (s < n_splits) wgt[s] = f;
+    lsum += f * ml[i].y;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off, 64);
+  if ((tid & 63) == 0) red[wave] = lsum;
+  __syncthreads();
+  lsum = red[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) lsum += red[w];
+  float osum = 0.f;
+  const float* po = part_o + qh * n_splits * D + tid;
+  int s = 0;
+  for (; s + 8 <= n_splits; s += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = po[(long long)(s + u) * D];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) osum += wgt[s + u] * v[u];
+  }
+  for (; s < n_splits; ++s) osum += wgt[s] * po[(long long)s * D];
   const float res = (lsum > 0.f) ? osum / lsum : 0.f;
   const uint32_t pk = pack_bf16(res, 0.f);
-  out[qh * D + dd] = (uint16_t)(pk & 0xffffu);
-  if (lse != nullptr && dd == 0) {
+  out[qh * D + tid] = (uint16_t)(pk & 0xffffu);
+  if (lse != nullptr && tid == 0) {
     lse[qh] = (lsum > 0.f) ? (mx + log2f(lsum)) * 0.6931471805599453f : -INFINITY;
   }
 }
@@ -386,6 +427,8 @@ AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc) {
   const long long pairs = (long long)BM * dm.Hkv;
   long long per = ((long long)p.steps_total * pairs + 1023) / 1024;  // aim at ~1024 blocks
   if (per < kAttWaves) per = kAttWaves;
+  const long long per_cap = (p.steps_total + kMaxAttSplits - 1) / kMaxAttSplits;  // n_splits <= 256
+  if (per < per_cap) per = per_cap;
   if (per > p.steps_total) per = p.steps_total;
   if (per < 1) per = 1;
   p.steps_per_split = (int)per;

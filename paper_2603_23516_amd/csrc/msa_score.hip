@@ -11,21 +11,27 @@
 // a bf16 (hi, lo) pair in two adjacent rows (row 2i = hi, row 2i+1 = lo), so one MFMA tile serves 8
 // queries at ~16 significant bits and the two halves of a score land in the same lane.  The index is
 // stored in tiles of 16 keys already in B-operand order, so a wave reads a tile with d/32 coalesced
-// 1 KiB loads and no LDS staging.  Document max = DPP max over the C lanes of a document; top-k =
-// per-wave threshold filter + candidate list in LDS, pruned by rank counting on 64-bit
-// (score, ~doc) keys, merged per block and then across blocks by a small second kernel.
+// 1 KiB loads and no LDS staging.
+//
+// Work split.  One wavefront = one workgroup = one contiguous stream of tiles of one KV head, with a
+// ring of kPrefetch tiles in flight; there is no synchronisation between waves.  Document max = DPP
+// max over the C lanes of a document.  Top-k = threshold filter + per-(wave, query) candidate list in
+// LDS: accepted lanes get their slots from a ballot and a population count (no atomics, counters live
+// in registers), lists are pruned to the k best by rank counting on 64-bit (score, ~doc) keys, and
+// the sorted per-wave lists are combined by a second, small kernel.
 #include "msa_device.h"
 #include "msa_host.h"
 
 namespace msa {
 
-constexpr int kScoreWaves = 4;
+constexpr int kPrefetch = 4;         // tiles in flight per wave
+constexpr int kListBytes = 16384;    // LDS per wave for candidate lists
 
 struct ScoreArgs {
   const uint16_t* q_route;  // [BM][Hq][D]
   const uint16_t* KR;       // tiled
   const float* inv_norm;    // may be null (dot)
-  unsigned long long* ws;   // [Hkv][BM][n_splits][k] candidate keys
+  unsigned long long* ws;   // [Hkv][BM][n_splits][k] candidate keys, each list sorted descending
   int BM, q0;               // total queries, first query of this pass
   int Hq, Hkv, r;
   int N, C, cos;
@@ -46,52 +52,61 @@ __device__ __forceinline__ float group_max_rt(float x, int C) {
   return x;
 }
 
-// Keep the k largest of the c (<= 128) keys of one candidate list, sorted descending, by rank
-// counting (keys are distinct).  Executed by one whole wave.  Returns the new count.
-__device__ __forceinline__ int prune_list(volatile unsigned long long* cl, int c, int k, int lane,
-                                          volatile float* thr_slot) {
-  const unsigned long long ka = (lane < c) ? cl[lane] : 0ull;
-  const unsigned long long kb = (lane + 64 < c) ? cl[lane + 64] : 0ull;
-  int ra = 0, rb = 0;
-  for (int j = 0; j < c; ++j) {
+// Keep the k largest of the c (<= CAP) distinct keys of one list, sorted descending, by rank
+// counting.  Executed by one whole wave.  Returns the new count min(c, k).
+template <int CAP>
+__device__ __forceinline__ int prune_list(unsigned long long* cl, int c, int k, int lane) {
+  constexpr int PER = CAP / 64;
+  unsigned long long key[PER];
+  int rank[PER];
+#pragma unroll
+  for (int p = 0; p < PER; ++p) {
+    key[p] = (lane + 64 * p < c) ? cl[lane + 64 * p] : 0ull;
+    rank[p] = 0;
+  }
+  int j = 0;
+  for (; j + 4 <= c; j += 4) {
+    const unsigned long long x0 = cl[j], x1 = cl[j + 1], x2 = cl[j + 2], x3 = cl[j + 3];
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      if (64 * p < c)
+        rank[p] += (x0 > key[p] ? 1 : 0) + (x1 > key[p] ? 1 : 0) + (x2 > key[p] ? 1 : 0) +
+                   (x3 > key[p] ? 1 : 0);
+    }
+  }
+  for (; j < c; ++j) {
     const unsigned long long x = cl[j];
-    ra += (x > ka) ? 1 : 0;
-    rb += (x > kb) ? 1 : 0;
+#pragma unroll
+    for (int p = 0; p < PER; ++p) rank[p] += (x > key[p]) ? 1 : 0;
   }
   wave_sync();
-  if (lane < c && ra < k) cl[ra] = ka;
-  if (lane + 64 < c && rb < k) cl[rb] = kb;
-  if (c >= k) {
-    if (lane < c && ra == k - 1) *thr_slot = key_score(ka);
-    if (lane + 64 < c && rb == k - 1) *thr_slot = key_score(kb);
-  }
+#pragma unroll
+  for (int p = 0; p < PER; ++p)
+    if (lane + 64 * p < c && rank[p] < k) cl[rank[p]] = key[p];
   wave_sync();
   return c < k ? c : k;
 }
 
 template <int D, int NQT>
-__global__ __launch_bounds__(256) void score_scan_kernel(ScoreArgs a) {
-  constexpr int NS = D / 32;              // MFMA k-slices per key
-  constexpr int NQ = 8 * NQT;             // queries per pass
-  constexpr int CAP = (NQT == 1) ? 128 : 96;
+__global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
+  constexpr int NS = D / 32;   // MFMA k-slices per key
+  constexpr int NQ = 8 * NQT;  // queries per pass
+  constexpr int CAP = kListBytes / (8 * NQ);
   constexpr int TILE_ELEMS = 16 * D;
+  static_assert(NQ * D * 4 <= kListBytes, "folded queries must fit in the list area");
 
-  __shared__ float qf[NQ][D];
-  __shared__ unsigned long long cand[kScoreWaves][NQ][CAP];
-  __shared__ int cnt[kScoreWaves][NQ];
-  __shared__ float thr_s[kScoreWaves][NQ];
-  __shared__ unsigned long long mbuf[256];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kListBytes];
+  float* qf = reinterpret_cast<float*>(smem);                             // [NQ][D], prologue only
+  unsigned long long* cand = reinterpret_cast<unsigned long long*>(smem);  // [NQ][CAP]
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int lane = threadIdx.x;
   const int rr = lane >> 4;  // MFMA k-group / D row-group
   const int n = lane & 15;   // A row / B column / D column
   const int sp = blockIdx.x;
   const int g = blockIdx.y;
 
   // ---- fold the r heads of this group into one fp32 routing query per token -------------------
-  for (int qi = wave; qi < NQ; qi += kScoreWaves) {
+  for (int qi = 0; qi < NQ; ++qi) {
     const int qg = a.q0 + qi;
     float f[D / 64];
 #pragma unroll
@@ -114,13 +129,9 @@ __global__ __launch_bounds__(256) void score_scan_kernel(ScoreArgs a) {
       }
     }
 #pragma unroll
-    for (int e = 0; e < D / 64; ++e) qf[qi][lane + 64 * e] = f[e] / (float)a.r;
+    for (int e = 0; e < D / 64; ++e) qf[qi * D + lane + 64 * e] = f[e] / (float)a.r;
   }
-  for (int qi = lane; qi < NQ; qi += 64) {
-    cnt[wave][qi] = 0;
-    thr_s[wave][qi] = (a.q0 + qi < a.BM) ? -INFINITY : INFINITY;
-  }
-  __syncthreads();
+  wave_sync();
 
   // ---- A operands: row n of tile t is query 8t + n/2, hi (even n) or lo (odd n) half ----------
   bf16x8_t A[NQT][NS];
@@ -133,22 +144,30 @@ __global__ __launch_bounds__(256) void score_scan_kernel(ScoreArgs a) {
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         float h0, l0, h1, l1;
-        split_bf16(qf[qi][32 * s + 8 * rr + 2 * jj], h0, l0);
-        split_bf16(qf[qi][32 * s + 8 * rr + 2 * jj + 1], h1, l1);
+        split_bf16(qf[qi * D + 32 * s + 8 * rr + 2 * jj], h0, l0);
+        split_bf16(qf[qi * D + 32 * s + 8 * rr + 2 * jj + 1], h1, l1);
         w[jj] = (n & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
       }
       A[t][s] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
     }
   }
-  // per-lane thresholds of the two queries this lane sees per tile: 8t + 2rr and 8t + 2rr + 1
-  float thr[NQT][2];
-#pragma unroll
-  for (int t = 0; t < NQT; ++t) {
-    thr[t][0] = thr_s[wave][8 * t + 2 * rr];
-    thr[t][1] = thr_s[wave][8 * t + 2 * rr + 1];
-  }
+  wave_sync();  // qf is dead from here on; the same LDS now holds the candidate lists
 
-  // ---- stream this block's tiles -------------------------------------------------------------
+  // This lane sees queries 8t + 2rr + e (e = 0, 1) of every tile; all 16 lanes of a row keep
+  // identical copies of their counters and thresholds.
+  float thr[NQT][2];
+  int cnt[NQT][2];
+#pragma unroll
+  for (int t = 0; t < NQT; ++t)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      thr[t][e] = (a.q0 + 8 * t + 2 * rr + e < a.BM) ? -INFINITY : INFINITY;
+      cnt[t][e] = 0;
+    }
+  int limit = 2 * a.k < 32 ? 32 : 2 * a.k;  // prune a list when it grows past this
+  if (limit > CAP - 16) limit = CAP - 16;
+
+  // ---- stream this wave's tiles -----------------------------------------------------------------
   const long long tb = (long long)sp * a.tiles_per_split;
   long long te = tb + a.tiles_per_split;
   if (te > a.tiles) te = a.tiles;
@@ -157,143 +176,208 @@ __global__ __launch_bounds__(256) void score_scan_kernel(ScoreArgs a) {
   const int dpt = 16 / a.C;  // documents per tile
   const int ndoc = n / a.C;  // this lane's document inside a tile
   const bool lead_lane = (n & (a.C - 1)) == 0;
+  const uint32_t below = (1u << n) - 1u;
 
-  uint4 cur[NS];
-  float cinv = 1.0f;
-  long long t = tb + wave;
-  if (t < te) {
+  uint4 buf[kPrefetch][NS];
+  float binv[kPrefetch];
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
-      cur[s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512 + lane * 8);
-    if (ing) cinv = ing[t * 16 + n];
-  }
-  for (; t < te; t += kScoreWaves) {
-    uint4 nxt[NS];
-    float ninv = 1.0f;
-    const long long tn = t + kScoreWaves;
-    if (tn < te) {
+  for (int u = 0; u < kPrefetch; ++u) {
+    const long long t = tb + u;
+    binv[u] = 1.0f;
+    if (t < te) {
 #pragma unroll
       for (int s = 0; s < NS; ++s)
-        nxt[s] = *reinterpret_cast<const uint4*>(KRg + tn * TILE_ELEMS + s * 512 + lane * 8);
-      if (ing) ninv = ing[tn * 16 + n];
+        buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512 + lane * 8);
+      if (ing) binv[u] = ing[t * 16 + n];
     } else {
 #pragma unroll
-      for (int s = 0; s < NS; ++s) nxt[s] = make_uint4(0, 0, 0, 0);
+      for (int s = 0; s < NS; ++s) buf[u][s] = make_uint4(0, 0, 0, 0);
     }
+  }
 
-    const long long doc = t * dpt + ndoc;
-    const bool lead = lead_lane && doc < a.N;
-    float sc[NQT][2];
-    bool hit = false;
+  for (long long base = tb; base < te; base += kPrefetch) {
 #pragma unroll
-    for (int tq = 0; tq < NQT; ++tq) {
-      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < kPrefetch; ++u) {
+      const long long t = base + u;
+      if (t >= te) break;  // wave-uniform
+      uint4 cur[NS];
 #pragma unroll
-      for (int s = 0; s < NS; ++s) acc = mfma16(A[tq][s], as_bf16x8(cur[s]), acc);
-      sc[tq][0] = group_max_rt((acc[0] + acc[1]) * cinv, a.C);
-      sc[tq][1] = group_max_rt((acc[2] + acc[3]) * cinv, a.C);
-      hit = hit || (lead && (sc[tq][0] >= thr[tq][0] || sc[tq][1] >= thr[tq][1]));
-    }
-    if (__any(hit)) {
+      for (int s = 0; s < NS; ++s) cur[s] = buf[u][s];
+      const float cinv = binv[u];
+      const long long tn = t + kPrefetch;
+      if (tn < te) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+          buf[u][s] = *reinterpret_cast<const uint4*>(KRg + tn * TILE_ELEMS + s * 512 + lane * 8);
+        if (ing) binv[u] = ing[tn * 16 + n];
+      }
+
+      const long long doc = t * dpt + ndoc;
+      const bool lead = lead_lane && doc < a.N;
+      bool over = false;
 #pragma unroll
       for (int tq = 0; tq < NQT; ++tq) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NS; ++s) acc = mfma16(A[tq][s], as_bf16x8(cur[s]), acc);
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-          if (lead && sc[tq][e] >= thr[tq][e]) {
+          const float sc = group_max_rt((acc[2 * e] + acc[2 * e + 1]) * cinv, a.C);
+          const bool pred = lead && sc >= thr[tq][e];
+          const unsigned long long m = __ballot(pred);
+          const uint32_t half = (rr & 2) ? (uint32_t)(m >> 32) : (uint32_t)m;
+          const uint32_t row = (half >> ((rr & 1) * 16)) & 0xffffu;
+          if (pred) {
             const int qi = 8 * tq + 2 * rr + e;
-            const int slot = atomicAdd(&cnt[wave][qi], 1);
-            cand[wave][qi][slot] = make_key(sc[tq][e], (uint32_t)doc);
+            cand[qi * CAP + cnt[tq][e] + __popc(row & below)] = make_key(sc, (uint32_t)doc);
           }
+          cnt[tq][e] += __popc(row);
+          over = over || cnt[tq][e] > limit;
         }
       }
-      wave_sync();
-      for (int qi = 0; qi < NQ; ++qi) {
-        const int c = ((volatile int*)cnt[wave])[qi];
-        if (c > CAP - 16) {
-          const int nc = prune_list(cand[wave][qi], c, a.k, lane, &thr_s[wave][qi]);
-          if (lane == 0) cnt[wave][qi] = nc;
-        }
-      }
-      wave_sync();
+      if (__any(over)) {
+        wave_sync();
 #pragma unroll
-      for (int tq = 0; tq < NQT; ++tq) {
-        thr[tq][0] = ((volatile float*)thr_s[wave])[8 * tq + 2 * rr];
-        thr[tq][1] = ((volatile float*)thr_s[wave])[8 * tq + 2 * rr + 1];
+        for (int tq = 0; tq < NQT; ++tq)
+#pragma unroll
+          for (int row = 0; row < 4; ++row)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              const int c = __builtin_amdgcn_readlane(cnt[tq][e], 16 * row);
+              if (c > limit) {  // wave-uniform
+                unsigned long long* cl = cand + (8 * tq + 2 * row + e) * CAP;
+                const int nc = prune_list<CAP>(cl, c, a.k, lane);
+                const float nt = key_score(cl[a.k - 1]);
+                if (rr == row) {
+                  cnt[tq][e] = nc;
+                  thr[tq][e] = nt;
+                }
+              }
+            }
+        wave_sync();
       }
     }
-#pragma unroll
-    for (int s = 0; s < NS; ++s) cur[s] = nxt[s];
-    cinv = ninv;
   }
 
-  // ---- per-wave lists -> sorted top-k; then merge the four waves per query --------------------
+  // ---- sort every list and hand the k best to the merge kernel --------------------------------
   wave_sync();
-  for (int qi = 0; qi < NQ; ++qi) {
-    const int c = ((volatile int*)cnt[wave])[qi];
-    const int nc = prune_list(cand[wave][qi], c, a.k, lane, &thr_s[wave][qi]);
-    if (lane == 0) cnt[wave][qi] = nc;
-  }
-  __syncthreads();
-  for (int qi = 0; qi < NQ; ++qi) {
-    const int qg = a.q0 + qi;
-    if (qg >= a.BM) break;  // block-uniform
-    unsigned long long key = 0ull;
-    if (lane < cnt[wave][qi]) key = cand[wave][qi][lane];
-    mbuf[tid] = key;
-    __syncthreads();
-    int rank = 0;
-    for (int j = 0; j < 256; ++j) rank += (mbuf[j] > key) ? 1 : 0;
-    const int total = __syncthreads_count(key != 0ull);
-    unsigned long long* dst = a.ws + (((long long)g * a.BM + qg) * a.n_splits + sp) * a.k;
-    if (key != 0ull && rank < a.k) dst[rank] = key;
-    if (tid >= total && tid < a.k) dst[tid] = 0ull;
-  }
+#pragma unroll
+  for (int tq = 0; tq < NQT; ++tq)
+#pragma unroll
+    for (int row = 0; row < 4; ++row)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int qi = 8 * tq + 2 * row + e;
+        const int qg = a.q0 + qi;
+        if (qg < a.BM) {  // wave-uniform
+          const int c = __builtin_amdgcn_readlane(cnt[tq][e], 16 * row);
+          unsigned long long* cl = cand + qi * CAP;
+          const int nc = prune_list<CAP>(cl, c, a.k, lane);
+          unsigned long long* dst = a.ws + (((long long)g * a.BM + qg) * a.n_splits + sp) * a.k;
+          if (lane < a.k) dst[lane] = (lane < nc) ? cl[lane] : 0ull;
+        }
+      }
 }
 
-// Merge the n_splits sorted lists of one (query, group): bitonic sort of n_splits*k keys in LDS.
+// Combine the n_lists sorted lists (k entries each, zero-padded) of one (query, group).
+//   1. A lower bound theta on the k-th best key: the first j+1 entries of every list, with
+//      n_lists*(j+1) >= k, are that many distinct candidates, so their k-th largest is one.
+//   2. Survivors (key >= theta) are compacted into LDS and ranked by counting.
+//   3. If more than kMaxSurv survive (adversarial order), fall back to k rounds of block-wide argmax.
+constexpr int kMaxSub = 1152;
+constexpr int kMaxSurv = 2048;
+
 __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long long* __restrict__ ws,
                                                           int32_t* __restrict__ out_idx,
                                                           float* __restrict__ out_score, int BM,
-                                                          int Hkv, int n_splits, int k, int n2) {
-  extern __shared__ unsigned long long buf[];
+                                                          int Hkv, int n_lists, int k) {
+  __shared__ unsigned long long sub[kMaxSub];
+  __shared__ unsigned long long surv[kMaxSurv];
+  __shared__ unsigned long long red[4];
+  __shared__ unsigned long long theta_s;
+  __shared__ int n_surv;
   const int tid = threadIdx.x;
   const int qg = blockIdx.x % BM;
   const int g = blockIdx.x / BM;
-  const int T = n_splits * k;
+  const int T = n_lists * k;
   const unsigned long long* src = ws + ((long long)g * BM + qg) * T;
-  for (int i = tid; i < n2; i += 256) buf[i] = (i < T) ? src[i] : 0ull;
-  for (int size = 2; size <= n2; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
-      for (int i = tid; i < (n2 >> 1); i += 256) {
-        const int pos = 2 * i - (i & (stride - 1));
-        const unsigned long long x = buf[pos], y = buf[pos + stride];
-        const bool desc = (pos & size) == 0;
-        if ((x < y) == desc) {
-          buf[pos] = y;
-          buf[pos + stride] = x;
-        }
-      }
+  const long long o_base = ((long long)qg * Hkv + g) * k;
+
+  const int depth = (k + n_lists - 1) / n_lists;  // entries taken from the head of every list
+  const int P = n_lists * depth;                  // k <= P < k + n_lists
+  for (int i = tid; i < P; i += 256) sub[i] = src[(i / depth) * k + (i % depth)];
+  if (tid == 0) {
+    n_surv = 0;
+    theta_s = 0ull;
+  }
+  __syncthreads();
+  for (int i = tid; i < P; i += 256) {
+    const unsigned long long x = sub[i];
+    int rank = 0;
+    for (int j = 0; j < P; ++j) rank += (sub[j] > x) ? 1 : 0;
+    if (rank == k - 1 && x != 0ull) theta_s = x;  // keys are distinct, zeros are padding
+  }
+  __syncthreads();
+  const unsigned long long theta = theta_s;
+  for (int i = tid; i < T; i += 256) {
+    const unsigned long long x = src[i];
+    if (x != 0ull && x >= theta) {
+      const int slot = atomicAdd(&n_surv, 1);
+      if (slot < kMaxSurv) surv[slot] = x;
     }
   }
   __syncthreads();
-  if (tid < k) {
-    const unsigned long long key = buf[tid];
-    const long long o = ((long long)qg * Hkv + g) * k + tid;
-    out_idx[o] = key ? (int32_t)key_doc(key) : -1;
-    if (out_score) out_score[o] = key ? key_score(key) : -INFINITY;
+  const int S = n_surv;
+  if (S <= kMaxSurv) {
+    for (int i = tid; i < S; i += 256) {
+      const unsigned long long x = surv[i];
+      int rank = 0;
+      for (int j = 0; j < S; ++j) rank += (surv[j] > x) ? 1 : 0;
+      if (rank < k) {
+        out_idx[o_base + rank] = (int32_t)key_doc(x);
+        if (out_score) out_score[o_base + rank] = key_score(x);
+      }
+    }
+    for (int i = S + tid; i < k; i += 256) {  // fewer than k valid candidates (cannot happen for k <= N)
+      out_idx[o_base + i] = -1;
+      if (out_score) out_score[o_base + i] = -INFINITY;
+    }
+    return;
+  }
+  // fallback: k rounds of "largest key below the previous winner"
+  unsigned long long prev = ~0ull;
+  for (int round = 0; round < k; ++round) {
+    unsigned long long best = 0ull;
+    for (int i = tid; i < T; i += 256) {
+      const unsigned long long x = src[i];
+      if (x < prev && x > best) best = x;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const unsigned long long y = __shfl_xor(best, off, 64);
+      best = y > best ? y : best;
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = best;
+    __syncthreads();
+    best = red[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) best = red[w] > best ? red[w] : best;
+    if (tid == 0) {
+      out_idx[o_base + round] = best ? (int32_t)key_doc(best) : -1;
+      if (out_score) out_score[o_base + round] = best ? key_score(best) : -INFINITY;
+    }
+    prev = best ? best : 0ull;
   }
 }
 
 ScorePlan plan_score(const Dims& dm, int BM, int k) {
   ScorePlan p;
-  long long want = 2048 / dm.Hkv;
-  if (want < 1) want = 1;
-  long long by_tiles = (dm.tiles + 7) / 8;
-  long long by_merge = 4096 / k;
-  long long ns = want;
+  long long ns = 2048 / dm.Hkv;  // ~8 waves per CU on 256 CUs
+  if (ns < 1) ns = 1;
+  const long long by_tiles = (dm.tiles + kPrefetch - 1) / kPrefetch;
   if (ns > by_tiles) ns = by_tiles;
-  if (ns > by_merge) ns = by_merge;
+  if (ns > 1024) ns = 1024;
   if (ns < 1) ns = 1;
   p.tiles_per_split = (int)((dm.tiles + ns - 1) / ns);
   p.n_splits = (int)((dm.tiles + p.tiles_per_split - 1) / p.tiles_per_split);
@@ -322,7 +406,7 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
   a.tiles_per_split = pl.tiles_per_split;
   a.n_splits = pl.n_splits;
   a.k = k;
-  dim3 grid(pl.n_splits, dm.Hkv), block(256);
+  dim3 grid(pl.n_splits, dm.Hkv), block(64);
   for (int pass = 0; pass < pl.n_pass; ++pass) {
     a.q0 = pass * pl.q_per_pass;
     if (dm.d == 128) {
@@ -338,11 +422,8 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
     }
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
-  int n2 = 2;
-  while (n2 < pl.n_splits * k) n2 <<= 1;
-  hipLaunchKernelGGL(score_merge_kernel, dim3(BM * dm.Hkv), dim3(256),
-                     (size_t)n2 * sizeof(unsigned long long), st, (const unsigned long long*)ws,
-                     out_idx, out_score, BM, dm.Hkv, pl.n_splits, k, n2);
+  hipLaunchKernelGGL(score_merge_kernel, dim3(BM * dm.Hkv), dim3(256), 0, st,
+                     (const unsigned long long*)ws, out_idx, out_score, BM, dm.Hkv, pl.n_splits, k);
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   return MSA_OK;
 }
