@@ -87,15 +87,31 @@ __device__ __forceinline__ int prune_list(unsigned long long* cl, int c, int k, 
   return c < k ? c : k;
 }
 
-template <int D, int NQT>
+// Sum over aligned groups of W consecutive lanes (W a power of two <= 64); every lane gets the sum.
+template <int W>
+__device__ __forceinline__ float group_sum(float x) {
+  if (W >= 2) x += dpp_f<kDppXor1>(x);
+  if (W >= 4) x += dpp_f<kDppXor2>(x);
+  if (W >= 8) x += dpp_f<kDppHalfMirror>(x);
+  if (W >= 16) x += dpp_f<kDppMirror>(x);
+  if (W >= 32) x += __shfl_xor(x, 16, 64);
+  if (W >= 64) x += __shfl_xor(x, 32, 64);
+  return x;
+}
+
+template <int D, int NQT, bool COS>
 __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
   constexpr int NS = D / 32;   // MFMA k-slices per key
   constexpr int NQ = 8 * NQT;  // queries per pass
   constexpr int CAP = kListBytes / (8 * NQ);
   constexpr int TILE_ELEMS = 16 * D;
+  constexpr int LPH = D / 8;    // lanes that hold one head vector (16-byte pieces)
+  constexpr int HPL = 64 / LPH; // head vectors per wave-wide load
   static_assert(NQ * D * 4 <= kListBytes, "folded queries must fit in the list area");
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[kListBytes];
+  __shared__ int cnt_s[NQ];
+  __shared__ float thr_s[NQ];
   float* qf = reinterpret_cast<float*>(smem);                             // [NQ][D], prologue only
   unsigned long long* cand = reinterpret_cast<unsigned long long*>(smem);  // [NQ][CAP]
 
@@ -106,30 +122,42 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
   const int g = blockIdx.y;
 
   // ---- fold the r heads of this group into one fp32 routing query per token -------------------
-  for (int qi = 0; qi < NQ; ++qi) {
-    const int qg = a.q0 + qi;
-    float f[D / 64];
+  // Lane = (head slot lane / LPH, 16-byte piece lane % LPH): one load covers HPL heads of a query.
+  {
+    const int piece = lane % LPH;
+    const int hs = lane / LPH;
+    const int n_hp = (a.r + HPL - 1) / HPL;  // loads per query (1 unless r > HPL)
+    for (int qi = 0; qi < NQ; ++qi) {
+      const int qg = a.q0 + qi;
+      float f[8];
 #pragma unroll
-    for (int e = 0; e < D / 64; ++e) f[e] = 0.f;
-    if (qg < a.BM) {
-      for (int hh = 0; hh < a.r; ++hh) {
-        const uint16_t* qp = a.q_route + ((long long)qg * a.Hq + g * a.r + hh) * D;
-        float x[D / 64];
+      for (int e = 0; e < 8; ++e) f[e] = 0.f;
+      for (int hp = 0; hp < n_hp; ++hp) {
+        const int hh = hp * HPL + hs;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (qg < a.BM && hh < a.r)
+          v = *reinterpret_cast<const uint4*>(a.q_route + ((long long)qg * a.Hq + g * a.r + hh) * D + piece * 8);
+        float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                      bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
         float ss = 0.f;
 #pragma unroll
-        for (int e = 0; e < D / 64; ++e) {
-          x[e] = __uint_as_float((uint32_t)qp[lane + 64 * e] << 16);
-          ss += x[e] * x[e];
-        }
+        for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+        ss = group_sum<LPH>(ss);
+        const float w = COS ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : 1.0f;
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) ss += __shfl_xor(ss, off, 64);
-        const float w = a.cos ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : 1.0f;
+        for (int e = 0; e < 8; ++e) f[e] += x[e] * w;
+      }
+      // add the head slots that hold the same piece (lanes piece, piece + LPH, ...)
 #pragma unroll
-        for (int e = 0; e < D / 64; ++e) f[e] += x[e] * w;
+      for (int off = LPH; off < 64; off <<= 1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] += __shfl_xor(f[e], off, 64);
+      }
+      if (hs == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[qi * D + piece * 8 + e] = f[e] / (float)a.r;
       }
     }
-#pragma unroll
-    for (int e = 0; e < D / 64; ++e) qf[qi * D + lane + 64 * e] = f[e] / (float)a.r;
   }
   wave_sync();
 
@@ -171,112 +199,120 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
   const long long tb = (long long)sp * a.tiles_per_split;
   long long te = tb + a.tiles_per_split;
   if (te > a.tiles) te = a.tiles;
-  const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS;
-  const float* ing = a.inv_norm ? a.inv_norm + (long long)g * a.tiles * 16 : nullptr;
+  const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS + lane * 8;
+  const float* ing = COS ? a.inv_norm + (long long)g * a.tiles * 16 + n : nullptr;
   const int dpt = 16 / a.C;  // documents per tile
   const int ndoc = n / a.C;  // this lane's document inside a tile
   const bool lead_lane = (n & (a.C - 1)) == 0;
   const uint32_t below = (1u << n) - 1u;
-
-  uint4 buf[kPrefetch][NS];
-  float binv[kPrefetch];
-#pragma unroll
-  for (int u = 0; u < kPrefetch; ++u) {
-    const long long t = tb + u;
-    binv[u] = 1.0f;
-    if (t < te) {
-#pragma unroll
-      for (int s = 0; s < NS; ++s)
-        buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512 + lane * 8);
-      if (ing) binv[u] = ing[t * 16 + n];
-    } else {
-#pragma unroll
-      for (int s = 0; s < NS; ++s) buf[u][s] = make_uint4(0, 0, 0, 0);
-    }
-  }
-
-  for (long long base = tb; base < te; base += kPrefetch) {
+  const long long t_last = te - 1;  // loads past the end re-read the last tile (always issued, so
+                                    // the number of loads in flight is the same on every path)
+  if (tb < te) {
+    uint4 buf[kPrefetch][NS];
+    float binv[kPrefetch];
 #pragma unroll
     for (int u = 0; u < kPrefetch; ++u) {
-      const long long t = base + u;
-      if (t >= te) break;  // wave-uniform
-      uint4 cur[NS];
+      const long long t = (tb + u < te) ? tb + u : t_last;
 #pragma unroll
-      for (int s = 0; s < NS; ++s) cur[s] = buf[u][s];
-      const float cinv = binv[u];
-      const long long tn = t + kPrefetch;
-      if (tn < te) {
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-          buf[u][s] = *reinterpret_cast<const uint4*>(KRg + tn * TILE_ELEMS + s * 512 + lane * 8);
-        if (ing) binv[u] = ing[tn * 16 + n];
-      }
+      for (int s = 0; s < NS; ++s)
+        buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512);
+      binv[u] = COS ? ing[t * 16] : 1.0f;
+    }
 
-      const long long doc = t * dpt + ndoc;
-      const bool lead = lead_lane && doc < a.N;
-      bool over = false;
+    for (long long base = tb; base < te; base += kPrefetch) {
 #pragma unroll
-      for (int tq = 0; tq < NQT; ++tq) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+      for (int u = 0; u < kPrefetch; ++u) {
+        const long long t = base + u;
+        uint4 cur[NS];
 #pragma unroll
-        for (int s = 0; s < NS; ++s) acc = mfma16(A[tq][s], as_bf16x8(cur[s]), acc);
+        for (int s = 0; s < NS; ++s) cur[s] = buf[u][s];
+        const float cinv = binv[u];
+        {
+          const long long tn = (t + kPrefetch < te) ? t + kPrefetch : t_last;
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const float sc = group_max_rt((acc[2 * e] + acc[2 * e + 1]) * cinv, a.C);
-          const bool pred = lead && sc >= thr[tq][e];
-          const unsigned long long m = __ballot(pred);
-          const uint32_t half = (rr & 2) ? (uint32_t)(m >> 32) : (uint32_t)m;
-          const uint32_t row = (half >> ((rr & 1) * 16)) & 0xffffu;
-          if (pred) {
-            const int qi = 8 * tq + 2 * rr + e;
-            cand[qi * CAP + cnt[tq][e] + __popc(row & below)] = make_key(sc, (uint32_t)doc);
-          }
-          cnt[tq][e] += __popc(row);
-          over = over || cnt[tq][e] > limit;
+          for (int s = 0; s < NS; ++s)
+            buf[u][s] = *reinterpret_cast<const uint4*>(KRg + tn * TILE_ELEMS + s * 512);
+          binv[u] = COS ? ing[tn * 16] : 1.0f;
         }
-      }
-      if (__any(over)) {
-        wave_sync();
+
+        const long long doc = t * dpt + ndoc;
+        const bool lead = lead_lane && t < te && doc < a.N;
+        bool over = false;
 #pragma unroll
-        for (int tq = 0; tq < NQT; ++tq)
+        for (int tq = 0; tq < NQT; ++tq) {
+          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int row = 0; row < 4; ++row)
+          for (int s = 0; s < NS; ++s) acc = mfma16(A[tq][s], as_bf16x8(cur[s]), acc);
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-              const int c = __builtin_amdgcn_readlane(cnt[tq][e], 16 * row);
-              if (c > limit) {  // wave-uniform
-                unsigned long long* cl = cand + (8 * tq + 2 * row + e) * CAP;
-                const int nc = prune_list<CAP>(cl, c, a.k, lane);
-                const float nt = key_score(cl[a.k - 1]);
-                if (rr == row) {
-                  cnt[tq][e] = nc;
-                  thr[tq][e] = nt;
-                }
+          for (int e = 0; e < 2; ++e) {
+            const float sc = group_max_rt((acc[2 * e] + acc[2 * e + 1]) * cinv, a.C);
+            const bool pred = lead && sc >= thr[tq][e];
+            const unsigned long long m = __ballot(pred);
+            const uint32_t half = (rr & 2) ? (uint32_t)(m >> 32) : (uint32_t)m;
+            const uint32_t row = (half >> ((rr & 1) * 16)) & 0xffffu;
+            if (pred) {
+              const int qi = 8 * tq + 2 * rr + e;
+              cand[qi * CAP + cnt[tq][e] + __popc(row & below)] = make_key(sc, (uint32_t)doc);
+            }
+            cnt[tq][e] += __popc(row);
+            over = over || cnt[tq][e] > limit;
+          }
+        }
+        if (__any(over)) {
+          // rare path: publish the counters, prune the lists that are too long, reload
+          if (n == 0) {
+#pragma unroll
+            for (int tq = 0; tq < NQT; ++tq) {
+              cnt_s[8 * tq + 2 * rr] = cnt[tq][0];
+              cnt_s[8 * tq + 2 * rr + 1] = cnt[tq][1];
+              thr_s[8 * tq + 2 * rr] = thr[tq][0];
+              thr_s[8 * tq + 2 * rr + 1] = thr[tq][1];
+            }
+          }
+          wave_sync();
+          for (int qi = 0; qi < NQ; ++qi) {
+            const int c = cnt_s[qi];
+            if (c > limit) {  // wave-uniform
+              unsigned long long* cl = cand + qi * CAP;
+              const int nc = prune_list<CAP>(cl, c, a.k, lane);
+              if (lane == 0) {
+                cnt_s[qi] = nc;
+                thr_s[qi] = key_score(cl[a.k - 1]);
               }
             }
-        wave_sync();
+          }
+          wave_sync();
+#pragma unroll
+          for (int tq = 0; tq < NQT; ++tq) {
+            cnt[tq][0] = cnt_s[8 * tq + 2 * rr];
+            cnt[tq][1] = cnt_s[8 * tq + 2 * rr + 1];
+            thr[tq][0] = thr_s[8 * tq + 2 * rr];
+            thr[tq][1] = thr_s[8 * tq + 2 * rr + 1];
+          }
+          wave_sync();
+        }
       }
     }
   }
 
   // ---- sort every list and hand the k best to the merge kernel --------------------------------
+  if (n == 0) {
+#pragma unroll
+    for (int tq = 0; tq < NQT; ++tq) {
+      cnt_s[8 * tq + 2 * rr] = cnt[tq][0];
+      cnt_s[8 * tq + 2 * rr + 1] = cnt[tq][1];
+    }
+  }
   wave_sync();
-#pragma unroll
-  for (int tq = 0; tq < NQT; ++tq)
-#pragma unroll
-    for (int row = 0; row < 4; ++row)
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const int qi = 8 * tq + 2 * row + e;
-        const int qg = a.q0 + qi;
-        if (qg < a.BM) {  // wave-uniform
-          const int c = __builtin_amdgcn_readlane(cnt[tq][e], 16 * row);
-          unsigned long long* cl = cand + qi * CAP;
-          const int nc = prune_list<CAP>(cl, c, a.k, lane);
-          unsigned long long* dst = a.ws + (((long long)g * a.BM + qg) * a.n_splits + sp) * a.k;
-          if (lane < a.k) dst[lane] = (lane < nc) ? cl[lane] : 0ull;
-        }
-      }
+  for (int qi = 0; qi < NQ; ++qi) {
+    const int qg = a.q0 + qi;
+    if (qg >= a.BM) break;  // wave-uniform
+    const int c = cnt_s[qi];
+    unsigned long long* cl = cand + qi * CAP;
+    const int nc = prune_list<CAP>(cl, c, a.k, lane);
+    unsigned long long* dst = a.ws + (((long long)g * a.BM + qg) * a.n_splits + sp) * a.k;
+    if (lane < a.k) dst[lane] = (lane < nc) ? cl[lane] : 0ull;
+  }
 }
 
 // Combine the n_lists sorted lists (k entries each, zero-padded) of one (query, group).
@@ -409,16 +445,16 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
   dim3 grid(pl.n_splits, dm.Hkv), block(64);
   for (int pass = 0; pass < pl.n_pass; ++pass) {
     a.q0 = pass * pl.q_per_pass;
-    if (dm.d == 128) {
-      if (pl.q_per_pass == 8)
-        hipLaunchKernelGGL((score_scan_kernel<128, 1>), grid, block, 0, st, a);
-      else
-        hipLaunchKernelGGL((score_scan_kernel<128, 2>), grid, block, 0, st, a);
-    } else {
-      if (pl.q_per_pass == 8)
-        hipLaunchKernelGGL((score_scan_kernel<64, 1>), grid, block, 0, st, a);
-      else
-        hipLaunchKernelGGL((score_scan_kernel<64, 2>), grid, block, 0, st, a);
+    const int sel = (dm.d == 128 ? 4 : 0) + (pl.q_per_pass == 16 ? 2 : 0) + (dm.cos ? 1 : 0);
+    switch (sel) {
+      case 0: hipLaunchKernelGGL((score_scan_kernel<64, 1, false>), grid, block, 0, st, a); break;
+      case 1: hipLaunchKernelGGL((score_scan_kernel<64, 1, true>), grid, block, 0, st, a); break;
+      case 2: hipLaunchKernelGGL((score_scan_kernel<64, 2, false>), grid, block, 0, st, a); break;
+      case 3: hipLaunchKernelGGL((score_scan_kernel<64, 2, true>), grid, block, 0, st, a); break;
+      case 4: hipLaunchKernelGGL((score_scan_kernel<128, 1, false>), grid, block, 0, st, a); break;
+      case 5: hipLaunchKernelGGL((score_scan_kernel<128, 1, true>), grid, block, 0, st, a); break;
+      case 6: hipLaunchKernelGGL((score_scan_kernel<128, 2, false>), grid, block, 0, st, a); break;
+      default: hipLaunchKernelGGL((score_scan_kernel<128, 2, true>), grid, block, 0, st, a); break;
     }
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
