@@ -64,7 +64,8 @@ __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeTheta th) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   constexpr int NS = D / 32;        // MFMA k-slices per key row
   constexpr int HALF = D / 2;
   constexpr int NU = (NS / 2) * 8;  // rotation pairs per lane
@@ -77,8 +78,9 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
   __shared__ float2 base0[16][HALF];  // e^{i n theta_u}: positions 0..15
   __shared__ float2 step16[HALF];     // e^{i 16 theta_u}
   __shared__ float qrot[8][D];        // rotated, scaled queries of this group
-  __shared__ __attribute__((aligned(16))) unsigned char stage[kAttWaves][STAGE];
+  __shared__ __attribute__((aligned(16))) uint16_t stage[kAttWaves][STAGE / 2];
   __shared__ float wm[kAttWaves][16], wl[kAttWaves][16];
+  __shared__ float2 estart[kAttWaves][HALF];  // e^{i p theta_u} at a wave's (re)start position
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -145,53 +147,95 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
   f32x4_t o[NCB];
 #pragma unroll
   for (int c = 0; c < NCB; ++c) o[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  unsigned char* vst = stage[wave];
+  constexpr int VS2 = VSTRIDE / 2;  // staged row stride in 16-bit elements
+  constexpr int NVL = 32 * D * 2 / 1024;  // wave-wide 16-byte loads covering 32 value rows
 
-  for (int st = wb; st < we; ++st) {
+  // selected documents of this (query, KV head): lane j holds idx[j] (k <= 64)
+  const int my_idx = (lane < a.k) ? a.idx[((long long)bm * a.Hkv + g) * a.k + lane] : -1;
+
+  // Where a step's 32 keys live (wave-uniform).  Returns false for a step with nothing to attend.
+  struct StepSrc {
     const uint16_t* Kb;
     const uint16_t* Vb;
-    int rows_valid = 32;
-    int p_first;
+    int rows_valid, p_first;
+  };
+  auto locate = [&](int st, StepSrc& ss) -> bool {
     if (st < a.steps_mem) {
       const int tok = st * 32;
       const int slot = tok / a.G;
       const int pin = tok - slot * a.G;
-      const int doc = a.idx[((long long)bm * a.Hkv + g) * a.k + slot];
-      if (doc < 0) continue;  // wave-uniform
+      const int doc = __builtin_amdgcn_readlane(my_idx, slot);
+      if (doc < 0) return false;
       const long long off = (((long long)doc * a.Hkv + g) * a.G + pin) * D;
-      Kb = a.K + off;
-      Vb = a.V + off;
-      p_first = pin;
-    } else {
-      const int t0 = (st - a.steps_mem) * 32;
-      if (t0 >= n_vis) break;  // wave-uniform; later steps are further right
-      const long long off = (((long long)b * a.Hkv + g) * a.Lloc + t0) * D;
-      Kb = a.Kloc + off;
-      Vb = a.Vloc + off;
-      rows_valid = n_vis - t0 < 32 ? n_vis - t0 : 32;
-      p_first = a.pos0 + t0;
+      ss.Kb = a.K + off;
+      ss.Vb = a.V + off;
+      ss.rows_valid = 32;
+      ss.p_first = pin;
+      return true;
     }
-
-    // ---- issue all global loads of the step --------------------------------------------------
-    uint4 kraw[2][NS];
+    const int t0 = (st - a.steps_mem) * 32;
+    if (t0 >= n_vis) return false;
+    const long long off = (((long long)b * a.Hkv + g) * a.Lloc + t0) * D;
+    ss.Kb = a.Kloc + off;
+    ss.Vb = a.Vloc + off;
+    ss.rows_valid = n_vis - t0 < 32 ? n_vis - t0 : 32;
+    ss.p_first = a.pos0 + t0;
+    return true;
+  };
+  auto next_valid = [&](int st, StepSrc& ss) -> int {  // first step >= st with keys, or we
+    while (st < we && !locate(st, ss)) ++st;
+    return st;
+  };
+  auto issue_loads = [&](const StepSrc& ss, uint4 (&kr)[2][NS], uint4 (&vr)[NVL]) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       int row = 16 * h + n;
-      row = row < rows_valid ? row : rows_valid - 1;
+      row = row < ss.rows_valid ? row : ss.rows_valid - 1;
 #pragma unroll
       for (int s = 0; s < NS; ++s)
-        kraw[h][s] = *reinterpret_cast<const uint4*>(Kb + row * D + 32 * s + 8 * rr);
+        kr[h][s] = *reinterpret_cast<const uint4*>(ss.Kb + row * D + 32 * s + 8 * rr);
     }
-    constexpr int NVL = 32 * D * 2 / 1024;  // wave-wide 16-byte loads covering 32 value rows
-    uint4 vraw[NVL];
 #pragma unroll
     for (int i = 0; i < NVL; ++i) {
       const int f = i * 64 + lane;
       int row = f / (D / 8);
       const int piece = f % (D / 8);
-      row = row < rows_valid ? row : rows_valid - 1;
-      vraw[i] = *reinterpret_cast<const uint4*>(Vb + row * D + piece * 8);
+      row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+      vr[i] = *reinterpret_cast<const uint4*>(ss.Vb + row * D + piece * 8);
     }
+  };
+
+  StepSrc cur_src;
+  int st = next_valid(wb, cur_src);
+  uint4 kraw[2][NS];
+  uint4 vraw[NVL];
+  if (st < we) issue_loads(cur_src, kraw, vraw);
+
+  while (st < we) {
+    const int rows_valid = cur_src.rows_valid;
+    const int p_first = cur_src.p_first;
+
+    // ---- stage this step's value rows in LDS (frees their registers), then prefetch the next
+    //      step.  The prefetch is always issued (re-reading this step when there is no next one) so
+    //      that the number of loads in flight does not depend on the path taken.
+#pragma unroll
+    for (int i = 0; i < NVL; ++i) {
+      const int f = i * 64 + lane;
+      const int row = f / (D / 8);
+      const int piece = f % (D / 8);
+      uint2* dst = reinterpret_cast<uint2*>(&stage[wave][row * VS2 + piece * 8]);
+      dst[0] = make_uint2(vraw[i].x, vraw[i].y);
+      dst[1] = make_uint2(vraw[i].z, vraw[i].w);
+    }
+    uint4 kcur[2][NS];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int s = 0; s < NS; ++s) kcur[h][s] = kraw[h][s];
+    StepSrc nxt_src = cur_src;
+    const int st_next = next_valid(st + 1, nxt_src);
+    if (st_next >= we) nxt_src = cur_src;
+    issue_loads(nxt_src, kraw, vraw);
 
     // ---- rotation state for this step ----------------------------------------------------------
     if (cur_p != p_first) {
@@ -201,13 +245,19 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
 #pragma unroll
           for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = base0[n][32 * s2 + 8 * rr + j];
       } else {
+        // wave-cooperative: lane u evaluates e^{i p theta_u} once, everyone combines it with e^{i n theta_u}
+        if (lane < HALF) estart[wave][lane] = cis_pos(p_first, th.th[lane]);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int s2 = 0; s2 < NS / 2; ++s2)
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const int u = 32 * s2 + 8 * rr + j;
-            cs[8 * s2 + j] = cmul(cis_pos(p_first, th.th[u]), base0[n][u]);
+            cs[8 * s2 + j] = cmul(estart[wave][u], base0[n][u]);
           }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
       cur_p = p_first;
     }
@@ -219,7 +269,7 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
       uint32_t y1[NS / 2][4], y2[NS / 2][4];
 #pragma unroll
       for (int s2 = 0; s2 < NS / 2; ++s2) {
-        const uint4 a1 = kraw[h][s2], a2 = kraw[h][s2 + NS / 2];
+        const uint4 a1 = kcur[h][s2], a2 = kcur[h][s2 + NS / 2];
         const uint32_t w1[4] = {a1.x, a1.y, a1.z, a1.w};
         const uint32_t w2[4] = {a2.x, a2.y, a2.z, a2.w};
 #pragma unroll
@@ -279,16 +329,7 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
     l_run = l_run * alpha + psum;
     const bf16x8_t pb = as_bf16x8(make_uint4(pw[0], pw[1], pw[2], pw[3]));
 
-    // ---- stage the 32 value rows in LDS, read them back transposed ----------------------------
-#pragma unroll
-    for (int i = 0; i < NVL; ++i) {
-      const int f = i * 64 + lane;
-      const int row = f / (D / 8);
-      const int piece = f % (D / 8);
-      uint2* dst = reinterpret_cast<uint2*>(vst + row * VSTRIDE + piece * 16);
-      dst[0] = make_uint2(vraw[i].x, vraw[i].y);
-      dst[1] = make_uint2(vraw[i].z, vraw[i].w);
-    }
+    // ---- second product: value rows are read back from LDS transposed ------------------------
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -300,8 +341,8 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
         const int j0 = 2 * jj, j1 = 2 * jj + 1;
         const int r0 = (j0 < 4) ? 4 * rr + j0 : 16 + 4 * rr + (j0 - 4);
         const int r1 = (j1 < 4) ? 4 * rr + j1 : 16 + 4 * rr + (j1 - 4);
-        const uint32_t lo = *reinterpret_cast<const volatile uint16_t*>(vst + r0 * VSTRIDE + (16 * c + n) * 2);
-        const uint32_t hi = *reinterpret_cast<const volatile uint16_t*>(vst + r1 * VSTRIDE + (16 * c + n) * 2);
+        const uint32_t lo = stage[wave][r0 * VS2 + 16 * c + n];
+        const uint32_t hi = stage[wave][r1 * VS2 + 16 * c + n];
         w[jj] = lo | (hi << 16);
       }
       f32x4_t oc = o[c];
@@ -313,6 +354,8 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
+    st = st_next;
+    cur_src = nxt_src;
   }
 
   // ---- merge the four waves ----------------------------------------------------------------------
@@ -320,7 +363,7 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
   l_run += __shfl_xor(l_run, 32, 64);
   __syncthreads();  // every wave is done with its value staging area
   {
-    float* wo = reinterpret_cast<float*>(stage[wave]);  // [16 slots][D]
+    float* wo = reinterpret_cast<float*>(&stage[wave][0]);  // [16 slots][D]
 #pragma unroll
     for (int c = 0; c < NCB; ++c)
 #pragma unroll
@@ -343,7 +386,7 @@ __global__ __launch_bounds__(256) void attend_partial_kernel(AttendArgs a, RopeT
       for (int w = 0; w < kAttWaves; ++w) {
         const float mw = wm[w][s0];
         const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mx);
-        const float* wo = reinterpret_cast<const float*>(stage[w]);
+        const float* wo = reinterpret_cast<const float*>(&stage[w][0]);
         osum += f * (wo[s0 * D + dd] + wo[(s0 + 1) * D + dd]);
         lsum += f * wl[w][s0];
       }
