@@ -24,6 +24,9 @@ struct ScorePlan {
   int tiles_per_split;
   int q_per_pass;        // queries scored per launch (8 or 16)
   int n_pass;
+  int exchange;          // 1: waves exchange running maxima to tighten their thresholds
+  int it_publish, it_adopt;
+  size_t off_gmax;       // byte offset of the exchange buffer inside the workspace
   size_t ws_bytes;
 };
 ScorePlan plan_score(const Dims& dm, int BM, int k);

@@ -37,6 +37,8 @@ struct ScoreArgs {
   int N, C, cos;
   long long tiles;
   int tiles_per_split, n_splits, k;
+  float* gmax;              // [Hkv][BM][n_splits] running per-wave maxima (threshold exchange), or null
+  int it_publish, it_adopt; // iterations at which a wave publishes its maxima / adopts the bound
 };
 
 __device__ __forceinline__ void wave_sync() {
@@ -121,12 +123,41 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
   const int sp = blockIdx.x;
   const int g = blockIdx.y;
 
+  // ---- start streaming at once: the first kPrefetch tiles are requested before the prologue ----
+  // Wave sp takes tiles sp, sp + n_splits, sp + 2 n_splits, ...: at any moment the waves of a head
+  // read one contiguous window of the index.  Loads past the end re-read the last tile: they are
+  // always issued, so the number of loads in flight is the same on every path.
+  const long long S = a.n_splits;
+  const long long n_it = (a.tiles - sp + S - 1) / S;  // >= 1 because n_splits <= tiles
+  const long long i_last = n_it - 1;
+  const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS + lane * 8;
+  const float* ing = COS ? a.inv_norm + (long long)g * a.tiles * 16 + n : nullptr;
+  uint4 buf[kPrefetch][NS];
+  float binv[kPrefetch];
+#pragma unroll
+  for (int u = 0; u < kPrefetch; ++u) {
+    const long long t = sp + ((u < n_it) ? u : i_last) * S;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512);
+    binv[u] = COS ? ing[t * 16] : 1.0f;
+  }
+
   // ---- fold the r heads of this group into one fp32 routing query per token -------------------
   // Lane = (head slot lane / LPH, 16-byte piece lane % LPH): one load covers HPL heads of a query.
   {
     const int piece = lane % LPH;
     const int hs = lane / LPH;
     const int n_hp = (a.r + HPL - 1) / HPL;  // loads per query (1 unless r > HPL)
+    uint4 v0[NQ];                            // all first loads are issued before any is used
+#pragma unroll
+    for (int qi = 0; qi < NQ; ++qi) {
+      v0[qi] = make_uint4(0, 0, 0, 0);
+      if (a.q0 + qi < a.BM && hs < a.r)
+        v0[qi] = *reinterpret_cast<const uint4*>(
+            a.q_route + ((long long)(a.q0 + qi) * a.Hq + g * a.r + hs) * D + piece * 8);
+    }
+#pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
       const int qg = a.q0 + qi;
       float f[8];
@@ -134,9 +165,12 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
       for (int e = 0; e < 8; ++e) f[e] = 0.f;
       for (int hp = 0; hp < n_hp; ++hp) {
         const int hh = hp * HPL + hs;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (qg < a.BM && hh < a.r)
-          v = *reinterpret_cast<const uint4*>(a.q_route + ((long long)qg * a.Hq + g * a.r + hh) * D + piece * 8);
+        uint4 v = v0[qi];
+        if (hp > 0) {
+          v = make_uint4(0, 0, 0, 0);
+          if (qg < a.BM && hh < a.r)
+            v = *reinterpret_cast<const uint4*>(a.q_route + ((long long)qg * a.Hq + g * a.r + hh) * D + piece * 8);
+        }
         float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
                       bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
         float ss = 0.f;
@@ -196,39 +230,25 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
   if (limit > CAP - 16) limit = CAP - 16;
 
   // ---- stream this wave's tiles -----------------------------------------------------------------
-  const long long tb = (long long)sp * a.tiles_per_split;
-  long long te = tb + a.tiles_per_split;
-  if (te > a.tiles) te = a.tiles;
-  const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS + lane * 8;
-  const float* ing = COS ? a.inv_norm + (long long)g * a.tiles * 16 + n : nullptr;
   const int dpt = 16 / a.C;  // documents per tile
   const int ndoc = n / a.C;  // this lane's document inside a tile
   const bool lead_lane = (n & (a.C - 1)) == 0;
   const uint32_t below = (1u << n) - 1u;
-  const long long t_last = te - 1;  // loads past the end re-read the last tile (always issued, so
-                                    // the number of loads in flight is the same on every path)
-  if (tb < te) {
-    uint4 buf[kPrefetch][NS];
-    float binv[kPrefetch];
+  float qmax[NQT][2];        // running maximum of this lane's document scores, per query
 #pragma unroll
-    for (int u = 0; u < kPrefetch; ++u) {
-      const long long t = (tb + u < te) ? tb + u : t_last;
-#pragma unroll
-      for (int s = 0; s < NS; ++s)
-        buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512);
-      binv[u] = COS ? ing[t * 16] : 1.0f;
-    }
-
-    for (long long base = tb; base < te; base += kPrefetch) {
+  for (int t = 0; t < NQT; ++t) qmax[t][0] = qmax[t][1] = -INFINITY;
+  {
+    for (long long base = 0; base < n_it; base += kPrefetch) {
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {
-        const long long t = base + u;
+        const long long it = base + u;
+        const long long t = sp + it * S;
         uint4 cur[NS];
 #pragma unroll
         for (int s = 0; s < NS; ++s) cur[s] = buf[u][s];
         const float cinv = binv[u];
         {
-          const long long tn = (t + kPrefetch < te) ? t + kPrefetch : t_last;
+          const long long tn = sp + ((it + kPrefetch < n_it) ? it + kPrefetch : i_last) * S;
 #pragma unroll
           for (int s = 0; s < NS; ++s)
             buf[u][s] = *reinterpret_cast<const uint4*>(KRg + tn * TILE_ELEMS + s * 512);
@@ -236,7 +256,7 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
         }
 
         const long long doc = t * dpt + ndoc;
-        const bool lead = lead_lane && t < te && doc < a.N;
+        const bool lead = lead_lane && it < n_it && doc < a.N;
         bool over = false;
 #pragma unroll
         for (int tq = 0; tq < NQT; ++tq) {
@@ -246,6 +266,7 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
             const float sc = group_max_rt((acc[2 * e] + acc[2 * e + 1]) * cinv, a.C);
+            if (lead) qmax[tq][e] = fmaxf(qmax[tq][e], sc);
             const bool pred = lead && sc >= thr[tq][e];
             const unsigned long long m = __ballot(pred);
             const uint32_t half = (rr & 2) ? (uint32_t)(m >> 32) : (uint32_t)m;
@@ -290,6 +311,49 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
             thr[tq][1] = thr_s[8 * tq + 2 * rr + 1];
           }
           wave_sync();
+        }
+        // ---- threshold exchange (long streams only): every wave publishes the best score it has
+        // seen per query; a little later it adopts theta = the k-th largest of all published maxima.
+        // The maxima belong to distinct documents, so at least k documents score >= theta: a valid
+        // lower bound on the k-th best score whatever the other waves have written so far.
+        if (a.gmax != nullptr && (it == a.it_publish || it == a.it_adopt)) {
+          if (it == a.it_publish) {
+#pragma unroll
+            for (int tq = 0; tq < NQT; ++tq)
+#pragma unroll
+              for (int e = 0; e < 2; ++e) {
+                const float mrow = group_max<16>(qmax[tq][e]);
+                const int qg = a.q0 + 8 * tq + 2 * rr + e;
+                if (n == 0 && qg < a.BM) a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp] = mrow;
+              }
+          } else {
+            for (int qi = 0; qi < NQ; ++qi) {
+              const int qg = a.q0 + qi;
+              if (qg >= a.BM) break;  // wave-uniform
+              const float* src = a.gmax + ((long long)g * a.BM + qg) * a.n_splits;
+              uint32_t ord[4];
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                ord[j] = (lane + 64 * j < a.n_splits) ? orderable(src[lane + 64 * j]) : 0u;
+              uint32_t prefix = 0u;
+              for (int bit = 31; bit >= 12; --bit) {
+                const uint32_t cnd = prefix | (1u << bit);
+                int ge = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) ge += __popcll(__ballot(ord[j] >= cnd));
+                if (ge >= a.k) prefix = cnd;  // wave-uniform
+              }
+              if (lane == 0) thr_s[qi] = prefix ? unorderable(prefix) : -INFINITY;
+            }
+            wave_sync();
+#pragma unroll
+            for (int tq = 0; tq < NQT; ++tq)
+#pragma unroll
+              for (int e = 0; e < 2; ++e)
+                if (a.q0 + 8 * tq + 2 * rr + e < a.BM)
+                  thr[tq][e] = fmaxf(thr[tq][e], thr_s[8 * tq + 2 * rr + e]);
+            wave_sync();
+          }
         }
       }
     }
@@ -355,11 +419,19 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
   }
   __syncthreads();
   const unsigned long long theta = theta_s;
-  for (int i = tid; i < T; i += 256) {
-    const unsigned long long x = src[i];
-    if (x != 0ull && x >= theta) {
-      const int slot = atomicAdd(&n_surv, 1);
-      if (slot < kMaxSurv) surv[slot] = x;
+  for (int i0 = 0; i0 < T; i0 += 256 * 8) {  // eight independent loads per thread in flight
+    unsigned long long x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u * 256 + tid;
+      x[u] = (i < T) ? src[i] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (x[u] != 0ull && x[u] >= theta) {
+        const int slot = atomicAdd(&n_surv, 1);
+        if (slot < kMaxSurv) surv[slot] = x[u];
+      }
     }
   }
   __syncthreads();
@@ -407,6 +479,11 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
   }
 }
 
+__global__ void fill_neg_inf_kernel(float* __restrict__ p, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = -INFINITY;
+}
+
 ScorePlan plan_score(const Dims& dm, int BM, int k) {
   ScorePlan p;
   long long ns = 2048 / dm.Hkv;  // ~8 waves per CU on 256 CUs
@@ -417,9 +494,16 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
   if (ns < 1) ns = 1;
   p.tiles_per_split = (int)((dm.tiles + ns - 1) / ns);
   p.n_splits = (int)((dm.tiles + p.tiles_per_split - 1) / p.tiles_per_split);
-  p.q_per_pass = (BM <= 8) ? 8 : 16;
+  p.q_per_pass = (BM <= 8) ? 8 : ((BM <= 16 || k > 24) ? 16 : 32);
   p.n_pass = (BM + p.q_per_pass - 1) / p.q_per_pass;
-  p.ws_bytes = round_up256((size_t)dm.Hkv * BM * p.n_splits * k * sizeof(unsigned long long));
+  const size_t list_bytes = round_up256((size_t)dm.Hkv * BM * p.n_splits * k * sizeof(unsigned long long));
+  // threshold exchange between waves: worth it (and sound) only for long streams with >= k waves per head
+  const long long n_it_min = dm.tiles / p.n_splits;
+  p.exchange = (n_it_min >= 64 && p.n_splits >= k && p.n_splits <= 256) ? 1 : 0;
+  p.it_publish = (int)(n_it_min / 12);
+  p.it_adopt = p.it_publish + 8;
+  p.off_gmax = list_bytes;
+  p.ws_bytes = list_bytes + (p.exchange ? round_up256((size_t)dm.Hkv * BM * p.n_splits * sizeof(float)) : 0);
   return p;
 }
 
@@ -442,20 +526,33 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
   a.tiles_per_split = pl.tiles_per_split;
   a.n_splits = pl.n_splits;
   a.k = k;
+  a.gmax = pl.exchange ? (float*)((char*)ws + pl.off_gmax) : nullptr;
+  a.it_publish = pl.it_publish;
+  a.it_adopt = pl.it_adopt;
+  if (pl.exchange) {
+    const long long n = (long long)dm.Hkv * BM * pl.n_splits;
+    hipLaunchKernelGGL(fill_neg_inf_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.gmax, n);
+    if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+  }
   dim3 grid(pl.n_splits, dm.Hkv), block(64);
   for (int pass = 0; pass < pl.n_pass; ++pass) {
     a.q0 = pass * pl.q_per_pass;
-    const int sel = (dm.d == 128 ? 4 : 0) + (pl.q_per_pass == 16 ? 2 : 0) + (dm.cos ? 1 : 0);
-    switch (sel) {
-      case 0: hipLaunchKernelGGL((score_scan_kernel<64, 1, false>), grid, block, 0, st, a); break;
-      case 1: hipLaunchKernelGGL((score_scan_kernel<64, 1, true>), grid, block, 0, st, a); break;
-      case 2: hipLaunchKernelGGL((score_scan_kernel<64, 2, false>), grid, block, 0, st, a); break;
-      case 3: hipLaunchKernelGGL((score_scan_kernel<64, 2, true>), grid, block, 0, st, a); break;
-      case 4: hipLaunchKernelGGL((score_scan_kernel<128, 1, false>), grid, block, 0, st, a); break;
-      case 5: hipLaunchKernelGGL((score_scan_kernel<128, 1, true>), grid, block, 0, st, a); break;
-      case 6: hipLaunchKernelGGL((score_scan_kernel<128, 2, false>), grid, block, 0, st, a); break;
-      default: hipLaunchKernelGGL((score_scan_kernel<128, 2, true>), grid, block, 0, st, a); break;
+    const int nqt = pl.q_per_pass / 8;  // 1, 2 or 4
+#define MSA_SCAN(DD, QQ, CC) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC>), grid, block, 0, st, a)
+    if (dm.d == 128) {
+      if (dm.cos) {
+        if (nqt == 1) MSA_SCAN(128, 1, true); else if (nqt == 2) MSA_SCAN(128, 2, true); else MSA_SCAN(128, 4, true);
+      } else {
+        if (nqt == 1) MSA_SCAN(128, 1, false); else if (nqt == 2) MSA_SCAN(128, 2, false); else MSA_SCAN(128, 4, false);
+      }
+    } else {
+      if (dm.cos) {
+        if (nqt == 1) MSA_SCAN(64, 1, true); else if (nqt == 2) MSA_SCAN(64, 2, true); else MSA_SCAN(64, 4, true);
+      } else {
+        if (nqt == 1) MSA_SCAN(64, 1, false); else if (nqt == 2) MSA_SCAN(64, 2, false); else MSA_SCAN(64, 4, false);
+      }
     }
+#undef MSA_SCAN
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
   hipLaunchKernelGGL(score_merge_kernel, dim3(BM * dm.Hkv), dim3(256), 0, st,

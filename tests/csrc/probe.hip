@@ -64,3 +64,15 @@ extern "C" void probe_keys(const void* score, const void* doc, void* key, void* 
   hipLaunchKernelGGL(probe_keys_kernel, dim3((n + 255) / 256), dim3(256), 0, 0, (const float*)score,
                      (const uint32_t*)doc, (unsigned long long*)key, (float*)sb, (uint32_t*)db, n);
 }
+
+// Plain copy of n 16-byte words, grid-stride: the known-size reference for HBM counter calibration.
+__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                         unsigned long long n) {
+  const unsigned long long stride = (unsigned long long)gridDim.x * blockDim.x;
+  for (unsigned long long i = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    dst[i] = src[i];
+}
+extern "C" void probe_copy(const void* src, void* dst, unsigned long long nbytes) {
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 16), dim3(256), 0, 0, (const uint4*)src, (uint4*)dst,
+                     nbytes / 16);
+}

@@ -247,6 +247,8 @@ CASES = {
     "d64_c2_batch20": (4000, 301, 2, 2, 64, 64, 32, 5, 4, 33, 1e4, 3),
     "c16_r8": (5000, 21, 1, 8, 256, 128, 16, 1, 2, 0, 1e4, 21),
     "c1_r1": (6000, 90, 3, 1, 64, 64, 64, 1, 3, 64, 1e6, 7),
+    "batch40_c4": (10000, 203, 2, 4, 64, 128, 16, 40, 1, 20, 1e6, 5),
+    "batch33_d64": (11000, 500, 1, 2, 32, 64, 8, 33, 1, 0, 1e4, 24),
 }
 
 
@@ -391,3 +393,27 @@ def test_single_document_bank():
                                      torch.from_numpy(q_pos.astype(np.int32)).cuda())
     torch.cuda.synchronize()
     check_attend(case, out, lse, idx.cpu().numpy().astype(np.int64), 64, q_pos)
+
+
+def test_score_long_streams_threshold_exchange():
+    """Scoring alone on a synthetic routing index long enough (64+ tiles per wave, >= k waves per
+    head) for the waves to exchange running maxima; the oracle scores the same index."""
+    say("case long streams: N=32768 docs, C=8, d=64, Hkv=8, B=3, k=16")
+    N, C, d, Hkv, r, B, k = 32768, 8, 64, 8, 2, 3, 16
+    cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e4)
+    _, KRb = S.normal_bf16(12000, (Hkv, N * C, d))
+    qb, q = S.normal_bf16(12001, (B, 1, Hkv * r, d))
+    inv = 1.0 / np.maximum(np.linalg.norm(KRb, axis=-1), O.EPS_NORM)
+    dKR, dinv = upload_oracle_index(cfg, KRb, inv)
+    idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+
+    class C_:
+        pass
+    case = C_()
+    case.q, case.C, case.B, case.M, case.Hkv, case.N = q, C, B, 1, Hkv, N
+    oi, n_band = check_topk(case, idx, val, KRb, k)
+    say(f"   top-k ok ({n_band} inside the tie band)")
+    i2, v2 = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    assert torch.equal(i2, idx) and torch.equal(v2, val)
