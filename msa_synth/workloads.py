@@ -22,6 +22,7 @@ WORKLOADS = {
     "cfg1_tiny_32k": dict(N=64, G=512, P=64, Hq=8, Hkv=2, d=64, B=1, M=1, k=4, Lloc=256, base=1e4, cfg_id=1),
     "cfg2_decode_1m": dict(N=2048, G=512, P=64, Hq=32, Hkv=8, d=128, B=1, M=1, k=16, Lloc=2048, base=1e6, cfg_id=2),
     "cfg3_batch32_4m": dict(N=8192, G=512, P=64, Hq=32, Hkv=8, d=128, B=32, M=1, k=16, Lloc=2048, base=1e6, cfg_id=3),
+    "cfg4_prefill_16m": dict(N=32768, G=512, P=64, Hq=32, Hkv=8, d=128, B=1, M=2048, k=8, Lloc=2048, base=1e6, cfg_id=4),
     "cfg5_decode_50m": dict(N=97656, G=512, P=64, Hq=32, Hkv=8, d=128, B=8, M=1, k=32, Lloc=2048, base=1e6, cfg_id=5),
 }
 
@@ -65,7 +66,11 @@ def make(name, device="cuda", plant_per_query=0, plant_a=0.12, plant_chunk=3):
     wl.Vloc = torch.empty_like(wl.Kloc)
     SD.fill_normal_(wl.Kloc, seeds["Kloc"])
     SD.fill_normal_(wl.Vloc, seeds["Vloc"])
-    wl.q_pos_host = np.full((wl.B, wl.M), wl.pos0 + wl.Lloc - 1, dtype=np.int32)   # decode: last local token
+    if wl.M == 1:     # decode: the query is the last local token
+        wl.q_pos_host = np.full((wl.B, wl.M), wl.pos0 + wl.Lloc - 1, dtype=np.int32)
+    else:             # prefill: the local context IS the M query tokens, causal (token m sees 0..m)
+        assert wl.Lloc == wl.M
+        wl.q_pos_host = np.tile(wl.pos0 + np.arange(wl.M, dtype=np.int32), (wl.B, 1))
     wl.q_pos = torch.from_numpy(wl.q_pos_host).to(device)
     wl.planted, wl.planted_K = {}, {}
     if plant_per_query > 0:
@@ -101,7 +106,10 @@ def algorithmic_bytes(wl):
     tiles = (NC + 15) // 16
     elem = 2
     build = wl.N * wl.Hkv * wl.G * wl.d * elem + wl.Hkv * tiles * 16 * (wl.d * elem + 4)
-    n_pass = 1 if wl.B * wl.M <= 8 else (wl.B * wl.M + 15) // 16
+    n_pass = 1 if wl.B * wl.M <= 32 else (wl.B * wl.M + 31) // 32
     score_once = wl.Hkv * tiles * 16 * (wl.d * elem + 4)
-    attend = wl.B * wl.M * wl.Hkv * (wl.k * wl.G + wl.Lloc) * wl.d * elem * 2
+    if wl.M == 1:
+        attend = wl.B * wl.M * wl.Hkv * (wl.k * wl.G + wl.Lloc) * wl.d * elem * 2
+    else:   # causal prefill: token m reads k documents + m + 1 local rows (upper bound: no reuse between tokens)
+        attend = wl.B * wl.Hkv * (wl.M * wl.k * wl.G + wl.M * (wl.M + 1) // 2) * wl.d * elem * 2
     return dict(build=build, score=score_once, score_passes=n_pass, attend=attend)

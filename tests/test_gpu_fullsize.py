@@ -47,7 +47,7 @@ def oracle_doc_scores(wl, q_sel, docs):
 
 
 @pytest.mark.parametrize("name,plant,a", [("cfg2_decode_1m", 8, 0.2), ("cfg3_batch32_4m", 25, 0.08),
-                                          ("cfg5_decode_50m", 16, 0.2)])
+                                          ("cfg5_decode_50m", 16, 0.2), ("cfg4_prefill_16m", 0, 0.0)])
 def test_fullsize_sampled_parity(name, plant, a):
     say(f"workload {name}: generating the bank on the device (planted {plant} documents per query, a={a})")
     wl = W.make(name, plant_per_query=plant, plant_a=a)
@@ -79,8 +79,10 @@ def test_fullsize_sampled_parity(name, plant, a):
     say("   score_topk")
     idx, val = msa.msa_score_topk(cfg, wl.q, KR, inv, k)
     torch.cuda.synchronize()
-    gi = idx.cpu().numpy().astype(np.int64)
-    gv = val.cpu().numpy().astype(np.float64)
+    gi = idx.cpu().numpy().astype(np.int64).reshape(B * M, 1, wl.Hkv, k)      # one row per query token
+    gv = val.cpu().numpy().astype(np.float64).reshape(B * M, 1, wl.Hkv, k)
+    q_flat = wl.q_host.reshape(B * M, 1, wl.Hq, wl.d)
+    B = B * M
     assert gi.min() >= 0 and gi.max() < wl.N
     for b in range(B):
         for g in range(wl.Hkv):
@@ -92,16 +94,17 @@ def test_fullsize_sampled_parity(name, plant, a):
     q_sample = sorted({0, B - 1})
     for b in q_sample:
         docs = sorted(set(gi[b, 0].reshape(-1).tolist()))
-        s = oracle_doc_scores(wl, wl.q_host[b], docs)             # [1, Hkv, n]
+        s = oracle_doc_scores(wl, q_flat[b], docs)                # [1, Hkv, n]
         pos = {dd: i for i, dd in enumerate(docs)}
         for g in range(wl.Hkv):
             want = np.array([s[0, g, pos[int(dd)]] for dd in gi[b, 0, g]])
             assert np.allclose(gv[b, 0, g], want, rtol=0, atol=1e-4), np.abs(gv[b, 0, g] - want).max()
     # non-selected documents: planted ones and a random sample must not beat the k-th score
     others = sorted(set(planted_docs[:160]) | set(rng.choice(wl.N, size=96, replace=False).tolist()))
-    s_all = oracle_doc_scores(wl, wl.q_host[:, 0], others)          # [B, Hkv, n]
+    q_chk = sorted(set(range(0, B, max(1, B // 32))) | {B - 1})    # all queries, or 33 sampled tokens in prefill
+    s_all = oracle_doc_scores(wl, q_flat[q_chk, 0], others)         # [len(q_chk), Hkv, n]
     n_planted_in = 0
-    for b in range(B):
+    for bi, b in enumerate(q_chk):
         for g in range(wl.Hkv):
             kth = gv[b, 0, g, k - 1]
             band = 1e-3 * abs(kth) + 1e-4
@@ -110,9 +113,9 @@ def test_fullsize_sampled_parity(name, plant, a):
                 if dd in chosen:
                     n_planted_in += dd in wl.planted_K
                     continue
-                assert s_all[b, g, j] <= kth + band, (b, g, dd, s_all[b, g, j], kth)
+                assert s_all[bi, g, j] <= kth + band, (b, g, dd, s_all[bi, g, j], kth)
     n_own = 0
-    for b in range(B):
+    for b in range(B if plant else 0):
         own = {wl.planted[(b, j)] for j in range(plant)}
         for g in range(wl.Hkv):
             n_own += len(own & set(gi[b, 0, g].tolist()))
@@ -124,21 +127,24 @@ def test_fullsize_sampled_parity(name, plant, a):
     say("   sparse_attend")
     out, lse = msa.msa_sparse_attend(cfg, wl.q, wl.K, wl.V, idx, wl.Kloc, wl.Vloc, wl.pos0, wl.q_pos)
     torch.cuda.synchronize()
-    go = out.float().cpu().numpy().astype(np.float64)
-    gl = lse.cpu().numpy().astype(np.float64)
+    go = out.float().cpu().numpy().astype(np.float64).reshape(B, 1, wl.Hq, wl.d)
+    gl = lse.cpu().numpy().astype(np.float64).reshape(B, 1, wl.Hq)
     assert np.all(np.isfinite(go)) and np.all(np.isfinite(gl))
     pairs = [(0, 0), (B - 1, wl.Hkv - 1)] if B > 1 else [(0, 0), (0, wl.Hkv - 1)]
+    if M > 1:
+        pairs.append((M // 3, 3))             # a token in the middle of the causal window
     per_bg = wl.Lloc * wl.d
+    qpos_flat = wl.q_pos_host.reshape(B, 1)
     for b, g in pairs:
         docs = gi[b, 0, g]
         K_sel = np.stack([W.host_doc(wl, "K", int(i))[1][g:g + 1] for i in docs])   # [k, 1, G, d]
         V_sel = np.stack([W.host_doc(wl, "V", int(i))[1][g:g + 1] for i in docs])
-        start = (b * wl.Hkv + g) * per_bg
+        start = ((b // M) * wl.Hkv + g) * per_bg
         Kl = S.normal_bf16(wl.seeds["Kloc"], (1, 1, wl.Lloc, wl.d), start=start)[1]
         Vl = S.normal_bf16(wl.seeds["Vloc"], (1, 1, wl.Lloc, wl.d), start=start)[1]
-        qh = wl.q_host[b:b + 1, :, g * wl.r:(g + 1) * wl.r]
+        qh = q_flat[b:b + 1, :, g * wl.r:(g + 1) * wl.r]
         oo, ol = O.sparse_attend(qh, K_sel, V_sel, np.arange(k)[None, None, None], Kl, Vl, wl.pos0,
-                                 wl.q_pos_host[b:b + 1], wl.base)
+                                 qpos_flat[b:b + 1], wl.base)
         got = go[b, 0, g * wl.r:(g + 1) * wl.r]
         err = np.abs(got - oo[0, 0])
         rel = np.linalg.norm(err) / np.linalg.norm(oo)
