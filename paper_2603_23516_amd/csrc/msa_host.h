@@ -17,6 +17,19 @@ struct Dims {
   int64_t tiles;  // ceil(NC / 16) tiles of 16 keys per KV head
 };
 
+// Work split of the MFMA-bound scoring path for many query tokens (msa_score_gemm.hip).
+struct GemmPlan {
+  int n_qblocks;         // blocks of 256 query tokens
+  int n_splits;          // key-range splits per (head, token block)
+  int sub_per_split;     // 32-key sub-tiles per split
+  size_t off_lists;      // byte offset of the candidate lists (after the folded fp32 queries)
+  size_t ws_bytes;
+};
+bool gemm_path_applies(const Dims& dm, int BM, int k);
+GemmPlan plan_score_gemm(const Dims& dm, int BM, int k);
+int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_route, int BM,
+                           const void* KR, const float* inv_norm, int k, void* ws, hipStream_t st);
+
 // Work split of the routing scan (depends only on the problem size, so the workspace size is a
 // pure function of the arguments).
 struct ScorePlan {
@@ -27,6 +40,8 @@ struct ScorePlan {
   int exchange;          // 1: waves exchange running maxima to tighten their thresholds
   int it_publish, it_adopt;
   size_t off_gmax;       // byte offset of the exchange buffer inside the workspace
+  int use_gemm;          // 1: many query tokens -> the GEMM path below
+  GemmPlan gemm;
   size_t ws_bytes;
 };
 ScorePlan plan_score(const Dims& dm, int BM, int k);

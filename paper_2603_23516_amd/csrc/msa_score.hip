@@ -486,6 +486,19 @@ __global__ void fill_neg_inf_kernel(float* __restrict__ p, long long n) {
 
 ScorePlan plan_score(const Dims& dm, int BM, int k) {
   ScorePlan p;
+  p.use_gemm = gemm_path_applies(dm, BM, k) ? 1 : 0;
+  if (p.use_gemm) {
+    p.gemm = plan_score_gemm(dm, BM, k);
+    p.n_splits = p.gemm.n_splits;
+    p.tiles_per_split = 0;
+    p.q_per_pass = BM;
+    p.n_pass = 1;
+    p.exchange = 0;
+    p.it_publish = p.it_adopt = 0;
+    p.off_gmax = 0;
+    p.ws_bytes = p.gemm.ws_bytes;
+    return p;
+  }
   long long ns = 2048 / dm.Hkv;  // ~8 waves per CU on 256 CUs
   if (ns < 1) ns = 1;
   const long long by_tiles = (dm.tiles + kPrefetch - 1) / kPrefetch;
@@ -510,6 +523,14 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
 int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int BM, const void* KR,
                  const float* inv_norm, int k, int32_t* out_idx, float* out_score, void* ws,
                  hipStream_t st) {
+  if (pl.use_gemm) {
+    const int rc = launch_score_gemm_scan(dm, pl.gemm, q_route, BM, KR, inv_norm, k, ws, st);
+    if (rc != MSA_OK) return rc;
+    hipLaunchKernelGGL(score_merge_kernel, dim3(BM * dm.Hkv), dim3(256), 0, st,
+                       (const unsigned long long*)((const char*)ws + pl.gemm.off_lists), out_idx,
+                       out_score, BM, dm.Hkv, pl.gemm.n_splits, k);
+    return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
+  }
   ScoreArgs a;
   a.q_route = (const uint16_t*)q_route;
   a.KR = (const uint16_t*)KR;

@@ -1,0 +1,352 @@
+// msa_score_topk for MANY query tokens (prefill routing, B*M >= 64): the relevance scores of Eq. 2
+// (paper, Section 3.2.1) as a real GEMM on the matrix cores, with the document max and a per-query
+// top-k fused into the epilogue so that scores never reach memory.  This is the one place on the
+// path that is MFMA-bound: 2 * (B*M) * Hkv * (N*C) * 2d flops (the factor 2d: the folded fp32 query is
+// carried as a bf16 hi part and a bf16 lo part laid side by side along the contraction, so one
+// accumulator receives q_hi.key + q_lo.key and a score keeps ~16 significant bits).
+//
+// Shape of the work
+//   fold_queries_kernel : (1/r) sum_h q_h/|q_h| per (token, KV group) in fp32, once.
+//   score_gemm_kernel   : a workgroup owns 256 query tokens of one KV head (4 waves x 64 tokens, the
+//     queries stay in registers as B operands for the whole kernel) and walks a range of key
+//     sub-tiles of 32 keys (= 4 documents at C = 8).  A sub-tile (two 16-key index tiles, 8 KiB,
+//     contiguous in the tiled index) is copied once to LDS (double buffered) and read by all four
+//     waves as the A operand of v_mfma_f32_32x32x16_bf16: D[key][token].
+//     Keys are the ROWS of the product, so the 8 chunks of a document sit in two lanes (l, l ^ 32)
+//     as four accumulator registers each: document max = 3 in-lane max + one half-wave swap.
+//     Each lane keeps a private sorted top-8 list (score, document) per token block in registers;
+//     the lower half of the wave serves documents 0,1 of a sub-tile, the upper half documents 2,3.
+//     Lists are merged per token at the end and written as sorted 64-bit keys, the same format the
+//     streaming scan writes, so score_merge_kernel combines the key-range splits.
+#include "msa_device.h"
+#include "msa_host.h"
+
+namespace msa {
+
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kGemmTokens = 256;  // tokens per workgroup (4 waves x 64)
+constexpr int kGemmK = 8;         // per-lane list length (k <= 8)
+
+__device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+  // D(32x32) += A(32x16) * B(16x32).  Lane l: A[l%32][8(l/32)..+8], B[8(l/32)..+8][l%32],
+  // D register i: row (i%4) + 8(i/4) + 4(l/32), column l%32.
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// max(x[l], x[l ^ 32]) in every lane.
+__device__ __forceinline__ float max_with_other_half(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+template <int W>
+__device__ __forceinline__ float gsum(float x) {
+  if (W >= 2) x += dpp_f<kDppXor1>(x);
+  if (W >= 4) x += dpp_f<kDppXor2>(x);
+  if (W >= 8) x += dpp_f<kDppHalfMirror>(x);
+  if (W >= 16) x += dpp_f<kDppMirror>(x);
+  return x;
+}
+
+// One wave per (token, KV group): qf[token][g][:] = (1/r) sum_h q_h / max(|q_h|, 1e-12)  (or the plain
+// mean for the dot product).
+template <int D>
+__global__ __launch_bounds__(64) void fold_queries_kernel(const uint16_t* __restrict__ q_route,
+                                                          float* __restrict__ qf, int Hq, int Hkv,
+                                                          int r, int cos) {
+  constexpr int LPH = D / 8, HPL = 64 / LPH;
+  const int lane = threadIdx.x;
+  const int g = blockIdx.x % Hkv;
+  const long long qg = blockIdx.x / Hkv;
+  const int piece = lane % LPH, hs = lane / LPH;
+  float f[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = 0.f;
+  for (int hp = 0; hp * HPL < r; ++hp) {
+    const int hh = hp * HPL + hs;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (hh < r) v = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hh) * D + piece * 8);
+    const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                        bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+    ss = gsum<LPH>(ss);
+    const float w = cos ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : 1.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] += x[e] * w;
+  }
+#pragma unroll
+  for (int off = LPH; off < 64; off <<= 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] += __shfl_xor(f[e], off, 64);
+  }
+  if (hs == 0) {
+    float* dst = qf + (qg * Hkv + g) * D + piece * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dst[e] = f[e] / (float)r;
+  }
+}
+
+struct GemmArgs {
+  const float* qf;          // [BM][Hkv][D]
+  const uint16_t* KR;       // tiled
+  const float* inv_norm;    // may be null (dot)
+  unsigned long long* ws;   // [Hkv][BM][n_splits][k]
+  int BM, Hkv, N, k;
+  long long tiles;          // 16-key tiles per head
+  int n_qblocks, n_splits, sub_per_split;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
+  constexpr int NS8 = D / 16;            // 16-wide contraction slices per half (hi / lo)
+  constexpr int SUB_BYTES = 32 * D * 2;  // one 32-key sub-tile
+  constexpr int TILE_ELEMS = 16 * D;
+  constexpr int LOADS = SUB_BYTES / (256 * 16);  // 16-byte loads per thread per sub-tile (2 at d=128)
+  __shared__ __attribute__((aligned(16))) unsigned char kbuf[2][SUB_BYTES];
+  __shared__ __attribute__((aligned(16))) float ibuf[2][32];
+  __shared__ unsigned long long mrg[4][64][2 * kGemmK];  // end-of-kernel merge of the two half lists
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int h = lane >> 5;   // half of the wave
+  const int c = lane & 31;   // token column / key row
+  const int g = blockIdx.x % a.Hkv;
+  const int rest = blockIdx.x / a.Hkv;
+  const int qb = rest % a.n_qblocks;
+  const int ks = rest / a.n_qblocks;
+  const long long n_sub = (a.tiles + 1) / 2;
+  const long long s0 = (long long)ks * a.sub_per_split;
+  long long s1 = s0 + a.sub_per_split;
+  if (s1 > n_sub) s1 = n_sub;
+
+  // ---- B operands: this wave's 64 tokens, hi and lo halves, resident for the whole kernel -----
+  const int tok0 = qb * kGemmTokens + wave * 64;
+  bf16x8_t Bhi[2][NS8], Blo[2][NS8];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    const int tok = tok0 + 32 * cb + c;
+#pragma unroll
+    for (int s = 0; s < NS8; ++s) {
+      float x[8];
+      if (tok < a.BM) {
+        const float4* src = reinterpret_cast<const float4*>(a.qf + ((long long)tok * a.Hkv + g) * D + 16 * s + 8 * h);
+        const float4 u0 = src[0], u1 = src[1];
+        x[0] = u0.x; x[1] = u0.y; x[2] = u0.z; x[3] = u0.w;
+        x[4] = u1.x; x[5] = u1.y; x[6] = u1.z; x[7] = u1.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = 0.f;
+      }
+      uint32_t wh[4], wl[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        float h0, l0, h1, l1;
+        split_bf16(x[2 * jj], h0, l0);
+        split_bf16(x[2 * jj + 1], h1, l1);
+        wh[jj] = pack_bf16(h0, h1);
+        wl[jj] = pack_bf16(l0, l1);
+      }
+      Bhi[cb][s] = as_bf16x8(make_uint4(wh[0], wh[1], wh[2], wh[3]));
+      Blo[cb][s] = as_bf16x8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
+    }
+  }
+
+  // per-lane sorted lists: [token block][rank]
+  float lsc[2][kGemmK];
+  int ldoc[2][kGemmK];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int p = 0; p < kGemmK; ++p) {
+      lsc[cb][p] = -INFINITY;
+      ldoc[cb][p] = -1;
+    }
+
+  // ---- staging of key sub-tiles: global -> registers -> LDS, one sub-tile ahead -----------------
+  const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS;
+  const float* ing = a.inv_norm ? a.inv_norm + (long long)g * a.tiles * 16 : nullptr;
+  uint4 stage_k[LOADS];
+  float stage_i = 1.0f;
+  auto fetch = [&](long long st) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int off = (i * 256 + tid) * 16;            // byte offset inside the sub-tile
+      long long tile = 2 * st + off / (TILE_ELEMS * 2);
+      if (tile >= a.tiles) tile = a.tiles - 1;         // odd tile count: repeat the last tile (masked)
+      stage_k[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(KRg) +
+                                                    tile * (TILE_ELEMS * 2) + off % (TILE_ELEMS * 2));
+    }
+    if (tid < 32) {
+      long long key = st * 32 + tid;
+      if (key >= a.tiles * 16) key = a.tiles * 16 - 1;
+      stage_i = ing ? ing[key] : 1.0f;
+    }
+  };
+  auto stash = [&](int b) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i)
+      *reinterpret_cast<uint4*>(&kbuf[b][(i * 256 + tid) * 16]) = stage_k[i];
+    if (tid < 32) ibuf[b][tid] = stage_i;
+  };
+
+  if (s0 < s1) {
+    fetch(s0);
+    stash(0);
+  }
+  __syncthreads();
+
+  for (long long st = s0; st < s1; ++st) {
+    const int b = (int)((st - s0) & 1);
+    const long long nxt = (st + 1 < s1) ? st + 1 : st;  // always issued (re-reads the last sub-tile)
+    fetch(nxt);
+
+    // ---- 32 keys x 64 tokens, contraction over [hi | lo] ---------------------------------------
+    f32x16_t acc[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS8; ++s) {
+      // A operand: key row c -> tile c/16, slot c%16; dims 16s + 8h .. +8 = piece 2s + h
+      const bf16x8_t av = as_bf16x8(*reinterpret_cast<const uint4*>(
+          &kbuf[b][(c >> 4) * (TILE_ELEMS * 2) + ((2 * s + h) * 16 + (c & 15)) * 16]));
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        acc[cb] = mfma32(av, Bhi[cb][s], acc[cb]);
+        acc[cb] = mfma32(av, Blo[cb][s], acc[cb]);
+      }
+    }
+    float inv[16];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float4 v = *reinterpret_cast<const float4*>(&ibuf[b][8 * j + 4 * h]);
+      inv[4 * j] = v.x;
+      inv[4 * j + 1] = v.y;
+      inv[4 * j + 2] = v.z;
+      inv[4 * j + 3] = v.w;
+    }
+
+    // ---- epilogue: document max, insertion into the per-lane lists ------------------------------
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      float m[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float x0 = acc[cb][4 * j] * inv[4 * j], x1 = acc[cb][4 * j + 1] * inv[4 * j + 1];
+        const float x2 = acc[cb][4 * j + 2] * inv[4 * j + 2], x3 = acc[cb][4 * j + 3] * inv[4 * j + 3];
+        m[j] = max_with_other_half(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
+      }
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const float sc = h ? m[2 + jj] : m[jj];
+        const long long doc = st * 4 + 2 * h + jj;
+        const bool ok = doc < a.N && sc > lsc[cb][kGemmK - 1];
+        if (__any(ok)) {
+          // branch-free insertion below every entry with score >= sc (documents arrive in
+          // increasing order, so equal scores keep the lower document first)
+#pragma unroll
+          for (int p = kGemmK - 1; p >= 0; --p) {
+            const float above = (p > 0) ? lsc[cb][p - 1] : INFINITY;
+            const int above_d = (p > 0) ? ldoc[cb][p - 1] : -1;
+            const bool shift = ok && sc > above;            // entry p-1 moves down to p
+            const bool here = ok && !shift && sc > lsc[cb][p];
+            lsc[cb][p] = shift ? above : (here ? sc : lsc[cb][p]);
+            ldoc[cb][p] = shift ? above_d : (here ? (int)doc : ldoc[cb][p]);
+          }
+        }
+      }
+    }
+
+    stash(b ^ 1);
+    __syncthreads();
+  }
+
+  // ---- merge the two half-wave lists of every token, write sorted keys -----------------------
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+#pragma unroll
+    for (int p = 0; p < kGemmK; ++p)
+      mrg[wave][32 * cb + c][h * kGemmK + p] =
+          (ldoc[cb][p] >= 0) ? make_key(lsc[cb][p], (uint32_t)ldoc[cb][p]) : 0ull;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    const int tok = tok0 + 32 * cb + c;
+    const unsigned long long* both = mrg[wave][32 * cb + c];
+#pragma unroll
+    for (int p = 0; p < kGemmK; ++p) {
+      const unsigned long long key = both[h * kGemmK + p];
+      int rank = p;  // entries above it in its own (sorted) list
+#pragma unroll
+      for (int o = 0; o < kGemmK; ++o) rank += (both[(1 - h) * kGemmK + o] > key) ? 1 : 0;
+      if (tok < a.BM && rank < a.k) {
+        unsigned long long* dst = a.ws + (((long long)g * a.BM + tok) * a.n_splits + ks) * a.k;
+        dst[rank] = key;  // zero keys (empty slots) rank last among themselves: harmless duplicates of 0
+      }
+    }
+  }
+}
+
+// ---- host side -----------------------------------------------------------------------------------
+bool gemm_path_applies(const Dims& dm, int BM, int k) {
+  return dm.C == 8 && k <= kGemmK && BM >= 64;
+}
+
+GemmPlan plan_score_gemm(const Dims& dm, int BM, int k) {
+  GemmPlan p;
+  p.n_qblocks = (BM + kGemmTokens - 1) / kGemmTokens;
+  const long long n_sub = (dm.tiles + 1) / 2;
+  long long want = (2 * 256) / ((long long)dm.Hkv * p.n_qblocks);  // ~2 workgroups per CU
+  if (want < 1) want = 1;
+  long long by_len = (n_sub + 63) / 64;                           // at least 64 sub-tiles per split
+  long long ns = want < by_len ? want : by_len;
+  if (ns < 1) ns = 1;
+  if (ns > 64) ns = 64;
+  p.sub_per_split = (int)((n_sub + ns - 1) / ns);
+  p.n_splits = (int)((n_sub + p.sub_per_split - 1) / p.sub_per_split);
+  p.off_lists = round_up256((size_t)BM * dm.Hkv * dm.d * sizeof(float));
+  p.ws_bytes = p.off_lists + round_up256((size_t)dm.Hkv * BM * p.n_splits * k * sizeof(unsigned long long));
+  return p;
+}
+
+int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_route, int BM, const void* KR,
+                           const float* inv_norm, int k, void* ws, hipStream_t st) {
+  float* qf = (float*)ws;
+  if (dm.d == 128)
+    hipLaunchKernelGGL(fold_queries_kernel<128>, dim3((unsigned)(BM * dm.Hkv)), dim3(64), 0, st,
+                       (const uint16_t*)q_route, qf, dm.Hq, dm.Hkv, dm.r, dm.cos);
+  else
+    hipLaunchKernelGGL(fold_queries_kernel<64>, dim3((unsigned)(BM * dm.Hkv)), dim3(64), 0, st,
+                       (const uint16_t*)q_route, qf, dm.Hq, dm.Hkv, dm.r, dm.cos);
+  if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+  GemmArgs a;
+  a.qf = qf;
+  a.KR = (const uint16_t*)KR;
+  a.inv_norm = dm.cos ? inv_norm : nullptr;
+  a.ws = (unsigned long long*)((char*)ws + pl.off_lists);
+  a.BM = BM;
+  a.Hkv = dm.Hkv;
+  a.N = dm.N;
+  a.k = k;
+  a.tiles = dm.tiles;
+  a.n_qblocks = pl.n_qblocks;
+  a.n_splits = pl.n_splits;
+  a.sub_per_split = pl.sub_per_split;
+  const unsigned blocks = (unsigned)(dm.Hkv * pl.n_qblocks * pl.n_splits);
+  if (dm.d == 128)
+    hipLaunchKernelGGL(score_gemm_kernel<128>, dim3(blocks), dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL(score_gemm_kernel<64>, dim3(blocks), dim3(256), 0, st, a);
+  if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+  return MSA_OK;
+}
+
+}  // namespace msa

@@ -19,6 +19,28 @@ __global__ void probe_mfma_kernel(const uint16_t* A, const uint16_t* B, float* D
   for (int i = 0; i < 4; ++i) D[(4 * rr + i) * 16 + n] = acc[i];
 }
 
+// A [32][16], B [16][32] bf16 row-major; D [32][32] fp32 row-major (v_mfma_f32_32x32x16_bf16 layout).
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+__global__ void probe_mfma32_kernel(const uint16_t* A, const uint16_t* B, float* D, float* swapped) {
+  const int lane = threadIdx.x, h = lane >> 5, c = lane & 31;
+  uint32_t aw[4], bw[4];
+  for (int jj = 0; jj < 4; ++jj) {
+    const int k0 = 8 * h + 2 * jj;
+    aw[jj] = (uint32_t)A[c * 16 + k0] | ((uint32_t)A[c * 16 + k0 + 1] << 16);
+    bw[jj] = (uint32_t)B[k0 * 32 + c] | ((uint32_t)B[(k0 + 1) * 32 + c] << 16);
+  }
+  probe_f32x16 acc;
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(make_uint4(aw[0], aw[1], aw[2], aw[3])),
+                                                as_bf16x8(make_uint4(bw[0], bw[1], bw[2], bw[3])), acc, 0, 0, 0);
+  for (int i = 0; i < 16; ++i) D[((i % 4) + 8 * (i / 4) + 4 * h) * 32 + c] = acc[i];
+  // half-wave exchange used by the GEMM epilogue: every lane must see max(x[l], x[l ^ 32])
+  const float x = (float)((lane * 37) % 101);
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  swapped[lane] = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 __global__ void probe_group_max_kernel(const float* in, float* out, int C) {
   const float x = in[threadIdx.x];
   float y = x;
@@ -52,6 +74,10 @@ __global__ void probe_keys_kernel(const float* score, const uint32_t* doc, unsig
 
 extern "C" void probe_mfma(const void* A, const void* B, void* D) {
   hipLaunchKernelGGL(probe_mfma_kernel, dim3(1), dim3(64), 0, 0, (const uint16_t*)A, (const uint16_t*)B, (float*)D);
+}
+extern "C" void probe_mfma32(const void* A, const void* B, void* D, void* swapped) {
+  hipLaunchKernelGGL(probe_mfma32_kernel, dim3(1), dim3(64), 0, 0, (const uint16_t*)A, (const uint16_t*)B,
+                     (float*)D, (float*)swapped);
 }
 extern "C" void probe_group_max(const void* in, void* out, int C) {
   hipLaunchKernelGGL(probe_group_max_kernel, dim3(1), dim3(64), 0, 0, (const float*)in, (float*)out, C);

@@ -105,6 +105,22 @@ def test_probe_mfma_layout(probe):
     assert np.allclose(got, want, rtol=1e-5, atol=1e-5), np.abs(got - want).max()
 
 
+def test_probe_mfma32_layout_and_half_swap(probe):
+    say("probe: mfma 32x32x16 bf16 operand layout, permlane32 swap")
+    Ab, A = S.normal_bf16(903, (32, 16))
+    Bb, B = S.normal_bf16(904, (16, 32))
+    dA, dB = dev(Ab), dev(Bb)
+    D = torch.zeros((32, 32), dtype=torch.float32, device="cuda")
+    sw = torch.zeros(64, dtype=torch.float32, device="cuda")
+    probe.probe_mfma32(*(ctypes.c_void_p(t.data_ptr()) for t in (dA, dB, D, sw)))
+    torch.cuda.synchronize()
+    got = D.cpu().numpy().astype(np.float64)
+    assert np.allclose(got, A @ B, rtol=1e-5, atol=1e-5), np.abs(got - A @ B).max()
+    x = np.array([(l * 37) % 101 for l in range(64)], dtype=np.float32)
+    want = np.maximum(x, np.concatenate([x[32:], x[:32]]))
+    assert np.array_equal(sw.cpu().numpy(), want)
+
+
 def test_probe_group_max_and_dpp(probe):
     say("probe: DPP group max")
     x = np.random.default_rng(3).standard_normal(64).astype(np.float32)
@@ -249,6 +265,8 @@ CASES = {
     "c1_r1": (6000, 90, 3, 1, 64, 64, 64, 1, 3, 64, 1e6, 7),
     "batch40_c4": (10000, 203, 2, 4, 64, 128, 16, 40, 1, 20, 1e6, 5),
     "batch33_d64": (11000, 500, 1, 2, 32, 64, 8, 33, 1, 0, 1e4, 24),
+    "prefill100_gemm": (13000, 301, 2, 4, 64, 128, 8, 1, 100, 100, 1e6, 8),
+    "prefill300_gemm_d64": (14000, 77, 2, 2, 64, 64, 8, 2, 150, 150, 1e4, 5),
 }
 
 
