@@ -106,8 +106,10 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
   constexpr int SUB_BYTES = 32 * D * 2;  // one 32-key sub-tile
   constexpr int TILE_ELEMS = 16 * D;
   constexpr int LOADS = SUB_BYTES / (256 * 16);  // 16-byte loads per thread per sub-tile (2 at d=128)
-  __shared__ __attribute__((aligned(16))) unsigned char kbuf[2][SUB_BYTES];
-  __shared__ __attribute__((aligned(16))) float ibuf[2][32];
+  __shared__ __attribute__((aligned(16))) unsigned char kbuf0[SUB_BYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char kbuf1[SUB_BYTES];
+  __shared__ __attribute__((aligned(16))) float ibuf0[32];
+  __shared__ __attribute__((aligned(16))) float ibuf1[32];
   __shared__ unsigned long long mrg[4][64][2 * kGemmK];  // end-of-kernel merge of the two half lists
 
   const int tid = threadIdx.x;
@@ -167,19 +169,25 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
       ldoc[cb][p] = -1;
     }
 
-  // ---- staging of key sub-tiles: global -> registers -> LDS, one sub-tile ahead -----------------
+  // ---- staging of key sub-tiles: global -> LDS directly (no registers), one sub-tile ahead -----
+  // A 64-lane global_load_lds_dwordx4 lands at LDS base + 16 * lane, and a sub-tile is contiguous in
+  // the tiled index, so wave w copies bytes [1024 (4i + w), +1024) of the sub-tile with load i.  The
+  // two buffers are separate arrays addressed statically (the loop body is instantiated for each),
+  // which lets the compiler see that reads of one never alias the copy into the other.
   const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS;
   const float* ing = a.inv_norm ? a.inv_norm + (long long)g * a.tiles * 16 : nullptr;
-  uint4 stage_k[LOADS];
   float stage_i = 1.0f;
-  auto fetch = [&](long long st) {
+  auto fetch = [&](long long st, unsigned char* kdst) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int off = (i * 256 + tid) * 16;            // byte offset inside the sub-tile
       long long tile = 2 * st + off / (TILE_ELEMS * 2);
       if (tile >= a.tiles) tile = a.tiles - 1;         // odd tile count: repeat the last tile (masked)
-      stage_k[i] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(KRg) +
-                                                    tile * (TILE_ELEMS * 2) + off % (TILE_ELEMS * 2));
+      const unsigned char* src = reinterpret_cast<const unsigned char*>(KRg) + tile * (TILE_ELEMS * 2) +
+                                 off % (TILE_ELEMS * 2);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)src,
+          (__attribute__((address_space(3))) void*)(kdst + (i * 256 + wave * 64) * 16), 16, 0, 0);
     }
     if (tid < 32) {
       long long key = st * 32 + tid;
@@ -187,23 +195,11 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
       stage_i = ing ? ing[key] : 1.0f;
     }
   };
-  auto stash = [&](int b) {
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i)
-      *reinterpret_cast<uint4*>(&kbuf[b][(i * 256 + tid) * 16]) = stage_k[i];
-    if (tid < 32) ibuf[b][tid] = stage_i;
-  };
 
-  if (s0 < s1) {
-    fetch(s0);
-    stash(0);
-  }
-  __syncthreads();
-
-  for (long long st = s0; st < s1; ++st) {
-    const int b = (int)((st - s0) & 1);
+  auto body = [&](long long st, const unsigned char* kcur, const float* icur, unsigned char* knxt,
+                  float* inxt) {
     const long long nxt = (st + 1 < s1) ? st + 1 : st;  // always issued (re-reads the last sub-tile)
-    fetch(nxt);
+    fetch(nxt, knxt);
 
     // ---- 32 keys x 64 tokens, contraction over [hi | lo] ---------------------------------------
     f32x16_t acc[2];
@@ -211,21 +207,25 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
+    // A operand: key row c -> tile c/16, slot c%16; dims 16s + 8h .. +8 = piece 2s + h.  All slices
+    // are requested before the first product so that LDS latency overlaps the matrix pipeline.
+    bf16x8_t av[NS8];
+#pragma unroll
+    for (int s = 0; s < NS8; ++s)
+      av[s] = as_bf16x8(*reinterpret_cast<const uint4*>(
+          &kcur[(c >> 4) * (TILE_ELEMS * 2) + ((2 * s + h) * 16 + (c & 15)) * 16]));
 #pragma unroll
     for (int s = 0; s < NS8; ++s) {
-      // A operand: key row c -> tile c/16, slot c%16; dims 16s + 8h .. +8 = piece 2s + h
-      const bf16x8_t av = as_bf16x8(*reinterpret_cast<const uint4*>(
-          &kbuf[b][(c >> 4) * (TILE_ELEMS * 2) + ((2 * s + h) * 16 + (c & 15)) * 16]));
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) {
-        acc[cb] = mfma32(av, Bhi[cb][s], acc[cb]);
-        acc[cb] = mfma32(av, Blo[cb][s], acc[cb]);
+        acc[cb] = mfma32(av[s], Bhi[cb][s], acc[cb]);
+        acc[cb] = mfma32(av[s], Blo[cb][s], acc[cb]);
       }
     }
     float inv[16];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const float4 v = *reinterpret_cast<const float4*>(&ibuf[b][8 * j + 4 * h]);
+      const float4 v = *reinterpret_cast<const float4*>(&icur[8 * j + 4 * h]);
       inv[4 * j] = v.x;
       inv[4 * j + 1] = v.y;
       inv[4 * j + 2] = v.z;
@@ -235,16 +235,21 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
     // ---- epilogue: document max, insertion into the per-lane lists ------------------------------
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
-      float m[4];
+      float m0, m1, m2, m3;
+      {
+        float m[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float x0 = acc[cb][4 * j] * inv[4 * j], x1 = acc[cb][4 * j + 1] * inv[4 * j + 1];
-        const float x2 = acc[cb][4 * j + 2] * inv[4 * j + 2], x3 = acc[cb][4 * j + 3] * inv[4 * j + 3];
-        m[j] = max_with_other_half(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
+        for (int j = 0; j < 4; ++j) {
+          const float x0 = acc[cb][4 * j] * inv[4 * j], x1 = acc[cb][4 * j + 1] * inv[4 * j + 1];
+          const float x2 = acc[cb][4 * j + 2] * inv[4 * j + 2], x3 = acc[cb][4 * j + 3] * inv[4 * j + 3];
+          m[j] = max_with_other_half(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
+        }
+        m0 = m[0]; m1 = m[1]; m2 = m[2]; m3 = m[3];
       }
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
-        const float sc = h ? m[2 + jj] : m[jj];
+        const float lo_half = jj ? m1 : m0, hi_half = jj ? m3 : m2;
+        const float sc = h ? hi_half : lo_half;
         const long long doc = st * 4 + 2 * h + jj;
         const bool ok = doc < a.N && sc > lsc[cb][kGemmK - 1];
         if (__any(ok)) {
@@ -262,9 +267,20 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
         }
       }
     }
-
-    stash(b ^ 1);
+    if (tid < 32) inxt[tid] = stage_i;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the copy into the other buffer has landed
     __syncthreads();
+  };
+
+  if (s0 < s1) {
+    fetch(s0, kbuf0);
+    if (tid < 32) ibuf0[tid] = stage_i;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  __syncthreads();
+  for (long long st = s0; st < s1; st += 2) {
+    body(st, kbuf0, ibuf0, kbuf1, ibuf1);
+    if (st + 1 < s1) body(st + 1, kbuf1, ibuf1, kbuf0, ibuf0);  // block-uniform
   }
 
   // ---- merge the two half-wave lists of every token, write sorted keys -----------------------

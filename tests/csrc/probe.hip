@@ -41,6 +41,17 @@ __global__ void probe_mfma32_kernel(const uint16_t* A, const uint16_t* B, float*
   swapped[lane] = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// Direct global -> LDS copy: a 64-lane global_load_lds_dwordx4 must land at LDS base + 16 * lane.
+__global__ void probe_load_lds_kernel(const uint4* src, uint4* out) {
+  __shared__ __attribute__((aligned(16))) unsigned char buf[4096];
+  const int wave = threadIdx.x >> 6;
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + threadIdx.x),
+                                   (__attribute__((address_space(3))) void*)(buf + wave * 1024), 16, 0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  out[threadIdx.x] = *reinterpret_cast<const uint4*>(buf + threadIdx.x * 16);
+}
+
 __global__ void probe_group_max_kernel(const float* in, float* out, int C) {
   const float x = in[threadIdx.x];
   float y = x;
@@ -78,6 +89,9 @@ extern "C" void probe_mfma(const void* A, const void* B, void* D) {
 extern "C" void probe_mfma32(const void* A, const void* B, void* D, void* swapped) {
   hipLaunchKernelGGL(probe_mfma32_kernel, dim3(1), dim3(64), 0, 0, (const uint16_t*)A, (const uint16_t*)B,
                      (float*)D, (float*)swapped);
+}
+extern "C" void probe_load_lds(const void* src, void* out) {
+  hipLaunchKernelGGL(probe_load_lds_kernel, dim3(1), dim3(256), 0, 0, (const uint4*)src, (uint4*)out);
 }
 extern "C" void probe_group_max(const void* in, void* out, int C) {
   hipLaunchKernelGGL(probe_group_max_kernel, dim3(1), dim3(64), 0, 0, (const float*)in, (float*)out, C);

@@ -121,6 +121,15 @@ def test_probe_mfma32_layout_and_half_swap(probe):
     assert np.array_equal(sw.cpu().numpy(), want)
 
 
+def test_probe_global_load_lds(probe):
+    say("probe: direct global -> LDS load lands at base + 16 * lane")
+    src = torch.arange(1024, dtype=torch.int32, device="cuda")
+    out = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    probe.probe_load_lds(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(out.data_ptr()))
+    torch.cuda.synchronize()
+    assert torch.equal(src, out)
+
+
 def test_probe_group_max_and_dpp(probe):
     say("probe: DPP group max")
     x = np.random.default_rng(3).standard_normal(64).astype(np.float32)
