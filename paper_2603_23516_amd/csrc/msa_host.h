@@ -40,6 +40,8 @@ struct ScorePlan {
   int exchange;          // 1: waves exchange running maxima to tighten their thresholds
   int it_publish, it_adopt;
   size_t off_gmax;       // byte offset of the exchange buffer inside the workspace
+  size_t off_qop;        // byte offset of the prepared query operands
+  int n_qtiles;          // 8-query operand tiles (padded to whole passes)
   int use_gemm;          // 1: many query tokens -> the GEMM path below
   GemmPlan gemm;
   size_t ws_bytes;

@@ -28,7 +28,8 @@ constexpr int kPrefetch = 4;         // tiles in flight per wave
 constexpr int kListBytes = 16384;    // LDS per wave for candidate lists
 
 struct ScoreArgs {
-  const uint16_t* q_route;  // [BM][Hq][D]
+  const uint4* qop;         // [Hkv][n_qtiles][D/32][64] A operands (bf16 hi/lo rows) of 8-query tiles
+  int n_qtiles;
   const uint16_t* KR;       // tiled
   const float* inv_norm;    // may be null (dot)
   unsigned long long* ws;   // [Hkv][BM][n_splits][k] candidate keys, each list sorted descending
@@ -107,14 +108,10 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
   constexpr int NQ = 8 * NQT;  // queries per pass
   constexpr int CAP = kListBytes / (8 * NQ);
   constexpr int TILE_ELEMS = 16 * D;
-  constexpr int LPH = D / 8;    // lanes that hold one head vector (16-byte pieces)
-  constexpr int HPL = 64 / LPH; // head vectors per wave-wide load
-  static_assert(NQ * D * 4 <= kListBytes, "folded queries must fit in the list area");
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[kListBytes];
   __shared__ int cnt_s[NQ];
   __shared__ float thr_s[NQ];
-  float* qf = reinterpret_cast<float*>(smem);                             // [NQ][D], prologue only
   unsigned long long* cand = reinterpret_cast<unsigned long long*>(smem);  // [NQ][CAP]
 
   const int lane = threadIdx.x;
@@ -143,77 +140,16 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
     binv[u] = COS ? ing[t * 16] : 1.0f;
   }
 
-  // ---- fold the r heads of this group into one fp32 routing query per token -------------------
-  // Lane = (head slot lane / LPH, 16-byte piece lane % LPH): one load covers HPL heads of a query.
-  {
-    const int piece = lane % LPH;
-    const int hs = lane / LPH;
-    const int n_hp = (a.r + HPL - 1) / HPL;  // loads per query (1 unless r > HPL)
-    uint4 v0[NQ];                            // all first loads are issued before any is used
-#pragma unroll
-    for (int qi = 0; qi < NQ; ++qi) {
-      v0[qi] = make_uint4(0, 0, 0, 0);
-      if (a.q0 + qi < a.BM && hs < a.r)
-        v0[qi] = *reinterpret_cast<const uint4*>(
-            a.q_route + ((long long)(a.q0 + qi) * a.Hq + g * a.r + hs) * D + piece * 8);
-    }
-#pragma unroll
-    for (int qi = 0; qi < NQ; ++qi) {
-      const int qg = a.q0 + qi;
-      float f[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] = 0.f;
-      for (int hp = 0; hp < n_hp; ++hp) {
-        const int hh = hp * HPL + hs;
-        uint4 v = v0[qi];
-        if (hp > 0) {
-          v = make_uint4(0, 0, 0, 0);
-          if (qg < a.BM && hh < a.r)
-            v = *reinterpret_cast<const uint4*>(a.q_route + ((long long)qg * a.Hq + g * a.r + hh) * D + piece * 8);
-        }
-        float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
-                      bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
-        ss = group_sum<LPH>(ss);
-        const float w = COS ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : 1.0f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] += x[e] * w;
-      }
-      // add the head slots that hold the same piece (lanes piece, piece + LPH, ...)
-#pragma unroll
-      for (int off = LPH; off < 64; off <<= 1) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] += __shfl_xor(f[e], off, 64);
-      }
-      if (hs == 0) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[qi * D + piece * 8 + e] = f[e] / (float)a.r;
-      }
-    }
-  }
-  wave_sync();
-
-  // ---- A operands: row n of tile t is query 8t + n/2, hi (even n) or lo (odd n) half ----------
+  // ---- A operands (prepared once per call by prep_scan_operands_kernel): row n of query tile t is
+  // query 8t + n/2, hi (even n) or lo (odd n) half of the folded fp32 routing query -----------------
   bf16x8_t A[NQT][NS];
 #pragma unroll
   for (int t = 0; t < NQT; ++t) {
-    const int qi = 8 * t + (n >> 1);
+    const long long qt = a.q0 / 8 + t;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      uint32_t w[4];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        float h0, l0, h1, l1;
-        split_bf16(qf[qi * D + 32 * s + 8 * rr + 2 * jj], h0, l0);
-        split_bf16(qf[qi * D + 32 * s + 8 * rr + 2 * jj + 1], h1, l1);
-        w[jj] = (n & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
-      }
-      A[t][s] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
-    }
+    for (int s = 0; s < NS; ++s)
+      A[t][s] = as_bf16x8(a.qop[(((long long)g * a.n_qtiles + qt) * NS + s) * 64 + lane]);
   }
-  wave_sync();  // qf is dead from here on; the same LDS now holds the candidate lists
 
   // This lane sees queries 8t + 2rr + e (e = 0, 1) of every tile; all 16 lanes of a row keep
   // identical copies of their counters and thresholds.
@@ -479,9 +415,83 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
   }
 }
 
-__global__ void fill_neg_inf_kernel(float* __restrict__ p, long long n) {
-  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = -INFINITY;
+// One wave per (tile of 8 queries, KV head): fold the r heads of the group into one fp32 routing
+// query per token,  qf = (1/r) sum_h q_h / max(|q_h|, 1e-12)  (plain mean for the dot product), split it
+// into bf16 hi + lo and store the MFMA A operands of the tile: lane 16q + n holds row n (query n/2,
+// hi for even n, lo for odd n), dims 32s + 8q .. +8 of slice s.  Also resets the threshold-exchange
+// buffer of the scan to -inf.
+template <int D>
+__global__ __launch_bounds__(64) void prep_scan_operands_kernel(const uint16_t* __restrict__ q_route,
+                                                                uint4* __restrict__ qop, int BM, int Hq,
+                                                                int Hkv, int r, int cos, int n_qtiles,
+                                                                float* __restrict__ gmax, long long n_gmax) {
+  constexpr int NS = D / 32, LPH = D / 8, HPL = 64 / LPH;
+  __shared__ float qf[8][D];
+  const int lane = threadIdx.x;
+  const int qt = blockIdx.x % n_qtiles;
+  const int g = blockIdx.x / n_qtiles;
+  if (gmax != nullptr) {
+    for (long long i = (long long)blockIdx.x * 64 + lane; i < n_gmax; i += (long long)gridDim.x * 64)
+      gmax[i] = -INFINITY;
+  }
+  const int piece = lane % LPH, hs = lane / LPH;
+  const int n_hp = (r + HPL - 1) / HPL;
+  uint4 v0[8];
+#pragma unroll
+  for (int qi = 0; qi < 8; ++qi) {
+    v0[qi] = make_uint4(0, 0, 0, 0);
+    const long long qg = (long long)qt * 8 + qi;
+    if (qg < BM && hs < r)
+      v0[qi] = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hs) * D + piece * 8);
+  }
+#pragma unroll
+  for (int qi = 0; qi < 8; ++qi) {
+    const long long qg = (long long)qt * 8 + qi;
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = 0.f;
+    for (int hp = 0; hp < n_hp; ++hp) {
+      const int hh = hp * HPL + hs;
+      uint4 v = v0[qi];
+      if (hp > 0) {
+        v = make_uint4(0, 0, 0, 0);
+        if (qg < BM && hh < r)
+          v = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hh) * D + piece * 8);
+      }
+      const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                          bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+      float ss = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+      ss = group_sum<LPH>(ss);
+      const float w = cos ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : 1.0f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] += x[e] * w;
+    }
+#pragma unroll
+    for (int off = LPH; off < 64; off <<= 1) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] += __shfl_xor(f[e], off, 64);
+    }
+    if (hs == 0) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[qi][piece * 8 + e] = f[e] / (float)r;
+    }
+  }
+  wave_sync();
+  const int rr = lane >> 4, n = lane & 15;
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    uint32_t w[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      float h0, l0, h1, l1;
+      split_bf16(qf[n >> 1][32 * s + 8 * rr + 2 * jj], h0, l0);
+      split_bf16(qf[n >> 1][32 * s + 8 * rr + 2 * jj + 1], h1, l1);
+      w[jj] = (n & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
+    }
+    qop[(((long long)g * n_qtiles + qt) * NS + s) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
 }
 
 ScorePlan plan_score(const Dims& dm, int BM, int k) {
@@ -496,19 +506,24 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
     p.exchange = 0;
     p.it_publish = p.it_adopt = 0;
     p.off_gmax = 0;
+    p.off_qop = 0;
+    p.n_qtiles = 0;
     p.ws_bytes = p.gemm.ws_bytes;
     return p;
   }
+  p.q_per_pass = (BM <= 8) ? 8 : ((BM <= 16 || k > 24) ? 16 : 32);
+  p.n_pass = (BM + p.q_per_pass - 1) / p.q_per_pass;
   long long ns = 2048 / dm.Hkv;  // ~8 waves per CU on 256 CUs
   if (ns < 1) ns = 1;
-  const long long by_tiles = (dm.tiles + kPrefetch - 1) / kPrefetch;
+  // streams of at least kPrefetch tiles; with 32 queries per pass the lists (64 entries each) must
+  // also hold every document of the stream without pruning, so streams stay short there
+  const long long min_len = kPrefetch;
+  const long long by_tiles = (dm.tiles + min_len - 1) / min_len;
   if (ns > by_tiles) ns = by_tiles;
   if (ns > 1024) ns = 1024;
   if (ns < 1) ns = 1;
   p.tiles_per_split = (int)((dm.tiles + ns - 1) / ns);
   p.n_splits = (int)((dm.tiles + p.tiles_per_split - 1) / p.tiles_per_split);
-  p.q_per_pass = (BM <= 8) ? 8 : ((BM <= 16 || k > 24) ? 16 : 32);
-  p.n_pass = (BM + p.q_per_pass - 1) / p.q_per_pass;
   const size_t list_bytes = round_up256((size_t)dm.Hkv * BM * p.n_splits * k * sizeof(unsigned long long));
   // threshold exchange between waves: worth it (and sound) only for long streams with >= k waves per head
   const long long n_it_min = dm.tiles / p.n_splits;
@@ -516,7 +531,9 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
   p.it_publish = (int)(n_it_min / 12);
   p.it_adopt = p.it_publish + 8;
   p.off_gmax = list_bytes;
-  p.ws_bytes = list_bytes + (p.exchange ? round_up256((size_t)dm.Hkv * BM * p.n_splits * sizeof(float)) : 0);
+  p.off_qop = list_bytes + (p.exchange ? round_up256((size_t)dm.Hkv * BM * p.n_splits * sizeof(float)) : 0);
+  p.n_qtiles = p.n_pass * (p.q_per_pass / 8);
+  p.ws_bytes = p.off_qop + round_up256((size_t)dm.Hkv * p.n_qtiles * (dm.d / 32) * 64 * 16);
   return p;
 }
 
@@ -532,7 +549,6 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
     return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
   }
   ScoreArgs a;
-  a.q_route = (const uint16_t*)q_route;
   a.KR = (const uint16_t*)KR;
   a.inv_norm = dm.cos ? inv_norm : nullptr;
   a.ws = (unsigned long long*)ws;
@@ -550,9 +566,19 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
   a.gmax = pl.exchange ? (float*)((char*)ws + pl.off_gmax) : nullptr;
   a.it_publish = pl.it_publish;
   a.it_adopt = pl.it_adopt;
-  if (pl.exchange) {
-    const long long n = (long long)dm.Hkv * BM * pl.n_splits;
-    hipLaunchKernelGGL(fill_neg_inf_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.gmax, n);
+  a.qop = (const uint4*)((char*)ws + pl.off_qop);
+  a.n_qtiles = pl.n_qtiles;
+  {
+    const long long n_gmax = pl.exchange ? (long long)dm.Hkv * BM * pl.n_splits : 0;
+    const unsigned blocks = (unsigned)(pl.n_qtiles * dm.Hkv);
+    if (dm.d == 128)
+      hipLaunchKernelGGL(prep_scan_operands_kernel<128>, dim3(blocks), dim3(64), 0, st,
+                         (const uint16_t*)q_route, (uint4*)((char*)ws + pl.off_qop), BM, dm.Hq, dm.Hkv,
+                         dm.r, dm.cos, pl.n_qtiles, a.gmax, n_gmax);
+    else
+      hipLaunchKernelGGL(prep_scan_operands_kernel<64>, dim3(blocks), dim3(64), 0, st,
+                         (const uint16_t*)q_route, (uint4*)((char*)ws + pl.off_qop), BM, dm.Hq, dm.Hkv,
+                         dm.r, dm.cos, pl.n_qtiles, a.gmax, n_gmax);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
   dim3 grid(pl.n_splits, dm.Hkv), block(64);
