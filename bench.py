@@ -22,6 +22,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+# HBM traffic per msa_score_topk call (bytes) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by the same counter's reading for a plain copy of known size (FETCH_SIZE reads 0.5 KiB per KiB
+# copied -> x2; WRITE_SIZE reads 1.0 -> x1); see profiles/pmc_traffic_cfg5_decode_50m.txt.
+MEASURED_SCORE_TRAFFIC = {"cfg5_decode_50m": (806571.4 * 2 + 4640.1 + 2088.0 * 2 + 16.0 + 9.6 * 2 + 64.0) * 1024}
 
 
 def parse():
@@ -152,6 +158,10 @@ def main():
     attend_gbs = ab["attend"] / (attend_ms * 1e-3) / 1e9
     build_gbs = ab["build"] / (build_ms * 1e-3) / 1e9
 
+    flops = None
+    if nq >= 64 and k <= 8:      # the MFMA GEMM path: flops issued = 2 * tokens * keys * (hi + lo) * d per head
+        tiles = (wl.N * wl.C + 15) // 16
+        flops = 2.0 * nq * wl.Hkv * tiles * 16 * 2 * wl.d
     res = {
         "metric": "routed decode queries/sec (score+top-k then sparse attend, one MSA layer)",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -160,10 +170,14 @@ def main():
         "config": {"workload": wl.name, "memory_tokens": wl.N * wl.G, "docs": wl.N, "doc_len": wl.G,
                    "chunk": wl.P, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.d, "batch": B,
                    "query_tokens": M, "top_k": k, "local_tokens": wl.Lloc, "rope_base": wl.base},
-        "roofline": {"bound": "hbm", "kernel": "msa_score_topk (score_scan_kernel + merge)",
-                     "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": score_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_launch": ab["score"], "avg_ms": score_ms},
+        "roofline": ({"bound": "hbm", "kernel": "msa_score_topk = prep + score_scan_kernel (dominant) + score_merge",
+                      "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": score_gbs / HBM_PEAK_GBS, "traffic": MEASURED_SCORE_TRAFFIC.get(wl.name),
+                      "algorithmic_bytes_per_launch": ab["score"], "avg_ms": score_ms} if flops is None else
+                     {"bound": "mfma", "kernel": "msa_score_topk = fold + score_gemm_kernel (dominant) + score_merge",
+                      "achieved": flops / (score_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                      "unit": "TFLOP/s", "frac": flops / (score_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                      "traffic": None, "flops_issued_per_launch": flops, "avg_ms": score_ms}),
         "attend": {"bound": "hbm", "achieved": attend_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                    "frac": attend_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": ab["attend"],
                    "avg_ms": attend_ms},

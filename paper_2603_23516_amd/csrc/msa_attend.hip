@@ -186,22 +186,51 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     while (st < we && !locate(st, ss)) ++st;
     return st;
   };
+  // Loads of one step.  The step's base addresses are wave-uniform (scalar registers) and every
+  // lane adds a fixed 32-bit byte offset, so a load costs no address arithmetic; only the ragged
+  // last step of the local context clamps its rows.
+  const unsigned kofs = (unsigned)(n * D * 2 + 16 * rr);  // key row n, 16-byte piece rr of a 64-byte slice
+  const unsigned vofs = (unsigned)(lane * 16);            // value rows are contiguous: piece `lane` of 1 KiB
   auto issue_loads = [&](const StepSrc& ss, uint4 (&kr)[2][NS], uint4 (&vr)[NVL]) {
+    const unsigned long long kaddr = (unsigned long long)ss.Kb, vaddr = (unsigned long long)ss.Vb;
+    typedef const __attribute__((address_space(1))) char* gptr_t;  // global memory, not generic
+    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(1))) u32x4_t* gvec_t;
+    auto ld = [](gvec_t p) { const u32x4_t v = *p; return make_uint4(v.x, v.y, v.z, v.w); };
+    // readfirstlane returns a signed int: both halves go through unsigned before widening, or a
+    // low word with bit 31 set would sign-extend into the high word
+    auto uni64 = [](unsigned long long v) {
+      const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+      const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+      return ((unsigned long long)hi << 32) | (unsigned long long)lo;
+    };
+    gptr_t kb = (gptr_t)uni64(kaddr);
+    gptr_t vb = (gptr_t)uni64(vaddr);
+    if (ss.rows_valid == 32) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      int row = 16 * h + n;
-      row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+      for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int s = 0; s < NS; ++s)
-        kr[h][s] = *reinterpret_cast<const uint4*>(ss.Kb + row * D + 32 * s + 8 * rr);
-    }
+        for (int s = 0; s < NS; ++s)
+          kr[h][s] = ld((gvec_t)(kb + kofs + (h * 16 * D * 2 + s * 64)));
 #pragma unroll
-    for (int i = 0; i < NVL; ++i) {
-      const int f = i * 64 + lane;
-      int row = f / (D / 8);
-      const int piece = f % (D / 8);
-      row = row < ss.rows_valid ? row : ss.rows_valid - 1;
-      vr[i] = *reinterpret_cast<const uint4*>(ss.Vb + row * D + piece * 8);
+      for (int i = 0; i < NVL; ++i) vr[i] = ld((gvec_t)(vb + vofs + i * 1024));
+    } else {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        int row = 16 * h + n;
+        row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+          kr[h][s] = ld((gvec_t)(kb + (unsigned)(row * D * 2 + 16 * rr + s * 64)));
+      }
+#pragma unroll
+      for (int i = 0; i < NVL; ++i) {
+        const int f = i * 64 + lane;
+        int row = f / (D / 8);
+        const int piece = f % (D / 8);
+        row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+        vr[i] = ld((gvec_t)(vb + (unsigned)(row * D * 2 + piece * 16)));
+      }
     }
   };
 
@@ -306,10 +335,23 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
                      fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-    m_run = m_new;
+    // The accumulator is rescaled only in the steps where some head's running maximum grows
+    // (wave-uniform branch); once the maxima have settled most steps skip it.
+    const bool bump = mx > m_run;
+    if (__any(bump)) {
+      const float m_new = bump ? mx : m_run;
+      const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int c = 0; c < NCB; ++c) {
+        o[c][0] *= alpha;
+        o[c][1] *= alpha;
+        o[c][2] *= alpha;
+        o[c][3] *= alpha;
+      }
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
     float psum = 0.f;
     uint32_t pw[4];
 #pragma unroll
@@ -326,7 +368,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       pw[2 * h] = pack_bf16(pv[0], pv[1]);
       pw[2 * h + 1] = pack_bf16(pv[2], pv[3]);
     }
-    l_run = l_run * alpha + psum;
+    l_run += psum;
     const bf16x8_t pb = as_bf16x8(make_uint4(pw[0], pw[1], pw[2], pw[3]));
 
     // ---- second product: value rows are read back from LDS transposed ------------------------
@@ -345,12 +387,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
         const uint32_t hi = stage[wave][r1 * VS2 + 16 * c + n];
         w[jj] = lo | (hi << 16);
       }
-      f32x4_t oc = o[c];
-      oc[0] *= alpha;
-      oc[1] *= alpha;
-      oc[2] *= alpha;
-      oc[3] *= alpha;
-      o[c] = mfma16(as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])), pb, oc);
+      o[c] = mfma16(as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])), pb, o[c]);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
