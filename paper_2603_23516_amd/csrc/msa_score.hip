@@ -434,49 +434,39 @@ __global__ __launch_bounds__(64) void prep_scan_operands_kernel(const uint16_t* 
     for (long long i = (long long)blockIdx.x * 64 + lane; i < n_gmax; i += (long long)gridDim.x * 64)
       gmax[i] = -INFINITY;
   }
-  const int piece = lane % LPH, hs = lane / LPH;
-  const int n_hp = (r + HPL - 1) / HPL;
-  uint4 v0[8];
+  // Lane = (query lane / LPH, 16-byte piece lane % LPH): a lane loads the same piece of all r heads of
+  // its query, so the head sum stays in the lane and the norms need only DPP sums over LPH <= 16 lanes.
+  const int piece = lane % LPH;
 #pragma unroll
-  for (int qi = 0; qi < 8; ++qi) {
-    v0[qi] = make_uint4(0, 0, 0, 0);
+  for (int pass = 0; pass < 8 / HPL; ++pass) {
+    const int qi = pass * HPL + lane / LPH;
     const long long qg = (long long)qt * 8 + qi;
-    if (qg < BM && hs < r)
-      v0[qi] = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hs) * D + piece * 8);
-  }
+    uint4 v[8];
 #pragma unroll
-  for (int qi = 0; qi < 8; ++qi) {
-    const long long qg = (long long)qt * 8 + qi;
+    for (int hh = 0; hh < 8; ++hh) {
+      v[hh] = make_uint4(0, 0, 0, 0);
+      if (qg < BM && hh < r)
+        v[hh] = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hh) * D + piece * 8);
+    }
     float f[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) f[e] = 0.f;
-    for (int hp = 0; hp < n_hp; ++hp) {
-      const int hh = hp * HPL + hs;
-      uint4 v = v0[qi];
-      if (hp > 0) {
-        v = make_uint4(0, 0, 0, 0);
-        if (qg < BM && hh < r)
-          v = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hh) * D + piece * 8);
+#pragma unroll
+    for (int hh = 0; hh < 8; ++hh) {
+      if (hh < r) {  // wave-uniform
+        const float x[8] = {bf16_lo(v[hh].x), bf16_hi(v[hh].x), bf16_lo(v[hh].y), bf16_hi(v[hh].y),
+                            bf16_lo(v[hh].z), bf16_hi(v[hh].z), bf16_lo(v[hh].w), bf16_hi(v[hh].w)};
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+        ss = group_sum<LPH>(ss);
+        const float w = cos ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] += x[e] * w;
       }
-      const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
-                          bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
-      float ss = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
-      ss = group_sum<LPH>(ss);
-      const float w = cos ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : 1.0f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] += x[e] * w;
     }
 #pragma unroll
-    for (int off = LPH; off < 64; off <<= 1) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] += __shfl_xor(f[e], off, 64);
-    }
-    if (hs == 0) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[qi][piece * 8 + e] = f[e] / (float)r;
-    }
+    for (int e = 0; e < 8; ++e) qf[qi][piece * 8 + e] = f[e] / (float)r;
   }
   wave_sync();
   const int rr = lane >> 4, n = lane & 15;
