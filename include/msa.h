@@ -24,7 +24,7 @@
  *   - Errors: 0 on success, a negative msa_status otherwise.  Arguments are validated on the host
  *     before anything is enqueued, so an error return (other than MSA_ERR_HIP) means no work was
  *     launched and no GPU is needed to observe it.  No exceptions, no aborts, no printing.
- *   - Inputs are finite by contract.  Out-of-range document ids in `idx` are the caller's bug.
+ *   - Inputs are finite by contract.  msa_sparse_attend skips document ids outside [0, N) like -1 pads.
  */
 #ifndef MSA_H_
 #define MSA_H_
@@ -143,7 +143,7 @@ int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int3
  *     out[b][m][h][:] = softmax_j( RoPE(q[b][m][h][:], q_pos[b][m]) . key_j / sqrt(d) ) . value_j
  *     lse[b][m][h]    = log sum_j exp( ... )          (natural log; -inf and out = 0 if no key is visible)
  * RoPE pairs element u with u + d/2, angle p * base^(-2u/d).  Positions restart at 0 in every document;
- * idx == -1 marks "no document"; a document listed twice is attended twice.
+ * idx == -1 (or any id outside [0, N)) marks "no document"; a document listed twice is attended twice.
  *   q         in   bf16 [B][M][Hq][d]
  *   K, V      in   bf16 [N][Hkv][G][d]
  *   idx       in   int32 [B][M][Hkv][k]

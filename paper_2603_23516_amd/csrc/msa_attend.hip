@@ -30,7 +30,9 @@ constexpr int kAttWaves = 4;
 constexpr int kMaxHalf = 64;  // d/2 <= 64
 
 struct RopeTheta {
-  double th[kMaxHalf];  // theta_u = base^(-2u/d), computed on the host in double
+  double th[kMaxHalf];   // theta_u = base^(-2u/d), computed on the host in double
+  float2 e1[kMaxHalf];   // (cos, sin)(theta_u), rounded from double on the host
+  float2 e16[kMaxHalf];  // (cos, sin)(16 theta_u)
 };
 
 struct AttendArgs {
@@ -43,7 +45,7 @@ struct AttendArgs {
   const int32_t* q_pos;  // [BM]
   float* part_o;         // [BM][Hq][n_splits][D]   unnormalised partial outputs
   float2* part_ml;       // [BM][Hq][n_splits]      (running max in log2 units, sum)
-  int M, Hq, Hkv, r, G, k, Lloc, pos0;
+  int M, Hq, Hkv, r, G, k, Lloc, pos0, N;
   int steps_mem, steps_total, steps_per_split, n_splits;
   float qscale;          // log2(e) / sqrt(d)
 };
@@ -96,8 +98,22 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   n_vis = n_vis < 0 ? 0 : (n_vis > a.Lloc ? a.Lloc : n_vis);
 
   // ---- block prologue: rotation tables and rotated queries ------------------------------------
-  for (int e = tid; e < 16 * HALF; e += 256) base0[e / HALF][e % HALF] = cis_pos(e / HALF, th.th[e % HALF]);
-  if (tid < HALF) step16[tid] = cis_pos(16, th.th[tid]);
+  // base0[n][u] = e^{i n theta_u}, n < 16, by repeated multiplication with the host's e^{i theta_u}
+  // (at most 15 fp32 complex products: error ~1e-6, far below the bf16 rounding of the rotated keys)
+  for (int e = tid; e < 4 * HALF; e += 256) {
+    const int u = e % HALF, n4 = e / HALF;  // this thread fills positions 4*n4 .. 4*n4 + 3
+    const float2 w = th.e1[u];
+    const float2 w2 = cmul(w, w);
+    const float2 w4 = cmul(w2, w2);
+    float2 cur = make_float2(1.f, 0.f);
+    for (int i = 0; i < n4; ++i) cur = cmul(cur, w4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      base0[4 * n4 + i][u] = cur;
+      cur = cmul(cur, w);
+    }
+  }
+  if (tid < HALF) step16[tid] = th.e16[tid];
   for (int e = tid; e < a.r * HALF; e += 256) {
     const int hh = e / HALF, u = e % HALF;
     const uint16_t* qp = a.q + ((long long)bm * a.Hq + g * a.r + hh) * D;
@@ -165,7 +181,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       const int slot = tok / a.G;
       const int pin = tok - slot * a.G;
       const int doc = __builtin_amdgcn_readlane(my_idx, slot);
-      if (doc < 0) return false;
+      if (doc < 0 || doc >= a.N) return false;  // -1 pads, and ids outside the bank, are skipped
       const long long off = (((long long)doc * a.Hkv + g) * a.G + pin) * D;
       ss.Kb = a.K + off;
       ss.Vb = a.V + off;
@@ -505,7 +521,9 @@ AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc) {
   p.steps_mem = (int)(((long long)k * dm.G) / 32);
   p.steps_total = p.steps_mem + (Lloc + 31) / 32;
   const long long pairs = (long long)BM * dm.Hkv;
-  long long per = ((long long)p.steps_total * pairs + 1023) / 1024;  // aim at ~1024 blocks
+  // aim at <= 512 blocks: two 256-thread blocks are resident per CU (register-limited), so 512 is
+  // one full wave of blocks on 256 CUs and nothing waits for a second round
+  long long per = ((long long)p.steps_total * pairs + 511) / 512;
   if (per < kAttWaves) per = kAttWaves;
   const long long per_cap = (p.steps_total + kMaxAttSplits - 1) / kMaxAttSplits;  // n_splits <= 256
   if (per < per_cap) per = per_cap;
@@ -539,6 +557,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.Hkv = dm.Hkv;
   a.r = dm.r;
   a.G = dm.G;
+  a.N = dm.N;
   a.k = k;
   a.Lloc = Lloc;
   a.pos0 = pos0;
@@ -548,8 +567,11 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.n_splits = pl.n_splits;
   a.qscale = (float)(1.4426950408889634 / sqrt((double)dm.d));
   RopeTheta th;
-  for (int u = 0; u < kMaxHalf; ++u)
+  for (int u = 0; u < kMaxHalf; ++u) {
     th.th[u] = (u < dm.d / 2) ? pow((double)dm.base, -2.0 * (double)u / (double)dm.d) : 0.0;
+    th.e1[u] = make_float2((float)cos(th.th[u]), (float)sin(th.th[u]));
+    th.e16[u] = make_float2((float)cos(16.0 * th.th[u]), (float)sin(16.0 * th.th[u]));
+  }
   const int BM = B * M;
   dim3 grid(pl.n_splits, dm.Hkv, BM), block(256);
   if (dm.d == 128)

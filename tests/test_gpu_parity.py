@@ -380,6 +380,15 @@ def test_ties_duplicates_and_pads():
     out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, case.dKl, case.dVl, pos0, dpos)
     torch.cuda.synchronize()
     check_attend(case, out, lse, sel, pos0, q_pos)
+    # ids outside [0, N) are skipped like -1 (the kernel checks the bound; nothing is read for them)
+    wild = sel.copy()
+    wild[0, 0, 0, 1] = 40
+    wild[0, 0, 1, 0] = 2 ** 31 - 1
+    wild[1, 0, 0, 3] = -7
+    dw = torch.from_numpy(wild.astype(np.int32)).cuda()
+    out_w, lse_w = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, dw, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    assert torch.equal(out_w.view(torch.int16), out.view(torch.int16)) and torch.equal(lse_w, lse)
     case.Kl = case.Vl = None
     out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, None, None, pos0, dpos)
     torch.cuda.synchronize()
