@@ -207,7 +207,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   // last step of the local context clamps its rows.
   const unsigned kofs = (unsigned)(n * D * 2 + 16 * rr);  // key row n, 16-byte piece rr of a 64-byte slice
   const unsigned vofs = (unsigned)(lane * 16);            // value rows are contiguous: piece `lane` of 1 KiB
-  auto issue_loads = [&](const StepSrc& ss, uint4 (&kr)[2][NS], uint4 (&vr)[NVL]) {
+  auto issue_loads = [&](const StepSrc& ss, uint4 (&kr)[2][NS], uint4 (&vr)[NVL], bool do_k, bool do_v) {
     const unsigned long long kaddr = (unsigned long long)ss.Kb, vaddr = (unsigned long long)ss.Vb;
     typedef const __attribute__((address_space(1))) char* gptr_t;  // global memory, not generic
     typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -223,29 +223,37 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     gptr_t kb = (gptr_t)uni64(kaddr);
     gptr_t vb = (gptr_t)uni64(vaddr);
     if (ss.rows_valid == 32) {
+      if (do_k) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
-          kr[h][s] = ld((gvec_t)(kb + kofs + (h * 16 * D * 2 + s * 64)));
-#pragma unroll
-      for (int i = 0; i < NVL; ++i) vr[i] = ld((gvec_t)(vb + vofs + i * 1024));
-    } else {
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        int row = 16 * h + n;
-        row = row < ss.rows_valid ? row : ss.rows_valid - 1;
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-          kr[h][s] = ld((gvec_t)(kb + (unsigned)(row * D * 2 + 16 * rr + s * 64)));
+          for (int s = 0; s < NS; ++s)
+            kr[h][s] = ld((gvec_t)(kb + kofs + (h * 16 * D * 2 + s * 64)));
       }
+      if (do_v) {
 #pragma unroll
-      for (int i = 0; i < NVL; ++i) {
-        const int f = i * 64 + lane;
-        int row = f / (D / 8);
-        const int piece = f % (D / 8);
-        row = row < ss.rows_valid ? row : ss.rows_valid - 1;
-        vr[i] = ld((gvec_t)(vb + (unsigned)(row * D * 2 + piece * 16)));
+        for (int i = 0; i < NVL; ++i) vr[i] = ld((gvec_t)(vb + vofs + i * 1024));
+      }
+    } else {
+      if (do_k) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          int row = 16 * h + n;
+          row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+#pragma unroll
+          for (int s = 0; s < NS; ++s)
+            kr[h][s] = ld((gvec_t)(kb + (unsigned)(row * D * 2 + 16 * rr + s * 64)));
+        }
+      }
+      if (do_v) {
+#pragma unroll
+        for (int i = 0; i < NVL; ++i) {
+          const int f = i * 64 + lane;
+          int row = f / (D / 8);
+          const int piece = f % (D / 8);
+          row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+          vr[i] = ld((gvec_t)(vb + (unsigned)(row * D * 2 + piece * 16)));
+        }
       }
     }
   };
@@ -254,7 +262,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   int st = next_valid(wb, cur_src);
   uint4 kraw[2][NS];
   uint4 vraw[NVL];
-  if (st < we) issue_loads(cur_src, kraw, vraw);
+  if (st < we) issue_loads(cur_src, kraw, vraw, true, true);
 
   while (st < we) {
     const int rows_valid = cur_src.rows_valid;
@@ -272,15 +280,10 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       dst[0] = make_uint2(vraw[i].x, vraw[i].y);
       dst[1] = make_uint2(vraw[i].z, vraw[i].w);
     }
-    uint4 kcur[2][NS];
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int s = 0; s < NS; ++s) kcur[h][s] = kraw[h][s];
     StepSrc nxt_src = cur_src;
     const int st_next = next_valid(st + 1, nxt_src);
     if (st_next >= we) nxt_src = cur_src;
-    issue_loads(nxt_src, kraw, vraw);
+    issue_loads(nxt_src, kraw, vraw, false, true);  // values now; keys once this step's keys are consumed
 
     // ---- rotation state for this step ----------------------------------------------------------
     if (cur_p != p_first) {
@@ -314,7 +317,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       uint32_t y1[NS / 2][4], y2[NS / 2][4];
 #pragma unroll
       for (int s2 = 0; s2 < NS / 2; ++s2) {
-        const uint4 a1 = kcur[h][s2], a2 = kcur[h][s2 + NS / 2];
+        const uint4 a1 = kraw[h][s2], a2 = kraw[h][s2 + NS / 2];
         const uint32_t w1[4] = {a1.x, a1.y, a1.z, a1.w};
         const uint32_t w2[4] = {a2.x, a2.y, a2.z, a2.w};
 #pragma unroll
@@ -345,6 +348,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
         for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = cmul(cs[8 * s2 + j], step16[32 * s2 + 8 * rr + j]);
     }
     cur_p += 32;
+    issue_loads(nxt_src, kraw, vraw, true, false);  // next step's keys (this step's are in the scores now)
 
     // ---- online softmax (exp2 domain) ---------------------------------------------------------
     float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
