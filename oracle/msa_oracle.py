@@ -24,6 +24,9 @@ Readings of the paper where it is silent (all listed again in the design documen
   * RoPE pairs element u with u + d/2, angle p * base**(-2u/d); values are never rotated;
   * memory keys are always visible; local key t is visible iff pos0 + t <= q_pos.
 
+The paper's own variant of Eq. 3 (pooled K-bar / V-bar of position-encoded keys, used as stored) is
+pool_rotated_keys / pool_values + sparse_attend(..., mem_rotated=True).
+
 Pins (tests/test_oracle_pins.py): brute-force dense attention when k = N, library softmax /
 scaled-dot-product attention on the G = 1 reduction, softmax and RoPE closed forms, the
 document-wise RoPE permutation invariant, log-sum-exp merge associativity, pooling and scoring
@@ -75,6 +78,38 @@ def routing_keys(K, P):
     KRb = bf16_round(pool_chunks(K, P))
     nrm = np.sqrt((KRb * KRb).sum(axis=-1))
     return KRb, 1.0 / np.maximum(nrm, EPS_NORM)
+
+
+def pool_rotated_keys(K, P, base):
+    """K-bar of Stage 1 (Section 3.4.1): the document is encoded with its own positions 0..G-1
+    (Section 3.2.2), then chunk-mean pooled (Section 3.2.1): mean over each chunk of RoPE(K[i,g,t], t).
+    K [N,Hkv,G,d] -> [N,Hkv,C,d] (exact float64; the stored bank is bf16_round of this)."""
+    K = np.asarray(K, dtype=np.float64)
+    N, Hkv, G, d = K.shape
+    assert G % P == 0
+    C = G // P
+    out = np.empty((N, Hkv, C, d), dtype=np.float64)
+    pos = np.arange(G)
+    for i in range(N):
+        for g in range(Hkv):
+            rot = rope(K[i, g], pos, base)
+            for j in range(C):
+                out[i, g, j, :] = rot[j * P:(j + 1) * P, :].sum(axis=0) / P
+    return out
+
+
+def pool_values(V, P):
+    """V-bar = phi(V): chunk-wise mean of the values (Section 3.2.1).  [N,Hkv,G,d] -> [N,Hkv,C,d]."""
+    V = np.asarray(V, dtype=np.float64)
+    N, Hkv, G, d = V.shape
+    assert G % P == 0
+    C = G // P
+    out = np.empty((N, Hkv, C, d), dtype=np.float64)
+    for i in range(N):
+        for g in range(Hkv):
+            for j in range(C):
+                out[i, g, j, :] = V[i, g, j * P:(j + 1) * P, :].sum(axis=0) / P
+    return out
 
 
 # --------------------------------------------------------------------------------------------
@@ -200,19 +235,24 @@ def merge_partials(parts):
     return out, top + np.log(w.sum())
 
 
-def assemble_context(K, V, doc_ids, g, Kloc_bg, Vloc_bg, pos0, q_pos, base):
+def assemble_context(K, V, doc_ids, g, Kloc_bg, Vloc_bg, pos0, q_pos, base, mem_rotated=False):
     """Eq. 3 with document-wise RoPE (Section 3.2.2).  K, V [N,Hkv,G,d]; doc_ids: the selected
     documents of this (query, scope), -1 entries skipped; Kloc_bg, Vloc_bg [Lloc,d] or None.
 
     Every selected document contributes all its G tokens, rotated with positions 0..G-1
-    (positions restart in every document).  Local token t sits at position pos0 + t and is
-    visible iff pos0 + t <= q_pos.  Returns (keys [n,d], vals [n,d])."""
+    (positions restart in every document).  With mem_rotated=True the bank's keys already carry
+    their positions (the pooled bank of Stage 1, see pool_rotated_keys) and are used as stored.
+    Local token t sits at position pos0 + t and is visible iff pos0 + t <= q_pos.
+    Returns (keys [n,d], vals [n,d])."""
     G, d = K.shape[2], K.shape[3]
     keys, vals = [], []
     for i in doc_ids:
         if i < 0:
             continue
-        keys.append(rope(K[i, g], np.arange(G), base))
+        if mem_rotated:
+            keys.append(np.asarray(K[i, g], dtype=np.float64))
+        else:
+            keys.append(rope(K[i, g], np.arange(G), base))
         vals.append(np.asarray(V[i, g], dtype=np.float64))
     if Kloc_bg is not None and Kloc_bg.shape[0] > 0:
         t = np.arange(Kloc_bg.shape[0])
@@ -225,7 +265,7 @@ def assemble_context(K, V, doc_ids, g, Kloc_bg, Vloc_bg, pos0, q_pos, base):
     return np.concatenate(keys, axis=0), np.concatenate(vals, axis=0)
 
 
-def sparse_attend(q, K, V, idx, Kloc, Vloc, pos0, q_pos, base):
+def sparse_attend(q, K, V, idx, Kloc, Vloc, pos0, q_pos, base, mem_rotated=False):
     """Eq. 3-4 for every query.  q [B,M,Hq,d]; K,V [N,Hkv,G,d]; idx [B,M',S,k] (M' in {1,M},
     S in {1,Hkv}); Kloc,Vloc [B,Hkv,Lloc,d] or None; q_pos [B,M] int.
 
@@ -244,7 +284,7 @@ def sparse_attend(q, K, V, idx, Kloc, Vloc, pos0, q_pos, base):
                 ids = idx[b, m if Mi > 1 else 0, g if S > 1 else 0]
                 kl = None if Kloc is None else Kloc[b, g]
                 vl = None if Vloc is None else Vloc[b, g]
-                keys, vals = assemble_context(K, V, ids, g, kl, vl, pos0, int(q_pos[b, m]), base)
+                keys, vals = assemble_context(K, V, ids, g, kl, vl, pos0, int(q_pos[b, m]), base, mem_rotated)
                 for h in range(g * r, (g + 1) * r):
                     qt = rope(q[b, m, h], np.float64(q_pos[b, m]), base)
                     out[b, m, h], lse[b, m, h] = softmax_attend(qt, keys, vals)

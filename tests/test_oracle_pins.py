@@ -413,6 +413,46 @@ def test_selected_documents_dominate_when_planted():
 
 
 # ------------------------------------------------------------------------------------------
+# pooled K-bar / V-bar (Eq. 3 as the paper writes it)
+# ------------------------------------------------------------------------------------------
+def test_pooled_bank_reduces_to_unpooled_path_when_P_is_1():
+    """With P = 1 the pooled, position-encoded bank is just RoPE(K) and V: attention over it with
+    mem_rotated=True must equal the default path (raw bank, rotation in the gather)."""
+    K, V, q, Kl, Vl = _tiny(seed=81)
+    N, Hkv, G, d = K.shape
+    B, M = q.shape[:2]
+    rng = np.random.default_rng(11)
+    idx = np.stack([rng.permutation(N)[:3] for _ in range(B * M * Hkv)]).reshape(B, M, Hkv, 3)
+    pos0, q_pos = G, np.full((B, M), G + 4)
+    want, lw = O.sparse_attend(q, K, V, idx, Kl, Vl, pos0, q_pos, 1e4)
+    Kbar, Vbar = O.pool_rotated_keys(K, 1, 1e4), O.pool_values(V, 1)
+    got, lg = O.sparse_attend(q, Kbar, Vbar, idx, Kl, Vl, pos0, q_pos, 1e4, mem_rotated=True)
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-13) and np.allclose(lg, lw, rtol=1e-13)
+
+
+def test_pooled_bank_closed_forms():
+    N, Hkv, G, d, P = 2, 1, 8, 4, 4
+    K = np.zeros((N, Hkv, G, d))
+    V = np.zeros((N, Hkv, G, d))
+    K[0, 0, 0] = [1.0, 0.0, 0.0, 0.0]            # position 0: identity rotation
+    K[1, 0, 5] = [1.0, 0.0, 0.0, 0.0]            # position 5: pair (0, 2) rotated by 5 rad (theta_0 = 1)
+    V[1, 0, 4:8] = [2.0, 4.0, 6.0, 8.0]
+    Kb, Vb = O.pool_rotated_keys(K, P, 100.0), O.pool_values(V, P)
+    assert Kb.shape == (N, Hkv, 2, d) and Vb.shape == (N, Hkv, 2, d)
+    assert np.allclose(Kb[0, 0, 0], [0.25, 0, 0, 0], atol=1e-16)
+    assert np.allclose(Kb[1, 0, 1], [np.cos(5.0) / 4, 0, np.sin(5.0) / 4, 0], rtol=1e-15)
+    assert np.array_equal(Vb[1, 0, 1], [2.0, 4.0, 6.0, 8.0]) and np.count_nonzero(Vb) == 4
+    # pooling commutes with nothing position-dependent: constant K over a chunk is NOT kept constant
+    K2 = np.ones((1, 1, 8, 4))
+    assert not np.allclose(O.pool_rotated_keys(K2, 4, 100.0)[0, 0, 0], 1.0)
+    # context length of the pooled variant (paper, Section 5.1): M + k G / P keys
+    K3, V3, q3, Kl3, Vl3 = _tiny(seed=91, G=16, Lloc=5)
+    keys, vals = O.assemble_context(O.pool_rotated_keys(K3, 4, 1e4), O.pool_values(V3, 4), [0, 2, 5], 0,
+                                    Kl3[0, 0], Vl3[0, 0], 3, 3 + 4, 1e4, mem_rotated=True)
+    assert keys.shape[0] == 5 + 3 * 16 // 4
+
+
+# ------------------------------------------------------------------------------------------
 # the number the paper prints (Section 3.4.2)
 # ------------------------------------------------------------------------------------------
 def test_paper_memory_estimate():
