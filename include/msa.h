@@ -53,8 +53,10 @@ enum { MSA_MAX_TOPK = 64 };
 
 typedef struct msa_config {
   int32_t n_docs;       /* N >= 1                                                                  */
-  int32_t doc_len;      /* G, tokens per document; G % P == 0; msa_sparse_attend needs G % 32 == 0 */
-  int32_t chunk;        /* P, pooling size (paper: 64); P % 8 == 0; C = G/P must be 1, 2, 4, 8 or 16 */
+  int32_t doc_len;      /* G, tokens per document; G % P == 0; msa_sparse_attend needs G % 32 == 0
+                           (or G in {8, 16} with bank_keys_rotated)                                */
+  int32_t chunk;        /* P, pooling size (paper: 64); must divide G.  Routing: P % 8 == 0 and C = G/P in
+                           {1, 2, 4, 8, 16}; msa_pool_kv: P % 8 == 0; msa_sparse_attend does not read it */
   int32_t n_q_heads;    /* Hq, multiple of Hkv; r = Hq/Hkv <= 8                                    */
   int32_t n_kv_heads;   /* Hkv                                                                     */
   int32_t head_dim;     /* d, 64 or 128                                                            */
@@ -64,6 +66,10 @@ typedef struct msa_config {
                            per KV head (S = Hkv).  MSA_SCOPE_ALL (literal Eq. 2, S = 1): UNSUPPORTED */
   int32_t token_pool;   /* 0: one selection per query token.  1 (literal Eq. 2 max over tokens):
                            UNSUPPORTED in this version                                             */
+  int32_t bank_keys_rotated; /* msa_sparse_attend only.  0: the bank holds raw keys, rotated in the gather with
+                           positions 0..G-1 (default).  1: the bank's keys already carry their positions
+                           (the pooled bank written by msa_pool_kv) and are used as stored; then doc_len
+                           may also be 8 or 16                                                      */
 } msa_config_t;
 
 /* Library version (major * 100 + minor). */
@@ -115,6 +121,20 @@ int msa_build_routing_keys(const msa_config_t* cfg, const void* K, int32_t doc_b
                            int32_t doc_count, void* KR, float* inv_norm, msa_stream_t stream);
 
 /*
+ * The paper's own memory bank (Section 3.4.1, Stage 1; Section 3.2.1, Eq. 3): every document is encoded
+ * with its own positions 0..G-1 (Section 3.2.2) and then chunk-mean pooled,
+ *     Kbar[i][g][j][:] = bf16_rne( (1/P) * sum_{t in chunk j} RoPE(K[i][g][t][:], t) )
+ *     Vbar[i][g][j][:] = bf16_rne( (1/P) * sum_{t in chunk j} V[i][g][t][:] )
+ * for documents i in [doc_begin, doc_begin + doc_count).  The result is a bank of N documents of C = G/P
+ * entries that msa_sparse_attend reads with a config whose doc_len = C and bank_keys_rotated = 1
+ * (context length M + k G/P, Section 5.1).
+ *   K, V        in   bf16 [N][Hkv][G][d]
+ *   Kbar, Vbar  out  bf16 [N][Hkv][C][d]   (either may be NULL to skip it)
+ */
+int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t doc_begin,
+                int32_t doc_count, void* Kbar, void* Vbar, msa_stream_t stream);
+
+/*
  * Routing (Section 3.2.1, Eq. 2 and the text after it), fused so chunk scores never reach memory:
  *     Sc(b,m,g,c) = (1/r) * sum_{h in group g} sim(q_route[b][m][h][:], KR(g,c,:))
  *     s(b,m,g,i)  = max_{j < C} Sc(b,m,g,i*C + j)
@@ -142,7 +162,8 @@ int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int3
  * with the matching un-rotated value rows, and
  *     out[b][m][h][:] = softmax_j( RoPE(q[b][m][h][:], q_pos[b][m]) . key_j / sqrt(d) ) . value_j
  *     lse[b][m][h]    = log sum_j exp( ... )          (natural log; -inf and out = 0 if no key is visible)
- * RoPE pairs element u with u + d/2, angle p * base^(-2u/d).  Positions restart at 0 in every document;
+ * RoPE pairs element u with u + d/2, angle p * base^(-2u/d).  Positions restart at 0 in every document
+ * (with cfg->bank_keys_rotated the bank keys are taken as stored, un-rotated here);
  * idx == -1 (or any id outside [0, N)) marks "no document"; a document listed twice is attended twice.
  *   q         in   bf16 [B][M][Hq][d]
  *   K, V      in   bf16 [N][Hkv][G][d]

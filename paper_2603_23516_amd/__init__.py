@@ -19,7 +19,7 @@ MSA_OK, MSA_ERR_INVALID_ARG, MSA_ERR_UNSUPPORTED, MSA_ERR_WORKSPACE, MSA_ERR_MIS
 
 EXPORTS = ("msa_version", "msa_status_string", "msa_routing_keys_bytes", "msa_inv_norm_bytes",
            "msa_pooled_bank_bytes", "msa_score_topk_workspace_bytes",
-           "msa_sparse_attend_workspace_bytes", "msa_build_routing_keys", "msa_score_topk",
+           "msa_sparse_attend_workspace_bytes", "msa_build_routing_keys", "msa_pool_kv", "msa_score_topk",
            "msa_sparse_attend")
 
 
@@ -28,12 +28,13 @@ class MsaConfig(ctypes.Structure):
     _fields_ = [("n_docs", ctypes.c_int32), ("doc_len", ctypes.c_int32), ("chunk", ctypes.c_int32),
                 ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("rope_base", ctypes.c_float), ("sim", ctypes.c_int32),
-                ("select_scope", ctypes.c_int32), ("token_pool", ctypes.c_int32)]
+                ("select_scope", ctypes.c_int32), ("token_pool", ctypes.c_int32),
+                ("bank_keys_rotated", ctypes.c_int32)]
 
     def __init__(self, n_docs, doc_len, chunk, n_q_heads, n_kv_heads, head_dim, rope_base=1e6,
-                 sim=MSA_SIM_COS, select_scope=MSA_SCOPE_GROUP, token_pool=0):
+                 sim=MSA_SIM_COS, select_scope=MSA_SCOPE_GROUP, token_pool=0, bank_keys_rotated=0):
         super().__init__(n_docs, doc_len, chunk, n_q_heads, n_kv_heads, head_dim, rope_base, sim,
-                         select_scope, token_pool)
+                         select_scope, token_pool, bank_keys_rotated)
 
     @property
     def chunks_per_doc(self):
@@ -79,6 +80,8 @@ def load_library():
     lib.msa_sparse_attend_workspace_bytes.argtypes = [cfgp, i32, i32, i32, i32]
     lib.msa_build_routing_keys.restype = ctypes.c_int
     lib.msa_build_routing_keys.argtypes = [cfgp, vp, i32, i32, vp, vp, vp]
+    lib.msa_pool_kv.restype = ctypes.c_int
+    lib.msa_pool_kv.argtypes = [cfgp, vp, vp, i32, i32, vp, vp, vp]
     lib.msa_score_topk.restype = ctypes.c_int
     lib.msa_score_topk.argtypes = [cfgp, vp, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.msa_sparse_attend.restype = ctypes.c_int
@@ -161,6 +164,24 @@ def msa_build_routing_keys(cfg, K, doc_begin=0, doc_count=None, KR=None, inv_nor
                                                _ptr(inv_norm), _stream(stream, K.device))
     _check(rc, "msa_build_routing_keys")
     return KR, inv_norm
+
+
+def msa_pool_kv(cfg, K, V, doc_begin=0, doc_count=None, Kbar=None, Vbar=None, stream=None):
+    """K, V bf16 [N][Hkv][G][d] -> pooled bank (Kbar, Vbar) bf16 [N][Hkv][C][d]; Kbar is the chunk mean of the
+    position-encoded keys.  Read it with a config whose doc_len = C and bank_keys_rotated = 1."""
+    _need(K, torch.bfloat16, "K")
+    _need(V, torch.bfloat16, "V")
+    if doc_count is None:
+        doc_count = cfg.n_docs - doc_begin
+    shape = (cfg.n_docs, cfg.n_kv_heads, cfg.chunks_per_doc, cfg.head_dim)
+    if Kbar is None:
+        Kbar = torch.empty(shape, dtype=torch.bfloat16, device=K.device)
+    if Vbar is None:
+        Vbar = torch.empty(shape, dtype=torch.bfloat16, device=K.device)
+    rc = load_library().msa_pool_kv(ctypes.byref(cfg), _ptr(K), _ptr(V), doc_begin, doc_count, _ptr(Kbar),
+                                    _ptr(Vbar), _stream(stream, K.device))
+    _check(rc, "msa_pool_kv")
+    return Kbar, Vbar
 
 
 def msa_score_topk(cfg, q_route, KR, inv_norm, k, out_idx=None, out_score=None, workspace=None,

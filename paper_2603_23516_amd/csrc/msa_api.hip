@@ -5,8 +5,11 @@ namespace msa {
 
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
-// Returns MSA_OK and fills dm, or the status that describes what is wrong with cfg.
-static int make_dims(const msa_config_t* cfg, Dims* dm) {
+// Returns MSA_OK and fills dm, or the status that describes what is wrong with cfg.  The limits on
+// the chunking belong to those who read it: routing needs whole 16-byte pieces per chunk and a
+// power-of-two C <= 16 (a tile holds whole documents), pooling only the former, attention neither.
+enum DimsFor { kForRouting, kForPooling, kForAttend };
+static int make_dims(const msa_config_t* cfg, Dims* dm, DimsFor use = kForRouting) {
   if (cfg == nullptr) return MSA_ERR_INVALID_ARG;
   if (cfg->n_docs < 1 || cfg->doc_len < 1 || cfg->chunk < 1 || cfg->n_q_heads < 1 ||
       cfg->n_kv_heads < 1 || cfg->head_dim < 1)
@@ -17,11 +20,12 @@ static int make_dims(const msa_config_t* cfg, Dims* dm) {
   if (cfg->select_scope != MSA_SCOPE_GROUP && cfg->select_scope != MSA_SCOPE_ALL)
     return MSA_ERR_INVALID_ARG;
   if (cfg->token_pool != 0 && cfg->token_pool != 1) return MSA_ERR_INVALID_ARG;
+  if (cfg->bank_keys_rotated != 0 && cfg->bank_keys_rotated != 1) return MSA_ERR_INVALID_ARG;
   if (!(cfg->rope_base > 1.0f)) return MSA_ERR_INVALID_ARG;
   if (cfg->head_dim != 64 && cfg->head_dim != 128) return MSA_ERR_UNSUPPORTED;
-  if (cfg->chunk % 8 != 0) return MSA_ERR_UNSUPPORTED;
   const int C = cfg->doc_len / cfg->chunk;
-  if (!pow2(C) || C > 16) return MSA_ERR_UNSUPPORTED;
+  if (use != kForAttend && cfg->chunk % 8 != 0) return MSA_ERR_UNSUPPORTED;
+  if (use == kForRouting && (!pow2(C) || C > 16)) return MSA_ERR_UNSUPPORTED;
   if (cfg->n_q_heads / cfg->n_kv_heads > 8) return MSA_ERR_UNSUPPORTED;
   if (cfg->select_scope != MSA_SCOPE_GROUP || cfg->token_pool != 0) return MSA_ERR_UNSUPPORTED;
   dm->N = cfg->n_docs;
@@ -39,6 +43,13 @@ static int make_dims(const msa_config_t* cfg, Dims* dm) {
   return MSA_OK;
 }
 
+// Document lengths the attention kernels read: whole 32-key steps, or (bank keys stored rotated) a
+// short power of two so that a step spans whole documents.
+static bool attend_doc_len_ok(const msa_config_t* cfg) {
+  if (cfg->doc_len % 32 == 0) return true;
+  return cfg->bank_keys_rotated == 1 && pow2(cfg->doc_len) && cfg->doc_len <= 16;
+}
+
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 }  // namespace msa
@@ -47,7 +58,7 @@ using namespace msa;
 
 extern "C" {
 
-int msa_version(void) { return 100; }
+int msa_version(void) { return 101; }
 
 const char* msa_status_string(int status) {
   switch (status) {
@@ -90,9 +101,9 @@ size_t msa_score_topk_workspace_bytes(const msa_config_t* cfg, int32_t B, int32_
 size_t msa_sparse_attend_workspace_bytes(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k,
                                          int32_t Lloc) {
   Dims dm;
-  if (make_dims(cfg, &dm) != MSA_OK) return 0;
+  if (make_dims(cfg, &dm, kForAttend) != MSA_OK) return 0;
   if (B < 1 || M < 1 || k < 1 || k > MSA_MAX_TOPK || Lloc < 0) return 0;
-  if ((int64_t)B * M > 65535 || dm.G % 32 != 0) return 0;
+  if ((int64_t)B * M > 65535 || !attend_doc_len_ok(cfg)) return 0;
   return plan_attend(dm, B * M, k, Lloc).ws_bytes;
 }
 
@@ -107,6 +118,18 @@ int msa_build_routing_keys(const msa_config_t* cfg, const void* K, int32_t doc_b
     return MSA_ERR_INVALID_ARG;
   if (misaligned(K) || misaligned(KR) || misaligned(inv_norm)) return MSA_ERR_MISALIGNED;
   return launch_build(dm, K, doc_begin, doc_count, KR, inv_norm, (hipStream_t)stream);
+}
+
+int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t doc_begin,
+                int32_t doc_count, void* Kbar, void* Vbar, msa_stream_t stream) {
+  Dims dm;
+  const int rc = make_dims(cfg, &dm, kForPooling);
+  if (rc != MSA_OK) return rc;
+  if ((Kbar != nullptr && K == nullptr) || (Vbar != nullptr && V == nullptr)) return MSA_ERR_INVALID_ARG;
+  if (doc_begin < 0 || doc_count < 0 || (int64_t)doc_begin + doc_count > dm.N)
+    return MSA_ERR_INVALID_ARG;
+  if (misaligned(K) || misaligned(V) || misaligned(Kbar) || misaligned(Vbar)) return MSA_ERR_MISALIGNED;
+  return launch_pool_kv(dm, K, V, doc_begin, doc_count, Kbar, Vbar, (hipStream_t)stream);
 }
 
 int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
@@ -136,7 +159,7 @@ int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t
                       void* out, float* lse, void* workspace, size_t workspace_bytes,
                       msa_stream_t stream) {
   Dims dm;
-  const int rc = make_dims(cfg, &dm);
+  const int rc = make_dims(cfg, &dm, kForAttend);
   if (rc != MSA_OK) return rc;
   if (q == nullptr || K == nullptr || V == nullptr || idx == nullptr || q_pos == nullptr ||
       out == nullptr || workspace == nullptr)
@@ -144,7 +167,8 @@ int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t
   if (B < 1 || M < 1 || Lloc < 0 || local_pos0 < 0) return MSA_ERR_INVALID_ARG;
   if (Lloc > 0 && (Kloc == nullptr || Vloc == nullptr)) return MSA_ERR_INVALID_ARG;
   if (k < 1) return MSA_ERR_INVALID_ARG;
-  if (k > MSA_MAX_TOPK || (int64_t)B * M > 65535 || dm.G % 32 != 0) return MSA_ERR_UNSUPPORTED;
+  if (k > MSA_MAX_TOPK || (int64_t)B * M > 65535 || !attend_doc_len_ok(cfg))
+    return MSA_ERR_UNSUPPORTED;
   if ((int64_t)local_pos0 + Lloc > (1 << 24)) return MSA_ERR_UNSUPPORTED;
   if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(idx) || misaligned(Kloc) ||
       misaligned(Vloc) || misaligned(q_pos) || misaligned(out) || misaligned(lse) ||
@@ -153,7 +177,7 @@ int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t
   const AttendPlan pl = plan_attend(dm, B * M, k, Lloc);
   if (workspace_bytes < pl.ws_bytes) return MSA_ERR_WORKSPACE;
   return launch_attend(dm, pl, q, B, M, K, V, idx, k, Kloc, Vloc, Lloc, local_pos0, q_pos, out,
-                       lse, workspace, (hipStream_t)stream);
+                       lse, workspace, cfg->bank_keys_rotated, (hipStream_t)stream);
 }
 
 }  // extern "C"

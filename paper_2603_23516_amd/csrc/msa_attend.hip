@@ -21,6 +21,14 @@
 //   O^T[dd][slot] += V^T[dd][key] P^T[key][slot]       (8 MFMAs per 32 keys at d = 128)
 // whose A operand (V transposed) is read from an LDS copy of the 32 value rows with 16-bit reads.
 // Every accumulator of a lane belongs to its own head slot, so the rescale needs no cross-lane data.
+//
+// MODE selects how the memory bank is read (the local context is always rotated here):
+//   0  raw keys, rotated in the gather with positions 0..G-1 (G % 32 == 0);
+//   1  keys that already carry their positions (the pooled bank of Section 3.4.1, Stage 1), used as
+//      stored, G % 32 == 0;
+//   2  the same with short documents, G in {1, 2, 4, 8, 16}: a 32-key step spans 32/G selected
+//      documents, so every lane looks up the document of each row it loads and a 32-bit mask
+//      records which rows belong to a valid selection.
 #include "msa_device.h"
 #include "msa_host.h"
 
@@ -46,26 +54,12 @@ struct AttendArgs {
   float* part_o;         // [BM][Hq][n_splits][D]   unnormalised partial outputs
   float2* part_ml;       // [BM][Hq][n_splits]      (running max in log2 units, sum)
   int M, Hq, Hkv, r, G, k, Lloc, pos0, N;
+  int gshift;            // log2(G) when G < 32 (MODE 2)
   int steps_mem, steps_total, steps_per_split, n_splits;
   float qscale;          // log2(e) / sqrt(d)
 };
 
-// (cos, sin)(p * theta): product and range reduction in double, sincos of the reduced angle in fp32.
-__device__ __forceinline__ float2 cis_pos(int p, double theta) {
-  const double x = (double)p * theta;
-  const double kk = rint(x * 0.15915494309189535);
-  double red = fma(-kk, 6.283185307179586, x);
-  red = fma(-kk, 2.4492935982947064e-16, red);
-  float s, c;
-  sincosf((float)red, &s, &c);
-  return make_float2(c, s);
-}
-
-__device__ __forceinline__ float2 cmul(float2 a, float2 b) {
-  return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
-}
-
-template <int D>
+template <int D, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   constexpr int NS = D / 32;        // MFMA k-slices per key row
@@ -174,8 +168,36 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     const uint16_t* Kb;
     const uint16_t* Vb;
     int rows_valid, p_first;
+    int st;         // step number
+    unsigned mask;  // MODE 2, memory steps: bit i set = key row i belongs to a valid selection
+    bool is_mem;    // a step over selected documents (else local context)
+  };
+  // MODE 2: bank element offset of key row `row` (0..31) of memory step st, and whether its document
+  // is a valid selection.  Rows of pads, of ids outside the bank and past the k-th document point at
+  // document 0 (always present) so that their loads stay inside the bank; their scores are masked.
+  auto gather_row = [&](int st, int row, long long& off) -> bool {
+    const int tok = st * 32 + row;
+    const int slot = tok >> a.gshift;
+    const int pin = tok & (a.G - 1);
+    const int doc = __shfl(my_idx, slot < a.k ? slot : 0, 64);
+    const bool ok = slot < a.k && doc >= 0 && doc < a.N;
+    off = (((long long)(ok ? doc : 0) * a.Hkv + g) * a.G + pin) * D;
+    return ok;
   };
   auto locate = [&](int st, StepSrc& ss) -> bool {
+    ss.st = st;
+    ss.mask = 0xffffffffu;
+    ss.is_mem = st < a.steps_mem;
+    if (MODE == 2 && st < a.steps_mem) {
+      long long off;
+      const bool ok = gather_row(st, lane & 31, off);
+      ss.mask = (unsigned)__ballot(ok);  // lanes 0..31 cover the 32 rows
+      ss.Kb = a.K;
+      ss.Vb = a.V;
+      ss.rows_valid = 32;
+      ss.p_first = 0;
+      return ss.mask != 0u;
+    }
     if (st < a.steps_mem) {
       const int tok = st * 32;
       const int slot = tok / a.G;
@@ -222,7 +244,26 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     };
     gptr_t kb = (gptr_t)uni64(kaddr);
     gptr_t vb = (gptr_t)uni64(vaddr);
-    if (ss.rows_valid == 32) {
+    if (MODE == 2 && ss.is_mem) {
+      if (do_k) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          long long off;
+          gather_row(ss.st, 16 * h + n, off);
+#pragma unroll
+          for (int s = 0; s < NS; ++s) kr[h][s] = ld((gvec_t)(kb + (off * 2 + 16 * rr + s * 64)));
+        }
+      }
+      if (do_v) {
+#pragma unroll
+        for (int i = 0; i < NVL; ++i) {
+          const int f = i * 64 + lane;
+          long long off;
+          gather_row(ss.st, f / (D / 8), off);
+          vr[i] = ld((gvec_t)(vb + (off * 2 + (f % (D / 8)) * 16)));
+        }
+      }
+    } else if (ss.rows_valid == 32) {
       if (do_k) {
 #pragma unroll
         for (int h = 0; h < 2; ++h)
@@ -277,8 +318,10 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       const int row = f / (D / 8);
       const int piece = f % (D / 8);
       uint2* dst = reinterpret_cast<uint2*>(&stage[wave][row * VS2 + piece * 8]);
-      dst[0] = make_uint2(vraw[i].x, vraw[i].y);
-      dst[1] = make_uint2(vraw[i].z, vraw[i].w);
+      uint4 vv = vraw[i];
+      if (MODE == 2 && !((cur_src.mask >> row) & 1u)) vv = make_uint4(0, 0, 0, 0);  // not a selected row
+      dst[0] = make_uint2(vv.x, vv.y);
+      dst[1] = make_uint2(vv.z, vv.w);
     }
     StepSrc nxt_src = cur_src;
     const int st_next = next_valid(st + 1, nxt_src);
@@ -286,7 +329,8 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     issue_loads(nxt_src, kraw, vraw, false, true);  // values now; keys once this step's keys are consumed
 
     // ---- rotation state for this step ----------------------------------------------------------
-    if (cur_p != p_first) {
+    const bool rot = (MODE == 0) || !cur_src.is_mem;  // wave-uniform: stored-as-rotated bank keys skip it
+    if (rot && cur_p != p_first) {
       if (p_first == 0) {
 #pragma unroll
         for (int s2 = 0; s2 < NS / 2; ++s2)
@@ -320,13 +364,21 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
         const uint4 a1 = kraw[h][s2], a2 = kraw[h][s2 + NS / 2];
         const uint32_t w1[4] = {a1.x, a1.y, a1.z, a1.w};
         const uint32_t w2[4] = {a2.x, a2.y, a2.z, a2.w};
+        if (rot) {
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const float2 c0 = cs[8 * s2 + 2 * jj], c1 = cs[8 * s2 + 2 * jj + 1];
-          const float p0 = bf16_lo(w1[jj]), p1 = bf16_hi(w1[jj]);
-          const float q0 = bf16_lo(w2[jj]), q1 = bf16_hi(w2[jj]);
-          y1[s2][jj] = pack_bf16(p0 * c0.x - q0 * c0.y, p1 * c1.x - q1 * c1.y);
-          y2[s2][jj] = pack_bf16(q0 * c0.x + p0 * c0.y, q1 * c1.x + p1 * c1.y);
+          for (int jj = 0; jj < 4; ++jj) {
+            const float2 c0 = cs[8 * s2 + 2 * jj], c1 = cs[8 * s2 + 2 * jj + 1];
+            const float p0 = bf16_lo(w1[jj]), p1 = bf16_hi(w1[jj]);
+            const float q0 = bf16_lo(w2[jj]), q1 = bf16_hi(w2[jj]);
+            y1[s2][jj] = pack_bf16(p0 * c0.x - q0 * c0.y, p1 * c1.x - q1 * c1.y);
+            y2[s2][jj] = pack_bf16(q0 * c0.x + p0 * c0.y, q1 * c1.x + p1 * c1.y);
+          }
+        } else {
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            y1[s2][jj] = w1[jj];
+            y2[s2][jj] = w2[jj];
+          }
         }
       }
       f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -339,15 +391,20 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float v = acc[i] + dpp_f<kDppXor1>(acc[i]);  // hi + lo column
-        sc[h][i] = (16 * h + 4 * rr + i < rows_valid) ? v : -INFINITY;
+        const int row = 16 * h + 4 * rr + i;
+        bool live = row < rows_valid;
+        if (MODE == 2) live = live && ((cur_src.mask >> row) & 1u);
+        sc[h][i] = live ? v : -INFINITY;
       }
       // advance the rotation state by 16 positions
+      if (rot) {
 #pragma unroll
-      for (int s2 = 0; s2 < NS / 2; ++s2)
+        for (int s2 = 0; s2 < NS / 2; ++s2)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = cmul(cs[8 * s2 + j], step16[32 * s2 + 8 * rr + j]);
+          for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = cmul(cs[8 * s2 + j], step16[32 * s2 + 8 * rr + j]);
+      }
     }
-    cur_p += 32;
+    if (rot) cur_p += 32;
     issue_loads(nxt_src, kraw, vraw, true, false);  // next step's keys (this step's are in the scores now)
 
     // ---- online softmax (exp2 domain) ---------------------------------------------------------
@@ -522,7 +579,7 @@ __global__ __launch_bounds__(D) void attend_merge_kernel(const float* __restrict
 
 AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc) {
   AttendPlan p;
-  p.steps_mem = (int)(((long long)k * dm.G) / 32);
+  p.steps_mem = (int)(((long long)k * dm.G + 31) / 32);
   p.steps_total = p.steps_mem + (Lloc + 31) / 32;
   const long long pairs = (long long)BM * dm.Hkv;
   // aim at <= 512 blocks: two 256-thread blocks are resident per CU (register-limited), so 512 is
@@ -545,7 +602,7 @@ AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc) {
 int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, int M, const void* K,
                   const void* V, const int32_t* idx, int k, const void* Kloc, const void* Vloc,
                   int Lloc, int pos0, const int32_t* q_pos, void* out, float* lse, void* ws,
-                  hipStream_t st) {
+                  int bank_keys_rotated, hipStream_t st) {
   AttendArgs a;
   a.q = (const uint16_t*)q;
   a.K = (const uint16_t*)K;
@@ -562,6 +619,8 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.r = dm.r;
   a.G = dm.G;
   a.N = dm.N;
+  a.gshift = 0;
+  while ((1 << a.gshift) < dm.G && a.gshift < 5) ++a.gshift;
   a.k = k;
   a.Lloc = Lloc;
   a.pos0 = pos0;
@@ -578,10 +637,21 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   }
   const int BM = B * M;
   dim3 grid(pl.n_splits, dm.Hkv, BM), block(256);
-  if (dm.d == 128)
-    hipLaunchKernelGGL(attend_partial_kernel<128>, grid, block, 0, st, a, th);
-  else
-    hipLaunchKernelGGL(attend_partial_kernel<64>, grid, block, 0, st, a, th);
+  const int mode = !bank_keys_rotated ? 0 : (dm.G % 32 == 0 ? 1 : 2);
+  if (mode != 2 && dm.G % 32 != 0) return MSA_ERR_UNSUPPORTED;
+  if (mode == 2 && ((1 << a.gshift) != dm.G || dm.G > 16)) return MSA_ERR_UNSUPPORTED;
+#define MSA_LAUNCH_ATTEND(DD, MM) \
+  hipLaunchKernelGGL((attend_partial_kernel<DD, MM>), grid, block, 0, st, a, th)
+  if (dm.d == 128) {
+    if (mode == 0) MSA_LAUNCH_ATTEND(128, 0);
+    else if (mode == 1) MSA_LAUNCH_ATTEND(128, 1);
+    else MSA_LAUNCH_ATTEND(128, 2);
+  } else {
+    if (mode == 0) MSA_LAUNCH_ATTEND(64, 0);
+    else if (mode == 1) MSA_LAUNCH_ATTEND(64, 1);
+    else MSA_LAUNCH_ATTEND(64, 2);
+  }
+#undef MSA_LAUNCH_ATTEND
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   if (dm.d == 128)
     hipLaunchKernelGGL(attend_merge_kernel<128>, dim3(BM * dm.Hq), dim3(128), 0, st,

@@ -56,6 +56,22 @@ __device__ __forceinline__ float group_max(float x) {
   return x;
 }
 
+// ---- rotary position encoding ---------------------------------------------------------------
+// (cos, sin)(p * theta): product and range reduction in double, sincos of the reduced angle in fp32.
+__device__ __forceinline__ float2 cis_pos(int p, double theta) {
+  const double x = (double)p * theta;
+  const double kk = rint(x * 0.15915494309189535);
+  double red = fma(-kk, 6.283185307179586, x);
+  red = fma(-kk, 2.4492935982947064e-16, red);
+  float s, c;
+  sincosf((float)red, &s, &c);
+  return make_float2(c, s);
+}
+
+__device__ __forceinline__ float2 cmul(float2 a, float2 b) {
+  return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+
 // ---- ordered 64-bit selection keys ---------------------------------------------------------------
 // Larger key = better candidate: score descending, then document index ascending.
 __device__ __forceinline__ uint32_t orderable(float s) {

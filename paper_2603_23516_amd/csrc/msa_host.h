@@ -49,7 +49,7 @@ struct ScorePlan {
 ScorePlan plan_score(const Dims& dm, int BM, int k);
 
 struct AttendPlan {
-  int steps_mem;         // 32-key steps over the selected documents (k * G / 32)
+  int steps_mem;         // 32-key steps over the selected documents, ceil(k * G / 32)
   int steps_total;       // + ceil(Lloc / 32)
   int steps_per_split;
   int n_splits;
@@ -66,7 +66,9 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
 int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, int M, const void* K,
                   const void* V, const int32_t* idx, int k, const void* Kloc, const void* Vloc,
                   int Lloc, int pos0, const int32_t* q_pos, void* out, float* lse, void* ws,
-                  hipStream_t st);
+                  int bank_keys_rotated, hipStream_t st);
+int launch_pool_kv(const Dims& dm, const void* K, const void* V, int doc_begin, int doc_count,
+                   void* Kbar, void* Vbar, hipStream_t st);
 
 inline size_t round_up256(size_t x) { return (x + 255) & ~(size_t)255; }
 

@@ -33,7 +33,7 @@ def test_exports_match_header(lib):
     assert declared == set(msa.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.msa_version() == 100
+    assert lib.msa_version() == 101
     for st in (0, -1, -2, -3, -4, -5, -99):
         assert len(msa.status_string(st)) > 0
 
@@ -139,6 +139,24 @@ def test_argument_validation_before_launch(lib):
     a = list(args)
     a[0] = ctypes.byref(c3)
     assert lib.msa_sparse_attend(*a) == E.MSA_ERR_UNSUPPORTED
+    # pooled bank: short documents are read only when the bank's keys are stored rotated
+    for G, rot, want in ((8, 1, E.MSA_ERR_WORKSPACE), (8, 0, E.MSA_ERR_UNSUPPORTED), (1, 1, E.MSA_ERR_WORKSPACE),
+                         (24, 1, E.MSA_ERR_UNSUPPORTED), (64, 1, E.MSA_ERR_WORKSPACE), (8, 2, E.MSA_ERR_INVALID_ARG)):
+        cp = _cfg(doc_len=G, chunk=G, bank_keys_rotated=rot)
+        a = list(args)
+        a[0] = ctypes.byref(cp)
+        a[16] = 64                                          # valid requests get as far as the workspace check
+        assert lib.msa_sparse_attend(*a) == want, (G, rot)
+    assert msa.sparse_attend_workspace_bytes(_cfg(doc_len=8, chunk=8, bank_keys_rotated=1), 1, 1, 16, 100) > 0
+    assert msa.sparse_attend_workspace_bytes(_cfg(doc_len=8, chunk=8), 1, 1, 16, 100) == 0
+    # pool_kv
+    assert lib.msa_pool_kv(cb, None, p, 0, 1, p, p, None) == E.MSA_ERR_INVALID_ARG      # Kbar wanted, no K
+    assert lib.msa_pool_kv(cb, p, None, 0, 1, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_pool_kv(cb, p, p, 60, 5, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_pool_kv(cb, p, p, -1, 1, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_pool_kv(cb, p, odd, 0, 1, p, p, None) == E.MSA_ERR_MISALIGNED
+    assert lib.msa_pool_kv(cb, p, p, 0, 0, p, p, None) == E.MSA_OK                      # nothing to do, nothing launched
+    assert lib.msa_pool_kv(ctypes.byref(_cfg(head_dim=96)), p, p, 0, 1, p, p, None) == E.MSA_ERR_UNSUPPORTED
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -453,3 +453,121 @@ def test_score_long_streams_threshold_exchange():
     i2, v2 = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
     torch.cuda.synchronize()
     assert torch.equal(i2, idx) and torch.equal(v2, val)
+
+
+# ------------------------------------------------------------------------------------------------
+# the pooled, position-encoded bank of Section 3.4.1 (Stage 1) and Eq. 3 over it
+# ------------------------------------------------------------------------------------------------
+def check_pooled(got_t, want_exact, what, tie_tol):
+    """got (device bf16) against bf16_round(want_exact): equal, or one bf16 step apart where the exact
+    mean lies within the kernel's fp32 arithmetic error of the rounding midpoint."""
+    got = bf16_to_f64(got_t)
+    want = O.bf16_round(want_exact)
+    diff = got != want
+    if diff.any():
+        mid = (got[diff] + want[diff]) / 2
+        assert np.all(np.abs(got[diff] - want[diff]) <= np.abs(want[diff]) * 2.0 ** -7 + 1e-30), \
+            f"{what}: more than one bf16 ulp off"
+        assert np.all(np.abs(want_exact[diff] - mid) <= tie_tol), f"{what}: not a rounding tie"
+    assert diff.mean() < 2e-3, (what, diff.mean())
+    return int(diff.sum()), want
+
+
+POOLED_CASES = {
+    # name: (seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k)   bank entries per document = G / P
+    "c8_d128_paper_decode": (21000, 40, 2, 4, 512, 128, 64, 2, 1, 50, 1e6, 16),
+    "c16_d64_ragged_steps": (22000, 23, 2, 2, 256, 64, 16, 1, 3, 37, 1e4, 5),
+    "c1_single_entry": (23000, 30, 3, 1, 64, 64, 64, 2, 1, 0, 1e4, 7),
+    "c2_r8": (24000, 19, 1, 8, 128, 128, 64, 1, 2, 64, 1e6, 19),
+    "c4_d128": (25000, 50, 2, 4, 32, 128, 8, 3, 1, 20, 1e6, 9),
+    "c32_whole_steps": (26000, 12, 2, 4, 256, 128, 8, 1, 2, 33, 1e6, 3),
+    "c64_whole_steps_d64": (27000, 9, 1, 2, 512, 64, 8, 2, 1, 0, 1e4, 4),
+}
+
+
+@pytest.mark.parametrize("name", list(POOLED_CASES))
+def test_pooled_bank_parity(name):
+    seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k = POOLED_CASES[name]
+    say(f"pooled case {name}: N={N} Hkv={Hkv} r={r} G={G} d={d} P={P} B={B} M={M} Lloc={Lloc} k={k}")
+    case = Case(seed, N, Hkv, r, G, d, P, B, M, Lloc, base).to_device()
+    cfg = case.cfg()
+    Gp = G // P
+    say("   pool_kv")
+    Kbar, Vbar = msa.msa_pool_kv(cfg, case.dK, case.dV)
+    torch.cuda.synchronize()
+    assert Kbar.shape == (N, Hkv, Gp, d)
+    nk, Kbar_o = check_pooled(Kbar, O.pool_rotated_keys(case.K, P, base), "Kbar", 2e-5)
+    nv, Vbar_o = check_pooled(Vbar, O.pool_values(case.V, P), "Vbar", 2e-5)
+    say(f"   pooled bank ok ({nk} + {nv} tie-adjacent roundings)")
+    # only a slice of the bank: the rest must stay untouched
+    Kpart = torch.full_like(Kbar, 7.0)
+    Vpart = torch.full_like(Vbar, 7.0)
+    lo, cnt = N // 3, N // 2
+    msa.msa_pool_kv(cfg, case.dK, case.dV, lo, cnt, Kpart, Vpart)
+    torch.cuda.synchronize()
+    assert torch.equal(Kpart[lo:lo + cnt].view(torch.int16), Kbar[lo:lo + cnt].view(torch.int16))
+    assert torch.equal(Vpart[lo:lo + cnt].view(torch.int16), Vbar[lo:lo + cnt].view(torch.int16))
+    assert torch.all(Kpart[:lo] == 7.0) and torch.all(Kpart[lo + cnt:] == 7.0)
+    assert torch.all(Vpart[:lo] == 7.0) and torch.all(Vpart[lo + cnt:] == 7.0)
+
+    say("   sparse_attend over the oracle's pooled bank")
+    rng = np.random.default_rng(seed)
+    sel = np.stack([rng.permutation(N)[:k] for _ in range(B * M * Hkv)]).reshape(B, M, Hkv, k)
+    sel[0, 0, 0, k // 2] = -1                                       # a pad in the middle
+    pos0 = k                                                        # Section 3.2.2: local positions start at k
+    q_pos = np.array([[pos0 + (Lloc - 1 - (5 * m + b) % Lloc if Lloc else 0) for m in range(M)]
+                      for b in range(B)])
+    acfg = msa.MsaConfig(N, Gp, Gp, case.Hq, Hkv, d, base, bank_keys_rotated=1)
+    dKo, dVo = dev(S.f64_to_bf16_bits(Kbar_o)), dev(S.f64_to_bf16_bits(Vbar_o))
+    didx = torch.from_numpy(sel.astype(np.int32)).cuda()
+    dpos = torch.from_numpy(q_pos.astype(np.int32)).cuda()
+    out, lse = msa.msa_sparse_attend(acfg, case.dq, dKo, dVo, didx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    oo, ol = O.sparse_attend(case.q, Kbar_o, Vbar_o, sel, case.Kl, case.Vl, pos0, q_pos, base,
+                             mem_rotated=True)
+
+    def cmp(out, lse):
+        go = out.float().cpu().numpy().astype(np.float64)
+        gl = lse.cpu().numpy().astype(np.float64)
+        err = np.abs(go - oo)
+        rel = np.linalg.norm(err) / max(np.linalg.norm(oo), 1e-30)
+        say(f"   attend: max-abs {err.max():.3e}  rel-L2 {rel:.3e}")
+        assert err.max() <= 2e-2 and rel <= 5e-3, (err.max(), rel)
+        assert np.allclose(gl, ol, rtol=0, atol=5e-3), np.abs(gl - ol).max()
+
+    cmp(out, lse)
+    say("   chained: the GPU's own pooled bank")
+    out2, lse2 = msa.msa_sparse_attend(acfg, case.dq, Kbar, Vbar, didx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    cmp(out2, lse2)
+    say("   ids outside the bank are skipped like pads")
+    wild = sel.copy()
+    wild[0, 0, 0, k // 2] = N
+    if k > 2:
+        sel2 = sel.copy()
+        sel2[-1, -1, -1, 0] = -1
+        wild[-1, -1, -1, 0] = -5
+    else:
+        sel2 = sel
+    o_a, l_a = msa.msa_sparse_attend(acfg, case.dq, Kbar, Vbar, torch.from_numpy(sel2.astype(np.int32)).cuda(),
+                                     case.dKl, case.dVl, pos0, dpos)
+    o_b, l_b = msa.msa_sparse_attend(acfg, case.dq, Kbar, Vbar, torch.from_numpy(wild.astype(np.int32)).cuda(),
+                                     case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    assert torch.equal(o_a.view(torch.int16), o_b.view(torch.int16)) and torch.equal(l_a, l_b)
+
+
+def test_pooled_bank_all_pads_and_unrotated_short_docs_rejected():
+    say("pooled case: nothing selected, no local context -> zeros; short documents need the rotated flag")
+    case = Case(28000, 10, 2, 4, 512, 128, 64, 1, 1, 0, 1e6).to_device()
+    Kbar, Vbar = msa.msa_pool_kv(case.cfg(), case.dK, case.dV)
+    acfg = msa.MsaConfig(10, 8, 8, case.Hq, 2, 128, 1e6, bank_keys_rotated=1)
+    didx = torch.full((1, 1, 2, 4), -1, dtype=torch.int32, device="cuda")
+    dpos = torch.zeros((1, 1), dtype=torch.int32, device="cuda")
+    out, lse = msa.msa_sparse_attend(acfg, case.dq, Kbar, Vbar, didx, None, None, 4, dpos)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0) and torch.all(torch.isinf(lse))
+    raw = msa.MsaConfig(10, 8, 8, case.Hq, 2, 128, 1e6)
+    with pytest.raises(msa.MsaError) as e:
+        msa.msa_sparse_attend(raw, case.dq, Kbar, Vbar, didx, None, None, 4, dpos)
+    assert e.value.status == msa.MSA_ERR_UNSUPPORTED
