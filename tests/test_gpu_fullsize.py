@@ -151,5 +151,51 @@ def test_fullsize_sampled_parity(name, plant, a):
         say(f"   attend (b={b}, g={g}): max-abs {err.max():.3e} rel-L2 {rel:.3e}")
         assert err.max() <= 2e-2 and rel <= 5e-3
         assert np.allclose(gl[b, 0, g * wl.r:(g + 1) * wl.r], ol[0, 0], rtol=0, atol=5e-3)
+    # ---- the pooled, position-encoded bank (Section 3.4.1, Stage 1) and Eq. 3 over it -----------------
+    if M == 1:
+        say("   pool_kv + sparse_attend over the pooled bank")
+        Kbar, Vbar = msa.msa_pool_kv(cfg, wl.K, wl.V)
+        torch.cuda.synchronize()
+        bad = 0
+        for doc in sample[:10]:
+            for which, bank, pooled in (("K", Kbar, lambda x: O.pool_rotated_keys(x, wl.P, wl.base)),
+                                        ("V", Vbar, lambda x: O.pool_values(x, wl.P))):
+                exact = pooled(W.host_doc(wl, which, doc)[1][None])[0]
+                want = O.bf16_round(exact)
+                got = S.bf16_bits_to_f64(SD.torch_to_bits(bank[doc]))
+                diff = got != want
+                if diff.any():                   # one bf16 step, next to a rounding tie
+                    # (or, for a mean that cancels to ~0, within the fp32 error of the rotated terms)
+                    assert np.all(np.abs(got[diff] - want[diff]) <= np.maximum(np.abs(want[diff]) * 2.0 ** -7, 1e-6))
+                    assert np.all(np.abs(exact[diff] - (got[diff] + want[diff]) / 2) <= 2e-5)
+                    bad += int(diff.sum())
+        assert bad <= 40, bad
+        say(f"   pooled K/V of 10 sampled documents ok ({bad} tie-adjacent roundings)")
+        acfg = msa.MsaConfig(wl.N, wl.C, wl.C, wl.Hq, wl.Hkv, wl.d, wl.base, bank_keys_rotated=1)
+        pos0 = k                                                   # Section 3.2.2: local positions start at k
+        qpos_p = (wl.q_pos - wl.pos0 + pos0).contiguous()
+        out, lse = msa.msa_sparse_attend(acfg, wl.q, Kbar, Vbar, idx, wl.Kloc, wl.Vloc, pos0, qpos_p)
+        torch.cuda.synchronize()
+        go = out.float().cpu().numpy().astype(np.float64).reshape(B, 1, wl.Hq, wl.d)
+        gl = lse.cpu().numpy().astype(np.float64).reshape(B, 1, wl.Hq)
+        for b, g in pairs:
+            docs = gi[b, 0, g]
+            Kb_sel = np.stack([O.bf16_round(O.pool_rotated_keys(W.host_doc(wl, "K", int(i))[1][None, g:g + 1],
+                                                                 wl.P, wl.base))[0] for i in docs])
+            Vb_sel = np.stack([O.bf16_round(O.pool_values(W.host_doc(wl, "V", int(i))[1][None, g:g + 1],
+                                                           wl.P))[0] for i in docs])
+            start = (b * wl.Hkv + g) * per_bg
+            Kl = S.normal_bf16(wl.seeds["Kloc"], (1, 1, wl.Lloc, wl.d), start=start)[1]
+            Vl = S.normal_bf16(wl.seeds["Vloc"], (1, 1, wl.Lloc, wl.d), start=start)[1]
+            qh = q_flat[b:b + 1, :, g * wl.r:(g + 1) * wl.r]
+            oo, ol = O.sparse_attend(qh, Kb_sel, Vb_sel, np.arange(k)[None, None, None], Kl, Vl, pos0,
+                                     qpos_flat[b:b + 1] - wl.pos0 + pos0, wl.base, mem_rotated=True)
+            got = go[b, 0, g * wl.r:(g + 1) * wl.r]
+            err = np.abs(got - oo[0, 0])
+            rel = np.linalg.norm(err) / np.linalg.norm(oo)
+            say(f"   pooled attend (b={b}, g={g}): max-abs {err.max():.3e} rel-L2 {rel:.3e}")
+            assert err.max() <= 2e-2 and rel <= 5e-3
+            assert np.allclose(gl[b, 0, g * wl.r:(g + 1) * wl.r], ol[0, 0], rtol=0, atol=5e-3)
+        del Kbar, Vbar
     del wl, KR, inv
     torch.cuda.empty_cache()

@@ -466,7 +466,8 @@ def check_pooled(got_t, want_exact, what, tie_tol):
     diff = got != want
     if diff.any():
         mid = (got[diff] + want[diff]) / 2
-        assert np.all(np.abs(got[diff] - want[diff]) <= np.abs(want[diff]) * 2.0 ** -7 + 1e-30), \
+        # one bf16 step; a mean that cancels to ~0 may instead differ by the fp32 error of its rotated terms
+        assert np.all(np.abs(got[diff] - want[diff]) <= np.maximum(np.abs(want[diff]) * 2.0 ** -7, 1e-6)), \
             f"{what}: more than one bf16 ulp off"
         assert np.all(np.abs(want_exact[diff] - mid) <= tie_tol), f"{what}: not a rounding tie"
     assert diff.mean() < 2e-3, (what, diff.mean())
