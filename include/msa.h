@@ -63,9 +63,11 @@ typedef struct msa_config {
   float rope_base;      /* RoPE base (theta_u = base^(-2u/d)), e.g. 1e4 or 1e6                      */
   int32_t sim;          /* MSA_SIM_COS (paper, Eq. 2) or MSA_SIM_DOT                               */
   int32_t select_scope; /* MSA_SCOPE_GROUP: head mean over the r heads of a KV group, one selection
-                           per KV head (S = Hkv).  MSA_SCOPE_ALL (literal Eq. 2, S = 1): UNSUPPORTED */
-  int32_t token_pool;   /* 0: one selection per query token.  1 (literal Eq. 2 max over tokens):
-                           UNSUPPORTED in this version                                             */
+                           per KV head (S = Hkv).  MSA_SCOPE_ALL (literal Eq. 2): head mean over every
+                           head, one selection shared by all heads (S = 1); Hkv in {1, 2, 4, 8}        */
+  int32_t token_pool;   /* 0: one selection per query token (M' = M).  1 (literal Eq. 2): the document
+                           score is the max over the M query tokens of a batch row, one selection per
+                           batch row (M' = 1)                                                         */
   int32_t bank_keys_rotated; /* msa_sparse_attend only.  0: the bank holds raw keys, rotated in the gather with
                            positions 0..G-1 (default).  1: the bank's keys already carry their positions
                            (the pooled bank written by msa_pool_kv) and are used as stored; then doc_len
@@ -141,11 +143,15 @@ int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t d
  *     out_idx[b][m][g][0..k) = the k documents with the largest s, ordered by (s descending,
  *                               document index ascending); out_score = their s.
  * sim = cosine: x.y / (max(|x|,1e-12) * max(|y|,1e-12)), or the plain dot product.
+ * cfg->select_scope == MSA_SCOPE_ALL replaces the group mean by the mean over all Hq heads (each head against
+ * the routing keys of its own KV group), giving one selection for all heads: S = 1 instead of S = Hkv.
+ * cfg->token_pool == 1 takes, before the document max, the max of Sc over the M query tokens of batch row b,
+ * giving one selection per batch row: M' = 1 instead of M' = M.  Both together are Eq. 2 as printed.
  *   q_route   in   bf16 [B][M][Hq][d]
  *   KR, inv_norm   as written by msa_build_routing_keys (inv_norm may be NULL iff sim == DOT)
  *   k              1 <= k <= min(N, MSA_MAX_TOPK)
- *   out_idx   out  int32 [B][M][Hkv][k]
- *   out_score out  fp32  [B][M][Hkv][k], may be NULL
+ *   out_idx   out  int32 [B][M'][S][k]
+ *   out_score out  fp32  [B][M'][S][k], may be NULL
  *   workspace      >= msa_score_topk_workspace_bytes(cfg, B, M, k); contents undefined on entry/exit
  * Scores are accumulated in fp32; each query is carried as a bf16 (hi, lo) pair, so a score differs
  * from exact arithmetic by a few 1e-6 relative.
@@ -167,7 +173,8 @@ int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int3
  * idx == -1 (or any id outside [0, N)) marks "no document"; a document listed twice is attended twice.
  *   q         in   bf16 [B][M][Hq][d]
  *   K, V      in   bf16 [N][Hkv][G][d]
- *   idx       in   int32 [B][M][Hkv][k]
+ *   idx       in   int32 [B][M'][S][k], M' and S as msa_score_topk writes them for this cfg (row m' = 0 /
+ *                  slot 0 is shared by all query tokens / all KV groups when M' = 1 / S = 1)
  *   Kloc,Vloc in   bf16 [B][Hkv][Lloc][d]; may be NULL iff Lloc == 0
  *   q_pos     in   int32 [B][M]
  *   out       out  bf16 [B][M][Hq][d]

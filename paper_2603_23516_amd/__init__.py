@@ -186,14 +186,16 @@ def msa_pool_kv(cfg, K, V, doc_begin=0, doc_count=None, Kbar=None, Vbar=None, st
 
 def msa_score_topk(cfg, q_route, KR, inv_norm, k, out_idx=None, out_score=None, workspace=None,
                    stream=None):
-    """q_route bf16 [B][M][Hq][d] -> (idx int32 [B][M][Hkv][k], score fp32 [B][M][Hkv][k])."""
+    """q_route bf16 [B][M][Hq][d] -> (idx int32 [B][M'][S][k], score fp32 [B][M'][S][k]); S = Hkv, or 1 with
+    select_scope = ALL; M' = M, or 1 with token_pool = 1."""
     _need(q_route, torch.bfloat16, "q_route")
     B, M = q_route.shape[0], q_route.shape[1]
     dev = q_route.device
+    shape = (B, 1 if cfg.token_pool else M, 1 if cfg.select_scope == MSA_SCOPE_ALL else cfg.n_kv_heads, k)
     if out_idx is None:
-        out_idx = torch.empty((B, M, cfg.n_kv_heads, k), dtype=torch.int32, device=dev)
+        out_idx = torch.empty(shape, dtype=torch.int32, device=dev)
     if out_score is None:
-        out_score = torch.empty((B, M, cfg.n_kv_heads, k), dtype=torch.float32, device=dev)
+        out_score = torch.empty(shape, dtype=torch.float32, device=dev)
     if workspace is None:
         workspace = torch.empty(max(score_topk_workspace_bytes(cfg, B, M, k), 256), dtype=torch.uint8,
                                 device=dev)
@@ -206,7 +208,8 @@ def msa_score_topk(cfg, q_route, KR, inv_norm, k, out_idx=None, out_score=None, 
 
 def msa_sparse_attend(cfg, q, K, V, idx, Kloc, Vloc, local_pos0, q_pos, out=None, lse=None,
                       workspace=None, stream=None):
-    """q bf16 [B][M][Hq][d], bank K/V, idx int32 [B][M][Hkv][k], local cache -> (out bf16, lse fp32)."""
+    """q bf16 [B][M][Hq][d], bank K/V, idx int32 [B][M'][S][k] as msa_score_topk writes it for cfg, local cache
+    -> (out bf16, lse fp32)."""
     _need(q, torch.bfloat16, "q")
     _need(idx, torch.int32, "idx")
     _need(q_pos, torch.int32, "q_pos")

@@ -27,7 +27,9 @@ static int make_dims(const msa_config_t* cfg, Dims* dm, DimsFor use = kForRoutin
   if (use != kForAttend && cfg->chunk % 8 != 0) return MSA_ERR_UNSUPPORTED;
   if (use == kForRouting && (!pow2(C) || C > 16)) return MSA_ERR_UNSUPPORTED;
   if (cfg->n_q_heads / cfg->n_kv_heads > 8) return MSA_ERR_UNSUPPORTED;
-  if (cfg->select_scope != MSA_SCOPE_GROUP || cfg->token_pool != 0) return MSA_ERR_UNSUPPORTED;
+  if (use == kForRouting && cfg->select_scope == MSA_SCOPE_ALL && cfg->n_kv_heads != 1 &&
+      cfg->n_kv_heads != 2 && cfg->n_kv_heads != 4 && cfg->n_kv_heads != 8)
+    return MSA_ERR_UNSUPPORTED;
   dm->N = cfg->n_docs;
   dm->G = cfg->doc_len;
   dm->P = cfg->chunk;
@@ -37,6 +39,8 @@ static int make_dims(const msa_config_t* cfg, Dims* dm, DimsFor use = kForRoutin
   dm->r = cfg->n_q_heads / cfg->n_kv_heads;
   dm->d = cfg->head_dim;
   dm->cos = cfg->sim == MSA_SIM_COS;
+  dm->scope_all = cfg->select_scope == MSA_SCOPE_ALL;
+  dm->token_pool = cfg->token_pool;
   dm->base = cfg->rope_base;
   dm->NC = (int64_t)dm->N * C;
   dm->tiles = (dm->NC + 15) / 16;
@@ -149,7 +153,7 @@ int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int3
     return MSA_ERR_MISALIGNED;
   const ScorePlan pl = plan_score(dm, B * M, k);
   if (workspace_bytes < pl.ws_bytes) return MSA_ERR_WORKSPACE;
-  return launch_score(dm, pl, q_route, B * M, KR, inv_norm, k, out_idx, out_score, workspace,
+  return launch_score(dm, pl, q_route, B, M, KR, inv_norm, k, out_idx, out_score, workspace,
                       (hipStream_t)stream);
 }
 

@@ -47,7 +47,7 @@ struct AttendArgs {
   const uint16_t* q;     // [BM][Hq][D]
   const uint16_t* K;     // [N][Hkv][G][D]
   const uint16_t* V;
-  const int32_t* idx;    // [BM][Hkv][k]
+  const int32_t* idx;    // [BM or B][Hkv or 1][k] (see idx_rows_per_b, idx_sel)
   const uint16_t* Kloc;  // [B][Hkv][Lloc][D]
   const uint16_t* Vloc;
   const int32_t* q_pos;  // [BM]
@@ -55,6 +55,8 @@ struct AttendArgs {
   float2* part_ml;       // [BM][Hq][n_splits]      (running max in log2 units, sum)
   int M, Hq, Hkv, r, G, k, Lloc, pos0, N;
   int gshift;            // log2(G) when G < 32 (MODE 2)
+  int idx_sel;           // selections per idx row: Hkv (one per KV group) or 1 (shared by all heads)
+  int idx_rows_per_b;    // idx rows per batch row: M (one per query token) or 1 (shared by the M tokens)
   int steps_mem, steps_total, steps_per_split, n_splits;
   float qscale;          // log2(e) / sqrt(d)
 };
@@ -161,7 +163,9 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   constexpr int NVL = 32 * D * 2 / 1024;  // wave-wide 16-byte loads covering 32 value rows
 
   // selected documents of this (query, KV head): lane j holds idx[j] (k <= 64)
-  const int my_idx = (lane < a.k) ? a.idx[((long long)bm * a.Hkv + g) * a.k + lane] : -1;
+  const long long idx_row = (a.idx_rows_per_b == 1) ? b : bm;
+  const int my_idx =
+      (lane < a.k) ? a.idx[(idx_row * a.idx_sel + (a.idx_sel == 1 ? 0 : g)) * a.k + lane] : -1;
 
   // Where a step's 32 keys live (wave-uniform).  Returns false for a step with nothing to attend.
   struct StepSrc {
@@ -619,6 +623,8 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.r = dm.r;
   a.G = dm.G;
   a.N = dm.N;
+  a.idx_sel = dm.scope_all ? 1 : dm.Hkv;
+  a.idx_rows_per_b = dm.token_pool ? 1 : M;
   a.gshift = 0;
   while ((1 << a.gshift) < dm.G && a.gshift < 5) ++a.gshift;
   a.k = k;

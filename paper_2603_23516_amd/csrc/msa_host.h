@@ -12,6 +12,8 @@ namespace msa {
 struct Dims {
   int N, G, P, C, Hq, Hkv, r, d;
   int cos;        // 1 = cosine, 0 = dot
+  int scope_all;  // 1 = head mean over every head, one selection for all KV heads (literal Eq. 2)
+  int token_pool; // 1 = document score is the max over the M tokens of a batch row (literal Eq. 2)
   float base;
   int64_t NC;     // N * C routing keys per KV head
   int64_t tiles;  // ceil(NC / 16) tiles of 16 keys per KV head
@@ -42,6 +44,9 @@ struct ScorePlan {
   size_t off_gmax;       // byte offset of the exchange buffer inside the workspace
   size_t off_qop;        // byte offset of the prepared query operands
   int n_qtiles;          // 8-query operand tiles (padded to whole passes)
+  int all_heads;         // 1: score_scan_all_kernel (scope ALL with more than one KV head)
+  int n_sel;             // selections per query token: Hkv, or 1 for scope ALL
+  size_t off_tok;        // byte offset of the per-token winner keys (token pooling)
   int use_gemm;          // 1: many query tokens -> the GEMM path below
   GemmPlan gemm;
   size_t ws_bytes;
@@ -60,7 +65,7 @@ AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc);
 
 int launch_build(const Dims& dm, const void* K, int doc_begin, int doc_count, void* KR,
                  float* inv_norm, hipStream_t st);
-int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int BM, const void* KR,
+int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B, int M, const void* KR,
                  const float* inv_norm, int k, int32_t* out_idx, float* out_score, void* ws,
                  hipStream_t st);
 int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, int M, const void* K,

@@ -315,6 +315,212 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
   }
 }
 
+// Literal Eq. 2 head mean (select_scope = ALL): the chunk score is the mean over EVERY query head of
+// the similarity with the routing key of that head's KV group, i.e. the mean over the Hkv groups of
+// the per-group scores above, so one selection serves all heads.  A wave's stream interleaves the
+// heads: entry e = (tile e / HKV, head e % HKV) through the same ring of kPrefetch loads; the
+// A operands of all HKV heads stay in registers (8 queries per pass), the per-head partial scores are
+// scaled by that head's 1/|key| and summed, and after the last head the document max / threshold /
+// candidate-list logic runs exactly as in score_scan_kernel.  HKV in {2, 4, 8} (one group: the plain
+// kernel already computes this).
+template <int D, int HKV, bool COS>
+__global__ __launch_bounds__(64) void score_scan_all_kernel(ScoreArgs a) {
+  constexpr int NS = D / 32;
+  constexpr int NQ = 8;
+  constexpr int CAP = kListBytes / (8 * NQ);
+  constexpr int TILE_ELEMS = 16 * D;
+  constexpr int UT = HKV >= kPrefetch ? 1 : kPrefetch / HKV;  // tiles per unrolled group of entries
+  static_assert((UT * HKV) % kPrefetch == 0, "ring slots must be compile-time");
+
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kListBytes];
+  __shared__ int cnt_s[NQ];
+  __shared__ float thr_s[NQ];
+  unsigned long long* cand = reinterpret_cast<unsigned long long*>(smem);  // [NQ][CAP]
+
+  const int lane = threadIdx.x;
+  const int rr = lane >> 4;
+  const int n = lane & 15;
+  const int sp = blockIdx.x;
+  const long long S = a.n_splits;
+  const long long n_it = (a.tiles - sp + S - 1) / S;  // >= 1 because n_splits <= tiles
+  const long long i_last = n_it - 1;
+  const uint16_t* KRl = a.KR + lane * 8;
+  const float* inl = COS ? a.inv_norm + n : nullptr;
+  auto tile_of = [&](long long it) { return sp + (it < n_it ? it : i_last) * S; };
+
+  uint4 buf[kPrefetch][NS];
+  float binv[kPrefetch];
+#pragma unroll
+  for (int u = 0; u < kPrefetch; ++u) {
+    const int h = u % HKV;
+    const long long t = tile_of(u / HKV);
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      buf[u][s] = *reinterpret_cast<const uint4*>(KRl + ((long long)h * a.tiles + t) * TILE_ELEMS + s * 512);
+    binv[u] = COS ? inl[((long long)h * a.tiles + t) * 16] : 1.0f;
+  }
+
+  bf16x8_t A[HKV][NS];
+#pragma unroll
+  for (int h = 0; h < HKV; ++h)
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      A[h][s] = as_bf16x8(a.qop[(((long long)h * a.n_qtiles + a.q0 / 8) * NS + s) * 64 + lane]);
+
+  float thr[2];
+  int cnt[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    thr[e] = (a.q0 + 2 * rr + e < a.BM) ? -INFINITY : INFINITY;
+    cnt[e] = 0;
+  }
+  int limit = 2 * a.k < 32 ? 32 : 2 * a.k;
+  if (limit > CAP - 16) limit = CAP - 16;
+  const int dpt = 16 / a.C;
+  const int ndoc = n / a.C;
+  const bool lead_lane = (n & (a.C - 1)) == 0;
+  const uint32_t below = (1u << n) - 1u;
+  const float inv_heads = 1.0f / (float)HKV;
+
+  for (long long base = 0; base < n_it; base += UT) {
+#pragma unroll
+    for (int ut = 0; ut < UT; ++ut) {
+      const long long it = base + ut;
+      const long long t = sp + it * S;
+      float tot[2] = {0.f, 0.f};
+#pragma unroll
+      for (int h = 0; h < HKV; ++h) {
+        const int slot = (ut * HKV + h) % kPrefetch;
+        uint4 cur[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) cur[s] = buf[slot][s];
+        const float cinv = binv[slot];
+        {  // the entry kPrefetch ahead of this one takes over the slot (always issued)
+          const int en = ut * HKV + h + kPrefetch;
+          const int hn = en % HKV;
+          const long long tn = tile_of(base + en / HKV);
+#pragma unroll
+          for (int s = 0; s < NS; ++s)
+            buf[slot][s] =
+                *reinterpret_cast<const uint4*>(KRl + ((long long)hn * a.tiles + tn) * TILE_ELEMS + s * 512);
+          binv[slot] = COS ? inl[((long long)hn * a.tiles + tn) * 16] : 1.0f;
+        }
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NS; ++s) acc = mfma16(A[h][s], as_bf16x8(cur[s]), acc);
+        tot[0] += (acc[0] + acc[1]) * cinv;
+        tot[1] += (acc[2] + acc[3]) * cinv;
+      }
+      const long long doc = t * dpt + ndoc;
+      const bool lead = lead_lane && it < n_it && doc < a.N;
+      bool over = false;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const float sc = group_max_rt(tot[e] * inv_heads, a.C);
+        const bool pred = lead && sc >= thr[e];
+        const unsigned long long m = __ballot(pred);
+        const uint32_t half = (rr & 2) ? (uint32_t)(m >> 32) : (uint32_t)m;
+        const uint32_t row = (half >> ((rr & 1) * 16)) & 0xffffu;
+        if (pred) cand[(2 * rr + e) * CAP + cnt[e] + __popc(row & below)] = make_key(sc, (uint32_t)doc);
+        cnt[e] += __popc(row);
+        over = over || cnt[e] > limit;
+      }
+      if (__any(over)) {
+        if (n == 0) {
+          cnt_s[2 * rr] = cnt[0];
+          cnt_s[2 * rr + 1] = cnt[1];
+          thr_s[2 * rr] = thr[0];
+          thr_s[2 * rr + 1] = thr[1];
+        }
+        wave_sync();
+        for (int qi = 0; qi < NQ; ++qi) {
+          const int c = cnt_s[qi];
+          if (c > limit) {  // wave-uniform
+            unsigned long long* cl = cand + qi * CAP;
+            const int nc = prune_list<CAP>(cl, c, a.k, lane);
+            if (lane == 0) {
+              cnt_s[qi] = nc;
+              thr_s[qi] = key_score(cl[a.k - 1]);
+            }
+          }
+        }
+        wave_sync();
+        cnt[0] = cnt_s[2 * rr];
+        cnt[1] = cnt_s[2 * rr + 1];
+        thr[0] = thr_s[2 * rr];
+        thr[1] = thr_s[2 * rr + 1];
+        wave_sync();
+      }
+    }
+  }
+
+  if (n == 0) {
+    cnt_s[2 * rr] = cnt[0];
+    cnt_s[2 * rr + 1] = cnt[1];
+  }
+  wave_sync();
+  for (int qi = 0; qi < NQ; ++qi) {
+    const int qg = a.q0 + qi;
+    if (qg >= a.BM) break;  // wave-uniform
+    const int c = cnt_s[qi];
+    unsigned long long* cl = cand + qi * CAP;
+    const int nc = prune_list<CAP>(cl, c, a.k, lane);
+    unsigned long long* dst = a.ws + ((long long)qg * a.n_splits + sp) * a.k;
+    if (lane < a.k) dst[lane] = (lane < nc) ? cl[lane] : 0ull;
+  }
+}
+
+// Literal Eq. 2 token pooling (token_pool = 1): the document score of a question is the max over its
+// M query tokens.  The k best documents under that score are all contained in the union of the
+// per-token top-k lists: if document D is among them and token m* attains its maximum, every document
+// ahead of D in token m*'s ranking is also ahead of D in the pooled ranking, so fewer than k are, and
+// D is in m*'s list with exactly its pooled score.  Ranking the union by (best listed score desc,
+// index asc) therefore reproduces the pooled top-k exactly.  One block per (batch row, scope slot):
+// k rounds of a block-wide arg-max over the M*k listed keys, skipping documents already taken.
+__global__ __launch_bounds__(256) void pool_tokens_kernel(const unsigned long long* __restrict__ tok_keys,
+                                                          int32_t* __restrict__ out_idx,
+                                                          float* __restrict__ out_score, int M, int S,
+                                                          int k) {
+  __shared__ unsigned long long red[4];
+  __shared__ uint32_t taken[MSA_MAX_TOPK];
+  const int tid = threadIdx.x;
+  const int b = blockIdx.x / S;
+  const int sl = blockIdx.x % S;
+  const long long o_base = ((long long)b * S + sl) * k;
+  const int T = M * k;
+  unsigned long long prev = ~0ull;
+  for (int round = 0; round < k; ++round) {
+    unsigned long long best = 0ull;
+    for (int i = tid; i < T; i += 256) {
+      const int m = i / k, j = i - m * k;
+      const unsigned long long x = tok_keys[(((long long)b * M + m) * S + sl) * k + j];
+      if (x == 0ull || x >= prev || x <= best) continue;  // keys of one document differ in the score bits only
+      const uint32_t doc = key_doc(x);
+      bool dup = false;
+      for (int w = 0; w < round; ++w) dup = dup || taken[w] == doc;
+      if (!dup) best = x;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const unsigned long long y = __shfl_xor(best, off, 64);
+      best = y > best ? y : best;
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = best;
+    __syncthreads();
+    best = red[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) best = red[w] > best ? red[w] : best;
+    if (tid == 0) {
+      out_idx[o_base + round] = best ? (int32_t)key_doc(best) : -1;
+      if (out_score) out_score[o_base + round] = best ? key_score(best) : -INFINITY;
+      taken[round] = best ? key_doc(best) : 0xffffffffu;
+    }
+    __syncthreads();
+    prev = best ? best : 0ull;
+  }
+}
+
 // Combine the n_lists sorted lists (k entries each, zero-padded) of one (query, group).
 //   1. A lower bound theta on the k-th best key: the first j+1 entries of every list, with
 //      n_lists*(j+1) >= k, are that many distinct candidates, so their k-th largest is one.
@@ -323,10 +529,12 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
 constexpr int kMaxSub = 1152;
 constexpr int kMaxSurv = 2048;
 
+// out_key != null: the winners are written as 64-bit keys instead (input of pool_tokens_kernel).
 __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long long* __restrict__ ws,
                                                           int32_t* __restrict__ out_idx,
-                                                          float* __restrict__ out_score, int BM,
-                                                          int Hkv, int n_lists, int k) {
+                                                          float* __restrict__ out_score,
+                                                          unsigned long long* __restrict__ out_key,
+                                                          int BM, int Hkv, int n_lists, int k) {
   __shared__ unsigned long long sub[kMaxSub];
   __shared__ unsigned long long surv[kMaxSurv];
   __shared__ unsigned long long red[4];
@@ -340,7 +548,8 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
   const long long o_base = ((long long)qg * Hkv + g) * k;
 
   const int depth = (k + n_lists - 1) / n_lists;  // entries taken from the head of every list
-  const int P = n_lists * depth;                  // k <= P < k + n_lists
+  // k <= P < k + n_lists; any kMaxSub >= k heads of lists bound the k-th best key just as well
+  const int P = (n_lists * depth <= kMaxSub) ? n_lists * depth : kMaxSub;
   for (int i = tid; i < P; i += 256) sub[i] = src[(i / depth) * k + (i % depth)];
   if (tid == 0) {
     n_surv = 0;
@@ -378,13 +587,21 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
       int rank = 0;
       for (int j = 0; j < S; ++j) rank += (surv[j] > x) ? 1 : 0;
       if (rank < k) {
-        out_idx[o_base + rank] = (int32_t)key_doc(x);
-        if (out_score) out_score[o_base + rank] = key_score(x);
+        if (out_key) {
+          out_key[o_base + rank] = x;
+        } else {
+          out_idx[o_base + rank] = (int32_t)key_doc(x);
+          if (out_score) out_score[o_base + rank] = key_score(x);
+        }
       }
     }
     for (int i = S + tid; i < k; i += 256) {  // fewer than k valid candidates (cannot happen for k <= N)
-      out_idx[o_base + i] = -1;
-      if (out_score) out_score[o_base + i] = -INFINITY;
+      if (out_key) {
+        out_key[o_base + i] = 0ull;
+      } else {
+        out_idx[o_base + i] = -1;
+        if (out_score) out_score[o_base + i] = -INFINITY;
+      }
     }
     return;
   }
@@ -408,8 +625,12 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
 #pragma unroll
     for (int w = 1; w < 4; ++w) best = red[w] > best ? red[w] : best;
     if (tid == 0) {
-      out_idx[o_base + round] = best ? (int32_t)key_doc(best) : -1;
-      if (out_score) out_score[o_base + round] = best ? key_score(best) : -INFINITY;
+      if (out_key) {
+        out_key[o_base + round] = best;
+      } else {
+        out_idx[o_base + round] = best ? (int32_t)key_doc(best) : -1;
+        if (out_score) out_score[o_base + round] = best ? key_score(best) : -INFINITY;
+      }
     }
     prev = best ? best : 0ull;
   }
@@ -484,9 +705,19 @@ __global__ __launch_bounds__(64) void prep_scan_operands_kernel(const uint16_t* 
   }
 }
 
+// Appends the per-token winner keys of the token-pooling pass to a finished plan.
+static void add_token_pool(const Dims& dm, int BM, int k, ScorePlan* p) {
+  p->off_tok = p->ws_bytes;
+  if (dm.token_pool)
+    p->ws_bytes += round_up256((size_t)BM * p->n_sel * k * sizeof(unsigned long long));
+}
+
 ScorePlan plan_score(const Dims& dm, int BM, int k) {
   ScorePlan p;
-  p.use_gemm = gemm_path_applies(dm, BM, k) ? 1 : 0;
+  // one selection per KV group, or (literal Eq. 2 head mean, more than one group) one for all heads
+  p.all_heads = (dm.scope_all && dm.Hkv > 1) ? 1 : 0;
+  p.n_sel = dm.scope_all ? 1 : dm.Hkv;
+  p.use_gemm = (!p.all_heads && gemm_path_applies(dm, BM, k)) ? 1 : 0;
   if (p.use_gemm) {
     p.gemm = plan_score_gemm(dm, BM, k);
     p.n_splits = p.gemm.n_splits;
@@ -499,44 +730,56 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
     p.off_qop = 0;
     p.n_qtiles = 0;
     p.ws_bytes = p.gemm.ws_bytes;
+    add_token_pool(dm, BM, k, &p);
     return p;
   }
-  p.q_per_pass = (BM <= 8) ? 8 : ((BM <= 16 || k > 24) ? 16 : 32);
+  p.q_per_pass = (BM <= 8 || p.all_heads) ? 8 : ((BM <= 16 || k > 24) ? 16 : 32);
   p.n_pass = (BM + p.q_per_pass - 1) / p.q_per_pass;
-  long long ns = 2048 / dm.Hkv;  // ~8 waves per CU on 256 CUs
+  long long ns = p.all_heads ? 2048 : 2048 / dm.Hkv;  // ~8 waves per CU on 256 CUs
   if (ns < 1) ns = 1;
   // streams of at least kPrefetch tiles; with 32 queries per pass the lists (64 entries each) must
   // also hold every document of the stream without pruning, so streams stay short there
   const long long min_len = kPrefetch;
   const long long by_tiles = (dm.tiles + min_len - 1) / min_len;
   if (ns > by_tiles) ns = by_tiles;
-  if (ns > 1024) ns = 1024;
+  if (ns > 1024 && !p.all_heads) ns = 1024;
   if (ns < 1) ns = 1;
   p.tiles_per_split = (int)((dm.tiles + ns - 1) / ns);
   p.n_splits = (int)((dm.tiles + p.tiles_per_split - 1) / p.tiles_per_split);
-  const size_t list_bytes = round_up256((size_t)dm.Hkv * BM * p.n_splits * k * sizeof(unsigned long long));
+  const size_t list_bytes = round_up256((size_t)p.n_sel * BM * p.n_splits * k * sizeof(unsigned long long));
   // threshold exchange between waves: worth it (and sound) only for long streams with >= k waves per head
   const long long n_it_min = dm.tiles / p.n_splits;
-  p.exchange = (n_it_min >= 64 && p.n_splits >= k && p.n_splits <= 256) ? 1 : 0;
+  p.exchange = (!p.all_heads && n_it_min >= 64 && p.n_splits >= k && p.n_splits <= 256) ? 1 : 0;
   p.it_publish = (int)(n_it_min / 12);
   p.it_adopt = p.it_publish + 8;
   p.off_gmax = list_bytes;
   p.off_qop = list_bytes + (p.exchange ? round_up256((size_t)dm.Hkv * BM * p.n_splits * sizeof(float)) : 0);
   p.n_qtiles = p.n_pass * (p.q_per_pass / 8);
   p.ws_bytes = p.off_qop + round_up256((size_t)dm.Hkv * p.n_qtiles * (dm.d / 32) * 64 * 16);
+  add_token_pool(dm, BM, k, &p);
   return p;
 }
 
-int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int BM, const void* KR,
+int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B, int M, const void* KR,
                  const float* inv_norm, int k, int32_t* out_idx, float* out_score, void* ws,
                  hipStream_t st) {
+  const int BM = B * M;
+  // with token pooling the per-token winners go to the workspace as keys and are pooled at the end
+  unsigned long long* tok_keys = dm.token_pool ? (unsigned long long*)((char*)ws + pl.off_tok) : nullptr;
+  auto pool_tokens = [&]() -> int {
+    if (!dm.token_pool) return MSA_OK;
+    hipLaunchKernelGGL(pool_tokens_kernel, dim3(B * pl.n_sel), dim3(256), 0, st,
+                       (const unsigned long long*)tok_keys, out_idx, out_score, M, pl.n_sel, k);
+    return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
+  };
   if (pl.use_gemm) {
     const int rc = launch_score_gemm_scan(dm, pl.gemm, q_route, BM, KR, inv_norm, k, ws, st);
     if (rc != MSA_OK) return rc;
     hipLaunchKernelGGL(score_merge_kernel, dim3(BM * dm.Hkv), dim3(256), 0, st,
                        (const unsigned long long*)((const char*)ws + pl.gemm.off_lists), out_idx,
-                       out_score, BM, dm.Hkv, pl.gemm.n_splits, k);
-    return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
+                       out_score, tok_keys, BM, dm.Hkv, pl.gemm.n_splits, k);
+    if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+    return pool_tokens();
   }
   ScoreArgs a;
   a.KR = (const uint16_t*)KR;
@@ -571,9 +814,24 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
                          dm.r, dm.cos, pl.n_qtiles, a.gmax, n_gmax);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
-  dim3 grid(pl.n_splits, dm.Hkv), block(64);
+  dim3 grid(pl.n_splits, pl.all_heads ? 1 : dm.Hkv), block(64);
   for (int pass = 0; pass < pl.n_pass; ++pass) {
     a.q0 = pass * pl.q_per_pass;
+    if (pl.all_heads) {
+#define MSA_SCAN_ALL(DD, HH) \
+  do { \
+    if (dm.cos) hipLaunchKernelGGL((score_scan_all_kernel<DD, HH, true>), grid, block, 0, st, a); \
+    else hipLaunchKernelGGL((score_scan_all_kernel<DD, HH, false>), grid, block, 0, st, a); \
+  } while (0)
+      if (dm.d == 128) {
+        if (dm.Hkv == 2) MSA_SCAN_ALL(128, 2); else if (dm.Hkv == 4) MSA_SCAN_ALL(128, 4); else MSA_SCAN_ALL(128, 8);
+      } else {
+        if (dm.Hkv == 2) MSA_SCAN_ALL(64, 2); else if (dm.Hkv == 4) MSA_SCAN_ALL(64, 4); else MSA_SCAN_ALL(64, 8);
+      }
+#undef MSA_SCAN_ALL
+      if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+      continue;
+    }
     const int nqt = pl.q_per_pass / 8;  // 1, 2 or 4
 #define MSA_SCAN(DD, QQ, CC) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC>), grid, block, 0, st, a)
     if (dm.d == 128) {
@@ -592,10 +850,10 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
 #undef MSA_SCAN
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
-  hipLaunchKernelGGL(score_merge_kernel, dim3(BM * dm.Hkv), dim3(256), 0, st,
-                     (const unsigned long long*)ws, out_idx, out_score, BM, dm.Hkv, pl.n_splits, k);
+  hipLaunchKernelGGL(score_merge_kernel, dim3(BM * pl.n_sel), dim3(256), 0, st,
+                     (const unsigned long long*)ws, out_idx, out_score, tok_keys, BM, pl.n_sel, pl.n_splits, k);
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
-  return MSA_OK;
+  return pool_tokens();
 }
 
 }  // namespace msa

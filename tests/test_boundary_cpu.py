@@ -82,8 +82,9 @@ def test_config_validation(lib):
         (dict(doc_len=64 * 12), msa.MSA_ERR_UNSUPPORTED),             # C = 12
         (dict(doc_len=64 * 32), msa.MSA_ERR_UNSUPPORTED),             # C = 32
         (dict(n_q_heads=32, n_kv_heads=2), msa.MSA_ERR_UNSUPPORTED),  # r = 16
-        (dict(select_scope=msa.MSA_SCOPE_ALL), msa.MSA_ERR_UNSUPPORTED),
-        (dict(token_pool=1), msa.MSA_ERR_UNSUPPORTED),
+        (dict(select_scope=msa.MSA_SCOPE_ALL, n_q_heads=6, n_kv_heads=3), msa.MSA_ERR_UNSUPPORTED),
+        (dict(select_scope=7), msa.MSA_ERR_INVALID_ARG),
+        (dict(token_pool=2), msa.MSA_ERR_INVALID_ARG),
     ]
     p = ctypes.c_void_p(0x10000)
     for kw, want in bad:
@@ -157,6 +158,15 @@ def test_argument_validation_before_launch(lib):
     assert lib.msa_pool_kv(cb, p, odd, 0, 1, p, p, None) == E.MSA_ERR_MISALIGNED
     assert lib.msa_pool_kv(cb, p, p, 0, 0, p, p, None) == E.MSA_OK                      # nothing to do, nothing launched
     assert lib.msa_pool_kv(ctypes.byref(_cfg(head_dim=96)), p, p, 0, 1, p, p, None) == E.MSA_ERR_UNSUPPORTED
+
+
+def test_literal_eq2_variants_are_planned(lib):
+    """select_scope = ALL and token_pool = 1 are valid requests with their own workspace sizes."""
+    base = msa.score_topk_workspace_bytes(_cfg(), 2, 5, 4)
+    pooled = msa.score_topk_workspace_bytes(_cfg(token_pool=1), 2, 5, 4)
+    assert pooled >= base + 2 * 5 * 2 * 4 * 8                       # + per-token winner keys [B*M][Hkv][k]
+    assert msa.score_topk_workspace_bytes(_cfg(select_scope=msa.MSA_SCOPE_ALL), 2, 5, 4) > 0
+    assert msa.score_topk_workspace_bytes(_cfg(select_scope=msa.MSA_SCOPE_ALL, token_pool=1), 2, 5, 4) > 0
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -572,3 +572,68 @@ def test_pooled_bank_all_pads_and_unrotated_short_docs_rejected():
     with pytest.raises(msa.MsaError) as e:
         msa.msa_sparse_attend(raw, case.dq, Kbar, Vbar, didx, None, None, 4, dpos)
     assert e.value.status == msa.MSA_ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------------------------------------
+# Eq. 2 as printed: head mean over every head (select_scope = ALL), max over query tokens (token_pool)
+# ------------------------------------------------------------------------------------------------
+def check_topk_generic(q, KRb, C, N, idx, val, k, sim, scope, pool, atol=2e-5):
+    """GPU selection against the oracle's for any scope / token pooling, with the tie band."""
+    oi, ov, s = O.score_topk(q, KRb, C, k, sim, scope, pool)
+    gi = idx.cpu().numpy().astype(np.int64)
+    gv = val.cpu().numpy().astype(np.float64)
+    assert gi.shape == oi.shape, (gi.shape, oi.shape)
+    n_band = 0
+    for b, m, sl in np.ndindex(*oi.shape[:3]):
+        srow, got, want = s[b, m, sl], gi[b, m, sl], oi[b, m, sl]
+        assert len(set(got.tolist())) == k and got.min() >= 0 and got.max() < N
+        assert np.allclose(gv[b, m, sl], srow[got], rtol=0, atol=atol), np.abs(gv[b, m, sl] - srow[got]).max()
+        assert np.all(np.diff(gv[b, m, sl]) <= 0)
+        if np.array_equal(got, want):
+            continue
+        sk = ov[b, m, sl, k - 1]
+        band = 1e-3 * abs(sk)
+        sure = want[srow[want] > sk + band]
+        assert set(sure.tolist()) <= set(got.tolist()), "a clear winner is missing"
+        assert np.all(srow[got] >= sk - band), "selected a document outside the tie band"
+        n_band += 1
+    return oi, n_band
+
+
+EQ2_CASES = {
+    # name: (seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k, sim)
+    "hkv8_d128_decode": (31000, 333, 8, 2, 128, 128, 16, 3, 1, 40, 1e6, 16, "cos"),
+    "hkv4_d64_batch20": (32000, 210, 4, 2, 64, 64, 32, 5, 4, 33, 1e4, 6, "cos"),
+    "hkv2_d128_c1_dot": (33000, 97, 2, 4, 64, 128, 64, 2, 9, 0, 1e6, 5, "dot"),
+    "hkv1_d64": (34000, 80, 1, 4, 128, 64, 32, 2, 3, 16, 1e4, 7, "cos"),
+    "hkv8_d64_c16": (35000, 41, 8, 1, 256, 64, 16, 1, 11, 20, 1e4, 9, "cos"),
+    "prefill80_gemm_pool": (36000, 150, 2, 4, 64, 128, 8, 2, 80, 80, 1e6, 8, "cos"),
+}
+
+
+@pytest.mark.parametrize("name", list(EQ2_CASES))
+def test_literal_eq2_scope_all_and_token_pool(name):
+    seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k, sim = EQ2_CASES[name]
+    say(f"Eq. 2 case {name}: N={N} Hkv={Hkv} r={r} G={G} d={d} P={P} B={B} M={M} Lloc={Lloc} k={k} {sim}")
+    case = Case(seed, N, Hkv, r, G, d, P, B, M, Lloc, base).to_device()
+    simc = msa.MSA_SIM_COS if sim == "cos" else msa.MSA_SIM_DOT
+    KRo, invo = O.routing_keys(case.K, P)
+    pos0 = G
+    q_pos = np.array([[pos0 + (min(Lloc - 1, (3 * m + b) % Lloc) if Lloc else 0) for m in range(M)]
+                      for b in range(B)])
+    dpos = torch.from_numpy(q_pos.astype(np.int32)).cuda()
+    for scope, pool in (("all", False), ("group", True), ("all", True)):
+        cfg = case.cfg(sim=simc, select_scope=msa.MSA_SCOPE_ALL if scope == "all" else msa.MSA_SCOPE_GROUP,
+                       token_pool=int(pool))
+        say(f"   score_topk scope={scope} token_pool={pool}")
+        dKRo, dinvo = upload_oracle_index(cfg, KRo, invo)
+        idx, val = msa.msa_score_topk(cfg, case.dq, dKRo, dinvo if sim == "cos" else None, k)
+        torch.cuda.synchronize()
+        oi, n_band = check_topk_generic(case.q, KRo, case.C, N, idx, val, k, sim, scope, pool,
+                                        atol=2e-5 if sim == "cos" else 2e-4)
+        say(f"   top-k ok, shape {tuple(idx.shape)} ({n_band} inside the tie band)")
+        say("   sparse_attend with the shared selection")
+        didx = torch.from_numpy(oi.astype(np.int32)).cuda()
+        out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, case.dKl, case.dVl, pos0, dpos)
+        torch.cuda.synchronize()
+        check_attend(case, out, lse, oi, pos0, q_pos)
