@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--bank", default="full", choices=("full", "pooled"),
                     help="what msa_sparse_attend reads: the un-pooled K/V bank (default) or the pooled, "
                          "position-encoded bank written by msa_pool_kv (Section 3.4.1, Stage 1)")
+    ap.add_argument("--scope", default="group", choices=("group", "all"),
+                    help="head mean of Eq. 2 over the r heads of a KV group (default, one selection per KV head) "
+                         "or over every head (as printed, one selection for all heads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-docs", type=int, default=512)
     return ap.parse_args()
@@ -106,7 +109,9 @@ def main():
     msa.load_library()
     torch.cuda.set_device(0)
     wl = W.make(args.workload)
-    cfg = msa.MsaConfig(wl.N, wl.G, wl.P, wl.Hq, wl.Hkv, wl.d, wl.base)
+    scope = msa.MSA_SCOPE_ALL if args.scope == "all" else msa.MSA_SCOPE_GROUP
+    n_sel = 1 if args.scope == "all" else wl.Hkv
+    cfg = msa.MsaConfig(wl.N, wl.G, wl.P, wl.Hq, wl.Hkv, wl.d, wl.base, select_scope=scope)
     ab = W.algorithmic_bytes(wl)
     stream = torch.cuda.current_stream()
 
@@ -132,7 +137,8 @@ def main():
         e1.record(stream)
         torch.cuda.synchronize()
         pool_ms = e0.elapsed_time(e1)
-        acfg = msa.MsaConfig(wl.N, wl.C, wl.C, wl.Hq, wl.Hkv, wl.d, wl.base, bank_keys_rotated=1)
+        acfg = msa.MsaConfig(wl.N, wl.C, wl.C, wl.Hq, wl.Hkv, wl.d, wl.base, select_scope=scope,
+                             bank_keys_rotated=1)
         pos0 = wl.k                                                      # Section 3.2.2: local positions start at k
         q_pos = (wl.q_pos - wl.pos0 + pos0).contiguous()
         local_rows = wl.M * wl.Lloc if wl.M == 1 else wl.M * (wl.M + 1) // 2   # causal prefill: token m sees m + 1
@@ -141,8 +147,8 @@ def main():
 
     # ---- online path: everything preallocated, nothing allocated inside the timed region --------
     B, M, k = wl.B, wl.M, wl.k
-    idx = torch.empty((B, M, wl.Hkv, k), dtype=torch.int32, device="cuda")
-    val = torch.empty((B, M, wl.Hkv, k), dtype=torch.float32, device="cuda")
+    idx = torch.empty((B, M, n_sel, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((B, M, n_sel, k), dtype=torch.float32, device="cuda")
     out = torch.empty_like(wl.q)
     lse = torch.empty((B, M, wl.Hq), dtype=torch.float32, device="cuda")
     ws_s = torch.empty(msa.score_topk_workspace_bytes(cfg, B, M, k), dtype=torch.uint8, device="cuda")
@@ -180,7 +186,7 @@ def main():
     build_gbs = ab["build"] / (build_ms * 1e-3) / 1e9
 
     flops = None
-    if nq >= 64 and k <= 8:      # the MFMA GEMM path: flops issued = 2 * tokens * keys * (hi + lo) * d per head
+    if nq >= 64 and k <= 8 and args.scope == "group":      # the MFMA GEMM path: flops issued = 2 * tokens * keys * (hi + lo) * d per head
         tiles = (wl.N * wl.C + 15) // 16
         flops = 2.0 * nq * wl.Hkv * tiles * 16 * 2 * wl.d
     res = {
@@ -188,7 +194,7 @@ def main():
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "bank": args.bank, "memory_tokens": wl.N * wl.G, "docs": wl.N, "doc_len": wl.G,
+        "config": {"workload": wl.name, "bank": args.bank, "select_scope": args.scope, "memory_tokens": wl.N * wl.G, "docs": wl.N, "doc_len": wl.G,
                    "chunk": wl.P, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.d, "batch": B,
                    "query_tokens": M, "top_k": k, "local_tokens": wl.Lloc, "rope_base": wl.base},
         "roofline": ({"bound": "hbm", "kernel": "msa_score_topk = prep + score_scan_kernel (dominant) + score_merge",

@@ -47,6 +47,9 @@ struct ScorePlan {
   int all_heads;         // 1: score_scan_all_kernel (scope ALL with more than one KV head)
   int n_sel;             // selections per query token: Hkv, or 1 for scope ALL
   size_t off_tok;        // byte offset of the per-token winner keys (token pooling)
+  int merge_parts;       // > 1: two-level merge, first level over merge_lpp lists per block
+  int merge_lpp;
+  size_t off_part;       // byte offset of the first-level winners
   int use_gemm;          // 1: many query tokens -> the GEMM path below
   GemmPlan gemm;
   size_t ws_bytes;

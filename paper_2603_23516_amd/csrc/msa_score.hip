@@ -319,28 +319,42 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
 // the similarity with the routing key of that head's KV group, i.e. the mean over the Hkv groups of
 // the per-group scores above, so one selection serves all heads.  A wave's stream interleaves the
 // heads: entry e = (tile e / HKV, head e % HKV) through the same ring of kPrefetch loads; the
-// A operands of all HKV heads stay in registers (8 queries per pass), the per-head partial scores are
-// scaled by that head's 1/|key| and summed, and after the last head the document max / threshold /
-// candidate-list logic runs exactly as in score_scan_kernel.  HKV in {2, 4, 8} (one group: the plain
-// kernel already computes this).
+// per-head partial scores are scaled by that head's 1/|key| and summed, and after the last head the
+// document max / threshold / candidate-list logic runs exactly as in score_scan_kernel.  The
+// A operands of all HKV heads (8 queries per pass) are too many for registers at two waves per SIMD,
+// so a workgroup of four waves (four independent streams) shares one LDS copy of them and every
+// wave re-reads the slices of the head at hand.  HKV in {2, 4, 8} (one group: the plain kernel
+// already computes this).
+constexpr int kAllWaves = 4;
+
 template <int D, int HKV, bool COS>
-__global__ __launch_bounds__(64) void score_scan_all_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(64 * kAllWaves) void score_scan_all_kernel(ScoreArgs a) {
   constexpr int NS = D / 32;
   constexpr int NQ = 8;
-  constexpr int CAP = kListBytes / (8 * NQ);
+  constexpr int CAP = 128;  // entries per (wave, query) list: 8 KiB of LDS per wave
   constexpr int TILE_ELEMS = 16 * D;
   constexpr int UT = HKV >= kPrefetch ? 1 : kPrefetch / HKV;  // tiles per unrolled group of entries
   static_assert((UT * HKV) % kPrefetch == 0, "ring slots must be compile-time");
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[kListBytes];
-  __shared__ int cnt_s[NQ];
-  __shared__ float thr_s[NQ];
-  unsigned long long* cand = reinterpret_cast<unsigned long long*>(smem);  // [NQ][CAP]
+  __shared__ uint4 Aop[HKV][NS][64];
+  __shared__ unsigned long long cand_all[kAllWaves][NQ * CAP];
+  __shared__ int cnt_all[kAllWaves][NQ];
+  __shared__ float thr_all[kAllWaves][NQ];
 
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  unsigned long long* cand = cand_all[wave];
+  int* cnt_s = cnt_all[wave];
+  float* thr_s = thr_all[wave];
+  for (int e = threadIdx.x; e < HKV * NS * 64; e += 64 * kAllWaves) {
+    const int h = e / (NS * 64), rest = e % (NS * 64);
+    Aop[h][rest / 64][rest % 64] = a.qop[((long long)h * a.n_qtiles + a.q0 / 8) * NS * 64 + rest];
+  }
+  __syncthreads();
   const int rr = lane >> 4;
   const int n = lane & 15;
-  const int sp = blockIdx.x;
+  const int sp = blockIdx.x * kAllWaves + wave;
+  if (sp >= a.n_splits) return;  // wave-uniform; no block-wide barrier follows
   const long long S = a.n_splits;
   const long long n_it = (a.tiles - sp + S - 1) / S;  // >= 1 because n_splits <= tiles
   const long long i_last = n_it - 1;
@@ -359,13 +373,6 @@ __global__ __launch_bounds__(64) void score_scan_all_kernel(ScoreArgs a) {
       buf[u][s] = *reinterpret_cast<const uint4*>(KRl + ((long long)h * a.tiles + t) * TILE_ELEMS + s * 512);
     binv[u] = COS ? inl[((long long)h * a.tiles + t) * 16] : 1.0f;
   }
-
-  bf16x8_t A[HKV][NS];
-#pragma unroll
-  for (int h = 0; h < HKV; ++h)
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-      A[h][s] = as_bf16x8(a.qop[(((long long)h * a.n_qtiles + a.q0 / 8) * NS + s) * 64 + lane]);
 
   float thr[2];
   int cnt[2];
@@ -407,7 +414,7 @@ __global__ __launch_bounds__(64) void score_scan_all_kernel(ScoreArgs a) {
         }
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < NS; ++s) acc = mfma16(A[h][s], as_bf16x8(cur[s]), acc);
+        for (int s = 0; s < NS; ++s) acc = mfma16(as_bf16x8(Aop[h][s][lane]), as_bf16x8(cur[s]), acc);
         tot[0] += (acc[0] + acc[1]) * cinv;
         tot[1] += (acc[2] + acc[3]) * cinv;
       }
@@ -530,22 +537,30 @@ constexpr int kMaxSub = 1152;
 constexpr int kMaxSurv = 2048;
 
 // out_key != null: the winners are written as 64-bit keys instead (input of pool_tokens_kernel).
+// parts > 1: first level of a two-level merge for very many lists.  Block (g, qg, part) combines
+// lists [part * lpp, (part + 1) * lpp) and writes its k winners as a sorted list of keys to
+// out_key[g][qg][part][k], the input layout of a second call with n_lists = parts.
 __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long long* __restrict__ ws,
                                                           int32_t* __restrict__ out_idx,
                                                           float* __restrict__ out_score,
                                                           unsigned long long* __restrict__ out_key,
-                                                          int BM, int Hkv, int n_lists, int k) {
+                                                          int BM, int Hkv, int n_lists_total, int k,
+                                                          int lpp, int parts) {
   __shared__ unsigned long long sub[kMaxSub];
   __shared__ unsigned long long surv[kMaxSurv];
   __shared__ unsigned long long red[4];
   __shared__ unsigned long long theta_s;
   __shared__ int n_surv;
   const int tid = threadIdx.x;
-  const int qg = blockIdx.x % BM;
-  const int g = blockIdx.x / BM;
+  const int part = blockIdx.x % parts;
+  const int qg = (blockIdx.x / parts) % BM;
+  const int g = blockIdx.x / parts / BM;
+  const int l0 = part * lpp;
+  const int n_lists = (n_lists_total - l0 < lpp) ? n_lists_total - l0 : lpp;
   const int T = n_lists * k;
-  const unsigned long long* src = ws + ((long long)g * BM + qg) * T;
-  const long long o_base = ((long long)qg * Hkv + g) * k;
+  const unsigned long long* src = ws + (((long long)g * BM + qg) * n_lists_total + l0) * k;
+  const long long o_base =
+      (parts > 1) ? (((long long)g * BM + qg) * parts + part) * k : ((long long)qg * Hkv + g) * k;
 
   const int depth = (k + n_lists - 1) / n_lists;  // entries taken from the head of every list
   // k <= P < k + n_lists; any kMaxSub >= k heads of lists bound the k-th best key just as well
@@ -705,8 +720,14 @@ __global__ __launch_bounds__(64) void prep_scan_operands_kernel(const uint16_t* 
   }
 }
 
-// Appends the per-token winner keys of the token-pooling pass to a finished plan.
+// Appends the buffers of the merge stage to a finished plan: the first-level winners of a two-level
+// merge (very many lists) and the per-token winner keys of the token-pooling pass.
 static void add_token_pool(const Dims& dm, int BM, int k, ScorePlan* p) {
+  p->merge_lpp = 64;
+  p->merge_parts = ((long long)p->n_splits * k > 16384) ? (p->n_splits + p->merge_lpp - 1) / p->merge_lpp : 1;
+  p->off_part = p->ws_bytes;
+  if (p->merge_parts > 1)
+    p->ws_bytes += round_up256((size_t)p->n_sel * BM * p->merge_parts * k * sizeof(unsigned long long));
   p->off_tok = p->ws_bytes;
   if (dm.token_pool)
     p->ws_bytes += round_up256((size_t)BM * p->n_sel * k * sizeof(unsigned long long));
@@ -772,14 +793,26 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
                        (const unsigned long long*)tok_keys, out_idx, out_score, M, pl.n_sel, k);
     return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
   };
+  // combine the per-split lists of every (query, selection): one level, or two for very many lists
+  auto merge = [&](const unsigned long long* lists, int n_lists) -> int {
+    if (pl.merge_parts > 1) {
+      unsigned long long* part_keys = (unsigned long long*)((char*)ws + pl.off_part);
+      hipLaunchKernelGGL(score_merge_kernel, dim3(BM * pl.n_sel * pl.merge_parts), dim3(256), 0, st, lists,
+                         (int32_t*)nullptr, (float*)nullptr, part_keys, BM, pl.n_sel, n_lists, k,
+                         pl.merge_lpp, pl.merge_parts);
+      if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+      lists = part_keys;
+      n_lists = pl.merge_parts;
+    }
+    hipLaunchKernelGGL(score_merge_kernel, dim3(BM * pl.n_sel), dim3(256), 0, st, lists, out_idx, out_score,
+                       tok_keys, BM, pl.n_sel, n_lists, k, n_lists, 1);
+    if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+    return pool_tokens();
+  };
   if (pl.use_gemm) {
     const int rc = launch_score_gemm_scan(dm, pl.gemm, q_route, BM, KR, inv_norm, k, ws, st);
     if (rc != MSA_OK) return rc;
-    hipLaunchKernelGGL(score_merge_kernel, dim3(BM * dm.Hkv), dim3(256), 0, st,
-                       (const unsigned long long*)((const char*)ws + pl.gemm.off_lists), out_idx,
-                       out_score, tok_keys, BM, dm.Hkv, pl.gemm.n_splits, k);
-    if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
-    return pool_tokens();
+    return merge((const unsigned long long*)((const char*)ws + pl.gemm.off_lists), pl.gemm.n_splits);
   }
   ScoreArgs a;
   a.KR = (const uint16_t*)KR;
@@ -814,7 +847,8 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
                          dm.r, dm.cos, pl.n_qtiles, a.gmax, n_gmax);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
-  dim3 grid(pl.n_splits, pl.all_heads ? 1 : dm.Hkv), block(64);
+  dim3 grid(pl.all_heads ? (pl.n_splits + kAllWaves - 1) / kAllWaves : pl.n_splits, pl.all_heads ? 1 : dm.Hkv);
+  dim3 block(pl.all_heads ? 64 * kAllWaves : 64);
   for (int pass = 0; pass < pl.n_pass; ++pass) {
     a.q0 = pass * pl.q_per_pass;
     if (pl.all_heads) {
@@ -850,10 +884,7 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
 #undef MSA_SCAN
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
-  hipLaunchKernelGGL(score_merge_kernel, dim3(BM * pl.n_sel), dim3(256), 0, st,
-                     (const unsigned long long*)ws, out_idx, out_score, tok_keys, BM, pl.n_sel, pl.n_splits, k);
-  if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
-  return pool_tokens();
+  return merge((const unsigned long long*)ws, pl.n_splits);
 }
 
 }  // namespace msa

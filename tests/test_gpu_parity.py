@@ -453,6 +453,12 @@ def test_score_long_streams_threshold_exchange():
     i2, v2 = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
     torch.cuda.synchronize()
     assert torch.equal(i2, idx) and torch.equal(v2, val)
+    say("   the same index, head mean over every head: 2048 waves, two-level merge of their lists")
+    cfg_all = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e4, select_scope=msa.MSA_SCOPE_ALL)
+    ia, va = msa.msa_score_topk(cfg_all, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    _, n_band = check_topk_generic(q, KRb, C, N, ia, va, k, "cos", "all", False)
+    say(f"   top-k ok ({n_band} inside the tie band)")
 
 
 # ------------------------------------------------------------------------------------------------
