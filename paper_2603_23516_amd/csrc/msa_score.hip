@@ -102,23 +102,29 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
+constexpr int kScanWaves = 4;  // independent streams per workgroup
+
 template <int D, int NQT, bool COS>
-__global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(64 * kScanWaves) void score_scan_kernel(ScoreArgs a) {
   constexpr int NS = D / 32;   // MFMA k-slices per key
   constexpr int NQ = 8 * NQT;  // queries per pass
   constexpr int CAP = kListBytes / (8 * NQ);
   constexpr int TILE_ELEMS = 16 * D;
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[kListBytes];
-  __shared__ int cnt_s[NQ];
-  __shared__ float thr_s[NQ];
-  unsigned long long* cand = reinterpret_cast<unsigned long long*>(smem);  // [NQ][CAP]
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kScanWaves][kListBytes];
+  __shared__ int cnt_all[kScanWaves][NQ];
+  __shared__ float thr_all[kScanWaves][NQ];
+  const int wave = threadIdx.x >> 6;
+  unsigned long long* cand = reinterpret_cast<unsigned long long*>(smem[wave]);  // [NQ][CAP]
+  int* cnt_s = cnt_all[wave];
+  float* thr_s = thr_all[wave];
 
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63;
   const int rr = lane >> 4;  // MFMA k-group / D row-group
   const int n = lane & 15;   // A row / B column / D column
-  const int sp = blockIdx.x;
+  const int sp = blockIdx.x * kScanWaves + wave;
   const int g = blockIdx.y;
+  if (sp >= a.n_splits) return;  // wave-uniform; the waves of a workgroup never synchronise
 
   // ---- start streaming at once: the first kPrefetch tiles are requested before the prologue ----
   // Wave sp takes tiles sp, sp + n_splits, sp + 2 n_splits, ...: at any moment the waves of a head
@@ -173,8 +179,83 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
   float qmax[NQT][2];        // running maximum of this lane's document scores, per query
 #pragma unroll
   for (int t = 0; t < NQT; ++t) qmax[t][0] = qmax[t][1] = -INFINITY;
+  // One 8-query tile per pass: the published maxima are requested kPrefetch iterations before they
+  // are used, all queries at once, so their latency hides behind that many tiles of the stream.
+  constexpr bool kEarlyFetch = (NQT == 1);
+  constexpr int kFetchLead = 1;  // in groups of kPrefetch iterations
+  float exq[kEarlyFetch ? NQ : 1][4];
   {
     for (long long base = 0; base < n_it; base += kPrefetch) {
+      // ---- threshold exchange (long streams only): every wave publishes the best score it has
+      // seen per query; a little later it adopts theta = the k-th largest of all published maxima.
+      // The maxima belong to distinct documents, so at least k documents score >= theta: a valid
+      // lower bound on the k-th best score whatever the other waves have written so far.
+      if (kEarlyFetch && a.gmax != nullptr && base == a.it_adopt - kFetchLead * kPrefetch) {
+#pragma unroll
+        for (int qi = 0; qi < (kEarlyFetch ? NQ : 1); ++qi) {
+          const int qg = a.q0 + qi < a.BM ? a.q0 + qi : a.BM - 1;
+          const float* src = a.gmax + ((long long)g * a.BM + qg) * a.n_splits;
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            exq[qi][j] = (lane + 64 * j < a.n_splits) ? src[lane + 64 * j] : -INFINITY;
+        }
+      }
+      if (a.gmax != nullptr && (base == a.it_publish || base == a.it_adopt)) {
+        if (base == a.it_publish) {
+#pragma unroll
+          for (int tq = 0; tq < NQT; ++tq)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              const float mrow = group_max<16>(qmax[tq][e]);
+              const int qg = a.q0 + 8 * tq + 2 * rr + e;
+              if (n == 0 && qg < a.BM) a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp] = mrow;
+            }
+        } else {
+          // theta = k-th largest of the published maxima of one query: bitwise search on the
+          // order-preserving integer image, 4 values per lane
+          auto kth_largest = [&](const uint32_t (&ord)[4]) -> float {
+            uint32_t prefix = 0u;
+            for (int bit = 31; bit >= 12; --bit) {
+              const uint32_t cnd = prefix | (1u << bit);
+              int ge = 0;
+#pragma unroll
+              for (int j = 0; j < 4; ++j) ge += __popcll(__ballot(ord[j] >= cnd));
+              if (ge >= a.k) prefix = cnd;  // wave-uniform
+            }
+            return prefix ? unorderable(prefix) : -INFINITY;
+          };
+          if constexpr (kEarlyFetch) {
+#pragma unroll
+            for (int qi = 0; qi < NQ; ++qi) {
+              uint32_t ord[4];
+#pragma unroll
+              for (int j = 0; j < 4; ++j) ord[j] = orderable(exq[qi][j]);
+              const float th = kth_largest(ord);
+              if (lane == 0) thr_s[qi] = th;
+            }
+          } else {
+            for (int qi = 0; qi < NQ; ++qi) {
+              const int qg = a.q0 + qi;
+              if (qg >= a.BM) break;  // wave-uniform
+              const float* src = a.gmax + ((long long)g * a.BM + qg) * a.n_splits;
+              uint32_t ord[4];
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                ord[j] = (lane + 64 * j < a.n_splits) ? orderable(src[lane + 64 * j]) : 0u;
+              const float th = kth_largest(ord);
+              if (lane == 0) thr_s[qi] = th;
+            }
+          }
+          wave_sync();
+#pragma unroll
+          for (int tq = 0; tq < NQT; ++tq)
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+              if (a.q0 + 8 * tq + 2 * rr + e < a.BM)
+                thr[tq][e] = fmaxf(thr[tq][e], thr_s[8 * tq + 2 * rr + e]);
+          wave_sync();
+        }
+      }
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {
         const long long it = base + u;
@@ -247,49 +328,6 @@ __global__ __launch_bounds__(64) void score_scan_kernel(ScoreArgs a) {
             thr[tq][1] = thr_s[8 * tq + 2 * rr + 1];
           }
           wave_sync();
-        }
-        // ---- threshold exchange (long streams only): every wave publishes the best score it has
-        // seen per query; a little later it adopts theta = the k-th largest of all published maxima.
-        // The maxima belong to distinct documents, so at least k documents score >= theta: a valid
-        // lower bound on the k-th best score whatever the other waves have written so far.
-        if (a.gmax != nullptr && (it == a.it_publish || it == a.it_adopt)) {
-          if (it == a.it_publish) {
-#pragma unroll
-            for (int tq = 0; tq < NQT; ++tq)
-#pragma unroll
-              for (int e = 0; e < 2; ++e) {
-                const float mrow = group_max<16>(qmax[tq][e]);
-                const int qg = a.q0 + 8 * tq + 2 * rr + e;
-                if (n == 0 && qg < a.BM) a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp] = mrow;
-              }
-          } else {
-            for (int qi = 0; qi < NQ; ++qi) {
-              const int qg = a.q0 + qi;
-              if (qg >= a.BM) break;  // wave-uniform
-              const float* src = a.gmax + ((long long)g * a.BM + qg) * a.n_splits;
-              uint32_t ord[4];
-#pragma unroll
-              for (int j = 0; j < 4; ++j)
-                ord[j] = (lane + 64 * j < a.n_splits) ? orderable(src[lane + 64 * j]) : 0u;
-              uint32_t prefix = 0u;
-              for (int bit = 31; bit >= 12; --bit) {
-                const uint32_t cnd = prefix | (1u << bit);
-                int ge = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) ge += __popcll(__ballot(ord[j] >= cnd));
-                if (ge >= a.k) prefix = cnd;  // wave-uniform
-              }
-              if (lane == 0) thr_s[qi] = prefix ? unorderable(prefix) : -INFINITY;
-            }
-            wave_sync();
-#pragma unroll
-            for (int tq = 0; tq < NQT; ++tq)
-#pragma unroll
-              for (int e = 0; e < 2; ++e)
-                if (a.q0 + 8 * tq + 2 * rr + e < a.BM)
-                  thr[tq][e] = fmaxf(thr[tq][e], thr_s[8 * tq + 2 * rr + e]);
-            wave_sync();
-          }
         }
       }
     }
@@ -771,8 +809,9 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
   // threshold exchange between waves: worth it (and sound) only for long streams with >= k waves per head
   const long long n_it_min = dm.tiles / p.n_splits;
   p.exchange = (!p.all_heads && n_it_min >= 64 && p.n_splits >= k && p.n_splits <= 256) ? 1 : 0;
-  p.it_publish = (int)(n_it_min / 12);
-  p.it_adopt = p.it_publish + 8;
+  // exchange events sit at the head of a group of kPrefetch iterations
+  p.it_publish = (int)(n_it_min / 12) / kPrefetch * kPrefetch;
+  p.it_adopt = p.it_publish + 3 * kPrefetch;
   p.off_gmax = list_bytes;
   p.off_qop = list_bytes + (p.exchange ? round_up256((size_t)dm.Hkv * BM * p.n_splits * sizeof(float)) : 0);
   p.n_qtiles = p.n_pass * (p.q_per_pass / 8);
@@ -847,8 +886,9 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
                          dm.r, dm.cos, pl.n_qtiles, a.gmax, n_gmax);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
-  dim3 grid(pl.all_heads ? (pl.n_splits + kAllWaves - 1) / kAllWaves : pl.n_splits, pl.all_heads ? 1 : dm.Hkv);
-  dim3 block(pl.all_heads ? 64 * kAllWaves : 64);
+  dim3 grid(pl.all_heads ? (pl.n_splits + kAllWaves - 1) / kAllWaves : (pl.n_splits + kScanWaves - 1) / kScanWaves,
+            pl.all_heads ? 1 : dm.Hkv);
+  dim3 block(pl.all_heads ? 64 * kAllWaves : 64 * kScanWaves);
   for (int pass = 0; pass < pl.n_pass; ++pass) {
     a.q0 = pass * pl.q_per_pass;
     if (pl.all_heads) {
