@@ -23,7 +23,7 @@ struct Dims {
 struct GemmPlan {
   int n_qblocks;         // blocks of 256 query tokens
   int n_splits;          // key-range splits per (head, token block)
-  int sub_per_split;     // 32-key sub-tiles per split
+  int stages_per_split;  // 64-key stages per split
   size_t off_lists;      // byte offset of the candidate lists (after the folded fp32 queries)
   size_t ws_bytes;
 };

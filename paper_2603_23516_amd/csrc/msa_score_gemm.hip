@@ -9,9 +9,10 @@
 //   fold_queries_kernel : (1/r) sum_h q_h/|q_h| per (token, KV group) in fp32, once.
 //   score_gemm_kernel   : a workgroup owns 256 query tokens of one KV head (4 waves x 64 tokens, the
 //     queries stay in registers as B operands for the whole kernel) and walks a range of key
-//     sub-tiles of 32 keys (= 4 documents at C = 8).  A sub-tile (two 16-key index tiles, 8 KiB,
-//     contiguous in the tiled index) is copied once to LDS (double buffered) and read by all four
-//     waves as the A operand of v_mfma_f32_32x32x16_bf16: D[key][token].
+//     sub-tiles of 32 keys (= 4 documents at C = 8).  Two sub-tiles (four 16-key index tiles, 16 KiB,
+//     contiguous in the tiled index) form a stage that is copied once to LDS (a ring of three
+//     buffers, two copies in flight, one workgroup barrier per stage) and read by all four waves as
+//     the A operand of v_mfma_f32_32x32x16_bf16: D[key][token].
 //     Keys are the ROWS of the product, so the 8 chunks of a document sit in two lanes (l, l ^ 32)
 //     as four accumulator registers each: document max = 3 in-lane max + one half-wave swap.
 //     Each lane keeps a private sorted top-8 list (score, document) per token block in registers;
@@ -97,20 +98,28 @@ struct GemmArgs {
   unsigned long long* ws;   // [Hkv][BM][n_splits][k]
   int BM, Hkv, N, k;
   long long tiles;          // 16-key tiles per head
-  int n_qblocks, n_splits, sub_per_split;
+  int n_qblocks, n_splits, stages_per_split;
 };
 
 template <int D>
 __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
   constexpr int NS8 = D / 16;            // 16-wide contraction slices per half (hi / lo)
   constexpr int SUB_BYTES = 32 * D * 2;  // one 32-key sub-tile
+  constexpr int STAGE_BYTES = 2 * SUB_BYTES;  // a stage = two sub-tiles = 64 keys, one barrier
   constexpr int TILE_ELEMS = 16 * D;
-  constexpr int LOADS = SUB_BYTES / (256 * 16);  // 16-byte loads per thread per sub-tile (2 at d=128)
-  __shared__ __attribute__((aligned(16))) unsigned char kbuf0[SUB_BYTES];
-  __shared__ __attribute__((aligned(16))) unsigned char kbuf1[SUB_BYTES];
-  __shared__ __attribute__((aligned(16))) float ibuf0[32];
-  __shared__ __attribute__((aligned(16))) float ibuf1[32];
-  __shared__ unsigned long long mrg[4][64][2 * kGemmK];  // end-of-kernel merge of the two half lists
+  constexpr int LOADS = STAGE_BYTES / (256 * 16);  // 16-byte copies per thread per stage (4 at d=128)
+  constexpr int MRG_BYTES = 4 * 64 * 2 * kGemmK * 8;
+  constexpr int RING_BYTES = 3 * STAGE_BYTES;
+  // ring of three stages (two copies in flight while one is multiplied); the end-of-kernel merge of
+  // the two half-wave lists reuses the same memory once the ring is drained
+  __shared__ __attribute__((aligned(16))) unsigned char smem[RING_BYTES > MRG_BYTES ? RING_BYTES : MRG_BYTES];
+  __shared__ __attribute__((aligned(16))) float ibuf[3][64];
+  __shared__ __attribute__((aligned(16))) float ones[64];
+  unsigned char* const kbuf0 = smem;
+  unsigned char* const kbuf1 = smem + STAGE_BYTES;
+  unsigned char* const kbuf2 = smem + 2 * STAGE_BYTES;
+  typedef unsigned long long mrg_row_t[2 * kGemmK];
+  mrg_row_t* const mrg = reinterpret_cast<mrg_row_t*>(smem);  // [4 waves * 64 tokens][2 * kGemmK]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -122,9 +131,11 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
   const int qb = rest % a.n_qblocks;
   const int ks = rest / a.n_qblocks;
   const long long n_sub = (a.tiles + 1) / 2;
-  const long long s0 = (long long)ks * a.sub_per_split;
-  long long s1 = s0 + a.sub_per_split;
-  if (s1 > n_sub) s1 = n_sub;
+  const long long n_stage = (n_sub + 1) / 2;
+  const long long s0 = (long long)ks * a.stages_per_split;
+  long long s1 = s0 + a.stages_per_split;
+  if (s1 > n_stage) s1 = n_stage;
+  if (tid < 64) ones[tid] = 1.0f;
 
   // ---- B operands: this wave's 64 tokens, hi and lo halves, resident for the whole kernel -----
   const int tok0 = qb * kGemmTokens + wave * 64;
@@ -169,39 +180,45 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
       ldoc[cb][p] = -1;
     }
 
-  // ---- staging of key sub-tiles: global -> LDS directly (no registers), one sub-tile ahead -----
-  // A 64-lane global_load_lds_dwordx4 lands at LDS base + 16 * lane, and a sub-tile is contiguous in
-  // the tiled index, so wave w copies bytes [1024 (4i + w), +1024) of the sub-tile with load i.  The
-  // two buffers are separate arrays addressed statically (the loop body is instantiated for each),
-  // which lets the compiler see that reads of one never alias the copy into the other.
+  // ---- staging of key stages: global -> LDS directly (no registers), two stages ahead ---------
+  // A 64-lane global_load_lds_dwordx4 lands at LDS base + 16 * lane, and a stage is contiguous in
+  // the tiled index, so wave w copies bytes [1024 (4i + w), +1024) of the stage with copy i; the
+  // 64 reciprocal norms follow with one dword copy (every wave writes the same 64 floats, so each
+  // wave issues exactly LOADS + 1 memory operations per stage and can wait on its own counter).
   const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS;
   const float* ing = a.inv_norm ? a.inv_norm + (long long)g * a.tiles * 16 : nullptr;
-  float stage_i = 1.0f;
-  auto fetch = [&](long long st, unsigned char* kdst) {
+  auto fetch = [&](long long sg, unsigned char* kdst, float* idst) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int off = (i * 256 + tid) * 16;            // byte offset inside the sub-tile
-      long long tile = 2 * st + off / (TILE_ELEMS * 2);
-      if (tile >= a.tiles) tile = a.tiles - 1;         // odd tile count: repeat the last tile (masked)
+      const int off = (i * 256 + tid) * 16;            // byte offset inside the stage
+      long long tile = 4 * sg + off / (TILE_ELEMS * 2);
+      if (tile >= a.tiles) tile = a.tiles - 1;         // past the end: repeat the last tile (masked)
       const unsigned char* src = reinterpret_cast<const unsigned char*>(KRg) + tile * (TILE_ELEMS * 2) +
                                  off % (TILE_ELEMS * 2);
       __builtin_amdgcn_global_load_lds(
           (const __attribute__((address_space(1))) void*)src,
           (__attribute__((address_space(3))) void*)(kdst + (i * 256 + wave * 64) * 16), 16, 0, 0);
     }
-    if (tid < 32) {
-      long long key = st * 32 + tid;
+    {
+      long long key = sg * 64 + lane;
       if (key >= a.tiles * 16) key = a.tiles * 16 - 1;
-      stage_i = ing ? ing[key] : 1.0f;
+      // dot product: no norms; the copy still runs (from the index itself) to keep the counts equal,
+      // and the multiply below reads the constant ones instead
+      const float* src = ing ? ing + key : reinterpret_cast<const float*>(KRg) + lane;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)idst, 4, 0, 0);
     }
   };
+  // wait until at most the copies of the newest stage are outstanding
+  auto wait_oldest_copy = [&]() __attribute__((always_inline)) {
+    if constexpr (LOADS == 4)
+      asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+  };
 
-  auto body = [&](long long st, const unsigned char* kcur, const float* icur, unsigned char* knxt,
-                  float* inxt) {
-    const long long nxt = (st + 1 < s1) ? st + 1 : st;  // always issued (re-reads the last sub-tile)
-    fetch(nxt, knxt);
-
-    // ---- 32 keys x 64 tokens, contraction over [hi | lo] ---------------------------------------
+  // 32 keys x 64 tokens, contraction over [hi | lo], then the epilogue for these four documents
+  auto sub_tile = [&](long long st, const unsigned char* kcur, const float* icur) __attribute__((always_inline)) {
     f32x16_t acc[2];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
@@ -267,28 +284,40 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
         }
       }
     }
-    if (tid < 32) inxt[tid] = stage_i;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the copy into the other buffer has landed
-    __syncthreads();
+  };
+
+  auto body = [&](long long sg, const unsigned char* kcur, const float* icur, unsigned char* knxt,
+                  float* inxt) __attribute__((always_inline)) {
+    // always issued (past the end it re-reads the last stage into a buffer nobody reads again)
+    fetch((sg + 2 < s1) ? sg + 2 : s1 - 1, knxt, inxt);
+    const float* isrc = ing ? icur : ones;
+    sub_tile(2 * sg, kcur, isrc);
+    sub_tile(2 * sg + 1, kcur + SUB_BYTES, ing ? icur + 32 : ones);
+    wait_oldest_copy();  // this wave's part of the next stage has landed ...
+    __syncthreads();     // ... and so has everyone's; all waves are done reading kcur
   };
 
   if (s0 < s1) {
-    fetch(s0, kbuf0);
-    if (tid < 32) ibuf0[tid] = stage_i;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    fetch(s0, kbuf0, ibuf[0]);
+    fetch(s0 + 1 < s1 ? s0 + 1 : s1 - 1, kbuf1, ibuf[1]);
+    wait_oldest_copy();
   }
   __syncthreads();
-  for (long long st = s0; st < s1; st += 2) {
-    body(st, kbuf0, ibuf0, kbuf1, ibuf1);
-    if (st + 1 < s1) body(st + 1, kbuf1, ibuf1, kbuf0, ibuf0);  // block-uniform
+  for (long long sg = s0; sg < s1; sg += 3) {  // the conditions are block-uniform
+    body(sg, kbuf0, ibuf[0], kbuf2, ibuf[2]);
+    if (sg + 1 < s1) body(sg + 1, kbuf1, ibuf[1], kbuf0, ibuf[0]);
+    if (sg + 2 < s1) body(sg + 2, kbuf2, ibuf[2], kbuf1, ibuf[1]);
   }
+  // drain the ring (re-reads issued past the end may still be landing) before its memory is reused
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
 
   // ---- merge the two half-wave lists of every token, write sorted keys -----------------------
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb) {
 #pragma unroll
     for (int p = 0; p < kGemmK; ++p)
-      mrg[wave][32 * cb + c][h * kGemmK + p] =
+      mrg[wave * 64 + 32 * cb + c][h * kGemmK + p] =
           (ldoc[cb][p] >= 0) ? make_key(lsc[cb][p], (uint32_t)ldoc[cb][p]) : 0ull;
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -296,7 +325,7 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb) {
     const int tok = tok0 + 32 * cb + c;
-    const unsigned long long* both = mrg[wave][32 * cb + c];
+    const unsigned long long* both = mrg[wave * 64 + 32 * cb + c];
 #pragma unroll
     for (int p = 0; p < kGemmK; ++p) {
       const unsigned long long key = both[h * kGemmK + p];
@@ -319,15 +348,15 @@ bool gemm_path_applies(const Dims& dm, int BM, int k) {
 GemmPlan plan_score_gemm(const Dims& dm, int BM, int k) {
   GemmPlan p;
   p.n_qblocks = (BM + kGemmTokens - 1) / kGemmTokens;
-  const long long n_sub = (dm.tiles + 1) / 2;
+  const long long n_stage = ((dm.tiles + 1) / 2 + 1) / 2;           // stages of 64 keys
   long long want = (2 * 256) / ((long long)dm.Hkv * p.n_qblocks);  // ~2 workgroups per CU
   if (want < 1) want = 1;
-  long long by_len = (n_sub + 63) / 64;                           // at least 64 sub-tiles per split
+  long long by_len = (n_stage + 31) / 32;                          // at least 32 stages per split
   long long ns = want < by_len ? want : by_len;
   if (ns < 1) ns = 1;
   if (ns > 64) ns = 64;
-  p.sub_per_split = (int)((n_sub + ns - 1) / ns);
-  p.n_splits = (int)((n_sub + p.sub_per_split - 1) / p.sub_per_split);
+  p.stages_per_split = (int)((n_stage + ns - 1) / ns);
+  p.n_splits = (int)((n_stage + p.stages_per_split - 1) / p.stages_per_split);
   p.off_lists = round_up256((size_t)BM * dm.Hkv * dm.d * sizeof(float));
   p.ws_bytes = p.off_lists + round_up256((size_t)dm.Hkv * BM * p.n_splits * k * sizeof(unsigned long long));
   return p;
@@ -355,7 +384,7 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
   a.tiles = dm.tiles;
   a.n_qblocks = pl.n_qblocks;
   a.n_splits = pl.n_splits;
-  a.sub_per_split = pl.sub_per_split;
+  a.stages_per_split = pl.stages_per_split;
   const unsigned blocks = (unsigned)(dm.Hkv * pl.n_qblocks * pl.n_splits);
   if (dm.d == 128)
     hipLaunchKernelGGL(score_gemm_kernel<128>, dim3(blocks), dim3(256), 0, st, a);
