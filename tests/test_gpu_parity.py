@@ -643,3 +643,24 @@ def test_literal_eq2_scope_all_and_token_pool(name):
         out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, case.dKl, case.dVl, pos0, dpos)
         torch.cuda.synchronize()
         check_attend(case, out, lse, oi, pos0, q_pos)
+
+
+def test_prefill_scoring_long_splits():
+    """Prefill routing large enough that heads x token blocks fill the GPU and the GEMM path walks long
+    key-range splits (many ring rotations per workgroup); the oracle scores 100 tokens at a time."""
+    N, C, d, Hkv, r, B, M, k = 6144, 8, 64, 8, 1, 1, 1100, 8
+    say(f"case prefill scoring, long splits: N={N} docs, C={C}, d={d}, Hkv={Hkv}, M={M}, k={k}")
+    cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e4)
+    _, KRb = S.normal_bf16(41000, (Hkv, N * C, d))
+    qb, q = S.normal_bf16(41001, (B, M, Hkv * r, d))
+    KRb[:, 5 * C + 2] = KRb[:, 4000 * C + 5]                      # an exact tie between two documents' best chunks
+    inv = 1.0 / np.maximum(np.linalg.norm(KRb, axis=-1), O.EPS_NORM)
+    dKR, dinv = upload_oracle_index(cfg, KRb, inv)
+    idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    n_band = 0
+    for m0 in range(0, M, 100):
+        sl = slice(m0, min(M, m0 + 100))
+        _, nb = check_topk_generic(q[:, sl], KRb, C, N, idx[:, sl], val[:, sl], k, "cos", "group", False)
+        n_band += nb
+    say(f"   top-k ok ({n_band} inside the tie band)")
