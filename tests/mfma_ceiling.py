@@ -16,9 +16,10 @@ def main():
     lib.probe_mfma_ceiling.restype = ctypes.c_float
     lib.probe_mfma_ceiling.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     scratch = torch.zeros(1024, dtype=torch.float32, device="cuda")
-    names = {0: "registers only", 1: "A operand from LDS", 2: "A from LDS + scale/max epilogue"}
+    names = {0: "registers only", 1: "A operand from LDS", 2: "A from LDS + scale/max epilogue",
+             3: "same, two accumulator sets"}
     iters = 2048
-    for mode in (0, 1, 2):
+    for mode in (0, 1, 2, 3):
         for blocks in (256, 512):
             ms = lib.probe_mfma_ceiling(mode, blocks, iters, ctypes.c_void_p(scratch.data_ptr()))
             assert ms > 0
