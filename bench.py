@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--scope", default="group", choices=("group", "all"),
                     help="head mean of Eq. 2 over the r heads of a KV group (default, one selection per KV head) "
                          "or over every head (as printed, one selection for all heads)")
+    ap.add_argument("--token-pool", action="store_true",
+                    help="max over the query tokens of a batch row (Eq. 2 as printed): one selection per batch row, "
+                         "and for many tokens the tiled shared-selection attention kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-docs", type=int, default=512)
     return ap.parse_args()
@@ -111,7 +114,8 @@ def main():
     wl = W.make(args.workload)
     scope = msa.MSA_SCOPE_ALL if args.scope == "all" else msa.MSA_SCOPE_GROUP
     n_sel = 1 if args.scope == "all" else wl.Hkv
-    cfg = msa.MsaConfig(wl.N, wl.G, wl.P, wl.Hq, wl.Hkv, wl.d, wl.base, select_scope=scope)
+    cfg = msa.MsaConfig(wl.N, wl.G, wl.P, wl.Hq, wl.Hkv, wl.d, wl.base, select_scope=scope,
+                        token_pool=int(args.token_pool))
     ab = W.algorithmic_bytes(wl)
     stream = torch.cuda.current_stream()
 
@@ -138,7 +142,7 @@ def main():
         torch.cuda.synchronize()
         pool_ms = e0.elapsed_time(e1)
         acfg = msa.MsaConfig(wl.N, wl.C, wl.C, wl.Hq, wl.Hkv, wl.d, wl.base, select_scope=scope,
-                             bank_keys_rotated=1)
+                             token_pool=int(args.token_pool), bank_keys_rotated=1)
         pos0 = wl.k                                                      # Section 3.2.2: local positions start at k
         q_pos = (wl.q_pos - wl.pos0 + pos0).contiguous()
         local_rows = wl.M * wl.Lloc if wl.M == 1 else wl.M * (wl.M + 1) // 2   # causal prefill: token m sees m + 1
@@ -147,8 +151,9 @@ def main():
 
     # ---- online path: everything preallocated, nothing allocated inside the timed region --------
     B, M, k = wl.B, wl.M, wl.k
-    idx = torch.empty((B, M, n_sel, k), dtype=torch.int32, device="cuda")
-    val = torch.empty((B, M, n_sel, k), dtype=torch.float32, device="cuda")
+    m_sel = 1 if args.token_pool else M
+    idx = torch.empty((B, m_sel, n_sel, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((B, m_sel, n_sel, k), dtype=torch.float32, device="cuda")
     out = torch.empty_like(wl.q)
     lse = torch.empty((B, M, wl.Hq), dtype=torch.float32, device="cuda")
     ws_s = torch.empty(msa.score_topk_workspace_bytes(cfg, B, M, k), dtype=torch.uint8, device="cuda")
@@ -194,7 +199,8 @@ def main():
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "bank": args.bank, "select_scope": args.scope, "memory_tokens": wl.N * wl.G, "docs": wl.N, "doc_len": wl.G,
+        "config": {"workload": wl.name, "bank": args.bank, "select_scope": args.scope, "token_pool": int(args.token_pool),
+                   "memory_tokens": wl.N * wl.G, "docs": wl.N, "doc_len": wl.G,
                    "chunk": wl.P, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.d, "batch": B,
                    "query_tokens": M, "top_k": k, "local_tokens": wl.Lloc, "rope_base": wl.base},
         "roofline": ({"bound": "hbm", "kernel": "msa_score_topk = prep + score_scan_kernel (dominant) + score_merge",

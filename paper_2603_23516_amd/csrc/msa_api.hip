@@ -108,7 +108,7 @@ size_t msa_sparse_attend_workspace_bytes(const msa_config_t* cfg, int32_t B, int
   if (make_dims(cfg, &dm, kForAttend) != MSA_OK) return 0;
   if (B < 1 || M < 1 || k < 1 || k > MSA_MAX_TOPK || Lloc < 0) return 0;
   if ((int64_t)B * M > 65535 || !attend_doc_len_ok(cfg)) return 0;
-  return plan_attend(dm, B * M, k, Lloc).ws_bytes;
+  return plan_attend(dm, B, M, k, Lloc, cfg->bank_keys_rotated).ws_bytes;
 }
 
 int msa_build_routing_keys(const msa_config_t* cfg, const void* K, int32_t doc_begin,
@@ -178,7 +178,7 @@ int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t
       misaligned(Vloc) || misaligned(q_pos) || misaligned(out) || misaligned(lse) ||
       misaligned(workspace))
     return MSA_ERR_MISALIGNED;
-  const AttendPlan pl = plan_attend(dm, B * M, k, Lloc);
+  const AttendPlan pl = plan_attend(dm, B, M, k, Lloc, cfg->bank_keys_rotated);
   if (workspace_bytes < pl.ws_bytes) return MSA_ERR_WORKSPACE;
   return launch_attend(dm, pl, q, B, M, K, V, idx, k, Kloc, Vloc, Lloc, local_pos0, q_pos, out,
                        lse, workspace, cfg->bank_keys_rotated, (hipStream_t)stream);

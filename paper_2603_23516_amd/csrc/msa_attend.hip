@@ -29,37 +29,9 @@
 //   2  the same with short documents, G in {1, 2, 4, 8, 16}: a 32-key step spans 32/G selected
 //      documents, so every lane looks up the document of each row it loads and a 32-bit mask
 //      records which rows belong to a valid selection.
-#include "msa_device.h"
-#include "msa_host.h"
+#include "msa_attend.h"
 
 namespace msa {
-
-constexpr int kAttWaves = 4;
-constexpr int kMaxHalf = 64;  // d/2 <= 64
-
-struct RopeTheta {
-  double th[kMaxHalf];   // theta_u = base^(-2u/d), computed on the host in double
-  float2 e1[kMaxHalf];   // (cos, sin)(theta_u), rounded from double on the host
-  float2 e16[kMaxHalf];  // (cos, sin)(16 theta_u)
-};
-
-struct AttendArgs {
-  const uint16_t* q;     // [BM][Hq][D]
-  const uint16_t* K;     // [N][Hkv][G][D]
-  const uint16_t* V;
-  const int32_t* idx;    // [BM or B][Hkv or 1][k] (see idx_rows_per_b, idx_sel)
-  const uint16_t* Kloc;  // [B][Hkv][Lloc][D]
-  const uint16_t* Vloc;
-  const int32_t* q_pos;  // [BM]
-  float* part_o;         // [BM][Hq][n_splits][D]   unnormalised partial outputs
-  float2* part_ml;       // [BM][Hq][n_splits]      (running max in log2 units, sum)
-  int M, Hq, Hkv, r, G, k, Lloc, pos0, N;
-  int gshift;            // log2(G) when G < 32 (MODE 2)
-  int idx_sel;           // selections per idx row: Hkv (one per KV group) or 1 (shared by all heads)
-  int idx_rows_per_b;    // idx rows per batch row: M (one per query token) or 1 (shared by the M tokens)
-  int steps_mem, steps_total, steps_per_split, n_splits;
-  float qscale;          // log2(e) / sqrt(d)
-};
 
 template <int D, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -581,11 +553,17 @@ __global__ __launch_bounds__(D) void attend_merge_kernel(const float* __restrict
   }
 }
 
-AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc) {
+AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_keys_rotated) {
   AttendPlan p;
+  const int BM = B * M;
   p.steps_mem = (int)(((long long)k * dm.G + 31) / 32);
   p.steps_total = p.steps_mem + (Lloc + 31) / 32;
-  const long long pairs = (long long)BM * dm.Hkv;
+  // many query tokens sharing one selection: the tiled prefill kernel (raw keys, r a power of two)
+  p.prefill = (dm.token_pool && M >= 8 && !bank_keys_rotated && dm.G % 32 == 0 &&
+               (dm.r == 1 || dm.r == 2 || dm.r == 4 || dm.r == 8)) ? 1 : 0;
+  p.tpw = p.prefill ? 16 / dm.r : 0;
+  p.n_ttiles = p.prefill ? (M + 4 * p.tpw - 1) / (4 * p.tpw) : 0;
+  const long long pairs = p.prefill ? (long long)B * p.n_ttiles * dm.Hkv : (long long)BM * dm.Hkv;
   // aim at <= 512 blocks: two 256-thread blocks are resident per CU (register-limited), so 512 is
   // one full wave of blocks on 256 CUs and nothing waits for a second round
   long long per = ((long long)p.steps_total * pairs + 511) / 512;
@@ -642,6 +620,10 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     th.e16[u] = make_float2((float)cos(16.0 * th.th[u]), (float)sin(16.0 * th.th[u]));
   }
   const int BM = B * M;
+  if (pl.prefill) {
+    const int rc = launch_attend_prefill_partial(dm, pl, a, th, B, st);
+    if (rc != MSA_OK) return rc;
+  } else {
   dim3 grid(pl.n_splits, dm.Hkv, BM), block(256);
   const int mode = !bank_keys_rotated ? 0 : (dm.G % 32 == 0 ? 1 : 2);
   if (mode != 2 && dm.G % 32 != 0) return MSA_ERR_UNSUPPORTED;
@@ -658,6 +640,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     else MSA_LAUNCH_ATTEND(64, 2);
   }
 #undef MSA_LAUNCH_ATTEND
+  }
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   if (dm.d == 128)
     hipLaunchKernelGGL(attend_merge_kernel<128>, dim3(BM * dm.Hq), dim3(128), 0, st,

@@ -1,0 +1,401 @@
+// msa_sparse_attend for MANY query tokens that SHARE one selection (token_pool = 1: the routing of
+// Eq. 2 as printed picks the documents once per question, so all M tokens of a batch row attend the
+// same k documents, Eq. 3-4).  Then the gathered keys and values are common to a whole tile of query
+// tokens and attention is a dense contraction: this kernel reads, rotates (Section 3.2.2: positions
+// restart at 0 in every document) and stages every 32-key step ONCE per workgroup and multiplies it
+// with 64 / r query tokens x r heads on the matrix cores.
+//
+// Work split.  A workgroup owns a tile of 4 * TPW query tokens of one (batch row, KV head), TPW =
+// 16 / r tokens per wave, and a contiguous range of 32-key steps (split-K as in the decode path; the
+// partials (max, sum, O) use the same layout and the same merge kernel).  Per step:
+//   all 256 threads  load the 32 key rows and 32 value rows (16-byte pieces), rotate the keys in
+//                    fp32 (thread = key x 8 rotation pairs, running (cos, sin) advanced by 32
+//                    positions per step), round to bf16 and write them to LDS in MFMA operand order;
+//                    values go to LDS as they are (padded rows for transposed 16-bit reads);
+//   every wave       S^T[32 keys][32 slots] = K~ Q~^T with v_mfma_f32_32x32x16_bf16; a slot is
+//                    (token, head, hi | lo): the rotated, scaled queries are carried as bf16 (hi, lo)
+//                    pairs in adjacent columns, exactly as in the decode kernel; online softmax per
+//                    column (16 keys per lane, the other 16 in lane ^ 32); the weights go back as
+//                    bf16 (hi, lo) and ARE the B operand of  O^T[dd][slot] += V^T[dd][key] P^T[key][slot]
+//                    (the contraction index runs over the lane's own 8 keys of each 16-key slice, and
+//                    V^T is read with 16-bit LDS reads in the same key order).
+// Causality: local key t is visible to token m iff pos0 + t <= q_pos[m]; the mask is per column and
+// the workgroup stops at the last step any of its tokens can see.  LDS is double buffered, one
+// barrier per step.
+#include "msa_attend.h"
+
+namespace msa {
+
+typedef float f32x16p_t __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ f32x16p_t mfma32p(bf16x8_t a, bf16x8_t b, f32x16p_t c) {
+  // D(32x32) += A(32x16) * B(16x32).  Lane l: A[l%32][8(l/32)..+8], B[8(l/32)..+8][l%32],
+  // D register i: row (i%4) + 8(i/4) + 4(l/32), column l%32.
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// After the swap of x with itself every lane holds the values of both lanes (l & 31) and (l & 31) + 32.
+__device__ __forceinline__ float both_halves_max(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float both_halves_sum(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
+                                                             int n_ttiles) {
+  constexpr int HALF = D / 2;
+  constexpr int NP = D / 8;          // 16-byte pieces per row
+  constexpr int NS = D / 16;         // 16-wide contraction slices of the score product
+  constexpr int NT = D / 32;         // 32-row tiles of the output product
+  constexpr int PPH = D / 16;        // rotating threads per key (8 rotation pairs each)
+  constexpr int VSTRIDE = D * 2 + 8; // bytes per staged value row (+8: conflict-free 16-bit reads)
+  constexpr int VS2 = VSTRIDE / 2;
+  constexpr int KT_BYTES = 32 * D * 2;
+  constexpr int VT_BYTES = 32 * VSTRIDE;
+  constexpr int NVL = 32 * NP / 256 > 0 ? 32 * NP / 256 : 1;  // value pieces per thread per step
+
+  constexpr int ANG_BYTES = 4 * 16 * HALF * 8;  // prologue only: (cos, sin)(q_pos theta_u), 16 tokens x 4 waves
+  constexpr int STAGE_BYTES = 2 * KT_BYTES + 2 * VT_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[STAGE_BYTES > ANG_BYTES ? STAGE_BYTES : ANG_BYTES];
+  unsigned char* const kt0 = smem;                       // rotated keys [piece][key][8 bf16], two buffers
+  uint16_t* const vt0 = reinterpret_cast<uint16_t*>(smem + 2 * KT_BYTES);  // value rows, two buffers
+  __shared__ float2 bt[32][HALF];  // e^{i key theta_u}, key < 32
+  __shared__ int nvis_s[64];       // visible local tokens of each token of the tile
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int h = lane >> 5;
+  const int col = lane & 31;
+  const int sp = blockIdx.x;
+  const int g = blockIdx.y;
+  const int b = blockIdx.z / n_ttiles;
+  const int tt = blockIdx.z % n_ttiles;
+  const int tile_tok = 4 * tpw;             // tokens per workgroup
+  const int m_tile = tt * tile_tok;         // first token of the tile
+  const int r = a.r;
+
+  // ---- prologue ---------------------------------------------------------------------------------
+  // bt[key][u] = e^{i key theta_u} by repeated multiplication with the host's e^{i theta_u}
+  for (int e = tid; e < 4 * HALF; e += 256) {
+    const int u = e % HALF, q8 = e / HALF;  // this thread fills keys 8 q8 .. 8 q8 + 7
+    const float2 w = th.e1[u];
+    const float2 w2 = cmul(w, w);
+    const float2 w4 = cmul(w2, w2);
+    const float2 w8 = cmul(w4, w4);
+    float2 cur = make_float2(1.f, 0.f);
+    for (int i = 0; i < q8; ++i) cur = cmul(cur, w8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      bt[8 * q8 + i][u] = cur;
+      cur = cmul(cur, w);
+    }
+  }
+  if (tid < 64) {
+    int nv = 0;
+    const int m = m_tile + tid;
+    if (tid < tile_tok && m < a.M) {
+      nv = a.q_pos[(long long)b * a.M + m] - a.pos0 + 1;
+      nv = nv < 0 ? 0 : (nv > a.Lloc ? a.Lloc : nv);
+    }
+    nvis_s[tid] = nv;
+  }
+  // (cos, sin)(q_pos theta_u) of this wave's tokens, staged in the (still unused) key buffer
+  float2* ang = reinterpret_cast<float2*>(smem) + wave * (16 * HALF);  // [tpw][HALF]
+  for (int e = lane; e < tpw * HALF; e += 64) {
+    const int tl = e / HALF, u = e % HALF;
+    const int m = m_tile + wave * tpw + tl;
+    const int qp = (m < a.M) ? a.q_pos[(long long)b * a.M + m] : 0;
+    ang[e] = cis_pos(qp, th.th[u]);
+  }
+  __syncthreads();
+  int nvis_blk = 0;
+  for (int i = 0; i < tile_tok; ++i) nvis_blk = nvis_s[i] > nvis_blk ? nvis_s[i] : nvis_blk;
+
+  // B operand of the score product: column = slot (pair col/2 = (token, head), hi for even, lo for odd)
+  const int pair = col >> 1;
+  const int tl = pair / r, hh = pair - tl * r;
+  const int m_tok = m_tile + wave * tpw + tl;           // this column's query token
+  const bool tok_ok = tl < tpw && m_tok < a.M;
+  const int nvis_col = tok_ok ? nvis_s[wave * tpw + tl] : 0;
+  bf16x8_t bq[NS];
+  {
+    const uint16_t* qp = a.q + (((long long)b * a.M + (tok_ok ? m_tok : 0)) * a.Hq + g * r + hh) * D;
+#pragma unroll
+    for (int s = 0; s < NS / 2; ++s) {
+      // dims 16 s + 8 h .. +8 (first half) and their partners + D/2 (slice s + NS/2)
+      const uint4 r1 = *reinterpret_cast<const uint4*>(qp + 16 * s + 8 * h);
+      const uint4 r2 = *reinterpret_cast<const uint4*>(qp + HALF + 16 * s + 8 * h);
+      const uint32_t w1[4] = {r1.x, r1.y, r1.z, r1.w}, w2[4] = {r2.x, r2.y, r2.z, r2.w};
+      uint32_t o1[4], o2[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        float y1[2], y2[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const float x1 = e ? bf16_hi(w1[jj]) : bf16_lo(w1[jj]);
+          const float x2 = e ? bf16_hi(w2[jj]) : bf16_lo(w2[jj]);
+          const float2 cs = ang[(tok_ok ? tl : 0) * HALF + 16 * s + 8 * h + 2 * jj + e];
+          y1[e] = tok_ok ? (x1 * cs.x - x2 * cs.y) * a.qscale : 0.f;
+          y2[e] = tok_ok ? (x2 * cs.x + x1 * cs.y) * a.qscale : 0.f;
+        }
+        float h0, l0, h1, l1;
+        split_bf16(y1[0], h0, l0);
+        split_bf16(y1[1], h1, l1);
+        o1[jj] = (col & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
+        split_bf16(y2[0], h0, l0);
+        split_bf16(y2[1], h1, l1);
+        o2[jj] = (col & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
+      }
+      bq[s] = as_bf16x8(make_uint4(o1[0], o1[1], o1[2], o1[3]));
+      bq[s + NS / 2] = as_bf16x8(make_uint4(o2[0], o2[1], o2[2], o2[3]));
+    }
+  }
+  __syncthreads();  // the angle staging area becomes the key buffer
+
+  // ---- this workgroup's steps -----------------------------------------------------------------
+  const int sb = sp * a.steps_per_split;
+  int se = sb + a.steps_per_split;
+  if (se > a.steps_total) se = a.steps_total;
+  const long long idx_row = (a.idx_rows_per_b == 1) ? b : (long long)b * a.M;  // shared selection: row of b
+  const int32_t* idx_g = a.idx + (idx_row * a.idx_sel + (a.idx_sel == 1 ? 0 : g)) * a.k;
+
+  struct StepSrc {
+    const uint16_t* Kb;
+    const uint16_t* Vb;
+    int rows_valid, p_first, t0;
+    bool is_mem;
+  };
+  auto locate = [&](int st, StepSrc& ss) -> bool {  // block-uniform
+    if (st < a.steps_mem) {
+      const int tok = st * 32;
+      const int slot = tok / a.G;
+      const int pin = tok - slot * a.G;
+      const int doc = idx_g[slot];
+      if (doc < 0 || doc >= a.N) return false;  // -1 pads, and ids outside the bank, are skipped
+      const long long off = (((long long)doc * a.Hkv + g) * a.G + pin) * D;
+      ss.Kb = a.K + off;
+      ss.Vb = a.V + off;
+      ss.rows_valid = 32;
+      ss.p_first = pin;
+      ss.t0 = 0;
+      ss.is_mem = true;
+      return true;
+    }
+    const int t0 = (st - a.steps_mem) * 32;
+    if (t0 >= nvis_blk) return false;
+    const long long off = (((long long)b * a.Hkv + g) * a.Lloc + t0) * D;
+    ss.Kb = a.Kloc + off;
+    ss.Vb = a.Vloc + off;
+    ss.rows_valid = nvis_blk - t0 < 32 ? nvis_blk - t0 : 32;
+    ss.p_first = a.pos0 + t0;
+    ss.t0 = t0;
+    ss.is_mem = false;
+    return true;
+  };
+  auto next_valid = [&](int st, StepSrc& ss) -> int {
+    while (st < se && !locate(st, ss)) ++st;
+    return st;
+  };
+
+  // loader / rotator role of this thread: key row kr, rotation pairs u = 8 pc + e and partners u + D/2
+  const int kr = tid / PPH;
+  const int pc = tid % PPH;
+  const bool rot_thread = tid < 32 * PPH;
+  uint4 kreg[2];
+  uint4 vreg[NVL];
+  auto issue_loads = [&](const StepSrc& ss) {
+    if (rot_thread) {
+      const int row = kr < ss.rows_valid ? kr : ss.rows_valid - 1;
+      const uint16_t* rp = ss.Kb + (long long)row * D + pc * 8;
+      kreg[0] = *reinterpret_cast<const uint4*>(rp);
+      kreg[1] = *reinterpret_cast<const uint4*>(rp + HALF);
+    }
+#pragma unroll
+    for (int i = 0; i < NVL; ++i) {
+      const int f = i * 256 + tid;
+      if (f < 32 * NP) {
+        int row = f / NP;
+        row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+        vreg[i] = *reinterpret_cast<const uint4*>(ss.Vb + (long long)row * D + (f % NP) * 8);
+      }
+    }
+  };
+
+  float2 cs[8];     // (cos, sin)((cur_p + kr) theta_u), u = 8 pc + e
+  int cur_p = -1;   // position of key row 0 the state is valid for; -1 = invalid
+  float2 st32[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float2 w16 = th.e16[(8 * pc + e) % HALF];
+    st32[e] = cmul(w16, w16);
+  }
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16p_t o[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[t][i] = 0.f;
+
+  StepSrc cur_src;
+  int st = next_valid(sb, cur_src);
+  if (st < se) issue_loads(cur_src);
+  int buf = 0;
+  while (st < se) {
+    // ---- (a) rotate this step's keys into LDS, stage its values -------------------------------
+    if (rot_thread) {
+      if (cur_p != cur_src.p_first) {
+        if (cur_src.p_first == 0) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) cs[e] = bt[kr][8 * pc + e];
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) cs[e] = cis_pos(cur_src.p_first + kr, th.th[8 * pc + e]);
+        }
+        cur_p = cur_src.p_first;
+      }
+      const uint32_t w1[4] = {kreg[0].x, kreg[0].y, kreg[0].z, kreg[0].w};
+      const uint32_t w2[4] = {kreg[1].x, kreg[1].y, kreg[1].z, kreg[1].w};
+      uint32_t y1[4], y2[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const float2 c0 = cs[2 * jj], c1 = cs[2 * jj + 1];
+        const float p0 = bf16_lo(w1[jj]), p1 = bf16_hi(w1[jj]);
+        const float q0 = bf16_lo(w2[jj]), q1 = bf16_hi(w2[jj]);
+        y1[jj] = pack_bf16(p0 * c0.x - q0 * c0.y, p1 * c1.x - q1 * c1.y);
+        y2[jj] = pack_bf16(q0 * c0.x + p0 * c0.y, q1 * c1.x + p1 * c1.y);
+      }
+      unsigned char* ktb = kt0 + buf * KT_BYTES;
+      *reinterpret_cast<uint4*>(&ktb[(pc * 32 + kr) * 16]) = make_uint4(y1[0], y1[1], y1[2], y1[3]);
+      *reinterpret_cast<uint4*>(&ktb[((pc + PPH) * 32 + kr) * 16]) = make_uint4(y2[0], y2[1], y2[2], y2[3]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) cs[e] = cmul(cs[e], st32[e]);
+      cur_p += 32;
+    }
+#pragma unroll
+    for (int i = 0; i < NVL; ++i) {
+      const int f = i * 256 + tid;
+      if (f < 32 * NP) {
+        uint2* dst = reinterpret_cast<uint2*>(&vt0[buf * (VT_BYTES / 2) + (f / NP) * VS2 + (f % NP) * 8]);
+        dst[0] = make_uint2(vreg[i].x, vreg[i].y);
+        dst[1] = make_uint2(vreg[i].z, vreg[i].w);
+      }
+    }
+    const int rows_valid = cur_src.rows_valid;
+    const int t0 = cur_src.t0;
+    const bool is_mem = cur_src.is_mem;
+    __syncthreads();  // (b) this step is staged; everyone is done with the other buffer's previous step
+
+    // ---- (c) request the next step ---------------------------------------------------------------
+    StepSrc nxt_src = cur_src;
+    const int st_next = next_valid(st + 1, nxt_src);
+    if (st_next < se) issue_loads(nxt_src);
+
+    // ---- (d) scores of 32 keys x 32 slots ------------------------------------------------------
+    f32x16p_t sacc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const bf16x8_t ak =
+          as_bf16x8(*reinterpret_cast<const uint4*>(&kt0[buf * KT_BYTES + ((2 * s + h) * 32 + col) * 16]));
+      sacc = mfma32p(ak, bq[s], sacc);
+    }
+    float sc[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int krow = (i & 3) + 8 * (i >> 2) + 4 * h;
+      const float v = sacc[i] + dpp_f<kDppXor1>(sacc[i]);  // hi + lo column
+      const bool live = is_mem ? true : (t0 + krow < nvis_col);
+      sc[i] = (krow < rows_valid && live) ? v : -INFINITY;
+      mx = fmaxf(mx, sc[i]);
+    }
+    mx = both_halves_max(mx);
+    if (mx > m_run) {  // per column; the accumulators of a lane all belong to its column
+      const float alpha = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - mx);
+      m_run = mx;
+      l_run *= alpha;
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[t][i] *= alpha;
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+    uint32_t pw[8];
+    float psum = 0.f;
+#pragma unroll
+    for (int i2 = 0; i2 < 8; ++i2) {
+      float pv[2];
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const float p = __builtin_amdgcn_exp2f(sc[2 * i2 + e] - m_use);
+        psum += p;
+        float hi, lo;
+        split_bf16(p, hi, lo);
+        pv[e] = (col & 1) ? lo : hi;
+      }
+      pw[i2] = pack_bf16(pv[0], pv[1]);
+    }
+    l_run += psum;
+
+    // ---- second product: O^T[dd][slot] += V^T[dd][key] P^T[key][slot] ---------------------------
+    // contraction slot j of slice sg and half h is key 16 sg + (j % 4) + 8 (j / 4) + 4 h: the lane's own
+    // score registers 8 sg .. 8 sg + 7
+#pragma unroll
+    for (int sg = 0; sg < 2; ++sg) {
+      const bf16x8_t pb = as_bf16x8(make_uint4(pw[4 * sg], pw[4 * sg + 1], pw[4 * sg + 2], pw[4 * sg + 3]));
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        uint32_t w[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int j0 = 2 * jj, j1 = 2 * jj + 1;
+          const int r0 = 16 * sg + (j0 & 3) + 8 * (j0 >> 2) + 4 * h;
+          const int r1 = 16 * sg + (j1 & 3) + 8 * (j1 >> 2) + 4 * h;
+          const uint32_t lo = vt0[buf * (VT_BYTES / 2) + r0 * VS2 + 32 * t + col];
+          const uint32_t hi = vt0[buf * (VT_BYTES / 2) + r1 * VS2 + 32 * t + col];
+          w[jj] = lo | (hi << 16);
+        }
+        o[t] = mfma32p(as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])), pb, o[t]);
+      }
+    }
+    st = st_next;
+    cur_src = nxt_src;
+    buf ^= 1;
+  }
+
+  // ---- partial results of this split ---------------------------------------------------------------
+  const float l_tot = both_halves_sum(l_run);
+  if (tok_ok) {  // the same for both columns of a pair, so the lane exchange below stays inside the mask
+    const long long ph = (((long long)b * a.M + m_tok) * a.Hq + g * r + hh) * a.n_splits + sp;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float v = o[t][i] + dpp_f<kDppXor1>(o[t][i]);  // hi + lo column
+        const int dd = 32 * t + (i & 3) + 8 * (i >> 2) + 4 * h;
+        if ((col & 1) == 0) a.part_o[ph * D + dd] = v;
+      }
+    if ((col & 1) == 0 && h == 0) a.part_ml[ph] = make_float2(m_run, l_tot);
+  }
+}
+
+int launch_attend_prefill_partial(const Dims& dm, const AttendPlan& pl, const AttendArgs& a,
+                                  const RopeTheta& th, int B, hipStream_t st) {
+  dim3 grid(pl.n_splits, dm.Hkv, B * pl.n_ttiles), block(256);
+  if (dm.d == 128)
+    hipLaunchKernelGGL(attend_prefill_kernel<128>, grid, block, 0, st, a, th, pl.tpw, pl.n_ttiles);
+  else
+    hipLaunchKernelGGL(attend_prefill_kernel<64>, grid, block, 0, st, a, th, pl.tpw, pl.n_ttiles);
+  return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
+}
+
+}  // namespace msa

@@ -61,10 +61,12 @@ struct AttendPlan {
   int steps_total;       // + ceil(Lloc / 32)
   int steps_per_split;
   int n_splits;
+  int prefill;           // 1: shared selection and many tokens -> attend_prefill_kernel
+  int tpw, n_ttiles;     // prefill: tokens per wave (16 / r), token tiles (4 waves each) per batch row
   size_t off_ml;         // byte offset of the (m, l) pairs inside the workspace
   size_t ws_bytes;
 };
-AttendPlan plan_attend(const Dims& dm, int BM, int k, int Lloc);
+AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_keys_rotated);
 
 int launch_build(const Dims& dm, const void* K, int doc_begin, int doc_count, void* KR,
                  float* inv_norm, hipStream_t st);

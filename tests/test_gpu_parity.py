@@ -664,3 +664,52 @@ def test_prefill_scoring_long_splits():
         _, nb = check_topk_generic(q[:, sl], KRb, C, N, idx[:, sl], val[:, sl], k, "cos", "group", False)
         n_band += nb
     say(f"   top-k ok ({n_band} inside the tie band)")
+
+
+# ------------------------------------------------------------------------------------------------
+# shared-selection prefill attention (token_pool = 1, many tokens): the tiled MFMA kernel
+# ------------------------------------------------------------------------------------------------
+PREFILL_ATT_CASES = {
+    # name: (seed, N, Hkv, r, G, d, B, M, Lloc, base, k)
+    "r4_d128_causal": (51000, 30, 2, 4, 128, 128, 2, 70, 70, 1e6, 6),
+    "r8_d128_ragged_local": (52000, 20, 1, 8, 64, 128, 1, 37, 45, 1e6, 5),
+    "r1_d64_wide_tile": (53000, 25, 3, 1, 96, 64, 2, 100, 33, 1e4, 7),
+    "r2_d64_long_context_few_tokens": (54000, 40, 2, 2, 512, 64, 1, 9, 300, 1e4, 12),
+    "r4_d128_no_local": (55000, 16, 2, 4, 256, 128, 1, 24, 0, 1e6, 4),
+}
+
+
+@pytest.mark.parametrize("name", list(PREFILL_ATT_CASES))
+def test_prefill_attention_shared_selection(name):
+    seed, N, Hkv, r, G, d, B, M, Lloc, base, k = PREFILL_ATT_CASES[name]
+    say(f"prefill attention {name}: N={N} Hkv={Hkv} r={r} G={G} d={d} B={B} M={M} Lloc={Lloc} k={k}")
+    case = Case(seed, N, Hkv, r, G, d, G, B, M, Lloc, base).to_device()
+    cfg = case.cfg(token_pool=1)
+    rng = np.random.default_rng(seed)
+    sel = np.stack([rng.permutation(N)[:k] for _ in range(B * Hkv)]).reshape(B, 1, Hkv, k)
+    sel[0, 0, 0, k // 2] = -1                                       # a pad in the middle of the shared list
+    pos0 = G
+    # staggered causal masks: some tokens see nothing local, some everything, most a prefix
+    q_pos = np.array([[pos0 - 1 if (m % 11 == 3 or Lloc == 0) else pos0 + min(Lloc - 1, (7 * m + 3 * b) % Lloc)
+                       for m in range(M)] for b in range(B)])
+    didx = torch.from_numpy(sel.astype(np.int32)).cuda()
+    dpos = torch.from_numpy(q_pos.astype(np.int32)).cuda()
+    out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    check_attend(case, out, lse, sel, pos0, q_pos)
+    say("   ids outside the bank are skipped like pads; run-to-run identical")
+    wild = sel.copy()
+    wild[0, 0, 0, k // 2] = N + 3
+    o2, l2 = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, torch.from_numpy(wild.astype(np.int32)).cuda(),
+                                   case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    assert torch.equal(o2.view(torch.int16), out.view(torch.int16)) and torch.equal(l2, lse)
+    say("   the per-token kernel on the same shared selection agrees")
+    per_tok = np.broadcast_to(sel, (B, M, Hkv, k)).copy()
+    o3, l3 = msa.msa_sparse_attend(case.cfg(), case.dq, case.dK, case.dV,
+                                   torch.from_numpy(per_tok.astype(np.int32)).cuda(), case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    d_out = (o3.float() - out.float()).abs().max().item()
+    fin = torch.isfinite(lse)
+    assert torch.equal(torch.isfinite(l3), fin)
+    assert d_out <= 2e-2 and (l3[fin] - lse[fin]).abs().max().item() <= 5e-3, d_out
