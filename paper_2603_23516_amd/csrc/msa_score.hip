@@ -526,29 +526,27 @@ __global__ __launch_bounds__(64 * kAllWaves) void score_scan_all_kernel(ScoreArg
 // D is in m*'s list with exactly its pooled score.  Ranking the union by (best listed score desc,
 // index asc) therefore reproduces the pooled top-k exactly.  One block per (batch row, scope slot):
 // k rounds of a block-wide arg-max over the M*k listed keys, skipping documents already taken.
+constexpr int kPoolSurv = 4096;  // survivors kept in LDS
+
 __global__ __launch_bounds__(256) void pool_tokens_kernel(const unsigned long long* __restrict__ tok_keys,
                                                           int32_t* __restrict__ out_idx,
                                                           float* __restrict__ out_score, int M, int S,
                                                           int k) {
+  __shared__ unsigned long long surv[kPoolSurv];
   __shared__ unsigned long long red[4];
   __shared__ uint32_t taken[MSA_MAX_TOPK];
+  __shared__ uint32_t floor_s;
+  __shared__ int n_surv;
   const int tid = threadIdx.x;
   const int b = blockIdx.x / S;
   const int sl = blockIdx.x % S;
   const long long o_base = ((long long)b * S + sl) * k;
   const int T = M * k;
-  unsigned long long prev = ~0ull;
-  for (int round = 0; round < k; ++round) {
-    unsigned long long best = 0ull;
-    for (int i = tid; i < T; i += 256) {
-      const int m = i / k, j = i - m * k;
-      const unsigned long long x = tok_keys[(((long long)b * M + m) * S + sl) * k + j];
-      if (x == 0ull || x >= prev || x <= best) continue;  // keys of one document differ in the score bits only
-      const uint32_t doc = key_doc(x);
-      bool dup = false;
-      for (int w = 0; w < round; ++w) dup = dup || taken[w] == doc;
-      if (!dup) best = x;
-    }
+  auto key_at = [&](int i) {
+    const int m = i / k, j = i - m * k;
+    return tok_keys[(((long long)b * M + m) * S + sl) * k + j];
+  };
+  auto block_max = [&](unsigned long long best) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
       const unsigned long long y = __shfl_xor(best, off, 64);
@@ -560,6 +558,64 @@ __global__ __launch_bounds__(256) void pool_tokens_kernel(const unsigned long lo
     best = red[0];
 #pragma unroll
     for (int w = 1; w < 4; ++w) best = red[w] > best ? red[w] : best;
+    return best;
+  };
+  // 1. A floor: one token's k listed documents already have pooled scores >= its k-th listed score,
+  //    so the pooled k-th best score is at least the largest such k-th score; lower entries drop out.
+  unsigned long long fl = 0ull;
+  for (int m = tid; m < M; m += 256) {
+    const unsigned long long x = tok_keys[(((long long)b * M + m) * S + sl) * k + (k - 1)];
+    fl = x > fl ? x : fl;
+  }
+  fl = block_max(fl);
+  if (tid == 0) {
+    floor_s = (uint32_t)(fl >> 32);  // score bits only: entries that tie with the floor stay
+    n_surv = 0;
+  }
+  __syncthreads();
+  const uint32_t floor_bits = floor_s;
+  // 2. Survivors into LDS.
+  for (int i = tid; i < T; i += 256) {
+    const unsigned long long x = key_at(i);
+    if (x != 0ull && (uint32_t)(x >> 32) >= floor_bits) {
+      const int slot = atomicAdd(&n_surv, 1);
+      if (slot < kPoolSurv) surv[slot] = x;
+    }
+  }
+  __syncthreads();
+  const int ns = n_surv;
+  if (ns <= kPoolSurv) {
+    // 3. k rounds of arg-max over the survivors; the entries of a chosen document are erased.
+    for (int round = 0; round < k; ++round) {
+      unsigned long long best = 0ull;
+      for (int i = tid; i < ns; i += 256) best = surv[i] > best ? surv[i] : best;
+      best = block_max(best);
+      if (tid == 0) {
+        out_idx[o_base + round] = best ? (int32_t)key_doc(best) : -1;
+        if (out_score) out_score[o_base + round] = best ? key_score(best) : -INFINITY;
+      }
+      if (best != 0ull) {
+        const uint32_t low = (uint32_t)best;  // ~doc: identical for every entry of that document
+        for (int i = tid; i < ns; i += 256)
+          if ((uint32_t)surv[i] == low) surv[i] = 0ull;
+      }
+      __syncthreads();
+    }
+    return;
+  }
+  // Fallback (more survivors than LDS holds): rounds over the lists in memory, skipping taken documents.
+  unsigned long long prev = ~0ull;
+  for (int round = 0; round < k; ++round) {
+    unsigned long long best = 0ull;
+    for (int i = tid; i < T; i += 256) {
+      const unsigned long long x = key_at(i);
+      if (x == 0ull || x >= prev || x <= best) continue;  // keys of one document differ in the score bits only
+      const uint32_t doc = key_doc(x);
+      bool dup = false;
+      for (int w = 0; w < round; ++w) dup = dup || taken[w] == doc;
+      if (!dup) best = x;
+    }
+    best = block_max(best);
     if (tid == 0) {
       out_idx[o_base + round] = best ? (int32_t)key_doc(best) : -1;
       if (out_score) out_score[o_base + round] = best ? key_score(best) : -INFINITY;

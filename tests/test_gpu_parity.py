@@ -713,3 +713,20 @@ def test_prefill_attention_shared_selection(name):
     fin = torch.isfinite(lse)
     assert torch.equal(torch.isfinite(l3), fin)
     assert d_out <= 2e-2 and (l3[fin] - lse[fin]).abs().max().item() <= 5e-3, d_out
+
+
+def test_token_pool_many_identical_tokens():
+    """Every token of the question is the same vector, so every per-token list survives the pooling
+    floor: more candidates than the pooling kernel keeps on chip, i.e. its in-memory path."""
+    say("case token_pool with 600 identical tokens (pooling fallback path)")
+    N, C, d, Hkv, r, M, k = 100, 8, 64, 1, 2, 600, 8
+    cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e4, token_pool=1)
+    _, KRb = S.normal_bf16(61000, (Hkv, N * C, d))
+    qb1, q1 = S.normal_bf16(61001, (1, 1, Hkv * r, d))
+    qb, q = np.repeat(qb1, M, axis=1), np.repeat(q1, M, axis=1)
+    inv = 1.0 / np.maximum(np.linalg.norm(KRb, axis=-1), O.EPS_NORM)
+    dKR, dinv = upload_oracle_index(cfg, KRb, inv)
+    idx, val = msa.msa_score_topk(cfg, dev(np.ascontiguousarray(qb)), dKR, dinv, k)
+    torch.cuda.synchronize()
+    assert tuple(idx.shape) == (1, 1, 1, k)
+    check_topk_generic(q, KRb, C, N, idx, val, k, "cos", "group", True)
