@@ -47,7 +47,8 @@ __device__ __forceinline__ float both_halves_sum(float x) {
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
                                                              int n_ttiles) {
   constexpr int HALF = D / 2;
   constexpr int NP = D / 8;          // 16-byte pieces per row
