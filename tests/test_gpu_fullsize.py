@@ -199,3 +199,63 @@ def test_fullsize_sampled_parity(name, plant, a):
         del Kbar, Vbar
     del wl, KR, inv
     torch.cuda.empty_cache()
+
+
+def test_fullsize_cfg4_question_level_routing():
+    """BASELINE config 4 with Eq. 2 as printed over the tokens (token_pool = 1): one selection per KV head
+    for the whole 2048-token question (GEMM scoring + token pooling), then the tiled shared-selection
+    attention kernel.  Sampled checks against the oracle as above."""
+    name = "cfg4_prefill_16m"
+    say(f"workload {name}, token_pool = 1")
+    wl = W.make(name, plant_per_query=0)
+    cfg = msa.MsaConfig(wl.N, wl.G, wl.P, wl.Hq, wl.Hkv, wl.d, wl.base, token_pool=1)
+    rng = np.random.default_rng(S.seed_for(wl.cfg_id, 78))
+    B, M, k = wl.B, wl.M, wl.k
+    KR, inv = msa.msa_build_routing_keys(cfg, wl.K)
+    idx, val = msa.msa_score_topk(cfg, wl.q, KR, inv, k)
+    torch.cuda.synchronize()
+    assert tuple(idx.shape) == (B, 1, wl.Hkv, k)
+    gi = idx.cpu().numpy().astype(np.int64)
+    gv = val.cpu().numpy().astype(np.float64)
+    assert gi.min() >= 0 and gi.max() < wl.N
+    others = rng.choice(wl.N, size=64, replace=False).tolist()
+    for b in range(B):
+        docs = sorted(set(gi[b, 0].reshape(-1).tolist()) | set(others))
+        Ks = np.stack([W.host_doc(wl, "K", int(i))[1] for i in docs])
+        KRb, _ = O.routing_keys(Ks, wl.P)
+        s = O.doc_scores(O.chunk_scores(wl.q_host[b:b + 1], KRb, token_pool=True), wl.C)[0, 0]   # [Hkv, n]
+        pos = {dd: i for i, dd in enumerate(docs)}
+        for g in range(wl.Hkv):
+            assert len(set(gi[b, 0, g].tolist())) == k and np.all(np.diff(gv[b, 0, g]) <= 0)
+            want = np.array([s[g, pos[int(dd)]] for dd in gi[b, 0, g]])
+            assert np.allclose(gv[b, 0, g], want, rtol=0, atol=1e-4), np.abs(gv[b, 0, g] - want).max()
+            kth = gv[b, 0, g, k - 1]
+            chosen = set(gi[b, 0, g].tolist())
+            for dd in others:
+                if dd not in chosen:
+                    assert s[g, pos[dd]] <= kth + 1e-3 * abs(kth) + 1e-4
+    say("   pooled top-k ok")
+    out, lse = msa.msa_sparse_attend(cfg, wl.q, wl.K, wl.V, idx, wl.Kloc, wl.Vloc, wl.pos0, wl.q_pos)
+    torch.cuda.synchronize()
+    go = out.float().cpu().numpy().astype(np.float64)
+    gl = lse.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(go)) and np.all(np.isfinite(gl))
+    per_bg = wl.Lloc * wl.d
+    for b, m, g in ((0, 0, 0), (B - 1, M // 3, 3), (B - 1, M - 1, wl.Hkv - 1)):
+        docs = gi[b, 0, g]
+        K_sel = np.stack([W.host_doc(wl, "K", int(i))[1][g:g + 1] for i in docs])
+        V_sel = np.stack([W.host_doc(wl, "V", int(i))[1][g:g + 1] for i in docs])
+        start = (b * wl.Hkv + g) * per_bg
+        Kl = S.normal_bf16(wl.seeds["Kloc"], (1, 1, wl.Lloc, wl.d), start=start)[1]
+        Vl = S.normal_bf16(wl.seeds["Vloc"], (1, 1, wl.Lloc, wl.d), start=start)[1]
+        qh = wl.q_host[b:b + 1, m:m + 1, g * wl.r:(g + 1) * wl.r]
+        oo, ol = O.sparse_attend(qh, K_sel, V_sel, np.arange(k)[None, None, None], Kl, Vl, wl.pos0,
+                                 wl.q_pos_host[b:b + 1, m:m + 1], wl.base)
+        got = go[b, m, g * wl.r:(g + 1) * wl.r]
+        err = np.abs(got - oo[0, 0])
+        rel = np.linalg.norm(err) / np.linalg.norm(oo)
+        say(f"   shared-selection attend (b={b}, m={m}, g={g}): max-abs {err.max():.3e} rel-L2 {rel:.3e}")
+        assert err.max() <= 2e-2 and rel <= 5e-3
+        assert np.allclose(gl[b, m, g * wl.r:(g + 1) * wl.r], ol[0, 0], rtol=0, atol=5e-3)
+    del wl, KR, inv
+    torch.cuda.empty_cache()
