@@ -47,7 +47,7 @@ def parse():
                     help="max over the query tokens of a batch row (Eq. 2 as printed): one selection per batch row, "
                          "and for many tokens the tiled shared-selection attention kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-docs", type=int, default=512)
+    ap.add_argument("--cpu-sample-docs", type=int, default=1024)
     return ap.parse_args()
 
 
@@ -73,7 +73,7 @@ def cpu_baseline(wl, sample_docs):
     KRb, _ = O.routing_keys(Ks, wl.P)
     t_build = time.perf_counter() - t0
     kk = min(wl.k, n_s)
-    reps = 3
+    reps = 10
     t0 = time.perf_counter()
     for _ in range(reps):
         idx, val, _ = O.score_topk(q, KRb, wl.C, kk)

@@ -189,6 +189,27 @@ int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t
                       void* out, float* lse, void* workspace, size_t workspace_bytes,
                       msa_stream_t stream);
 
+/*
+ * Tiered bank (Section 3.4.2): the K/V of the whole bank stay in HOST memory and only the selected documents
+ * travel to the device, into a staging bank that msa_sparse_attend then reads.
+ *   K_host, V_host  in   bf16 [N][Hkv][G][d] in pinned host memory that is mapped into the device's address
+ *                        space (hipHostMalloc; anything else is refused with MSA_ERR_INVALID_ARG): one
+ *                        kernel reads it directly over the host link
+ *   idx             in   DEVICE int32 [B][M'][S][k] as msa_score_topk writes it for cfg
+ *   K_stage,V_stage out  DEVICE bf16 [n_slots][Hkv][G][d], n_slots = msa_fetch_slots(cfg, B, M, k) = B*M'*k.
+ *                        Entry (b, m', j) owns slot (b*M' + m')*k + j; of a slot only the (slot, g) slabs of
+ *                        the KV heads g that select for that entry are written (all Hkv when S = 1)
+ *   idx_stage       out  DEVICE int32 [B][M'][S][k]: the slot of every entry, -1 for entries that are -1 or
+ *                        outside [0, N)
+ * Then call msa_sparse_attend with a config whose n_docs = n_slots (everything else as cfg), K = K_stage,
+ * V = V_stage, idx = idx_stage: the result is bit-identical to attending the bank in device memory.
+ * Asynchronous on `stream`; there is no host synchronisation inside.
+ */
+int64_t msa_fetch_slots(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k);
+int msa_fetch_selected(const msa_config_t* cfg, const void* K_host, const void* V_host, const int32_t* idx,
+                       int32_t B, int32_t M, int32_t k, void* K_stage, void* V_stage, int32_t* idx_stage,
+                       msa_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ MSA_OK, MSA_ERR_INVALID_ARG, MSA_ERR_UNSUPPORTED, MSA_ERR_WORKSPACE, MSA_ERR_MIS
 EXPORTS = ("msa_version", "msa_status_string", "msa_routing_keys_bytes", "msa_inv_norm_bytes",
            "msa_pooled_bank_bytes", "msa_score_topk_workspace_bytes",
            "msa_sparse_attend_workspace_bytes", "msa_build_routing_keys", "msa_pool_kv", "msa_score_topk",
-           "msa_sparse_attend")
+           "msa_sparse_attend", "msa_fetch_slots", "msa_fetch_selected")
 
 
 class MsaConfig(ctypes.Structure):
@@ -82,6 +82,10 @@ def load_library():
     lib.msa_build_routing_keys.argtypes = [cfgp, vp, i32, i32, vp, vp, vp]
     lib.msa_pool_kv.restype = ctypes.c_int
     lib.msa_pool_kv.argtypes = [cfgp, vp, vp, i32, i32, vp, vp, vp]
+    lib.msa_fetch_slots.restype = ctypes.c_int64
+    lib.msa_fetch_slots.argtypes = [cfgp, i32, i32, i32]
+    lib.msa_fetch_selected.restype = ctypes.c_int
+    lib.msa_fetch_selected.argtypes = [cfgp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.msa_score_topk.restype = ctypes.c_int
     lib.msa_score_topk.argtypes = [cfgp, vp, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.msa_sparse_attend.restype = ctypes.c_int
@@ -229,3 +233,32 @@ def msa_sparse_attend(cfg, q, K, V, idx, Kloc, Vloc, local_pos0, q_pos, out=None
                                           _ptr(lse), _ptr(workspace), workspace.numel(), _stream(stream, dev))
     _check(rc, "msa_sparse_attend")
     return out, lse
+
+
+def fetch_slots(cfg, B, M, k):
+    return load_library().msa_fetch_slots(ctypes.byref(cfg), B, M, k)
+
+
+def msa_fetch_selected(cfg, K_host, V_host, idx, B, M, K_stage=None, V_stage=None, idx_stage=None, stream=None):
+    """K_host, V_host: pinned host bf16 [N][Hkv][G][d]; idx: device int32 [B][M'][S][k] ->
+    (K_stage, V_stage device bf16 [n_slots][Hkv][G][d], idx_stage device int32 like idx, staging config)."""
+    if not (K_host.is_pinned() and V_host.is_pinned() and K_host.dtype == torch.bfloat16 and
+            V_host.dtype == torch.bfloat16 and K_host.is_contiguous() and V_host.is_contiguous()):
+        raise ValueError("K_host, V_host: expected contiguous pinned host tensors of torch.bfloat16")
+    _need(idx, torch.int32, "idx")
+    k = idx.shape[-1]
+    n_slots = fetch_slots(cfg, B, M, k)
+    shape = (n_slots, cfg.n_kv_heads, cfg.doc_len, cfg.head_dim)
+    dev = idx.device
+    if K_stage is None:
+        K_stage = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    if V_stage is None:
+        V_stage = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    if idx_stage is None:
+        idx_stage = torch.empty_like(idx)
+    rc = load_library().msa_fetch_selected(ctypes.byref(cfg), _ptr(K_host), _ptr(V_host), _ptr(idx), B, M, k,
+                                           _ptr(K_stage), _ptr(V_stage), _ptr(idx_stage), _stream(stream, dev))
+    _check(rc, "msa_fetch_selected")
+    scfg = MsaConfig(n_slots, cfg.doc_len, cfg.chunk, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rope_base,
+                     cfg.sim, cfg.select_scope, cfg.token_pool, cfg.bank_keys_rotated)
+    return K_stage, V_stage, idx_stage, scfg

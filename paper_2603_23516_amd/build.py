@@ -12,7 +12,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 
 LIBMSA = os.path.join(HERE, "libmsa.so")
 LIBMSA_SRC = [os.path.join(HERE, "csrc", f) for f in
-              ("msa_api.hip", "msa_build.hip", "msa_pool.hip", "msa_score.hip", "msa_score_gemm.hip", "msa_attend.hip", "msa_attend_prefill.hip")]
+              ("msa_api.hip", "msa_build.hip", "msa_pool.hip", "msa_score.hip", "msa_score_gemm.hip", "msa_attend.hip", "msa_attend_prefill.hip", "msa_fetch.hip")]
 LIBSYNTH = os.path.join(ROOT, "msa_synth", "libmsa_synth.so")
 LIBSYNTH_SRC = [os.path.join(ROOT, "msa_synth", "csrc", "synth_fill.hip")]
 LIBPROBE = os.path.join(ROOT, "tests", "libmsa_probe.so")

@@ -136,6 +136,48 @@ int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t d
   return launch_pool_kv(dm, K, V, doc_begin, doc_count, Kbar, Vbar, (hipStream_t)stream);
 }
 
+int64_t msa_fetch_slots(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k) {
+  Dims dm;
+  if (make_dims(cfg, &dm, kForAttend) != MSA_OK) return 0;
+  if (B < 1 || M < 1 || k < 1 || k > MSA_MAX_TOPK) return 0;
+  return (int64_t)B * (dm.token_pool ? 1 : M) * k;
+}
+
+int msa_fetch_selected(const msa_config_t* cfg, const void* K_host, const void* V_host,
+                       const int32_t* idx, int32_t B, int32_t M, int32_t k, void* K_stage,
+                       void* V_stage, int32_t* idx_stage, msa_stream_t stream) {
+  Dims dm;
+  const int rc = make_dims(cfg, &dm, kForAttend);
+  if (rc != MSA_OK) return rc;
+  if (K_host == nullptr || V_host == nullptr || idx == nullptr || K_stage == nullptr ||
+      V_stage == nullptr || idx_stage == nullptr)
+    return MSA_ERR_INVALID_ARG;
+  if (B < 1 || M < 1 || k < 1) return MSA_ERR_INVALID_ARG;
+  if (k > MSA_MAX_TOPK) return MSA_ERR_UNSUPPORTED;
+  if (((int64_t)dm.G * dm.d * 2) % 16 != 0) return MSA_ERR_UNSUPPORTED;
+  if (misaligned(K_host) || misaligned(V_host) || misaligned(idx) || misaligned(K_stage) ||
+      misaligned(V_stage) || misaligned(idx_stage))
+    return MSA_ERR_MISALIGNED;
+  // the kernel dereferences the host bank: it must be pinned and mapped into the device's address space
+  void* Kd = nullptr;
+  void* Vd = nullptr;
+  {
+    hipPointerAttribute_t ka, va;
+    const bool k_ok = hipPointerGetAttributes(&ka, K_host) == hipSuccess && ka.type == hipMemoryTypeHost &&
+                      ka.devicePointer != nullptr;
+    const bool v_ok = k_ok && hipPointerGetAttributes(&va, V_host) == hipSuccess &&
+                      va.type == hipMemoryTypeHost && va.devicePointer != nullptr;
+    if (!k_ok || !v_ok) {
+      (void)hipGetLastError();  // clear the sticky error of a failed query
+      return MSA_ERR_INVALID_ARG;
+    }
+    Kd = ka.devicePointer;
+    Vd = va.devicePointer;
+  }
+  const long long n_rows = (long long)B * (dm.token_pool ? 1 : M);
+  return launch_fetch(dm, Kd, Vd, idx, n_rows, k, K_stage, V_stage, idx_stage, (hipStream_t)stream);
+}
+
 int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
                    const void* KR, const float* inv_norm, int32_t k, int32_t* out_idx,
                    float* out_score, void* workspace, size_t workspace_bytes, msa_stream_t stream) {

@@ -36,7 +36,6 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
 // pure function of the arguments).
 struct ScorePlan {
   int n_splits;          // blocks per KV head
-  int tiles_per_split;
   int q_per_pass;        // queries scored per launch (8 or 16)
   int n_pass;
   int exchange;          // 1: waves exchange running maxima to tighten their thresholds
@@ -79,6 +78,10 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
                   int bank_keys_rotated, hipStream_t st);
 int launch_pool_kv(const Dims& dm, const void* K, const void* V, int doc_begin, int doc_count,
                    void* Kbar, void* Vbar, hipStream_t st);
+
+int launch_fetch(const Dims& dm, const void* K_dev_view, const void* V_dev_view, const int32_t* idx,
+                 long long n_rows, int k, void* K_stage, void* V_stage, int32_t* idx_stage,
+                 hipStream_t st);
 
 inline size_t round_up256(size_t x) { return (x + 255) & ~(size_t)255; }
 

@@ -37,7 +37,7 @@ struct ScoreArgs {
   int Hq, Hkv, r;
   int N, C, cos;
   long long tiles;
-  int tiles_per_split, n_splits, k;
+  int n_splits, k;
   float* gmax;              // [Hkv][BM][n_splits] running per-wave maxima (threshold exchange), or null
   int it_publish, it_adopt; // iterations at which a wave publishes its maxima / adopts the bound
 };
@@ -840,7 +840,6 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
   if (p.use_gemm) {
     p.gemm = plan_score_gemm(dm, BM, k);
     p.n_splits = p.gemm.n_splits;
-    p.tiles_per_split = 0;
     p.q_per_pass = BM;
     p.n_pass = 1;
     p.exchange = 0;
@@ -863,8 +862,8 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
   if (ns > by_tiles) ns = by_tiles;
   if (ns > 1024 && !p.all_heads) ns = 1024;
   if (ns < 1) ns = 1;
-  p.tiles_per_split = (int)((dm.tiles + ns - 1) / ns);
-  p.n_splits = (int)((dm.tiles + p.tiles_per_split - 1) / p.tiles_per_split);
+  const long long tiles_per_split = (dm.tiles + ns - 1) / ns;
+  p.n_splits = (int)((dm.tiles + tiles_per_split - 1) / tiles_per_split);
   const size_t list_bytes = round_up256((size_t)p.n_sel * BM * p.n_splits * k * sizeof(unsigned long long));
   // threshold exchange between waves: worth it (and sound) only for long streams with >= k waves per head
   const long long n_it_min = dm.tiles / p.n_splits;
@@ -925,7 +924,6 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
   a.C = dm.C;
   a.cos = dm.cos;
   a.tiles = dm.tiles;
-  a.tiles_per_split = pl.tiles_per_split;
   a.n_splits = pl.n_splits;
   a.k = k;
   a.gmax = pl.exchange ? (float*)((char*)ws + pl.off_gmax) : nullptr;

@@ -160,6 +160,26 @@ def test_argument_validation_before_launch(lib):
     assert lib.msa_pool_kv(ctypes.byref(_cfg(head_dim=96)), p, p, 0, 1, p, p, None) == E.MSA_ERR_UNSUPPORTED
 
 
+def test_fetch_validation(lib):
+    c = _cfg()
+    cb = ctypes.byref(c)
+    p = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x10008)
+    E = msa
+    assert msa.fetch_slots(c, 2, 5, 4) == 2 * 5 * 4
+    assert msa.fetch_slots(_cfg(token_pool=1), 2, 5, 4) == 2 * 4
+    assert msa.fetch_slots(c, 2, 5, 65) == 0
+    f = lib.msa_fetch_selected
+    assert f(cb, None, p, p, 1, 1, 4, p, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, None, 1, 1, 4, p, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, p, 1, 1, 4, p, p, None, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, p, 0, 1, 4, p, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, p, 1, 1, 65, p, p, p, None) == E.MSA_ERR_UNSUPPORTED
+    assert f(cb, odd, p, p, 1, 1, 4, p, p, p, None) == E.MSA_ERR_MISALIGNED
+    # a bank that is not pinned, device-mapped host memory is refused before anything is launched
+    assert f(cb, p, p, p, 1, 1, 4, p, p, p, None) == E.MSA_ERR_INVALID_ARG
+
+
 def test_literal_eq2_variants_are_planned(lib):
     """select_scope = ALL and token_pool = 1 are valid requests with their own workspace sizes."""
     base = msa.score_topk_workspace_bytes(_cfg(), 2, 5, 4)

@@ -730,3 +730,56 @@ def test_token_pool_many_identical_tokens():
     torch.cuda.synchronize()
     assert tuple(idx.shape) == (1, 1, 1, k)
     check_topk_generic(q, KRb, C, N, idx, val, k, "cos", "group", True)
+
+
+# ------------------------------------------------------------------------------------------------
+# tiered bank: K/V in pinned host memory, selected documents fetched into a staging bank (Section 3.4.2)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("scope,pool", [("group", 0), ("all", 0), ("group", 1)])
+def test_fetch_selected_from_host_bank(scope, pool):
+    seed, N, Hkv, r, G, d, B, M, Lloc, base, k = 71000, 60, 2, 4, 128, 128, 2, 9, 40, 1e6, 5
+    say(f"tiered bank: N={N} Hkv={Hkv} r={r} G={G} d={d} B={B} M={M} Lloc={Lloc} k={k} scope={scope} token_pool={pool}")
+    case = Case(seed, N, Hkv, r, G, d, G, B, M, Lloc, base).to_device()
+    cfg = case.cfg(select_scope=msa.MSA_SCOPE_ALL if scope == "all" else msa.MSA_SCOPE_GROUP, token_pool=pool)
+    Kh = torch.empty(case.dK.shape, dtype=torch.bfloat16, pin_memory=True)
+    Vh = torch.empty(case.dV.shape, dtype=torch.bfloat16, pin_memory=True)
+    Kh.copy_(case.dK)
+    Vh.copy_(case.dV)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(seed)
+    Mi, S_ = (1 if pool else M), (1 if scope == "all" else Hkv)
+    sel = np.stack([rng.permutation(N)[:k] for _ in range(B * Mi * S_)]).reshape(B, Mi, S_, k)
+    sel[0, 0, 0, 1] = -1
+    sel[-1, -1, -1, 0] = N + 7                                      # outside the bank: skipped like a pad
+    didx = torch.from_numpy(sel.astype(np.int32)).cuda()
+    pos0 = G
+    q_pos = np.array([[pos0 + (5 * m + b) % Lloc for m in range(M)] for b in range(B)])
+    dpos = torch.from_numpy(q_pos.astype(np.int32)).cuda()
+    Ks, Vs, idx_s, scfg = msa.msa_fetch_selected(cfg, Kh, Vh, didx, B, M)
+    torch.cuda.synchronize()
+    assert scfg.n_docs == B * Mi * k
+    gi = idx_s.cpu().numpy()
+    want_slots = np.broadcast_to((np.arange(B * Mi).reshape(B, Mi, 1, 1) * k + np.arange(k)), sel.shape)
+    valid = (sel >= 0) & (sel < N)
+    assert np.array_equal(gi[valid], want_slots[valid]) and np.all(gi[~valid] == -1)
+    for b, m, sl, j in zip(*np.nonzero(valid)):                     # every fetched slab equals the bank's
+        heads = range(Hkv) if S_ == 1 else [sl]
+        for g in heads:
+            slot = (b * Mi + m) * k + j
+            assert torch.equal(Ks[slot, g].view(torch.int16), case.dK[sel[b, m, sl, j], g].view(torch.int16))
+            assert torch.equal(Vs[slot, g].view(torch.int16), case.dV[sel[b, m, sl, j], g].view(torch.int16))
+    out_t, lse_t = msa.msa_sparse_attend(scfg, case.dq, Ks, Vs, idx_s, case.dKl, case.dVl, pos0, dpos)
+    out_d, lse_d = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, didx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    assert torch.equal(out_t.view(torch.int16), out_d.view(torch.int16)) and torch.equal(lse_t, lse_d)
+    sel_o = np.where(valid, sel, -1)
+    check_attend(case, out_t, lse_t, sel_o, pos0, q_pos)
+    say("   a bank that is not pinned host memory is refused")
+    with pytest.raises(msa.MsaError) as e:
+        rc = msa.load_library().msa_fetch_selected(ctypes.byref(cfg), ctypes.c_void_p(case.dK.data_ptr()),
+                                                    ctypes.c_void_p(case.dV.data_ptr()), ctypes.c_void_p(didx.data_ptr()),
+                                                    B, M, k, ctypes.c_void_p(Ks.data_ptr()), ctypes.c_void_p(Vs.data_ptr()),
+                                                    ctypes.c_void_p(idx_s.data_ptr()), None)
+        if rc != 0:
+            raise msa.MsaError(rc, "msa_fetch_selected")
+    assert e.value.status == msa.MSA_ERR_INVALID_ARG
