@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--token-pool", action="store_true",
                     help="max over the query tokens of a batch row (Eq. 2 as printed): one selection per batch row, "
                          "and for many tokens the tiled shared-selection attention kernel")
+    ap.add_argument("--tier", default="hbm", choices=("hbm", "host"),
+                    help="host: additionally time the tiered bank of Section 3.4.2 (K/V in pinned host memory, the "
+                         "selected documents fetched over the host link); reported in \"host_tier\", never in value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-docs", type=int, default=1024)
     return ap.parse_args()
@@ -96,6 +99,41 @@ def cpu_baseline(wl, sample_docs):
                    f"of 1 query, 1 of {wl.Hkv} KV groups over {kk} documents + {wl.Lloc} local tokens "
                    f"{t_att:.3f}s (scaled x{wl.Hkv}); pooling {n_s} documents {t_build:.3f}s (offline, not in value)"),
     }
+
+
+def host_tier(msa, wl, cfg, KR, inv, idx, val, ws_s, out, lse, stream, steps):
+    """The same step with the K/V bank in pinned host memory: score+top-k, fetch of the selected documents
+    into a staging bank (one kernel reading host memory over the host link), attention over the staging bank."""
+    import torch
+    Kh = torch.empty(wl.K.shape, dtype=torch.bfloat16, pin_memory=True)
+    Vh = torch.empty(wl.V.shape, dtype=torch.bfloat16, pin_memory=True)
+    Kh.copy_(wl.K)
+    Vh.copy_(wl.V)
+    torch.cuda.synchronize()
+    B, M, k = wl.B, wl.M, wl.k
+    Ks, Vs, idx_s, scfg = msa.msa_fetch_selected(cfg, Kh, Vh, idx, B, M)
+    ws_a = torch.empty(msa.sparse_attend_workspace_bytes(scfg, B, M, k, wl.Lloc), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for i in range(steps):
+        ev[i][0].record(stream)
+        msa.msa_score_topk(cfg, wl.q, KR, inv, k, idx, val, ws_s, stream=stream)
+        ev[i][1].record(stream)
+        msa.msa_fetch_selected(cfg, Kh, Vh, idx, B, M, Ks, Vs, idx_s, stream=stream)
+        ev[i][2].record(stream)
+        msa.msa_sparse_attend(scfg, wl.q, Ks, Vs, idx_s, wl.Kloc, wl.Vloc, wl.pos0, wl.q_pos, out, lse, ws_a,
+                              stream=stream)
+        ev[i][3].record(stream)
+    torch.cuda.synchronize()
+    fetch_ms = sum(e[1].elapsed_time(e[2]) for e in ev[1:]) / (steps - 1)
+    step_ms = sum(e[0].elapsed_time(e[3]) for e in ev[1:]) / (steps - 1)
+    n_sel = idx.shape[2]
+    heads_per_entry = wl.Hkv if n_sel == 1 else 1
+    fetched = idx.numel() * heads_per_entry * wl.G * wl.d * 2 * 2
+    return {"fetch_ms": fetch_ms, "fetched_bytes": fetched, "fetch_GBps": fetched / (fetch_ms * 1e-3) / 1e9,
+            "ms_per_step": step_ms, "queries_per_s": B * M / (step_ms * 1e-3),
+            "host_bank_bytes": 2 * Kh.numel() * 2,
+            "note": "host-link inclusive; serial on one stream (no overlap with the next layer's scoring)"}
 
 
 def main():
@@ -218,6 +256,8 @@ def main():
                   "frac": build_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": ab["build"],
                   "ms": build_ms, "note": "offline Stage 1, once per bank version; outside the timed steps"},
     }
+    if args.tier == "host" and args.bank == "full":
+        res["host_tier"] = host_tier(msa, wl, cfg, KR, inv, idx, val, ws_s, out, lse, stream, min(args.steps, 20))
     if pool_ms is not None:
         res["pool"] = {"bound": "hbm", "achieved": ab["pool"] / (pool_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                        "unit": "GB/s", "frac": ab["pool"] / (pool_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
