@@ -279,6 +279,9 @@ void score_scan_kernel(ScoreArgs a) {
         const long long doc = t * dpt + ndoc;
         const bool lead = lead_lane && it < n_it && doc < a.N;
         bool over = false;
+        // scores first; the slot arithmetic runs only for tiles in which some lane passes its threshold
+        float scv[NQT][2];
+        bool any_pred = false;
 #pragma unroll
         for (int tq = 0; tq < NQT; ++tq) {
           f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -287,17 +290,28 @@ void score_scan_kernel(ScoreArgs a) {
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
             const float sc = group_max_rt((acc[2 * e] + acc[2 * e + 1]) * cinv, a.C);
+            scv[tq][e] = sc;
             if (lead) qmax[tq][e] = fmaxf(qmax[tq][e], sc);
-            const bool pred = lead && sc >= thr[tq][e];
-            const unsigned long long m = __ballot(pred);
-            const uint32_t half = (rr & 2) ? (uint32_t)(m >> 32) : (uint32_t)m;
-            const uint32_t row = (half >> ((rr & 1) * 16)) & 0xffffu;
-            if (pred) {
-              const int qi = 8 * tq + 2 * rr + e;
-              cand[qi * CAP + cnt[tq][e] + __popc(row & below)] = make_key(sc, (uint32_t)doc);
+            any_pred = any_pred || (lead && sc >= thr[tq][e]);
+          }
+        }
+        if (__any(any_pred)) {
+#pragma unroll
+          for (int tq = 0; tq < NQT; ++tq) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              const float sc = scv[tq][e];
+              const bool pred = lead && sc >= thr[tq][e];
+              const unsigned long long m = __ballot(pred);
+              const uint32_t half = (rr & 2) ? (uint32_t)(m >> 32) : (uint32_t)m;
+              const uint32_t row = (half >> ((rr & 1) * 16)) & 0xffffu;
+              if (pred) {
+                const int qi = 8 * tq + 2 * rr + e;
+                cand[qi * CAP + cnt[tq][e] + __popc(row & below)] = make_key(sc, (uint32_t)doc);
+              }
+              cnt[tq][e] += __popc(row);
+              over = over || cnt[tq][e] > limit;
             }
-            cnt[tq][e] += __popc(row);
-            over = over || cnt[tq][e] > limit;
           }
         }
         if (__any(over)) {
