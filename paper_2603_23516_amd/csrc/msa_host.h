@@ -38,6 +38,9 @@ struct ScorePlan {
   int n_splits;          // blocks per KV head
   int q_per_pass;        // queries scored per launch (8 or 16)
   int n_pass;
+  int mode;              // scan mode: 0 filter, 1 dense lists, 2 score matrix + row top-k
+  int tiles_per_wave;    // mode 2: contiguous tiles per wave
+  size_t off_mat;        // mode 2: byte offset of the fp32 score matrix [Hkv][BM][N]
   int exchange;          // 1: waves exchange running maxima to tighten their thresholds
   int it_publish, it_adopt;
   size_t off_gmax;       // byte offset of the exchange buffer inside the workspace

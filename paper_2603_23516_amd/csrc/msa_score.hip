@@ -38,6 +38,8 @@ struct ScoreArgs {
   int N, C, cos;
   long long tiles;
   int n_splits, k;
+  float* mat;               // MODE 2: document scores [Hkv][BM][N]
+  int tiles_per_wave;       // MODE 2: contiguous tiles per wave
   float* gmax;              // [Hkv][BM][n_splits] running per-wave maxima (threshold exchange), or null
   int it_publish, it_adopt; // iterations at which a wave publishes its maxima / adopts the bound
 };
@@ -102,17 +104,25 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
-// Independent streams (waves) per workgroup.  Four for the 8-query kernel: measured 5 % faster than
-// single-wave workgroups on the 50M-token scan; the register-heavy multi-tile variants stay at one.
-constexpr int scan_waves(int nqt) { return nqt == 1 ? 4 : 1; }
+// Independent streams (waves) per workgroup: measured 3-5 % faster than single-wave workgroups.
+constexpr int kScanWaves = 4;
 
-template <int D, int NQT, bool COS>
-__global__ __launch_bounds__(64 * scan_waves(NQT)) __attribute__((amdgpu_waves_per_eu(2)))
+// MODE 0  filter: thresholds, candidate lists, pruning (long streams).
+// MODE 1  dense lists: a wave's whole stream holds no more documents than a list has slots, so every
+//         document score goes straight to slot (iteration, document-in-tile) of its query's list and
+//         the lists are sorted once at the end; no thresholds, ballots or counters in the stream.
+// MODE 2  score matrix: like MODE 1 but the wave owns a CONTIGUOUS range of tiles and, instead of
+//         sorting, writes the fp32 document scores of every query as one coalesced run of the row
+//         mat[g][query][:]; topk_rows_kernel then selects per row.  For short streams (small banks,
+//         many queries) the per-wave sorts and the list merge cost more than the stream itself.
+template <int D, int NQT, bool COS, int MODE>
+__global__ __launch_bounds__(64 * kScanWaves) __attribute__((amdgpu_waves_per_eu(2)))
 void score_scan_kernel(ScoreArgs a) {
-  constexpr int kScanWaves = scan_waves(NQT);
+  constexpr bool DENSE = MODE != 0;
   constexpr int NS = D / 32;   // MFMA k-slices per key
   constexpr int NQ = 8 * NQT;  // queries per pass
   constexpr int CAP = kListBytes / (8 * NQ);
+  constexpr int CAPF = kListBytes / (4 * NQ);  // MODE 2: fp32 scores per query
   constexpr int TILE_ELEMS = 16 * D;
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[kScanWaves][kListBytes];
@@ -120,6 +130,7 @@ void score_scan_kernel(ScoreArgs a) {
   __shared__ float thr_all[kScanWaves][NQ];
   const int wave = threadIdx.x >> 6;
   unsigned long long* cand = reinterpret_cast<unsigned long long*>(smem[wave]);  // [NQ][CAP]
+  float* candf = reinterpret_cast<float*>(smem[wave]);                            // MODE 2: [NQ][CAPF]
   int* cnt_s = cnt_all[wave];
   float* thr_s = thr_all[wave];
 
@@ -135,15 +146,18 @@ void score_scan_kernel(ScoreArgs a) {
   // read one contiguous window of the index.  Loads past the end re-read the last tile: they are
   // always issued, so the number of loads in flight is the same on every path.
   const long long S = a.n_splits;
-  const long long n_it = (a.tiles - sp + S - 1) / S;  // >= 1 because n_splits <= tiles
+  const long long t0 = (long long)sp * a.tiles_per_wave;  // MODE 2: first tile of this wave
+  const long long n_it = (MODE == 2) ? ((a.tiles - t0 < a.tiles_per_wave) ? a.tiles - t0 : a.tiles_per_wave)
+                                     : (a.tiles - sp + S - 1) / S;  // >= 1 by construction of n_splits
   const long long i_last = n_it - 1;
+  auto tile_at = [&](long long it) { return (MODE == 2) ? t0 + it : sp + it * S; };
   const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS + lane * 8;
   const float* ing = COS ? a.inv_norm + (long long)g * a.tiles * 16 + n : nullptr;
   uint4 buf[kPrefetch][NS];
   float binv[kPrefetch];
 #pragma unroll
   for (int u = 0; u < kPrefetch; ++u) {
-    const long long t = sp + ((u < n_it) ? u : i_last) * S;
+    const long long t = tile_at((u < n_it) ? u : i_last);
 #pragma unroll
     for (int s = 0; s < NS; ++s)
       buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512);
@@ -194,7 +208,7 @@ void score_scan_kernel(ScoreArgs a) {
       // seen per query; a little later it adopts theta = the k-th largest of all published maxima.
       // The maxima belong to distinct documents, so at least k documents score >= theta: a valid
       // lower bound on the k-th best score whatever the other waves have written so far.
-      if (kEarlyFetch && a.gmax != nullptr && base == a.it_adopt - kFetchLead * kPrefetch) {
+      if (!DENSE && kEarlyFetch && a.gmax != nullptr && base == a.it_adopt - kFetchLead * kPrefetch) {
 #pragma unroll
         for (int qi = 0; qi < (kEarlyFetch ? NQ : 1); ++qi) {
           const int qg = a.q0 + qi < a.BM ? a.q0 + qi : a.BM - 1;
@@ -204,7 +218,7 @@ void score_scan_kernel(ScoreArgs a) {
             exq[qi][j] = (lane + 64 * j < a.n_splits) ? src[lane + 64 * j] : -INFINITY;
         }
       }
-      if (a.gmax != nullptr && (base == a.it_publish || base == a.it_adopt)) {
+      if (!DENSE && a.gmax != nullptr && (base == a.it_publish || base == a.it_adopt)) {
         if (base == a.it_publish) {
 #pragma unroll
           for (int tq = 0; tq < NQT; ++tq)
@@ -263,13 +277,13 @@ void score_scan_kernel(ScoreArgs a) {
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {
         const long long it = base + u;
-        const long long t = sp + it * S;
+        const long long t = tile_at(it);
         uint4 cur[NS];
 #pragma unroll
         for (int s = 0; s < NS; ++s) cur[s] = buf[u][s];
         const float cinv = binv[u];
         {
-          const long long tn = sp + ((it + kPrefetch < n_it) ? it + kPrefetch : i_last) * S;
+          const long long tn = tile_at((it + kPrefetch < n_it) ? it + kPrefetch : i_last);
 #pragma unroll
           for (int s = 0; s < NS; ++s)
             buf[u][s] = *reinterpret_cast<const uint4*>(KRg + tn * TILE_ELEMS + s * 512);
@@ -290,12 +304,18 @@ void score_scan_kernel(ScoreArgs a) {
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
             const float sc = group_max_rt((acc[2 * e] + acc[2 * e + 1]) * cinv, a.C);
-            scv[tq][e] = sc;
-            if (lead) qmax[tq][e] = fmaxf(qmax[tq][e], sc);
-            any_pred = any_pred || (lead && sc >= thr[tq][e]);
+            if (MODE == 2) {
+              if (lead) candf[(8 * tq + 2 * rr + e) * CAPF + (int)it * dpt + ndoc] = sc;
+            } else if (MODE == 1) {
+              if (lead) cand[(8 * tq + 2 * rr + e) * CAP + (int)it * dpt + ndoc] = make_key(sc, (uint32_t)doc);
+            } else {
+              scv[tq][e] = sc;
+              if (lead) qmax[tq][e] = fmaxf(qmax[tq][e], sc);
+              any_pred = any_pred || (lead && sc >= thr[tq][e]);
+            }
           }
         }
-        if (__any(any_pred)) {
+        if (!DENSE && __any(any_pred)) {
 #pragma unroll
           for (int tq = 0; tq < NQT; ++tq) {
 #pragma unroll
@@ -360,10 +380,27 @@ void score_scan_kernel(ScoreArgs a) {
     }
   }
   wave_sync();
+  // MODE 1, 2: every list holds the same documents, those of the wave's tiles in order; only the
+  // last tile of the index can end early
+  int c_dense = 0;
+  if (DENSE) {
+    const long long left = (long long)a.N - tile_at(i_last) * dpt;
+    c_dense = (int)i_last * dpt + (int)(left < dpt ? (left < 0 ? 0 : left) : dpt);
+  }
+  if (MODE == 2) {
+    const long long doc0 = t0 * dpt;  // the wave's documents are doc0 .. doc0 + c_dense - 1
+    for (int qi = 0; qi < NQ; ++qi) {
+      const int qg = a.q0 + qi;
+      if (qg >= a.BM) break;  // wave-uniform
+      float* row = a.mat + ((long long)g * a.BM + qg) * a.N + doc0;
+      for (int j = lane; j < c_dense; j += 64) row[j] = candf[qi * CAPF + j];
+    }
+    return;
+  }
   for (int qi = 0; qi < NQ; ++qi) {
     const int qg = a.q0 + qi;
     if (qg >= a.BM) break;  // wave-uniform
-    const int c = cnt_s[qi];
+    const int c = DENSE ? c_dense : cnt_s[qi];
     unsigned long long* cl = cand + qi * CAP;
     const int nc = prune_list<CAP>(cl, c, a.k, lane);
     unsigned long long* dst = a.ws + (((long long)g * a.BM + qg) * a.n_splits + sp) * a.k;
@@ -640,6 +677,118 @@ __global__ __launch_bounds__(256) void pool_tokens_kernel(const unsigned long lo
   }
 }
 
+// Top-k of one row of document scores (MODE 2 of the scan): mat[g][qg][0..N).  One workgroup per row.
+//   1. every thread takes the best key of its strided share of the row; the k-th best of these 256
+//      keys (rank counting) is a lower bound theta on the k-th best key of the row: they are k distinct
+//      documents scoring at least that much;
+//   2. every key >= theta goes to LDS (typically between k and 2k of them) and is ranked by counting.
+// Exact, ties included (keys are (score, ~doc): a total order).  If more survive than LDS holds
+// (adversarial order), k rounds of a block-wide arg-max over the row take over.
+constexpr int kRowSurv = 2048;
+constexpr int kRowRegs = 32;  // scores a thread keeps in registers between the two passes
+
+__global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict__ mat,
+                                                        int32_t* __restrict__ out_idx,
+                                                        float* __restrict__ out_score,
+                                                        unsigned long long* __restrict__ out_key, int BM,
+                                                        int n_sel, int N, int k) {
+  __shared__ unsigned long long tmax[256];
+  __shared__ unsigned long long surv[kRowSurv];
+  __shared__ unsigned long long red[4];
+  __shared__ unsigned long long theta_s;
+  __shared__ int n_surv;
+  const int tid = threadIdx.x;
+  const int qg = blockIdx.x % BM;
+  const int g = blockIdx.x / BM;
+  const float* row = mat + ((long long)g * BM + qg) * N;
+  const long long o_base = ((long long)qg * n_sel + g) * k;
+  float v[kRowRegs];
+  unsigned long long best = 0ull;
+#pragma unroll
+  for (int u = 0; u < kRowRegs; ++u) {
+    const int i = u * 256 + tid;
+    v[u] = (i < N) ? row[i] : 0.f;
+  }
+#pragma unroll
+  for (int u = 0; u < kRowRegs; ++u) {
+    const int i = u * 256 + tid;
+    const unsigned long long x = (i < N) ? make_key(v[u], (uint32_t)i) : 0ull;
+    best = x > best ? x : best;
+  }
+  for (int i = kRowRegs * 256 + tid; i < N; i += 256) {  // rows longer than the register share
+    const unsigned long long x = make_key(row[i], (uint32_t)i);
+    best = x > best ? x : best;
+  }
+  tmax[tid] = best;
+  if (tid == 0) {
+    n_surv = 0;
+    theta_s = 0ull;
+  }
+  __syncthreads();
+  {
+    const int have = N < 256 ? N : 256;  // threads that hold a document
+    const int kk = k < have ? k : have;
+    int rank = 0;
+    for (int j = 0; j < 256; ++j) rank += (tmax[j] > best) ? 1 : 0;
+    if (best != 0ull && rank == kk - 1) theta_s = best;  // keys are distinct
+  }
+  __syncthreads();
+  const unsigned long long theta = theta_s;
+  auto keep = [&](unsigned long long x) {
+    if (x != 0ull && x >= theta) {
+      const int slot = atomicAdd(&n_surv, 1);
+      if (slot < kRowSurv) surv[slot] = x;
+    }
+  };
+#pragma unroll
+  for (int u = 0; u < kRowRegs; ++u) {
+    const int i = u * 256 + tid;
+    keep((i < N) ? make_key(v[u], (uint32_t)i) : 0ull);
+  }
+  for (int i = kRowRegs * 256 + tid; i < N; i += 256) keep(make_key(row[i], (uint32_t)i));
+  __syncthreads();
+  const int ns = n_surv;
+  auto emit = [&](int rank, unsigned long long x) {
+    if (out_key) {
+      out_key[o_base + rank] = x;
+    } else {
+      out_idx[o_base + rank] = x ? (int32_t)key_doc(x) : -1;
+      if (out_score) out_score[o_base + rank] = x ? key_score(x) : -INFINITY;
+    }
+  };
+  if (ns <= kRowSurv) {
+    for (int i = tid; i < ns; i += 256) {
+      const unsigned long long x = surv[i];
+      int rank = 0;
+      for (int j = 0; j < ns; ++j) rank += (surv[j] > x) ? 1 : 0;
+      if (rank < k) emit(rank, x);
+    }
+    for (int i = ns + tid; i < k; i += 256) emit(i, 0ull);  // fewer than k documents (cannot happen for k <= N)
+    return;
+  }
+  unsigned long long prev = ~0ull;
+  for (int round = 0; round < k; ++round) {
+    unsigned long long bst = 0ull;
+    for (int i = tid; i < N; i += 256) {
+      const unsigned long long x = make_key(row[i], (uint32_t)i);
+      if (x < prev && x > bst) bst = x;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const unsigned long long y = __shfl_xor(bst, off, 64);
+      bst = y > bst ? y : bst;
+    }
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = bst;
+    __syncthreads();
+    bst = red[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) bst = red[w] > bst ? red[w] : bst;
+    if (tid == 0) emit(round, bst);
+    prev = bst ? bst : 0ull;
+  }
+}
+
 // Combine the n_lists sorted lists (k entries each, zero-padded) of one (query, group).
 //   1. A lower bound theta on the k-th best key: the first j+1 entries of every list, with
 //      n_lists*(j+1) >= k, are that many distinct candidates, so their k-th largest is one.
@@ -857,6 +1006,9 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
     p.q_per_pass = BM;
     p.n_pass = 1;
     p.exchange = 0;
+    p.mode = 0;
+    p.tiles_per_wave = 0;
+    p.off_mat = 0;
     p.it_publish = p.it_adopt = 0;
     p.off_gmax = 0;
     p.off_qop = 0;
@@ -881,7 +1033,25 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
   const size_t list_bytes = round_up256((size_t)p.n_sel * BM * p.n_splits * k * sizeof(unsigned long long));
   // threshold exchange between waves: worth it (and sound) only for long streams with >= k waves per head
   const long long n_it_min = dm.tiles / p.n_splits;
-  p.exchange = (!p.all_heads && n_it_min >= 64 && p.n_splits >= k && p.n_splits <= 256) ? 1 : 0;
+  // Short streams: nothing to filter.  MODE 2 (score matrix + row top-k) when its fp32 rows fit the
+  // lists' LDS and the matrix stays small; else MODE 1 (dense lists) when the lists hold the stream.
+  p.mode = 0;
+  p.tiles_per_wave = 0;
+  if (!p.all_heads) {
+    const long long dpt = 16 / dm.C;
+    const long long n_it_max = (dm.tiles + p.n_splits - 1) / p.n_splits;
+    const long long cap = kListBytes / (8 * p.q_per_pass), capf = kListBytes / (4 * p.q_per_pass);
+    const size_t mat_bytes = (size_t)dm.Hkv * BM * dm.N * sizeof(float);
+    const long long L = n_it_max < kPrefetch ? kPrefetch : n_it_max;
+    if (L * dpt <= capf && L <= 64 && mat_bytes <= ((size_t)256 << 20)) {
+      p.mode = 2;
+      p.tiles_per_wave = (int)L;
+      p.n_splits = (int)((dm.tiles + L - 1) / L);
+    } else if (n_it_max * dpt <= cap) {
+      p.mode = 1;
+    }
+  }
+  p.exchange = (!p.all_heads && p.mode == 0 && n_it_min >= 64 && p.n_splits >= k && p.n_splits <= 256) ? 1 : 0;
   // exchange events sit at the head of a group of kPrefetch iterations
   p.it_publish = (int)(n_it_min / 12) / kPrefetch * kPrefetch;
   p.it_adopt = p.it_publish + 3 * kPrefetch;
@@ -889,6 +1059,8 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
   p.off_qop = list_bytes + (p.exchange ? round_up256((size_t)dm.Hkv * BM * p.n_splits * sizeof(float)) : 0);
   p.n_qtiles = p.n_pass * (p.q_per_pass / 8);
   p.ws_bytes = p.off_qop + round_up256((size_t)dm.Hkv * p.n_qtiles * (dm.d / 32) * 64 * 16);
+  p.off_mat = p.ws_bytes;
+  if (p.mode == 2) p.ws_bytes += round_up256((size_t)dm.Hkv * BM * dm.N * sizeof(float));
   add_token_pool(dm, BM, k, &p);
   return p;
 }
@@ -944,6 +1116,8 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
   a.it_publish = pl.it_publish;
   a.it_adopt = pl.it_adopt;
   a.qop = (const uint4*)((char*)ws + pl.off_qop);
+  a.mat = (pl.mode == 2) ? (float*)((char*)ws + pl.off_mat) : nullptr;
+  a.tiles_per_wave = pl.tiles_per_wave;
   a.n_qtiles = pl.n_qtiles;
   {
     const long long n_gmax = pl.exchange ? (long long)dm.Hkv * BM * pl.n_splits : 0;
@@ -958,7 +1132,7 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
                          dm.r, dm.cos, pl.n_qtiles, a.gmax, n_gmax);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
-  const int wpb = pl.all_heads ? kAllWaves : scan_waves(pl.q_per_pass / 8);
+  const int wpb = pl.all_heads ? kAllWaves : kScanWaves;
   dim3 grid((pl.n_splits + wpb - 1) / wpb, pl.all_heads ? 1 : dm.Hkv), block(64 * wpb);
   for (int pass = 0; pass < pl.n_pass; ++pass) {
     a.q0 = pass * pl.q_per_pass;
@@ -978,7 +1152,12 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
       continue;
     }
     const int nqt = pl.q_per_pass / 8;  // 1, 2 or 4
-#define MSA_SCAN(DD, QQ, CC) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC>), grid, block, 0, st, a)
+#define MSA_SCAN(DD, QQ, CC) \
+  do { \
+    if (pl.mode == 2) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 2>), grid, block, 0, st, a); \
+    else if (pl.mode == 1) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 1>), grid, block, 0, st, a); \
+    else hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 0>), grid, block, 0, st, a); \
+  } while (0)
     if (dm.d == 128) {
       if (dm.cos) {
         if (nqt == 1) MSA_SCAN(128, 1, true); else if (nqt == 2) MSA_SCAN(128, 2, true); else MSA_SCAN(128, 4, true);
@@ -994,6 +1173,12 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
     }
 #undef MSA_SCAN
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+  }
+  if (pl.mode == 2) {
+    hipLaunchKernelGGL(topk_rows_kernel, dim3(BM * pl.n_sel), dim3(256), 0, st, (const float*)a.mat, out_idx,
+                       out_score, tok_keys, BM, pl.n_sel, dm.N, k);
+    if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+    return pool_tokens();
   }
   return merge((const unsigned long long*)ws, pl.n_splits);
 }

@@ -431,11 +431,14 @@ def test_single_document_bank():
     check_attend(case, out, lse, idx.cpu().numpy().astype(np.int64), 64, q_pos)
 
 
-def test_score_long_streams_threshold_exchange():
-    """Scoring alone on a synthetic routing index long enough (64+ tiles per wave, >= k waves per
-    head) for the waves to exchange running maxima; the oracle scores the same index."""
-    say("case long streams: N=32768 docs, C=8, d=64, Hkv=8, B=3, k=16")
-    N, C, d, Hkv, r, B, k = 32768, 8, 64, 8, 2, 3, 16
+@pytest.mark.parametrize("N", [40000, 70000])
+def test_score_long_streams_threshold_exchange(N):
+    """Scoring alone on synthetic routing indexes with long per-wave streams; the oracle scores the same
+    index.  N = 40000: 79 tiles per wave, every document still fits the wave's lists (dense lists, no
+    filtering).  N = 70000: 137 tiles per wave, the filtering scan with its threshold exchange between
+    waves.  (Shorter streams take the score-matrix path, which all the small cases cover.)"""
+    say(f"case long streams: N={N} docs, C=8, d=64, Hkv=8, B=3, k=16")
+    C, d, Hkv, r, B, k = 8, 64, 8, 2, 3, 16
     cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e4)
     _, KRb = S.normal_bf16(12000, (Hkv, N * C, d))
     qb, q = S.normal_bf16(12001, (B, 1, Hkv * r, d))
@@ -783,3 +786,18 @@ def test_fetch_selected_from_host_bank(scope, pool):
         if rc != 0:
             raise msa.MsaError(rc, "msa_fetch_selected")
     assert e.value.status == msa.MSA_ERR_INVALID_ARG
+
+
+def test_all_scores_equal_more_than_on_chip_survivors():
+    """3000 documents with all-zero keys: every score ties at 0, so every document survives any
+    threshold (more than the row top-k keeps on chip): the in-memory path, and the tie-break by index."""
+    say("case 3000 all-zero documents: ties everywhere")
+    N, Hkv, r, G, d, P, B, k = 3000, 1, 2, 64, 64, 64, 2, 9
+    cfg = msa.MsaConfig(N, G, P, Hkv * r, Hkv, d, 1e4)
+    K = torch.zeros((N, Hkv, G, d), dtype=torch.bfloat16, device="cuda")
+    qb, _ = S.normal_bf16(81000, (B, 1, Hkv * r, d))
+    KR, inv = msa.msa_build_routing_keys(cfg, K)
+    idx, val = msa.msa_score_topk(cfg, dev(qb), KR, inv, k)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), np.broadcast_to(np.arange(k), (B, 1, Hkv, k)))
+    assert np.all(val.cpu().numpy() == 0)
