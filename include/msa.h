@@ -8,6 +8,11 @@
  *                           top-k documents (Section 3.2.1)
  *   msa_sparse_attend       context assembly (Eq. 3) with document-wise RoPE (Section 3.2.2) and
  *                           attention (Eq. 4) over [selected documents ; local context]
+ * and two around them:
+ *   msa_pool_kv             offline: the pooled, position-encoded bank K-bar, V-bar of Stage 1 that Eq. 3
+ *                           concatenates as printed (attended with bank_keys_rotated = 1)
+ *   msa_fetch_selected      the host-DRAM tier of Section 3.4.2: gathers the selected documents from a
+ *                           pinned host bank into a device staging bank
  *
  * Notation: N documents, G tokens per document, P chunk size, C = G/P chunks per document,
  * Hq query heads, Hkv key/value heads, r = Hq/Hkv, d head dimension, B sequences, M query tokens per
@@ -15,8 +20,9 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers (HIP), 16-byte aligned, dense, row-major in the index
- *     order written next to them; bf16 = bfloat16 bit patterns (uint16_t).  The config struct is a
- *     HOST pointer and is read before the call returns.
+ *     order written next to them (the one exception, the pinned host bank of msa_fetch_selected, says
+ *     so); bf16 = bfloat16 bit patterns (uint16_t).  The config struct is a HOST pointer and is read
+ *     before the call returns.
  *   - Ownership: the caller owns every buffer, workspace included.  The library allocates nothing,
  *     frees nothing and keeps no state between calls.
  *   - Asynchrony: work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
@@ -54,7 +60,7 @@ enum { MSA_MAX_TOPK = 64 };
 typedef struct msa_config {
   int32_t n_docs;       /* N >= 1                                                                  */
   int32_t doc_len;      /* G, tokens per document; G % P == 0; msa_sparse_attend needs G % 32 == 0
-                           (or G in {8, 16} with bank_keys_rotated)                                */
+                           (or G in {1, 2, 4, 8, 16} with bank_keys_rotated)                       */
   int32_t chunk;        /* P, pooling size (paper: 64); must divide G.  Routing: P % 8 == 0 and C = G/P in
                            {1, 2, 4, 8, 16}; msa_pool_kv: P % 8 == 0; msa_sparse_attend does not read it */
   int32_t n_q_heads;    /* Hq, multiple of Hkv; r = Hq/Hkv <= 8                                    */
@@ -71,7 +77,7 @@ typedef struct msa_config {
   int32_t bank_keys_rotated; /* msa_sparse_attend only.  0: the bank holds raw keys, rotated in the gather with
                            positions 0..G-1 (default).  1: the bank's keys already carry their positions
                            (the pooled bank written by msa_pool_kv) and are used as stored; then doc_len
-                           may also be 8 or 16                                                      */
+                           may also be 1, 2, 4, 8 or 16                                             */
 } msa_config_t;
 
 /* Library version (major * 100 + minor). */
