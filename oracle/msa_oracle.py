@@ -56,59 +56,87 @@ def bf16_round(x):
 # --------------------------------------------------------------------------------------------
 # Section 3.2.1, chunk-wise mean pooling phi(.)  ->  routing keys
 # --------------------------------------------------------------------------------------------
-def pool_chunks(K, P):
+def chunk_valid(lens, G, P):
+    """Documents of different lengths (the paper's G is an average, Section 5.1) in slots of G tokens:
+    document i holds lens[i] <= G tokens, i.e. ceil(lens[i] / P) chunks, the last one possibly short.
+    Returns valid [N*C] bool: chunk j of document i exists iff j * P < lens[i]."""
+    lens = np.asarray(lens, dtype=np.int64)
+    C = G // P
+    assert np.all((lens >= 0) & (lens <= G))
+    return (np.arange(C)[None, :] * P < lens[:, None]).reshape(-1)
+
+
+def pool_chunks(K, P, lens=None):
     """phi(K): mean over each fixed-length chunk of P tokens (Section 3.2.1, after Eq. 1).
 
-    K  [N, Hkv, G, d]  ->  [Hkv, N*C, d], row i*C + j is chunk j of document i."""
+    K  [N, Hkv, G, d]  ->  [Hkv, N*C, d], row i*C + j is chunk j of document i.  With lens (document
+    lengths, see chunk_valid) a chunk is the mean over the tokens the document really has in it (the
+    tail chunk is short); chunks past the end are zero."""
     K = np.asarray(K, dtype=np.float64)
     N, Hkv, G, d = K.shape
     assert G % P == 0
     C = G // P
-    out = np.empty((Hkv, N * C, d), dtype=np.float64)
+    out = np.zeros((Hkv, N * C, d), dtype=np.float64)
     for i in range(N):
+        n_i = G if lens is None else int(lens[i])
         for g in range(Hkv):
             for j in range(C):
-                out[g, i * C + j, :] = K[i, g, j * P:(j + 1) * P, :].sum(axis=0) / P
+                hi = min((j + 1) * P, n_i)
+                if hi > j * P:
+                    out[g, i * C + j, :] = K[i, g, j * P:hi, :].sum(axis=0) / (hi - j * P)
     return out
 
 
-def routing_keys(K, P):
+def routing_keys(K, P, lens=None):
     """The stored routing index: pooled keys rounded to bfloat16, and 1/max(norm, eps) of the
-    ROUNDED key (what the scoring stage multiplies by).  Returns (KRb [Hkv,N*C,d], inv_norm [Hkv,N*C])."""
-    KRb = bf16_round(pool_chunks(K, P))
+    ROUNDED key (what the scoring stage multiplies by).  Returns (KRb [Hkv,N*C,d], inv_norm [Hkv,N*C]).
+    With lens, chunks past a document's end carry inv_norm = -1: the stored mark of "no such chunk"
+    (a real reciprocal norm is positive)."""
+    KRb = bf16_round(pool_chunks(K, P, lens))
     nrm = np.sqrt((KRb * KRb).sum(axis=-1))
-    return KRb, 1.0 / np.maximum(nrm, EPS_NORM)
+    inv = 1.0 / np.maximum(nrm, EPS_NORM)
+    if lens is not None:
+        inv[:, ~chunk_valid(lens, K.shape[2], P)] = -1.0
+    return KRb, inv
 
 
-def pool_rotated_keys(K, P, base):
+def pool_rotated_keys(K, P, base, lens=None):
     """K-bar of Stage 1 (Section 3.4.1): the document is encoded with its own positions 0..G-1
     (Section 3.2.2), then chunk-mean pooled (Section 3.2.1): mean over each chunk of RoPE(K[i,g,t], t).
-    K [N,Hkv,G,d] -> [N,Hkv,C,d] (exact float64; the stored bank is bf16_round of this)."""
+    K [N,Hkv,G,d] -> [N,Hkv,C,d] (exact float64; the stored bank is bf16_round of this).  With lens a
+    chunk is the mean over the tokens the document has in it; chunks past the end are zero."""
     K = np.asarray(K, dtype=np.float64)
     N, Hkv, G, d = K.shape
     assert G % P == 0
     C = G // P
-    out = np.empty((N, Hkv, C, d), dtype=np.float64)
+    out = np.zeros((N, Hkv, C, d), dtype=np.float64)
     pos = np.arange(G)
     for i in range(N):
+        n_i = G if lens is None else int(lens[i])
         for g in range(Hkv):
             rot = rope(K[i, g], pos, base)
             for j in range(C):
-                out[i, g, j, :] = rot[j * P:(j + 1) * P, :].sum(axis=0) / P
+                hi = min((j + 1) * P, n_i)
+                if hi > j * P:
+                    out[i, g, j, :] = rot[j * P:hi, :].sum(axis=0) / (hi - j * P)
     return out
 
 
-def pool_values(V, P):
-    """V-bar = phi(V): chunk-wise mean of the values (Section 3.2.1).  [N,Hkv,G,d] -> [N,Hkv,C,d]."""
+def pool_values(V, P, lens=None):
+    """V-bar = phi(V): chunk-wise mean of the values (Section 3.2.1).  [N,Hkv,G,d] -> [N,Hkv,C,d];
+    lens as in pool_rotated_keys."""
     V = np.asarray(V, dtype=np.float64)
     N, Hkv, G, d = V.shape
     assert G % P == 0
     C = G // P
-    out = np.empty((N, Hkv, C, d), dtype=np.float64)
+    out = np.zeros((N, Hkv, C, d), dtype=np.float64)
     for i in range(N):
+        n_i = G if lens is None else int(lens[i])
         for g in range(Hkv):
             for j in range(C):
-                out[i, g, j, :] = V[i, g, j * P:(j + 1) * P, :].sum(axis=0) / P
+                hi = min((j + 1) * P, n_i)
+                if hi > j * P:
+                    out[i, g, j, :] = V[i, g, j * P:hi, :].sum(axis=0) / (hi - j * P)
     return out
 
 
@@ -125,8 +153,9 @@ def similarity(x, Y, sim="cos"):
     return dots / (nx * ny)
 
 
-def chunk_scores(qr, KRb, sim="cos", select_scope="group", token_pool=False):
-    """Eq. 2.  qr [B,M,Hq,d], KRb [Hkv,NC,d]  ->  Sc [B, M', S, NC].
+def chunk_scores(qr, KRb, sim="cos", select_scope="group", token_pool=False, valid=None):
+    """Eq. 2.  qr [B,M,Hq,d], KRb [Hkv,NC,d]  ->  Sc [B, M', S, NC].  valid [NC] bool (documents of
+    different lengths, see chunk_valid): a chunk that does not exist scores -inf.
 
     Head h is compared with the routing keys of its own KV head g = h // r.  The head mean is
     taken first, at chunk level; select_scope="group" averages the r heads of each group
@@ -149,6 +178,8 @@ def chunk_scores(qr, KRb, sim="cos", select_scope="group", token_pool=False):
         Sc = per_head.sum(axis=2, keepdims=True) / Hq
     else:
         raise ValueError(select_scope)
+    if valid is not None:
+        Sc[..., ~np.asarray(valid, dtype=bool)] = -np.inf
     if token_pool:
         Sc = Sc.max(axis=1, keepdims=True)
     return Sc
@@ -179,9 +210,9 @@ def topk_docs(s, k):
     return idx.reshape(s.shape[:-1] + (k,)), val.reshape(s.shape[:-1] + (k,))
 
 
-def score_topk(qr, KRb, C, k, sim="cos", select_scope="group", token_pool=False):
+def score_topk(qr, KRb, C, k, sim="cos", select_scope="group", token_pool=False, valid=None):
     """Eq. 2 -> document max -> top-k, chained.  Returns (idx, val, s) with s the document scores."""
-    s = doc_scores(chunk_scores(qr, KRb, sim, select_scope, token_pool), C)
+    s = doc_scores(chunk_scores(qr, KRb, sim, select_scope, token_pool, valid), C)
     idx, val = topk_docs(s, k)
     return idx, val, s
 
@@ -235,7 +266,7 @@ def merge_partials(parts):
     return out, top + np.log(w.sum())
 
 
-def assemble_context(K, V, doc_ids, g, Kloc_bg, Vloc_bg, pos0, q_pos, base, mem_rotated=False):
+def assemble_context(K, V, doc_ids, g, Kloc_bg, Vloc_bg, pos0, q_pos, base, mem_rotated=False, lens=None):
     """Eq. 3 with document-wise RoPE (Section 3.2.2).  K, V [N,Hkv,G,d]; doc_ids: the selected
     documents of this (query, scope), -1 entries skipped; Kloc_bg, Vloc_bg [Lloc,d] or None.
 
@@ -243,17 +274,19 @@ def assemble_context(K, V, doc_ids, g, Kloc_bg, Vloc_bg, pos0, q_pos, base, mem_
     (positions restart in every document).  With mem_rotated=True the bank's keys already carry
     their positions (the pooled bank of Stage 1, see pool_rotated_keys) and are used as stored.
     Local token t sits at position pos0 + t and is visible iff pos0 + t <= q_pos.
+    lens [N]: document i contributes only its first lens[i] rows (positions 0..lens[i]-1).
     Returns (keys [n,d], vals [n,d])."""
     G, d = K.shape[2], K.shape[3]
     keys, vals = [], []
     for i in doc_ids:
         if i < 0:
             continue
+        n_i = G if lens is None else int(lens[i])
         if mem_rotated:
-            keys.append(np.asarray(K[i, g], dtype=np.float64))
+            keys.append(np.asarray(K[i, g, :n_i], dtype=np.float64))
         else:
-            keys.append(rope(K[i, g], np.arange(G), base))
-        vals.append(np.asarray(V[i, g], dtype=np.float64))
+            keys.append(rope(K[i, g, :n_i], np.arange(n_i), base))
+        vals.append(np.asarray(V[i, g, :n_i], dtype=np.float64))
     if Kloc_bg is not None and Kloc_bg.shape[0] > 0:
         t = np.arange(Kloc_bg.shape[0])
         vis = (pos0 + t) <= q_pos
@@ -265,7 +298,7 @@ def assemble_context(K, V, doc_ids, g, Kloc_bg, Vloc_bg, pos0, q_pos, base, mem_
     return np.concatenate(keys, axis=0), np.concatenate(vals, axis=0)
 
 
-def sparse_attend(q, K, V, idx, Kloc, Vloc, pos0, q_pos, base, mem_rotated=False):
+def sparse_attend(q, K, V, idx, Kloc, Vloc, pos0, q_pos, base, mem_rotated=False, lens=None):
     """Eq. 3-4 for every query.  q [B,M,Hq,d]; K,V [N,Hkv,G,d]; idx [B,M',S,k] (M' in {1,M},
     S in {1,Hkv}); Kloc,Vloc [B,Hkv,Lloc,d] or None; q_pos [B,M] int.
 
@@ -284,7 +317,8 @@ def sparse_attend(q, K, V, idx, Kloc, Vloc, pos0, q_pos, base, mem_rotated=False
                 ids = idx[b, m if Mi > 1 else 0, g if S > 1 else 0]
                 kl = None if Kloc is None else Kloc[b, g]
                 vl = None if Vloc is None else Vloc[b, g]
-                keys, vals = assemble_context(K, V, ids, g, kl, vl, pos0, int(q_pos[b, m]), base, mem_rotated)
+                keys, vals = assemble_context(K, V, ids, g, kl, vl, pos0, int(q_pos[b, m]), base, mem_rotated,
+                                              lens)
                 for h in range(g * r, (g + 1) * r):
                     qt = rope(q[b, m, h], np.float64(q_pos[b, m]), base)
                     out[b, m, h], lse[b, m, h] = softmax_attend(qt, keys, vals)

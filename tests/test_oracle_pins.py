@@ -479,3 +479,118 @@ def test_synth_slices_and_distribution():
     assert not np.array_equal(S.normal_bf16_bits(1, 0, 64), S.normal_bf16_bits(2, 0, 64))
     t = S.bf16_bits_to_f64(S.quantile_table())
     assert np.all(np.diff(t) >= 0) and t[0] < -4 and t[-1] > 4 and np.allclose(t, -t[::-1])
+
+
+# --------------------------------------------------------------------------------------------
+# documents of different lengths (lens): tail chunks, chunks that do not exist, shorter contexts
+# --------------------------------------------------------------------------------------------
+def _ragged_case(seed=900):
+    rng = np.random.default_rng(seed)
+    N, Hkv, r, G, d, P = 7, 2, 2, 32, 8, 8
+    K = rng.standard_normal((N, Hkv, G, d))
+    V = rng.standard_normal((N, Hkv, G, d))
+    q = rng.standard_normal((2, 3, Hkv * r, d))
+    lens = np.array([32, 5, 0, 17, 8, 31, 24])
+    return N, Hkv, r, G, d, P, K, V, q, lens
+
+
+def test_ragged_full_lengths_reduce_to_uniform():
+    N, Hkv, r, G, d, P, K, V, q, _ = _ragged_case()
+    full = np.full(N, G)
+    a, ai = O.routing_keys(K, P)
+    b, bi = O.routing_keys(K, P, full)
+    assert np.array_equal(a, b) and np.array_equal(ai, bi)
+    assert np.all(O.chunk_valid(full, G, P))
+    assert np.array_equal(O.pool_rotated_keys(K, P, 1e4), O.pool_rotated_keys(K, P, 1e4, full))
+    assert np.array_equal(O.pool_values(V, P), O.pool_values(V, P, full))
+    idx = np.tile(np.arange(3), (2, 3, Hkv, 1))
+    qp = np.full((2, 3), G + 4)
+    o1, l1 = O.sparse_attend(q, K, V, idx, None, None, G, qp, 1e4)
+    o2, l2 = O.sparse_attend(q, K, V, idx, None, None, G, qp, 1e4, lens=full)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_ragged_chunks_closed_forms():
+    N, Hkv, r, G, d, P, K, V, q, lens = _ragged_case()
+    C = G // P
+    valid = O.chunk_valid(lens, G, P)
+    assert valid.reshape(N, C).sum(axis=1).tolist() == [-(-int(n) // P) for n in lens]     # ceil(len / P) chunks
+    # rows that are constant inside a document: every existing chunk, the short tail included, is that row
+    Kc = np.broadcast_to(K[:, :, :1, :], K.shape)
+    pooled = O.pool_chunks(Kc, P, lens)
+    for i in range(N):
+        for j in range(C):
+            want = Kc[i, :, 0, :] if j * P < lens[i] else 0.0
+            assert np.allclose(pooled[:, i * C + j, :], want, rtol=1e-15, atol=0)
+    # the tail chunk is the mean over the tokens that exist, not over P
+    i, j = 3, 2                                                                           # lens[3] = 17: one token in chunk 2
+    assert np.allclose(O.pool_chunks(K, P, lens)[:, i * C + j, :], K[i, :, 16, :], rtol=1e-15)
+    assert np.allclose(O.pool_values(V, P, lens)[i, :, j, :], V[i, :, 16, :], rtol=1e-15)
+    assert np.allclose(O.pool_rotated_keys(K, P, 1e4, lens)[i, :, j, :], O.rope(K[i, :, 16, :], 16, 1e4), rtol=1e-13)
+    KRb, inv = O.routing_keys(K, P, lens)
+    assert np.all(inv[:, ~valid] == -1.0) and np.all(inv[:, valid] > 0)
+    # chunks that do not exist score -inf; the empty document ranks last and a full ranking lists it last
+    Sc = O.chunk_scores(q, KRb, valid=valid)
+    assert np.all(np.isneginf(Sc[..., ~valid])) and np.all(np.isfinite(Sc[..., valid]))
+    idx, val, s = O.score_topk(q, KRb, C, N, valid=valid)
+    assert np.all(idx[..., -1] == 2) and np.all(np.isneginf(val[..., -1]))
+    # scores of existing chunks do not depend on what lies past the end of a document
+    K2 = K.copy()
+    for i in range(N):
+        K2[i, :, lens[i]:, :] = 99.0
+    KRb2, inv2 = O.routing_keys(K2, P, lens)
+    assert np.array_equal(KRb2[:, valid], KRb[:, valid]) and np.array_equal(inv2, inv)
+
+
+def test_ragged_attention_is_attention_over_the_existing_tokens():
+    """k = N and lens given: plain softmax attention (PyTorch SDPA, float64) over the concatenation of the
+    rows every document really has, each rotated by its in-document position with the complex form of RoPE
+    written out here, plus the visible local rows."""
+    import torch
+    N, Hkv, r, G, d, P, K, V, q, lens = _ragged_case(901)
+    base, Lloc, pos0 = 1e4, 6, 11
+    rng = np.random.default_rng(5)
+    Kl = rng.standard_normal((2, Hkv, Lloc, d))
+    Vl = rng.standard_normal((2, Hkv, Lloc, d))
+    q_pos = np.array([[pos0 + 5, pos0 + 2, pos0 - 1], [pos0, pos0 + 3, pos0 + 5]])
+    idx = np.tile(np.arange(N), (2, 3, Hkv, 1))
+    out, lse = O.sparse_attend(q, K, V, idx, Kl, Vl, pos0, q_pos, base, lens=lens)
+
+    def rot(x, p):                                                   # (x_u + i x_{u+d/2}) * exp(i p theta_u)
+        th = base ** (-2.0 * np.arange(d // 2) / d)
+        z = (x[..., :d // 2] + 1j * x[..., d // 2:]) * np.exp(1j * np.asarray(p)[..., None] * th)
+        return np.concatenate([z.real, z.imag], axis=-1)
+    for b in range(2):
+        for m in range(3):
+            for h in range(Hkv * r):
+                g = h // r
+                ks = [rot(K[i, g, :lens[i]], np.arange(lens[i])) for i in range(N)]
+                vs = [V[i, g, :lens[i]] for i in range(N)]
+                nv = int(np.clip(q_pos[b, m] - pos0 + 1, 0, Lloc))
+                ks.append(rot(Kl[b, g, :nv], pos0 + np.arange(nv)))
+                vs.append(Vl[b, g, :nv])
+                kk, vv = np.concatenate(ks), np.concatenate(vs)
+                assert kk.shape[0] == lens.sum() + nv
+                qq = rot(q[b, m, h], q_pos[b, m])
+                want = torch.nn.functional.scaled_dot_product_attention(
+                    torch.from_numpy(qq)[None, None], torch.from_numpy(kk)[None], torch.from_numpy(vv)[None])[0, 0].numpy()
+                assert np.allclose(out[b, m, h], want, rtol=1e-12, atol=1e-13)
+
+
+def test_ragged_whole_chunk_lengths_equal_a_shorter_uniform_bank():
+    """Documents that all have the same length n < G (a multiple of P): the existing chunks and the attention
+    are those of the uniform bank cut to n tokens."""
+    N, Hkv, r, G, d, P, K, V, q, _ = _ragged_case(902)
+    n = 16
+    lens = np.full(N, n)
+    valid = O.chunk_valid(lens, G, P)
+    KRb, inv = O.routing_keys(K, P, lens)
+    KRs, invs = O.routing_keys(K[:, :, :n], P)
+    assert np.array_equal(KRb[:, valid], KRs) and np.array_equal(inv[:, valid], invs)
+    i1, v1, _ = O.score_topk(q, KRb, G // P, 3, valid=valid)
+    i2, v2, _ = O.score_topk(q, KRs, n // P, 3)
+    assert np.array_equal(i1, i2) and np.allclose(v1, v2, rtol=1e-13, atol=0)    # BLAS blocks the two shapes differently
+    qp = np.full((2, 3), G)
+    o1, l1 = O.sparse_attend(q, K, V, i1, None, None, G, qp, 1e4, lens=lens)
+    o2, l2 = O.sparse_attend(q, K[:, :, :n], V[:, :, :n], i1, None, None, G, qp, 1e4)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
