@@ -78,6 +78,12 @@ typedef struct msa_config {
                            positions 0..G-1 (default).  1: the bank's keys already carry their positions
                            (the pooled bank written by msa_pool_kv) and are used as stored; then doc_len
                            may also be 1, 2, 4, 8 or 16                                             */
+  const int32_t* doc_lens; /* NULL: every document holds G tokens.  Else DEVICE int32 [N]: document i holds
+                           doc_lens[i] tokens, stored in the first rows of its G-row slot of the bank (the
+                           paper's G is an average document length, Section 5.1); the kernels clamp each
+                           value to [1, G].  Read by msa_build_routing_keys, msa_pool_kv,
+                           msa_sparse_attend and msa_fetch_selected; msa_score_topk does not need it (the
+                           index already accounts for the lengths)                                    */
 } msa_config_t;
 
 /* Library version (major * 100 + minor). */
@@ -121,6 +127,10 @@ size_t msa_sparse_attend_workspace_bytes(const msa_config_t* cfg, int32_t B, int
  *     KR(g, i*C + j, :) = bf16_rne( (1/P) * sum_{t in chunk j} K[i][g][t][:] )      fp32 accumulate
  *     inv_norm(g, i*C + j) = 1 / max(||KR(g, i*C + j, :)||, 1e-12)                   of the ROUNDED key
  * for documents i in [doc_begin, doc_begin + doc_count), so a bank can be built or updated in pieces.
+ * With cfg->doc_lens a document has ceil(len/P) chunks; its last chunk is the mean over the tokens it holds
+ * (phi averages the tokens of a chunk).  The slots of the chunks a document does not have repeat the
+ * document's chunk 0, key and norm: the document score is a max over chunks, so a repeated chunk never
+ * changes it and msa_score_topk reads the index with no knowledge of the lengths.
  *   K         in   bf16 [N][Hkv][G][d]   (whole bank; only the addressed documents are read)
  *   KR        out  bf16, tiled layout above (whole index; only the addressed keys are written)
  *   inv_norm  out  fp32 [Hkv][tiles*16]; may be NULL iff cfg->sim == MSA_SIM_DOT
@@ -135,12 +145,15 @@ int msa_build_routing_keys(const msa_config_t* cfg, const void* K, int32_t doc_b
  *     Vbar[i][g][j][:] = bf16_rne( (1/P) * sum_{t in chunk j} V[i][g][t][:] )
  * for documents i in [doc_begin, doc_begin + doc_count).  The result is a bank of N documents of C = G/P
  * entries that msa_sparse_attend reads with a config whose doc_len = C and bank_keys_rotated = 1
- * (context length M + k G/P, Section 5.1).
+ * (context length M + k G/P, Section 5.1).  With cfg->doc_lens the last chunk of a document is the mean over
+ * the tokens it holds, the rows of chunks it does not have are zero, and pooled_lens receives the number of
+ * chunks ceil(len/P) of every addressed document: the doc_lens of the pooled bank's config.
  *   K, V        in   bf16 [N][Hkv][G][d]
  *   Kbar, Vbar  out  bf16 [N][Hkv][C][d]   (either may be NULL to skip it)
+ *   pooled_lens out  int32 [N]; may be NULL; written only when cfg->doc_lens is given
  */
 int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t doc_begin,
-                int32_t doc_count, void* Kbar, void* Vbar, msa_stream_t stream);
+                int32_t doc_count, void* Kbar, void* Vbar, int32_t* pooled_lens, msa_stream_t stream);
 
 /*
  * Routing (Section 3.2.1, Eq. 2 and the text after it), fused so chunk scores never reach memory:
@@ -169,7 +182,8 @@ int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int3
 /*
  * Sparse attention (Eq. 3-4 with the position scheme of Section 3.2.2).  For query (b,m), head h of
  * KV group g, the keys are, in order:
- *     every token p < G of every document i = idx[b][m][g][j] >= 0:  RoPE(K[i][g][p][:], p)
+ *     every token p < G (p < doc_lens[i] when cfg->doc_lens is given) of every document
+ *         i = idx[b][m][g][j] >= 0:                                   RoPE(K[i][g][p][:], p)
  *     every local token t < Lloc with local_pos0 + t <= q_pos[b][m]:  RoPE(Kloc[b][g][t][:], local_pos0 + t)
  * with the matching un-rotated value rows, and
  *     out[b][m][h][:] = softmax_j( RoPE(q[b][m][h][:], q_pos[b][m]) . key_j / sqrt(d) ) . value_j
@@ -207,14 +221,19 @@ int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t
  *                        the KV heads g that select for that entry are written (all Hkv when S = 1)
  *   idx_stage       out  DEVICE int32 [B][M'][S][k]: the slot of every entry, -1 for entries that are -1 or
  *                        outside [0, N)
- * Then call msa_sparse_attend with a config whose n_docs = n_slots (everything else as cfg), K = K_stage,
+ *   lens_stage      out  DEVICE int32 [n_slots]: with cfg->doc_lens (then required, and only the rows a document
+ *                        holds are copied) the length of the document in every slot, the doc_lens of the staging
+ *                        bank's config; else ignored, may be NULL.  Lengths need one document per slot, so
+ *                        cfg->doc_lens with S = Hkv > 1 is MSA_ERR_UNSUPPORTED
+ * Then call msa_sparse_attend with a config whose n_docs = n_slots and doc_lens = lens_stage (or NULL; everything
+ * else as cfg), K = K_stage,
  * V = V_stage, idx = idx_stage: the result is bit-identical to attending the bank in device memory.
  * Asynchronous on `stream`; there is no host synchronisation inside.
  */
 int64_t msa_fetch_slots(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k);
 int msa_fetch_selected(const msa_config_t* cfg, const void* K_host, const void* V_host, const int32_t* idx,
                        int32_t B, int32_t M, int32_t k, void* K_stage, void* V_stage, int32_t* idx_stage,
-                       msa_stream_t stream);
+                       int32_t* lens_stage, msa_stream_t stream);
 
 #ifdef __cplusplus
 }

@@ -29,12 +29,29 @@ class MsaConfig(ctypes.Structure):
                 ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("rope_base", ctypes.c_float), ("sim", ctypes.c_int32),
                 ("select_scope", ctypes.c_int32), ("token_pool", ctypes.c_int32),
-                ("bank_keys_rotated", ctypes.c_int32)]
+                ("bank_keys_rotated", ctypes.c_int32), ("doc_lens", ctypes.c_void_p)]
 
     def __init__(self, n_docs, doc_len, chunk, n_q_heads, n_kv_heads, head_dim, rope_base=1e6,
-                 sim=MSA_SIM_COS, select_scope=MSA_SCOPE_GROUP, token_pool=0, bank_keys_rotated=0):
+                 sim=MSA_SIM_COS, select_scope=MSA_SCOPE_GROUP, token_pool=0, bank_keys_rotated=0,
+                 doc_lens=None):
+        """doc_lens: None, or a contiguous CUDA int32 tensor [n_docs] (kept alive by this object)."""
+        if doc_lens is not None:
+            if not (doc_lens.is_cuda and doc_lens.dtype == torch.int32 and doc_lens.is_contiguous() and
+                    doc_lens.numel() == n_docs):
+                raise ValueError("doc_lens: expected a contiguous CUDA int32 tensor of n_docs entries")
+        self.doc_lens_tensor = doc_lens
         super().__init__(n_docs, doc_len, chunk, n_q_heads, n_kv_heads, head_dim, rope_base, sim,
-                         select_scope, token_pool, bank_keys_rotated)
+                         select_scope, token_pool, bank_keys_rotated,
+                         None if doc_lens is None else doc_lens.data_ptr())
+
+    def replace(self, **kw):
+        """A copy with some fields changed (doc_lens: a tensor or None)."""
+        f = dict(n_docs=self.n_docs, doc_len=self.doc_len, chunk=self.chunk, n_q_heads=self.n_q_heads,
+                 n_kv_heads=self.n_kv_heads, head_dim=self.head_dim, rope_base=self.rope_base, sim=self.sim,
+                 select_scope=self.select_scope, token_pool=self.token_pool,
+                 bank_keys_rotated=self.bank_keys_rotated, doc_lens=self.doc_lens_tensor)
+        f.update(kw)
+        return MsaConfig(**f)
 
     @property
     def chunks_per_doc(self):
@@ -81,11 +98,11 @@ def load_library():
     lib.msa_build_routing_keys.restype = ctypes.c_int
     lib.msa_build_routing_keys.argtypes = [cfgp, vp, i32, i32, vp, vp, vp]
     lib.msa_pool_kv.restype = ctypes.c_int
-    lib.msa_pool_kv.argtypes = [cfgp, vp, vp, i32, i32, vp, vp, vp]
+    lib.msa_pool_kv.argtypes = [cfgp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.msa_fetch_slots.restype = ctypes.c_int64
     lib.msa_fetch_slots.argtypes = [cfgp, i32, i32, i32]
     lib.msa_fetch_selected.restype = ctypes.c_int
-    lib.msa_fetch_selected.argtypes = [cfgp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.msa_fetch_selected.argtypes = [cfgp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.msa_score_topk.restype = ctypes.c_int
     lib.msa_score_topk.argtypes = [cfgp, vp, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.msa_sparse_attend.restype = ctypes.c_int
@@ -170,9 +187,10 @@ def msa_build_routing_keys(cfg, K, doc_begin=0, doc_count=None, KR=None, inv_nor
     return KR, inv_norm
 
 
-def msa_pool_kv(cfg, K, V, doc_begin=0, doc_count=None, Kbar=None, Vbar=None, stream=None):
+def msa_pool_kv(cfg, K, V, doc_begin=0, doc_count=None, Kbar=None, Vbar=None, pooled_lens=None, stream=None):
     """K, V bf16 [N][Hkv][G][d] -> pooled bank (Kbar, Vbar) bf16 [N][Hkv][C][d]; Kbar is the chunk mean of the
-    position-encoded keys.  Read it with a config whose doc_len = C and bank_keys_rotated = 1."""
+    position-encoded keys.  Read it with a config whose doc_len = C and bank_keys_rotated = 1.  When cfg carries
+    doc_lens the result is (Kbar, Vbar, pooled_lens int32 [N]), pooled_lens being the pooled bank's doc_lens."""
     _need(K, torch.bfloat16, "K")
     _need(V, torch.bfloat16, "V")
     if doc_count is None:
@@ -182,10 +200,13 @@ def msa_pool_kv(cfg, K, V, doc_begin=0, doc_count=None, Kbar=None, Vbar=None, st
         Kbar = torch.empty(shape, dtype=torch.bfloat16, device=K.device)
     if Vbar is None:
         Vbar = torch.empty(shape, dtype=torch.bfloat16, device=K.device)
+    ragged = cfg.doc_lens_tensor is not None
+    if ragged and pooled_lens is None:
+        pooled_lens = torch.empty(cfg.n_docs, dtype=torch.int32, device=K.device)
     rc = load_library().msa_pool_kv(ctypes.byref(cfg), _ptr(K), _ptr(V), doc_begin, doc_count, _ptr(Kbar),
-                                    _ptr(Vbar), _stream(stream, K.device))
+                                    _ptr(Vbar), _ptr(pooled_lens), _stream(stream, K.device))
     _check(rc, "msa_pool_kv")
-    return Kbar, Vbar
+    return (Kbar, Vbar, pooled_lens) if ragged else (Kbar, Vbar)
 
 
 def msa_score_topk(cfg, q_route, KR, inv_norm, k, out_idx=None, out_score=None, workspace=None,
@@ -239,9 +260,11 @@ def fetch_slots(cfg, B, M, k):
     return load_library().msa_fetch_slots(ctypes.byref(cfg), B, M, k)
 
 
-def msa_fetch_selected(cfg, K_host, V_host, idx, B, M, K_stage=None, V_stage=None, idx_stage=None, stream=None):
+def msa_fetch_selected(cfg, K_host, V_host, idx, B, M, K_stage=None, V_stage=None, idx_stage=None,
+                       lens_stage=None, stream=None):
     """K_host, V_host: pinned host bf16 [N][Hkv][G][d]; idx: device int32 [B][M'][S][k] ->
-    (K_stage, V_stage device bf16 [n_slots][Hkv][G][d], idx_stage device int32 like idx, staging config)."""
+    (K_stage, V_stage device bf16 [n_slots][Hkv][G][d], idx_stage device int32 like idx, staging config; the
+    staging config carries lens_stage as its doc_lens when cfg has doc_lens)."""
     if not (K_host.is_pinned() and V_host.is_pinned() and K_host.dtype == torch.bfloat16 and
             V_host.dtype == torch.bfloat16 and K_host.is_contiguous() and V_host.is_contiguous()):
         raise ValueError("K_host, V_host: expected contiguous pinned host tensors of torch.bfloat16")
@@ -256,9 +279,11 @@ def msa_fetch_selected(cfg, K_host, V_host, idx, B, M, K_stage=None, V_stage=Non
         V_stage = torch.empty(shape, dtype=torch.bfloat16, device=dev)
     if idx_stage is None:
         idx_stage = torch.empty_like(idx)
+    if cfg.doc_lens_tensor is not None and lens_stage is None:
+        lens_stage = torch.empty(n_slots, dtype=torch.int32, device=dev)
     rc = load_library().msa_fetch_selected(ctypes.byref(cfg), _ptr(K_host), _ptr(V_host), _ptr(idx), B, M, k,
-                                           _ptr(K_stage), _ptr(V_stage), _ptr(idx_stage), _stream(stream, dev))
+                                           _ptr(K_stage), _ptr(V_stage), _ptr(idx_stage), _ptr(lens_stage),
+                                           _stream(stream, dev))
     _check(rc, "msa_fetch_selected")
-    scfg = MsaConfig(n_slots, cfg.doc_len, cfg.chunk, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rope_base,
-                     cfg.sim, cfg.select_scope, cfg.token_pool, cfg.bank_keys_rotated)
+    scfg = cfg.replace(n_docs=n_slots, doc_lens=lens_stage if cfg.doc_lens_tensor is not None else None)
     return K_stage, V_stage, idx_stage, scfg

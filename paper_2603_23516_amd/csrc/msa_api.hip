@@ -42,6 +42,7 @@ static int make_dims(const msa_config_t* cfg, Dims* dm, DimsFor use = kForRoutin
   dm->scope_all = cfg->select_scope == MSA_SCOPE_ALL;
   dm->token_pool = cfg->token_pool;
   dm->base = cfg->rope_base;
+  dm->lens = cfg->doc_lens;
   dm->NC = (int64_t)dm->N * C;
   dm->tiles = (dm->NC + 15) / 16;
   return MSA_OK;
@@ -55,6 +56,7 @@ static bool attend_doc_len_ok(const msa_config_t* cfg) {
 }
 
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+static bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
 
 }  // namespace msa
 
@@ -62,7 +64,7 @@ using namespace msa;
 
 extern "C" {
 
-int msa_version(void) { return 101; }
+int msa_version(void) { return 102; }
 
 const char* msa_status_string(int status) {
   switch (status) {
@@ -120,20 +122,23 @@ int msa_build_routing_keys(const msa_config_t* cfg, const void* K, int32_t doc_b
   if (inv_norm == nullptr && dm.cos) return MSA_ERR_INVALID_ARG;
   if (doc_begin < 0 || doc_count < 0 || (int64_t)doc_begin + doc_count > dm.N)
     return MSA_ERR_INVALID_ARG;
-  if (misaligned(K) || misaligned(KR) || misaligned(inv_norm)) return MSA_ERR_MISALIGNED;
+  if (misaligned(K) || misaligned(KR) || misaligned(inv_norm) || misaligned4(dm.lens))
+    return MSA_ERR_MISALIGNED;
   return launch_build(dm, K, doc_begin, doc_count, KR, inv_norm, (hipStream_t)stream);
 }
 
 int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t doc_begin,
-                int32_t doc_count, void* Kbar, void* Vbar, msa_stream_t stream) {
+                int32_t doc_count, void* Kbar, void* Vbar, int32_t* pooled_lens, msa_stream_t stream) {
   Dims dm;
   const int rc = make_dims(cfg, &dm, kForPooling);
   if (rc != MSA_OK) return rc;
   if ((Kbar != nullptr && K == nullptr) || (Vbar != nullptr && V == nullptr)) return MSA_ERR_INVALID_ARG;
   if (doc_begin < 0 || doc_count < 0 || (int64_t)doc_begin + doc_count > dm.N)
     return MSA_ERR_INVALID_ARG;
-  if (misaligned(K) || misaligned(V) || misaligned(Kbar) || misaligned(Vbar)) return MSA_ERR_MISALIGNED;
-  return launch_pool_kv(dm, K, V, doc_begin, doc_count, Kbar, Vbar, (hipStream_t)stream);
+  if (misaligned(K) || misaligned(V) || misaligned(Kbar) || misaligned(Vbar) || misaligned4(dm.lens) ||
+      misaligned4(pooled_lens))
+    return MSA_ERR_MISALIGNED;
+  return launch_pool_kv(dm, K, V, doc_begin, doc_count, Kbar, Vbar, pooled_lens, (hipStream_t)stream);
 }
 
 int64_t msa_fetch_slots(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k) {
@@ -145,7 +150,7 @@ int64_t msa_fetch_slots(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k
 
 int msa_fetch_selected(const msa_config_t* cfg, const void* K_host, const void* V_host,
                        const int32_t* idx, int32_t B, int32_t M, int32_t k, void* K_stage,
-                       void* V_stage, int32_t* idx_stage, msa_stream_t stream) {
+                       void* V_stage, int32_t* idx_stage, int32_t* lens_stage, msa_stream_t stream) {
   Dims dm;
   const int rc = make_dims(cfg, &dm, kForAttend);
   if (rc != MSA_OK) return rc;
@@ -153,10 +158,13 @@ int msa_fetch_selected(const msa_config_t* cfg, const void* K_host, const void* 
       V_stage == nullptr || idx_stage == nullptr)
     return MSA_ERR_INVALID_ARG;
   if (B < 1 || M < 1 || k < 1) return MSA_ERR_INVALID_ARG;
+  if (dm.lens != nullptr && lens_stage == nullptr) return MSA_ERR_INVALID_ARG;
   if (k > MSA_MAX_TOPK) return MSA_ERR_UNSUPPORTED;
   if (((int64_t)dm.G * dm.d * 2) % 16 != 0) return MSA_ERR_UNSUPPORTED;
+  // a staging slot holds one document per KV head: a length per slot needs them to be the same document
+  if (dm.lens != nullptr && !dm.scope_all && dm.Hkv > 1) return MSA_ERR_UNSUPPORTED;
   if (misaligned(K_host) || misaligned(V_host) || misaligned(idx) || misaligned(K_stage) ||
-      misaligned(V_stage) || misaligned(idx_stage))
+      misaligned(V_stage) || misaligned(idx_stage) || misaligned4(dm.lens) || misaligned4(lens_stage))
     return MSA_ERR_MISALIGNED;
   // the kernel dereferences the host bank: it must be pinned and mapped into the device's address space
   void* Kd = nullptr;
@@ -175,7 +183,8 @@ int msa_fetch_selected(const msa_config_t* cfg, const void* K_host, const void* 
     Vd = va.devicePointer;
   }
   const long long n_rows = (long long)B * (dm.token_pool ? 1 : M);
-  return launch_fetch(dm, Kd, Vd, idx, n_rows, k, K_stage, V_stage, idx_stage, (hipStream_t)stream);
+  return launch_fetch(dm, Kd, Vd, idx, n_rows, k, K_stage, V_stage, idx_stage, lens_stage,
+                      (hipStream_t)stream);
 }
 
 int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
@@ -218,7 +227,7 @@ int msa_sparse_attend(const msa_config_t* cfg, const void* q, int32_t B, int32_t
   if ((int64_t)local_pos0 + Lloc > (1 << 24)) return MSA_ERR_UNSUPPORTED;
   if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(idx) || misaligned(Kloc) ||
       misaligned(Vloc) || misaligned(q_pos) || misaligned(out) || misaligned(lse) ||
-      misaligned(workspace))
+      misaligned(workspace) || misaligned4(dm.lens))
     return MSA_ERR_MISALIGNED;
   const AttendPlan pl = plan_attend(dm, B, M, k, Lloc, cfg->bank_keys_rotated);
   if (workspace_bytes < pl.ws_bytes) return MSA_ERR_WORKSPACE;

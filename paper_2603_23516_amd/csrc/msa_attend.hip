@@ -138,6 +138,12 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   const long long idx_row = (a.idx_rows_per_b == 1) ? b : bm;
   const int my_idx =
       (lane < a.k) ? a.idx[(idx_row * a.idx_sel + (a.idx_sel == 1 ? 0 : g)) * a.k + lane] : -1;
+  // ... and the number of rows that document holds
+  int my_len = a.G;
+  if (a.lens != nullptr && my_idx >= 0 && my_idx < a.N) {
+    const int l = a.lens[my_idx];
+    my_len = l < 1 ? 1 : (l > a.G ? a.G : l);
+  }
 
   // Where a step's 32 keys live (wave-uniform).  Returns false for a step with nothing to attend.
   struct StepSrc {
@@ -156,8 +162,9 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     const int slot = tok >> a.gshift;
     const int pin = tok & (a.G - 1);
     const int doc = __shfl(my_idx, slot < a.k ? slot : 0, 64);
-    const bool ok = slot < a.k && doc >= 0 && doc < a.N;
-    off = (((long long)(ok ? doc : 0) * a.Hkv + g) * a.G + pin) * D;
+    const int len = __shfl(my_len, slot < a.k ? slot : 0, 64);
+    const bool ok = slot < a.k && doc >= 0 && doc < a.N && pin < len;
+    off = (((long long)(ok ? doc : 0) * a.Hkv + g) * a.G + (ok ? pin : 0)) * D;
     return ok;
   };
   auto locate = [&](int st, StepSrc& ss) -> bool {
@@ -180,10 +187,12 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       const int pin = tok - slot * a.G;
       const int doc = __builtin_amdgcn_readlane(my_idx, slot);
       if (doc < 0 || doc >= a.N) return false;  // -1 pads, and ids outside the bank, are skipped
+      const int len = __builtin_amdgcn_readlane(my_len, slot);
+      if (pin >= len) return false;             // past the document's last token
       const long long off = (((long long)doc * a.Hkv + g) * a.G + pin) * D;
       ss.Kb = a.K + off;
       ss.Vb = a.V + off;
-      ss.rows_valid = 32;
+      ss.rows_valid = len - pin < 32 ? len - pin : 32;
       ss.p_first = pin;
       return true;
     }
@@ -593,6 +602,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.Kloc = (const uint16_t*)Kloc;
   a.Vloc = (const uint16_t*)Vloc;
   a.q_pos = q_pos;
+  a.lens = dm.lens;
   a.part_o = (float*)ws;
   a.part_ml = (float2*)((char*)ws + pl.off_ml);
   a.M = M;

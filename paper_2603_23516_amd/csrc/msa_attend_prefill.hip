@@ -180,10 +180,16 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
       const int pin = tok - slot * a.G;
       const int doc = idx_g[slot];
       if (doc < 0 || doc >= a.N) return false;  // -1 pads, and ids outside the bank, are skipped
+      int len = a.G;
+      if (a.lens != nullptr) {
+        len = a.lens[doc];
+        len = len < 1 ? 1 : (len > a.G ? a.G : len);
+      }
+      if (pin >= len) return false;             // past the document's last token
       const long long off = (((long long)doc * a.Hkv + g) * a.G + pin) * D;
       ss.Kb = a.K + off;
       ss.Vb = a.V + off;
-      ss.rows_valid = 32;
+      ss.rows_valid = len - pin < 32 ? len - pin : 32;
       ss.p_first = pin;
       ss.t0 = 0;
       ss.is_mem = true;

@@ -15,7 +15,8 @@ namespace msa {
 template <int D>
 __global__ __launch_bounds__(256) void build_routing_keys_kernel(
     const uint16_t* __restrict__ K, uint16_t* __restrict__ KR, float* __restrict__ inv_norm,
-    int doc_begin, long long n_chunks, int Hkv, int G, int P, int C, long long tiles) {
+    const int32_t* __restrict__ lens, int doc_begin, long long n_chunks, int Hkv, int G, int P, int C,
+    long long tiles) {
   constexpr int LPR = D / 8;     // lanes per row (16-byte pieces)
   constexpr int RPL = 64 / LPR;  // rows per wave-wide load
   const int lane = threadIdx.x & 63;
@@ -26,7 +27,20 @@ __global__ __launch_bounds__(256) void build_routing_keys_kernel(
   const long long t = cid / C;
   const int g = (int)(t % Hkv);
   const long long doc = doc_begin + t / Hkv;
-  const uint16_t* src = K + ((doc * Hkv + g) * (long long)G + (long long)j * P) * D;
+  // Tokens of this chunk (wave-uniform).  A chunk past the document's end repeats chunk 0: the
+  // document score is a max over chunks, which a repeated chunk cannot change.
+  int n_rows = P, jsrc = j;
+  if (lens != nullptr) {
+    int len = lens[doc];
+    len = len < 1 ? 1 : (len > G ? G : len);
+    n_rows = len - j * P;
+    if (n_rows <= 0) {
+      jsrc = 0;
+      n_rows = len;
+    }
+    n_rows = n_rows > P ? P : n_rows;
+  }
+  const uint16_t* src = K + ((doc * Hkv + g) * (long long)G + (long long)jsrc * P) * D;
   const int piece = lane % LPR;
   const int rowoff = lane / LPR;
 
@@ -40,7 +54,7 @@ __global__ __launch_bounds__(256) void build_routing_keys_kernel(
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int it = it0 + u;
-      if (it < iters) {
+      if (it < iters && it * RPL + rowoff < n_rows) {
         v[u] = *reinterpret_cast<const uint4*>(src + (long long)(it * RPL + rowoff) * D + piece * 8);
       } else {
         v[u] = make_uint4(0, 0, 0, 0);
@@ -64,7 +78,7 @@ __global__ __launch_bounds__(256) void build_routing_keys_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], off, 64);
   }
-  const float fp = (float)P;
+  const float fp = (float)n_rows;
   uint4 o;
   o.x = pack_bf16(acc[0] / fp, acc[1] / fp);
   o.y = pack_bf16(acc[2] / fp, acc[3] / fp);
@@ -119,11 +133,11 @@ int launch_build(const Dims& dm, const void* K, int doc_begin, int doc_count, vo
     dim3 grid((unsigned)blocks), block(256);
     if (dm.d == 128) {
       hipLaunchKernelGGL(build_routing_keys_kernel<128>, grid, block, 0, st, (const uint16_t*)K,
-                         (uint16_t*)KR, inv_norm, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C,
+                         (uint16_t*)KR, inv_norm, dm.lens, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C,
                          (long long)dm.tiles);
     } else {
       hipLaunchKernelGGL(build_routing_keys_kernel<64>, grid, block, 0, st, (const uint16_t*)K,
-                         (uint16_t*)KR, inv_norm, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C,
+                         (uint16_t*)KR, inv_norm, dm.lens, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C,
                          (long long)dm.tiles);
     }
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;

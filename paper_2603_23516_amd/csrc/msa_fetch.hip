@@ -18,8 +18,11 @@ struct FetchArgs {
   uint4* K_stage;        // [n_slots][Hkv][G][d]
   uint4* V_stage;
   int32_t* idx_stage;    // [B][M'][S][k]
-  int N, Hkv, S, k;
+  const int32_t* lens;   // [N] document lengths, or null
+  int32_t* lens_stage;   // [n_slots] (with lens; then S == 1 or Hkv == 1: one document per slot)
+  int N, Hkv, S, k, G;
   long long slab16;      // 16-byte words per (document, head) slab: G * d * 2 / 16
+  int row16;             // 16-byte words per token row: d * 2 / 16
 };
 
 // One workgroup per (selection entry, head to copy, half = K or V).
@@ -34,24 +37,31 @@ __global__ __launch_bounds__(256) void fetch_selected_kernel(FetchArgs a) {
   const bool ok = doc >= 0 && doc < a.N;
   const long long slot = bm * a.k + j;
   if (hc == 0 && blockIdx.z == 0 && threadIdx.x == 0) a.idx_stage[e] = ok ? (int32_t)slot : -1;
+  long long n16 = a.slab16;  // 16-byte words to copy: only the rows the document holds
+  if (a.lens != nullptr) {
+    int len = ok ? a.lens[doc] : 1;
+    len = len < 1 ? 1 : (len > a.G ? a.G : len);
+    n16 = (long long)len * a.row16;
+    if (hc == 0 && blockIdx.z == 0 && threadIdx.x == 0) a.lens_stage[slot] = len;
+  }
   if (!ok) return;  // block-uniform
   const int g = (a.S == 1) ? hc : sl;
   const uint4* src = (blockIdx.z == 0 ? a.K_host : a.V_host) + ((long long)doc * a.Hkv + g) * a.slab16;
   uint4* dst = (blockIdx.z == 0 ? a.K_stage : a.V_stage) + (slot * a.Hkv + g) * a.slab16;
-  for (long long i = threadIdx.x; i < a.slab16; i += 256 * 4) {
+  for (long long i = threadIdx.x; i < n16; i += 256 * 4) {
     uint4 v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-      if (i + u * 256 < a.slab16) v[u] = src[i + u * 256];
+      if (i + u * 256 < n16) v[u] = src[i + u * 256];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-      if (i + u * 256 < a.slab16) dst[i + u * 256] = v[u];
+      if (i + u * 256 < n16) dst[i + u * 256] = v[u];
   }
 }
 
 int launch_fetch(const Dims& dm, const void* K_dev_view, const void* V_dev_view, const int32_t* idx,
                  long long n_rows, int k, void* K_stage, void* V_stage, int32_t* idx_stage,
-                 hipStream_t st) {
+                 int32_t* lens_stage, hipStream_t st) {
   FetchArgs a;
   a.K_host = (const uint4*)K_dev_view;
   a.V_host = (const uint4*)V_dev_view;
@@ -63,7 +73,11 @@ int launch_fetch(const Dims& dm, const void* K_dev_view, const void* V_dev_view,
   a.Hkv = dm.Hkv;
   a.S = dm.scope_all ? 1 : dm.Hkv;
   a.k = k;
+  a.lens = dm.lens;
+  a.lens_stage = lens_stage;
+  a.G = dm.G;
   a.slab16 = (long long)dm.G * dm.d * 2 / 16;
+  a.row16 = dm.d * 2 / 16;
   const long long entries = n_rows * a.S * k;
   if (entries > 0x7fffffffLL) return MSA_ERR_UNSUPPORTED;
   dim3 grid((unsigned)entries, a.S == 1 ? dm.Hkv : 1, 2), block(256);

@@ -15,6 +15,7 @@ struct Dims {
   int scope_all;  // 1 = head mean over every head, one selection for all KV heads (literal Eq. 2)
   int token_pool; // 1 = document score is the max over the M tokens of a batch row (literal Eq. 2)
   float base;
+  const int32_t* lens;  // device [N] document lengths, or null (every document holds G tokens)
   int64_t NC;     // N * C routing keys per KV head
   int64_t tiles;  // ceil(NC / 16) tiles of 16 keys per KV head
 };
@@ -80,11 +81,11 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
                   int Lloc, int pos0, const int32_t* q_pos, void* out, float* lse, void* ws,
                   int bank_keys_rotated, hipStream_t st);
 int launch_pool_kv(const Dims& dm, const void* K, const void* V, int doc_begin, int doc_count,
-                   void* Kbar, void* Vbar, hipStream_t st);
+                   void* Kbar, void* Vbar, int32_t* pooled_lens, hipStream_t st);
 
 int launch_fetch(const Dims& dm, const void* K_dev_view, const void* V_dev_view, const int32_t* idx,
                  long long n_rows, int k, void* K_stage, void* V_stage, int32_t* idx_stage,
-                 hipStream_t st);
+                 int32_t* lens_stage, hipStream_t st);
 
 inline size_t round_up256(size_t x) { return (x + 255) & ~(size_t)255; }
 

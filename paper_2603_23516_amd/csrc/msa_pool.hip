@@ -20,7 +20,9 @@ struct PoolTheta {
 
 template <int D, bool ROT>
 __global__ __launch_bounds__(256) void pool_chunks_kernel(const uint16_t* __restrict__ X,
-                                                          uint16_t* __restrict__ Xbar, int doc_begin,
+                                                          uint16_t* __restrict__ Xbar,
+                                                          const int32_t* __restrict__ lens,
+                                                          int32_t* __restrict__ pooled_lens, int doc_begin,
                                                           long long n_chunks, int Hkv, int G, int P,
                                                           int C, PoolTheta th) {
   constexpr int LPR = D / 16;    // lanes per row (each holds a piece and its partner half)
@@ -36,6 +38,15 @@ __global__ __launch_bounds__(256) void pool_chunks_kernel(const uint16_t* __rest
   const uint16_t* src = X + ((doc * Hkv + g) * (long long)G + (long long)j * P) * D;
   const int pc = lane % LPR;
   const int rowoff = lane / LPR;
+  // tokens of this chunk (wave-uniform): a tail chunk is short, a chunk past the end has none and pools to zero
+  int n_rows = P;
+  if (lens != nullptr) {
+    int len = lens[doc];
+    len = len < 1 ? 1 : (len > G ? G : len);
+    n_rows = len - j * P;
+    n_rows = n_rows < 0 ? 0 : (n_rows > P ? P : n_rows);
+    if (pooled_lens != nullptr && g == 0 && j == 0 && lane == 0) pooled_lens[doc] = (len + P - 1) / P;
+  }
 
   float2 cs[8], stp[8];
   if (ROT) {
@@ -55,7 +66,7 @@ __global__ __launch_bounds__(256) void pool_chunks_kernel(const uint16_t* __rest
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int row = (it0 + u) * RPL + rowoff;
-      if (row < P) {
+      if (row < n_rows) {
         const uint16_t* rp = src + (long long)row * D + pc * 8;
         v1[u] = *reinterpret_cast<const uint4*>(rp);
         v2[u] = *reinterpret_cast<const uint4*>(rp + D / 2);
@@ -100,7 +111,7 @@ __global__ __launch_bounds__(256) void pool_chunks_kernel(const uint16_t* __rest
     }
   }
   if (rowoff == 0) {
-    const float fp = (float)P;
+    const float fp = (float)(n_rows > 0 ? n_rows : 1);
     uint16_t* dst = Xbar + (((doc * Hkv + g) * (long long)C + j) * D) + pc * 8;
     *reinterpret_cast<uint4*>(dst) =
         make_uint4(pack_bf16(a1[0] / fp, a1[1] / fp), pack_bf16(a1[2] / fp, a1[3] / fp),
@@ -112,7 +123,7 @@ __global__ __launch_bounds__(256) void pool_chunks_kernel(const uint16_t* __rest
 }
 
 int launch_pool_kv(const Dims& dm, const void* K, const void* V, int doc_begin, int doc_count,
-                   void* Kbar, void* Vbar, hipStream_t st) {
+                   void* Kbar, void* Vbar, int32_t* pooled_lens, hipStream_t st) {
   const long long n_chunks = (long long)doc_count * dm.Hkv * dm.C;
   if (n_chunks == 0) return MSA_OK;
   const long long blocks = (n_chunks + 3) / 4;
@@ -127,19 +138,19 @@ int launch_pool_kv(const Dims& dm, const void* K, const void* V, int doc_begin, 
   if (Kbar != nullptr) {
     if (dm.d == 128)
       hipLaunchKernelGGL((pool_chunks_kernel<128, true>), grid, block, 0, st, (const uint16_t*)K,
-                         (uint16_t*)Kbar, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C, th);
+                         (uint16_t*)Kbar, dm.lens, pooled_lens, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C, th);
     else
       hipLaunchKernelGGL((pool_chunks_kernel<64, true>), grid, block, 0, st, (const uint16_t*)K,
-                         (uint16_t*)Kbar, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C, th);
+                         (uint16_t*)Kbar, dm.lens, pooled_lens, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C, th);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
   if (Vbar != nullptr) {
     if (dm.d == 128)
       hipLaunchKernelGGL((pool_chunks_kernel<128, false>), grid, block, 0, st, (const uint16_t*)V,
-                         (uint16_t*)Vbar, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C, th);
+                         (uint16_t*)Vbar, dm.lens, Kbar == nullptr ? pooled_lens : nullptr, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C, th);
     else
       hipLaunchKernelGGL((pool_chunks_kernel<64, false>), grid, block, 0, st, (const uint16_t*)V,
-                         (uint16_t*)Vbar, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C, th);
+                         (uint16_t*)Vbar, dm.lens, Kbar == nullptr ? pooled_lens : nullptr, doc_begin, n_chunks, dm.Hkv, dm.G, dm.P, dm.C, th);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
   return MSA_OK;

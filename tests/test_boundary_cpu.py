@@ -33,7 +33,7 @@ def test_exports_match_header(lib):
     assert declared == set(msa.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.msa_version() == 101
+    assert lib.msa_version() == 102
     for st in (0, -1, -2, -3, -4, -5, -99):
         assert len(msa.status_string(st)) > 0
 
@@ -151,13 +151,13 @@ def test_argument_validation_before_launch(lib):
     assert msa.sparse_attend_workspace_bytes(_cfg(doc_len=8, chunk=8, bank_keys_rotated=1), 1, 1, 16, 100) > 0
     assert msa.sparse_attend_workspace_bytes(_cfg(doc_len=8, chunk=8), 1, 1, 16, 100) == 0
     # pool_kv
-    assert lib.msa_pool_kv(cb, None, p, 0, 1, p, p, None) == E.MSA_ERR_INVALID_ARG      # Kbar wanted, no K
-    assert lib.msa_pool_kv(cb, p, None, 0, 1, p, p, None) == E.MSA_ERR_INVALID_ARG
-    assert lib.msa_pool_kv(cb, p, p, 60, 5, p, p, None) == E.MSA_ERR_INVALID_ARG
-    assert lib.msa_pool_kv(cb, p, p, -1, 1, p, p, None) == E.MSA_ERR_INVALID_ARG
-    assert lib.msa_pool_kv(cb, p, odd, 0, 1, p, p, None) == E.MSA_ERR_MISALIGNED
-    assert lib.msa_pool_kv(cb, p, p, 0, 0, p, p, None) == E.MSA_OK                      # nothing to do, nothing launched
-    assert lib.msa_pool_kv(ctypes.byref(_cfg(head_dim=96)), p, p, 0, 1, p, p, None) == E.MSA_ERR_UNSUPPORTED
+    assert lib.msa_pool_kv(cb, None, p, 0, 1, p, p, None, None) == E.MSA_ERR_INVALID_ARG      # Kbar wanted, no K
+    assert lib.msa_pool_kv(cb, p, None, 0, 1, p, p, None, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_pool_kv(cb, p, p, 60, 5, p, p, None, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_pool_kv(cb, p, p, -1, 1, p, p, None, None) == E.MSA_ERR_INVALID_ARG
+    assert lib.msa_pool_kv(cb, p, odd, 0, 1, p, p, None, None) == E.MSA_ERR_MISALIGNED
+    assert lib.msa_pool_kv(cb, p, p, 0, 0, p, p, None, None) == E.MSA_OK                      # nothing to do, nothing launched
+    assert lib.msa_pool_kv(ctypes.byref(_cfg(head_dim=96)), p, p, 0, 1, p, p, None, None) == E.MSA_ERR_UNSUPPORTED
 
 
 def test_fetch_validation(lib):
@@ -170,14 +170,23 @@ def test_fetch_validation(lib):
     assert msa.fetch_slots(_cfg(token_pool=1), 2, 5, 4) == 2 * 4
     assert msa.fetch_slots(c, 2, 5, 65) == 0
     f = lib.msa_fetch_selected
-    assert f(cb, None, p, p, 1, 1, 4, p, p, p, None) == E.MSA_ERR_INVALID_ARG
-    assert f(cb, p, p, None, 1, 1, 4, p, p, p, None) == E.MSA_ERR_INVALID_ARG
-    assert f(cb, p, p, p, 1, 1, 4, p, p, None, None) == E.MSA_ERR_INVALID_ARG
-    assert f(cb, p, p, p, 0, 1, 4, p, p, p, None) == E.MSA_ERR_INVALID_ARG
-    assert f(cb, p, p, p, 1, 1, 65, p, p, p, None) == E.MSA_ERR_UNSUPPORTED
-    assert f(cb, odd, p, p, 1, 1, 4, p, p, p, None) == E.MSA_ERR_MISALIGNED
+    assert f(cb, None, p, p, 1, 1, 4, p, p, p, None, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, None, 1, 1, 4, p, p, p, None, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, p, 1, 1, 4, p, p, None, None, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, p, 0, 1, 4, p, p, p, None, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, p, 1, 1, 65, p, p, p, None, None) == E.MSA_ERR_UNSUPPORTED
+    assert f(cb, odd, p, p, 1, 1, 4, p, p, p, None, None) == E.MSA_ERR_MISALIGNED
+    # document lengths: a length per staging slot is an output, and needs one document per slot
+    ca = _cfg(select_scope=msa.MSA_SCOPE_ALL)
+    ca.doc_lens = 0x20000
+    assert f(ctypes.byref(ca), p, p, p, 1, 1, 4, p, p, p, None, None) == E.MSA_ERR_INVALID_ARG
+    cg = _cfg()
+    cg.doc_lens = 0x20000
+    assert f(ctypes.byref(cg), p, p, p, 1, 1, 4, p, p, p, p, None) == E.MSA_ERR_UNSUPPORTED
+    ca.doc_lens = 0x20002
+    assert f(ctypes.byref(ca), p, p, p, 1, 1, 4, p, p, p, p, None) == E.MSA_ERR_MISALIGNED
     # a bank that is not pinned, device-mapped host memory is refused before anything is launched
-    assert f(cb, p, p, p, 1, 1, 4, p, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, p, p, 1, 1, 4, p, p, p, None, None) == E.MSA_ERR_INVALID_ARG
 
 
 def test_literal_eq2_variants_are_planned(lib):

@@ -586,9 +586,10 @@ def test_pooled_bank_all_pads_and_unrotated_short_docs_rejected():
 # ------------------------------------------------------------------------------------------------
 # Eq. 2 as printed: head mean over every head (select_scope = ALL), max over query tokens (token_pool)
 # ------------------------------------------------------------------------------------------------
-def check_topk_generic(q, KRb, C, N, idx, val, k, sim, scope, pool, atol=2e-5):
-    """GPU selection against the oracle's for any scope / token pooling, with the tie band."""
-    oi, ov, s = O.score_topk(q, KRb, C, k, sim, scope, pool)
+def check_topk_generic(q, KRb, C, N, idx, val, k, sim, scope, pool, atol=2e-5, valid=None):
+    """GPU selection against the oracle's for any scope / token pooling, with the tie band.  valid: the
+    oracle's mask of the chunks that exist (documents of different lengths)."""
+    oi, ov, s = O.score_topk(q, KRb, C, k, sim, scope, pool, valid)
     gi = idx.cpu().numpy().astype(np.int64)
     gv = val.cpu().numpy().astype(np.float64)
     assert gi.shape == oi.shape, (gi.shape, oi.shape)
@@ -782,7 +783,7 @@ def test_fetch_selected_from_host_bank(scope, pool):
         rc = msa.load_library().msa_fetch_selected(ctypes.byref(cfg), ctypes.c_void_p(case.dK.data_ptr()),
                                                     ctypes.c_void_p(case.dV.data_ptr()), ctypes.c_void_p(didx.data_ptr()),
                                                     B, M, k, ctypes.c_void_p(Ks.data_ptr()), ctypes.c_void_p(Vs.data_ptr()),
-                                                    ctypes.c_void_p(idx_s.data_ptr()), None)
+                                                    ctypes.c_void_p(idx_s.data_ptr()), None, None)
         if rc != 0:
             raise msa.MsaError(rc, "msa_fetch_selected")
     assert e.value.status == msa.MSA_ERR_INVALID_ARG
