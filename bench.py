@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--tier", default="hbm", choices=("hbm", "host"),
                     help="host: additionally time the tiered bank of Section 3.4.2 (K/V in pinned host memory, the "
                          "selected documents fetched over the host link); reported in \"host_tier\", never in value")
+    ap.add_argument("--ragged", action="store_true",
+                    help="documents of different lengths: seeded lengths in [G/8, G] passed as cfg.doc_lens (the "
+                         "bank keeps its G-row slots); byte counts then follow the lengths")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-docs", type=int, default=1024)
     return ap.parse_args()
@@ -152,9 +155,13 @@ def main():
     wl = W.make(args.workload)
     scope = msa.MSA_SCOPE_ALL if args.scope == "all" else msa.MSA_SCOPE_GROUP
     n_sel = 1 if args.scope == "all" else wl.Hkv
+    lens = torch.from_numpy(W.doc_lens(wl)).cuda() if args.ragged else None
     cfg = msa.MsaConfig(wl.N, wl.G, wl.P, wl.Hq, wl.Hkv, wl.d, wl.base, select_scope=scope,
-                        token_pool=int(args.token_pool))
+                        token_pool=int(args.token_pool), doc_lens=lens)
     ab = W.algorithmic_bytes(wl)
+    if args.ragged:
+        assert args.bank == "full" and args.tier == "hbm", "--ragged is measured on the full bank in HBM"
+        ab["build"] = int(lens.sum().item()) * wl.Hkv * wl.d * 2 + ab["score"]
     stream = torch.cuda.current_stream()
 
     # ---- offline stage: routing index (timed on its own, outside the metric) -------------------
@@ -211,6 +218,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.ragged:     # rows the attention really reads: the lengths of the documents selected (same every step)
+        sel_rows = int(lens[idx.long().reshape(-1)].sum().item()) * (wl.Hkv if n_sel == 1 else 1)
+        if args.token_pool:
+            sel_rows *= M
+        local = ab["attend"] - B * M * wl.Hkv * k * wl.G * wl.d * 2 * 2
+        ab["attend"] = sel_rows * wl.d * 2 * 2 + local
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -237,7 +250,7 @@ def main():
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "bank": args.bank, "select_scope": args.scope, "token_pool": int(args.token_pool),
+        "config": {"workload": wl.name, "ragged": bool(args.ragged), "bank": args.bank, "select_scope": args.scope, "token_pool": int(args.token_pool),
                    "memory_tokens": wl.N * wl.G, "docs": wl.N, "doc_len": wl.G,
                    "chunk": wl.P, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.d, "batch": B,
                    "query_tokens": M, "top_k": k, "local_tokens": wl.Lloc, "rope_base": wl.base},

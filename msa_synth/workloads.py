@@ -100,6 +100,13 @@ def host_doc(wl, which, doc):
     return S.doc_slice(wl.seeds[which], wl.Hkv, wl.G, wl.d, doc)
 
 
+def doc_lens(wl, lo_frac=0.125):
+    """Seeded document lengths for banks whose documents differ in length (the paper's G is an average,
+    Section 5.1): uniform integers in [lo_frac * G, G], int32 [N] on the host."""
+    rng = np.random.default_rng(S.seed_for(wl.cfg_id, 55))
+    return rng.integers(max(1, int(lo_frac * wl.G)), wl.G + 1, size=wl.N).astype(np.int32)
+
+
 def algorithmic_bytes(wl):
     """Bytes each stage must move once (the roofline's numerator)."""
     NC = wl.N * wl.C

@@ -259,3 +259,87 @@ def test_fullsize_cfg4_question_level_routing():
         assert np.allclose(gl[b, m, g * wl.r:(g + 1) * wl.r], ol[0, 0], rtol=0, atol=5e-3)
     del wl, KR, inv
     torch.cuda.empty_cache()
+
+
+def test_fullsize_cfg3_documents_of_different_lengths():
+    """BASELINE config 3 with seeded document lengths in [G/8, G] (cfg.doc_lens): sampled checks of the index,
+    the selection and the attention against the oracle's lens / valid arguments."""
+    name = "cfg3_batch32_4m"
+    say(f"workload {name} with document lengths")
+    wl = W.make(name, plant_per_query=0)
+    lens = W.doc_lens(wl).astype(np.int64)
+    dlens = torch.from_numpy(lens.astype(np.int32)).cuda()
+    cfg = msa.MsaConfig(wl.N, wl.G, wl.P, wl.Hq, wl.Hkv, wl.d, wl.base, doc_lens=dlens)
+    rng = np.random.default_rng(S.seed_for(wl.cfg_id, 79))
+    B, k, C = wl.B, wl.k, wl.C
+    KR, inv = msa.msa_build_routing_keys(cfg, wl.K)
+    torch.cuda.synchronize()
+    sample = [0, wl.N - 1, int(np.argmin(lens)), int(np.argmax(lens))] + rng.choice(wl.N, size=12, replace=False).tolist()
+    bad = 0
+    for doc in sample:
+        bits, ginv = kr_rows(cfg, KR, inv, doc)
+        got = S.bf16_bits_to_f64(bits)
+        want, winv = O.routing_keys(W.host_doc(wl, "K", doc)[1][None], wl.P, lens[doc:doc + 1])
+        ok = winv[0] > 0                                           # chunks the document has
+        diff = (got != want) & ok[None, :, None]
+        if diff.any():
+            assert np.all(np.abs(got[diff] - want[diff]) <= np.abs(want[diff]) * 2.0 ** -7 + 1e-30)
+            bad += int(diff.sum())
+        assert np.array_equal(got[:, ~ok], np.repeat(got[:, :1], int((~ok).sum()), axis=1))   # repeat chunk 0
+        assert np.allclose(ginv, 1.0 / np.maximum(np.linalg.norm(got, axis=-1), O.EPS_NORM), rtol=1e-6)
+    assert bad <= 4, bad
+    say(f"   routing keys of {len(sample)} sampled documents ok ({bad} tie-adjacent roundings)")
+
+    idx, val = msa.msa_score_topk(cfg, wl.q, KR, inv, k)
+    torch.cuda.synchronize()
+    gi = idx.cpu().numpy().astype(np.int64)
+    gv = val.cpu().numpy().astype(np.float64)
+    assert gi.min() >= 0 and gi.max() < wl.N
+    others = rng.choice(wl.N, size=96, replace=False).tolist()
+
+    def scores(q_sel, docs):                                       # oracle document scores [nq, Hkv, n]
+        Ks = np.stack([W.host_doc(wl, "K", int(i))[1] for i in docs])
+        dl = lens[np.asarray(docs)]
+        KRb, _ = O.routing_keys(Ks, wl.P, dl)
+        return O.doc_scores(O.chunk_scores(q_sel[:, None], KRb, valid=O.chunk_valid(dl, wl.G, wl.P)), C)[:, 0]
+
+    for b in (0, B // 2, B - 1):
+        docs = sorted(set(gi[b, 0].reshape(-1).tolist()) | set(others))
+        s = scores(wl.q_host[b], docs)[0]
+        pos = {dd: i for i, dd in enumerate(docs)}
+        for g in range(wl.Hkv):
+            assert len(set(gi[b, 0, g].tolist())) == k and np.all(np.diff(gv[b, 0, g]) <= 0)
+            want = np.array([s[g, pos[int(dd)]] for dd in gi[b, 0, g]])
+            assert np.allclose(gv[b, 0, g], want, rtol=0, atol=1e-4), np.abs(gv[b, 0, g] - want).max()
+            kth = gv[b, 0, g, k - 1]
+            chosen = set(gi[b, 0, g].tolist())
+            for dd in others:
+                if dd not in chosen:
+                    assert s[g, pos[dd]] <= kth + 1e-3 * abs(kth) + 1e-4
+    say("   top-k ok")
+
+    out, lse = msa.msa_sparse_attend(cfg, wl.q, wl.K, wl.V, idx, wl.Kloc, wl.Vloc, wl.pos0, wl.q_pos)
+    torch.cuda.synchronize()
+    go = out.float().cpu().numpy().astype(np.float64)
+    gl = lse.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(go)) and np.all(np.isfinite(gl))
+    per_bg = wl.Lloc * wl.d
+    for b, g in ((0, 0), (B - 1, wl.Hkv - 1), (B // 2, 3)):
+        docs = gi[b, 0, g]
+        K_sel = np.stack([W.host_doc(wl, "K", int(i))[1][g:g + 1] for i in docs])
+        V_sel = np.stack([W.host_doc(wl, "V", int(i))[1][g:g + 1] for i in docs])
+        start = (b * wl.Hkv + g) * per_bg
+        Kl = S.normal_bf16(wl.seeds["Kloc"], (1, 1, wl.Lloc, wl.d), start=start)[1]
+        Vl = S.normal_bf16(wl.seeds["Vloc"], (1, 1, wl.Lloc, wl.d), start=start)[1]
+        qh = wl.q_host[b:b + 1, :, g * wl.r:(g + 1) * wl.r]
+        oo, ol = O.sparse_attend(qh, K_sel, V_sel, np.arange(k)[None, None, None], Kl, Vl, wl.pos0,
+                                 wl.q_pos_host[b:b + 1], wl.base, lens=lens[docs])
+        got = go[b, 0, g * wl.r:(g + 1) * wl.r]
+        err = np.abs(got - oo[0, 0])
+        rel = np.linalg.norm(err) / np.linalg.norm(oo)
+        say(f"   attend (b={b}, g={g}, lengths {lens[docs].min()}..{lens[docs].max()}): max-abs {err.max():.3e} "
+            f"rel-L2 {rel:.3e}")
+        assert err.max() <= 2e-2 and rel <= 5e-3
+        assert np.allclose(gl[b, 0, g * wl.r:(g + 1) * wl.r], ol[0, 0], rtol=0, atol=5e-3)
+    del wl, KR, inv
+    torch.cuda.empty_cache()
