@@ -802,3 +802,50 @@ def test_all_scores_equal_more_than_on_chip_survivors():
     torch.cuda.synchronize()
     assert np.array_equal(idx.cpu().numpy(), np.broadcast_to(np.arange(k), (B, 1, Hkv, k)))
     assert np.all(val.cpu().numpy() == 0)
+
+
+def test_hip_graph_replays_match_eager():
+    """The online step (score + top-k, then attention) captured once into a HIP graph on the caller's side --
+    the library only enqueues kernels on the stream it is given and allocates nothing -- and replayed with
+    new queries: every replay must equal the eager result bit for bit, with eager work between replays."""
+    say("case HIP graph: capture score_topk + sparse_attend, replay with new queries")
+    case = Case(81000, 700, 2, 4, 64, 128, 16, 3, 1, 50, 1e6).to_device()
+    cfg = case.cfg()
+    N, G, k, B, M, Lloc = 700, 64, 6, 3, 1, 50
+    KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+    pos0 = G
+    dpos = torch.full((B, M), pos0 + Lloc - 1, dtype=torch.int32, device="cuda")
+    q_static = case.dq.clone()
+    idx = torch.empty((B, M, 2, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((B, M, 2, k), dtype=torch.float32, device="cuda")
+    out = torch.empty_like(q_static)
+    lse = torch.empty((B, M, case.Hq), dtype=torch.float32, device="cuda")
+    ws_s = torch.empty(msa.score_topk_workspace_bytes(cfg, B, M, k), dtype=torch.uint8, device="cuda")
+    ws_a = torch.empty(msa.sparse_attend_workspace_bytes(cfg, B, M, k, Lloc), dtype=torch.uint8, device="cuda")
+
+    def step():
+        msa.msa_score_topk(cfg, q_static, KR, inv, k, idx, val, ws_s)
+        msa.msa_sparse_attend(cfg, q_static, case.dK, case.dV, idx, case.dKl, case.dVl, pos0, dpos, out, lse, ws_a)
+
+    step()                                                          # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        qb, _ = S.normal_bf16(81100 + rep, (B, M, case.Hq, 128))
+        q_static.copy_(dev(qb))
+        step()                                                      # eager reference with the same buffers
+        torch.cuda.synchronize()
+        want = (idx.clone(), val.clone(), out.clone(), lse.clone())
+        for t in (idx, val, out, lse):
+            t.zero_()
+        ws_s.fill_(0xAB)                                            # the workspaces carry nothing between calls
+        ws_a.fill_(0xCD)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, want[0]) and torch.equal(val, want[1]), rep
+        assert torch.equal(out.view(torch.int16), want[2].view(torch.int16)) and torch.equal(lse, want[3]), rep
+    say("   4 replays equal their eager runs")
