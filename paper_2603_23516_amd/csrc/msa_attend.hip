@@ -116,15 +116,6 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     }
   }
 
-  // ---- this wave's steps -----------------------------------------------------------------------
-  const int sb = sp * a.steps_per_split;
-  int se = sb + a.steps_per_split;
-  if (se > a.steps_total) se = a.steps_total;
-  const int spw = (se - sb + kAttWaves - 1) / kAttWaves;
-  const int wb = sb + wave * spw;
-  int we = wb + spw;
-  if (we > se) we = se;
-
   float2 cs[NU];         // (cos, sin)((cur_p + n) * theta_u), u = 32s' + 8rr + j at index 8s' + j
   int cur_p = -1;        // position of key 0 of the sub-tile the state is valid for; -1 = invalid
   float m_run = -INFINITY, l_run = 0.f;
@@ -144,6 +135,35 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     const int l = a.lens[my_idx];
     my_len = l < 1 ? 1 : (l > a.G ? a.G : l);
   }
+
+  // ---- this wave's steps -----------------------------------------------------------------------
+  // With document lengths (MODE 0, 1) the steps are numbered over what is really there -- slot j
+  // contributes ceil(len_j / 32) steps, none for a pad, then come the steps of the visible local rows
+  // -- so that the split into blocks and waves stays even when documents are short.  pre = inclusive
+  // prefix sum of the slots' step counts over the lanes.  Otherwise the host's numbering over whole
+  // slots is used as it is.
+  const bool compact = MODE != 2 && a.lens != nullptr;  // wave-uniform
+  int pre = 0;
+  int mem_steps = a.steps_mem, steps_total = a.steps_total, steps_per_split = a.steps_per_split;
+  if (compact) {
+    pre = (my_idx >= 0 && my_idx < a.N) ? (my_len + 31) >> 5 : 0;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(pre, off, 64);
+      if (lane >= off) pre += t;
+    }
+    mem_steps = __builtin_amdgcn_readlane(pre, 63);
+    steps_total = mem_steps + ((n_vis + 31) >> 5);
+    steps_per_split = (steps_total + a.n_splits - 1) / a.n_splits;
+  }
+  const int sb = sp * steps_per_split;
+  int se = sb + steps_per_split;
+  if (se > steps_total) se = steps_total;
+  if (se < sb) se = sb;  // nothing left for this block
+  const int spw = (se - sb + kAttWaves - 1) / kAttWaves;
+  const int wb = sb + wave * spw;
+  int we = wb + spw;
+  if (we > se) we = se;
 
   // Where a step's 32 keys live (wave-uniform).  Returns false for a step with nothing to attend.
   struct StepSrc {
@@ -170,8 +190,8 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   auto locate = [&](int st, StepSrc& ss) -> bool {
     ss.st = st;
     ss.mask = 0xffffffffu;
-    ss.is_mem = st < a.steps_mem;
-    if (MODE == 2 && st < a.steps_mem) {
+    ss.is_mem = st < mem_steps;
+    if (MODE == 2 && st < mem_steps) {
       long long off;
       const bool ok = gather_row(st, lane & 31, off);
       ss.mask = (unsigned)__ballot(ok);  // lanes 0..31 cover the 32 rows
@@ -181,10 +201,18 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       ss.p_first = 0;
       return ss.mask != 0u;
     }
-    if (st < a.steps_mem) {
-      const int tok = st * 32;
-      const int slot = tok / a.G;
-      const int pin = tok - slot * a.G;
+    if (st < mem_steps) {
+      int slot, pin;
+      if (compact) {
+        // the slot whose steps contain st: the first lane whose inclusive prefix exceeds st (pads, ids
+        // outside the bank and rows past a document's end own no steps, so they are never reached)
+        slot = __popcll(__ballot(pre <= st));
+        pin = (st - (slot > 0 ? __builtin_amdgcn_readlane(pre, slot - 1) : 0)) * 32;
+      } else {
+        const int tok = st * 32;
+        slot = tok / a.G;
+        pin = tok - slot * a.G;
+      }
       const int doc = __builtin_amdgcn_readlane(my_idx, slot);
       if (doc < 0 || doc >= a.N) return false;  // -1 pads, and ids outside the bank, are skipped
       const int len = __builtin_amdgcn_readlane(my_len, slot);
@@ -196,7 +224,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       ss.p_first = pin;
       return true;
     }
-    const int t0 = (st - a.steps_mem) * 32;
+    const int t0 = (st - mem_steps) * 32;
     if (t0 >= n_vis) return false;
     const long long off = (((long long)b * a.Hkv + g) * a.Lloc + t0) * D;
     ss.Kb = a.Kloc + off;
