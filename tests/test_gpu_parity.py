@@ -849,3 +849,39 @@ def test_hip_graph_replays_match_eager():
         assert torch.equal(idx, want[0]) and torch.equal(val, want[1]), rep
         assert torch.equal(out.view(torch.int16), want[2].view(torch.int16)) and torch.equal(lse, want[3]), rep
     say("   4 replays equal their eager runs")
+
+
+def test_two_streams_share_nothing():
+    """Two independent calls enqueued on two non-default streams at the same time (own outputs and
+    workspaces, the same read-only bank and index) give exactly what they give one after the other:
+    the library keeps no state of its own."""
+    say("case two streams: concurrent score_topk + sparse_attend on separate streams")
+    case = Case(82000, 3000, 2, 4, 64, 128, 16, 4, 1, 40, 1e6).to_device()
+    cfg = case.cfg()
+    N, G, k, B, M, Lloc = 3000, 64, 9, 4, 1, 40
+    KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+    pos0 = G
+    dpos = torch.full((B, M), pos0 + Lloc - 1, dtype=torch.int32, device="cuda")
+    qs = [case.dq, dev(S.normal_bf16(82001, (B, M, case.Hq, 128))[0])]
+    torch.cuda.synchronize()
+
+    def run(q, stream):
+        idx, val = msa.msa_score_topk(cfg, q, KR, inv, k, stream=stream)
+        out, lse = msa.msa_sparse_attend(cfg, q, case.dK, case.dV, idx, case.dKl, case.dVl, pos0, dpos, stream=stream)
+        return idx, val, out, lse
+
+    serial = []
+    for q in qs:
+        serial.append(run(q, None))
+        torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        conc = []
+        for q, st in zip(qs, streams):
+            with torch.cuda.stream(st):                            # outputs and workspaces are allocated on st
+                conc.append(run(q, st))
+        torch.cuda.synchronize()
+        for a, b in zip(serial, conc):
+            assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+            assert torch.equal(a[2].view(torch.int16), b[2].view(torch.int16)) and torch.equal(a[3], b[3])
+    say("   3 concurrent rounds equal the serial results")
