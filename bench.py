@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--ragged", action="store_true",
                     help="documents of different lengths: seeded lengths in [G/8, G] passed as cfg.doc_lens (the "
                          "bank keeps its G-row slots); byte counts then follow the lengths")
+    ap.add_argument("--local-tokens", type=int, default=None,
+                    help="decode workloads: local-context length instead of the workload's (BASELINE does not state "
+                         "it for configs 3 and 5; 2048 is used, 0 is the other case asked for)")
     ap.add_argument("--cold", action="store_true",
                     help="additionally time the step with nothing left in the 256 MB Infinity Cache from the step "
                          "before: round-robin over copies of the routing index (> 512 MB in all) and over 16 "
@@ -94,8 +97,8 @@ def cpu_baseline(wl, sample_docs):
     sel = idx[0, 0, 0]
     K_sel = Ks[sel][:, :1]
     V_sel = np.stack([W.host_doc(wl, "V", int(i))[1][:1] for i in sel])
-    Kl = S.normal_bf16(wl.seeds["Kloc"], (1, 1, wl.Lloc, wl.d))[1]
-    Vl = S.normal_bf16(wl.seeds["Vloc"], (1, 1, wl.Lloc, wl.d))[1]
+    Kl = S.normal_bf16(wl.seeds["Kloc"], (1, 1, wl.Lloc, wl.d))[1] if wl.Lloc else None
+    Vl = S.normal_bf16(wl.seeds["Vloc"], (1, 1, wl.Lloc, wl.d))[1] if wl.Lloc else None
     t0 = time.perf_counter()
     O.sparse_attend(q[:1, :1, :wl.r], K_sel, V_sel, np.arange(kk)[None, None, None], Kl, Vl, wl.pos0,
                     wl.q_pos_host[:1, :1], wl.base)
@@ -159,7 +162,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     msa.load_library()
     torch.cuda.set_device(0)
-    wl = W.make(args.workload)
+    wl = W.make(args.workload, Lloc=args.local_tokens)
     scope = msa.MSA_SCOPE_ALL if args.scope == "all" else msa.MSA_SCOPE_GROUP
     n_sel = 1 if args.scope == "all" else wl.Hkv
     lens = torch.from_numpy(W.doc_lens(wl)).cuda() if args.ragged else None

@@ -41,7 +41,7 @@ def planted_chunk(q_b, r, g, noise, a):
     return S.f64_to_bf16_bits(a * u[None, :] + noise)
 
 
-def make(name, device="cuda", plant_per_query=0, plant_a=0.12, plant_chunk=3):
+def make(name, device="cuda", plant_per_query=0, plant_a=0.12, plant_chunk=3, Lloc=None):
     """Allocate and fill the workload `name` on the device.  Returns a Workload with the shapes,
     device tensors (K, V, q, Kloc, Vloc, q_pos) and, if plant_per_query > 0, the planted documents
     (wl.planted[(b, j)] = doc id; their K slices are in wl.planted_K[doc] as bits [Hkv, G, d])."""
@@ -50,6 +50,9 @@ def make(name, device="cuda", plant_per_query=0, plant_a=0.12, plant_chunk=3):
     wl.name = name
     for key, v in p.items():
         setattr(wl, key, v)
+    if Lloc is not None:                              # decode workloads only: another local-context length
+        assert wl.M == 1 and Lloc >= 0
+        wl.Lloc = Lloc
     wl.r = wl.Hq // wl.Hkv
     wl.C = wl.G // wl.P
     wl.pos0 = wl.G                                   # local context follows a document's last token
@@ -62,12 +65,15 @@ def make(name, device="cuda", plant_per_query=0, plant_a=0.12, plant_chunk=3):
     SD.fill_normal_(wl.V, seeds["V"])
     wl.q_bits, wl.q_host = S.normal_bf16(seeds["q"], (wl.B, wl.M, wl.Hq, wl.d))
     wl.q = SD.bits_to_torch(wl.q_bits, device)
-    wl.Kloc = torch.empty((wl.B, wl.Hkv, wl.Lloc, wl.d), dtype=torch.bfloat16, device=device)
-    wl.Vloc = torch.empty_like(wl.Kloc)
-    SD.fill_normal_(wl.Kloc, seeds["Kloc"])
-    SD.fill_normal_(wl.Vloc, seeds["Vloc"])
-    if wl.M == 1:     # decode: the query is the last local token
-        wl.q_pos_host = np.full((wl.B, wl.M), wl.pos0 + wl.Lloc - 1, dtype=np.int32)
+    if wl.Lloc > 0:
+        wl.Kloc = torch.empty((wl.B, wl.Hkv, wl.Lloc, wl.d), dtype=torch.bfloat16, device=device)
+        wl.Vloc = torch.empty_like(wl.Kloc)
+        SD.fill_normal_(wl.Kloc, seeds["Kloc"])
+        SD.fill_normal_(wl.Vloc, seeds["Vloc"])
+    else:
+        wl.Kloc = wl.Vloc = None
+    if wl.M == 1:     # decode: the query is the last local token (position pos0 when there is no local context)
+        wl.q_pos_host = np.full((wl.B, wl.M), wl.pos0 + max(wl.Lloc, 1) - 1, dtype=np.int32)
     else:             # prefill: the local context IS the M query tokens, causal (token m sees 0..m)
         assert wl.Lloc == wl.M
         wl.q_pos_host = np.tile(wl.pos0 + np.arange(wl.M, dtype=np.int32), (wl.B, 1))
