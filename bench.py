@@ -27,7 +27,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM traffic per msa_score_topk call (bytes) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by the same counter's reading for a plain copy of known size (FETCH_SIZE reads 0.5 KiB per KiB
 # copied -> x2; WRITE_SIZE reads 1.0 -> x1); see profiles/pmc_traffic_cfg5_decode_50m.txt.
-MEASURED_SCORE_TRAFFIC = {"cfg5_decode_50m": 1660.7e6}   # prep + scan + merge, read + write
+MEASURED_SCORE_TRAFFIC = {"cfg5_decode_50m": 1660.7e6,   # prep + scan + merge, read + write
+                          "cfg3_batch32_4m": 155.2e6}    # prep + scan (score matrix) + row top-k; profiles/pmc_traffic_cfg3_batch32_4m.txt
 
 
 def parse():
