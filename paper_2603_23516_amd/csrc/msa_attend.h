@@ -31,6 +31,7 @@ struct AttendArgs {
   int idx_sel;           // selections per idx row: Hkv (one per KV group) or 1 (shared by all heads)
   int idx_rows_per_b;    // idx rows per batch row: M (one per query token) or 1 (shared by the M tokens)
   int steps_mem, steps_total, steps_per_split, n_splits;
+  int ph_splits, split0;  // partial slots per (query, head) in the workspace, and this launch's first slot
   float qscale;          // log2(e) / sqrt(d)
 };
 

@@ -518,7 +518,7 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
         lsum += f * wl[w][s0];
       }
     }
-    const long long ph = ((long long)bm * a.Hq + g * a.r + hh) * a.n_splits + sp;
+    const long long ph = ((long long)bm * a.Hq + g * a.r + hh) * a.ph_splits + a.split0 + sp;
     a.part_o[ph * D + dd] = osum;
     if (dd == 0) a.part_ml[ph] = make_float2(mx, lsum);
   }
@@ -603,15 +603,35 @@ AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_k
   const long long pairs = p.prefill ? (long long)B * p.n_ttiles * dm.Hkv : (long long)BM * dm.Hkv;
   // aim at <= 512 blocks: two 256-thread blocks are resident per CU (register-limited), so 512 is
   // one full wave of blocks on 256 CUs and nothing waits for a second round
-  long long per = ((long long)p.steps_total * pairs + 511) / 512;
-  if (per < kAttWaves) per = kAttWaves;
-  const long long per_cap = (p.steps_total + kMaxAttSplits - 1) / kMaxAttSplits;  // n_splits <= 256
-  if (per < per_cap) per = per_cap;
-  if (per > p.steps_total) per = p.steps_total;
-  if (per < 1) per = 1;
-  p.steps_per_split = (int)per;
-  p.n_splits = (p.steps_total + p.steps_per_split - 1) / p.steps_per_split;
-  if (p.n_splits < 1) p.n_splits = 1;
+  auto split = [](long long steps, long long prs, long long min_per, int max_splits, int* per_out) -> int {
+    long long per = (steps * prs + 511) / 512;
+    if (per < min_per) per = min_per;
+    const long long per_cap = (steps + max_splits - 1) / max_splits;
+    if (per < per_cap) per = per_cap;
+    if (per > steps) per = steps;
+    if (per < 1) per = 1;
+    *per_out = (int)per;
+    const long long n = (steps + per - 1) / per;
+    return n < 1 ? 1 : (int)n;
+  };
+  // Many query tokens with their own selections: every token gathers its documents (decode kernel), but
+  // the local context is the same rows for all tokens of a batch row, so it goes through the tiled
+  // kernel once per token tile instead of once per token; the partials of both land in one slot range.
+  p.split_local = (!p.prefill && !dm.token_pool && M >= 16 && Lloc >= 32 &&
+                   (dm.r == 1 || dm.r == 2 || dm.r == 4 || dm.r == 8)) ? 1 : 0;
+  p.mem_splits = p.loc_splits = 0;
+  p.mem_steps_per_split = p.loc_steps_per_split = 0;
+  if (p.split_local) {
+    p.tpw = 16 / dm.r;
+    p.n_ttiles = (M + 4 * p.tpw - 1) / (4 * p.tpw);
+    p.mem_splits = split(p.steps_mem, (long long)BM * dm.Hkv, kAttWaves, kMaxAttSplits / 2, &p.mem_steps_per_split);
+    p.loc_splits = split((Lloc + 31) / 32, (long long)B * p.n_ttiles * dm.Hkv, 1, kMaxAttSplits / 2,
+                         &p.loc_steps_per_split);
+    p.n_splits = p.mem_splits + p.loc_splits;
+    p.steps_per_split = p.mem_steps_per_split;
+  } else {
+    p.n_splits = split(p.steps_total, pairs, kAttWaves, kMaxAttSplits, &p.steps_per_split);
+  }
   const size_t o_bytes = round_up256((size_t)BM * dm.Hq * p.n_splits * dm.d * sizeof(float));
   p.off_ml = o_bytes;
   p.ws_bytes = o_bytes + round_up256((size_t)BM * dm.Hq * p.n_splits * sizeof(float2));
@@ -650,6 +670,8 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.steps_total = pl.steps_total;
   a.steps_per_split = pl.steps_per_split;
   a.n_splits = pl.n_splits;
+  a.ph_splits = pl.n_splits;
+  a.split0 = 0;
   a.qscale = (float)(1.4426950408889634 / sqrt((double)dm.d));
   RopeTheta th;
   for (int u = 0; u < kMaxHalf; ++u) {
@@ -658,11 +680,29 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     th.e16[u] = make_float2((float)cos(16.0 * th.th[u]), (float)sin(16.0 * th.th[u]));
   }
   const int BM = B * M;
+  if (pl.split_local) {
+    // local context through the tiled kernel (it never touches the bank or the selection: no memory steps) ...
+    AttendArgs al = a;
+    al.steps_mem = 0;
+    al.steps_total = (Lloc + 31) / 32;
+    al.steps_per_split = pl.loc_steps_per_split;
+    al.n_splits = pl.loc_splits;
+    al.split0 = pl.mem_splits;
+    AttendPlan pll = pl;
+    pll.n_splits = pl.loc_splits;
+    const int rc = launch_attend_prefill_partial(dm, pll, al, th, B, st);
+    if (rc != MSA_OK) return rc;
+    // ... and the selected documents through the decode kernel below, which sees no local context
+    a.Lloc = 0;
+    a.steps_total = pl.steps_mem;
+    a.steps_per_split = pl.mem_steps_per_split;
+    a.n_splits = pl.mem_splits;
+  }
   if (pl.prefill) {
     const int rc = launch_attend_prefill_partial(dm, pl, a, th, B, st);
     if (rc != MSA_OK) return rc;
   } else {
-  dim3 grid(pl.n_splits, dm.Hkv, BM), block(256);
+  dim3 grid(a.n_splits, dm.Hkv, BM), block(256);
   const int mode = !bank_keys_rotated ? 0 : (dm.G % 32 == 0 ? 1 : 2);
   if (mode != 2 && dm.G % 32 != 0) return MSA_ERR_UNSUPPORTED;
   if (mode == 2 && ((1 << a.gshift) != dm.G || dm.G > 16)) return MSA_ERR_UNSUPPORTED;

@@ -382,7 +382,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   // ---- partial results of this split ---------------------------------------------------------------
   const float l_tot = both_halves_sum(l_run);
   if (tok_ok) {  // the same for both columns of a pair, so the lane exchange below stays inside the mask
-    const long long ph = (((long long)b * a.M + m_tok) * a.Hq + g * r + hh) * a.n_splits + sp;
+    const long long ph = (((long long)b * a.M + m_tok) * a.Hq + g * r + hh) * a.ph_splits + a.split0 + sp;
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll

@@ -65,6 +65,10 @@ struct AttendPlan {
   int steps_per_split;
   int n_splits;
   int prefill;           // 1: shared selection and many tokens -> attend_prefill_kernel
+  int split_local;       // 1: per-token selections and many tokens: the selected documents go through the decode
+                         //    kernel, the local context (shared by the tokens) through attend_prefill_kernel
+  int mem_splits, mem_steps_per_split;  // split_local: decode kernel over the documents
+  int loc_splits, loc_steps_per_split;  // split_local: tiled kernel over the local context
   int tpw, n_ttiles;     // prefill: tokens per wave (16 / r), token tiles (4 waves each) per batch row
   size_t off_ml;         // byte offset of the (m, l) pairs inside the workspace
   size_t ws_bytes;
