@@ -614,10 +614,11 @@ AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_k
     const long long n = (steps + per - 1) / per;
     return n < 1 ? 1 : (int)n;
   };
-  // Many query tokens with their own selections: every token gathers its documents (decode kernel), but
-  // the local context is the same rows for all tokens of a batch row, so it goes through the tiled
-  // kernel once per token tile instead of once per token; the partials of both land in one slot range.
-  p.split_local = (!p.prefill && !dm.token_pool && M >= 16 && Lloc >= 32 &&
+  // Many query tokens that the shared-selection kernel above does not take (their own selections, or a
+  // bank whose keys are stored rotated): every token gathers its documents (decode kernel), but the local
+  // context is the same rows for all tokens of a batch row, so it goes through the tiled kernel once per
+  // token tile instead of once per token; the partials of both land in one slot range.
+  p.split_local = (!p.prefill && M >= 16 && Lloc >= 32 &&
                    (dm.r == 1 || dm.r == 2 || dm.r == 4 || dm.r == 8)) ? 1 : 0;
   p.mem_splits = p.loc_splits = 0;
   p.mem_steps_per_split = p.loc_steps_per_split = 0;
