@@ -317,13 +317,21 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     }
     float sc[16];
     float mx = -INFINITY;
+    if (is_mem && rows_valid == 32) {  // block-uniform: a whole step of document rows, nothing to mask
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int krow = (i & 3) + 8 * (i >> 2) + 4 * h;
-      const float v = sacc[i] + dpp_f<kDppXor1>(sacc[i]);  // hi + lo column
-      const bool live = is_mem ? true : (t0 + krow < nvis_col);
-      sc[i] = (krow < rows_valid && live) ? v : -INFINITY;
-      mx = fmaxf(mx, sc[i]);
+      for (int i = 0; i < 16; ++i) {
+        sc[i] = sacc[i] + dpp_f<kDppXor1>(sacc[i]);  // hi + lo column
+        mx = fmaxf(mx, sc[i]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int krow = (i & 3) + 8 * (i >> 2) + 4 * h;
+        const float v = sacc[i] + dpp_f<kDppXor1>(sacc[i]);  // hi + lo column
+        const bool live = is_mem ? true : (t0 + krow < nvis_col);
+        sc[i] = (krow < rows_valid && live) ? v : -INFINITY;
+        mx = fmaxf(mx, sc[i]);
+      }
     }
     mx = both_halves_max(mx);
     if (mx > m_run) {  // per column; the accumulators of a lane all belong to its column
