@@ -681,6 +681,10 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     th.e16[u] = make_float2((float)cos(16.0 * th.th[u]), (float)sin(16.0 * th.th[u]));
   }
   const int BM = B * M;
+  // how the bank is read (checked before anything is enqueued)
+  const int mode = !bank_keys_rotated ? 0 : (dm.G % 32 == 0 ? 1 : 2);
+  if (mode != 2 && dm.G % 32 != 0) return MSA_ERR_UNSUPPORTED;
+  if (mode == 2 && ((1 << a.gshift) != dm.G || dm.G > 16)) return MSA_ERR_UNSUPPORTED;
   if (pl.split_local) {
     // local context through the tiled kernel (it never touches the bank or the selection: no memory steps) ...
     AttendArgs al = a;
@@ -703,21 +707,18 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     const int rc = launch_attend_prefill_partial(dm, pl, a, th, B, st);
     if (rc != MSA_OK) return rc;
   } else {
-  dim3 grid(a.n_splits, dm.Hkv, BM), block(256);
-  const int mode = !bank_keys_rotated ? 0 : (dm.G % 32 == 0 ? 1 : 2);
-  if (mode != 2 && dm.G % 32 != 0) return MSA_ERR_UNSUPPORTED;
-  if (mode == 2 && ((1 << a.gshift) != dm.G || dm.G > 16)) return MSA_ERR_UNSUPPORTED;
+    dim3 grid(a.n_splits, dm.Hkv, BM), block(256);
 #define MSA_LAUNCH_ATTEND(DD, MM) \
   hipLaunchKernelGGL((attend_partial_kernel<DD, MM>), grid, block, 0, st, a, th)
-  if (dm.d == 128) {
-    if (mode == 0) MSA_LAUNCH_ATTEND(128, 0);
-    else if (mode == 1) MSA_LAUNCH_ATTEND(128, 1);
-    else MSA_LAUNCH_ATTEND(128, 2);
-  } else {
-    if (mode == 0) MSA_LAUNCH_ATTEND(64, 0);
-    else if (mode == 1) MSA_LAUNCH_ATTEND(64, 1);
-    else MSA_LAUNCH_ATTEND(64, 2);
-  }
+    if (dm.d == 128) {
+      if (mode == 0) MSA_LAUNCH_ATTEND(128, 0);
+      else if (mode == 1) MSA_LAUNCH_ATTEND(128, 1);
+      else MSA_LAUNCH_ATTEND(128, 2);
+    } else {
+      if (mode == 0) MSA_LAUNCH_ATTEND(64, 0);
+      else if (mode == 1) MSA_LAUNCH_ATTEND(64, 1);
+      else MSA_LAUNCH_ATTEND(64, 2);
+    }
 #undef MSA_LAUNCH_ATTEND
   }
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
