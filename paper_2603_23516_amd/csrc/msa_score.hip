@@ -13,8 +13,8 @@
 // stored in tiles of 16 keys already in B-operand order, so a wave reads a tile with d/32 coalesced
 // 1 KiB loads and no LDS staging.
 //
-// Work split.  One wavefront = one workgroup = one contiguous stream of tiles of one KV head, with a
-// ring of kPrefetch tiles in flight; there is no synchronisation between waves.  Document max = DPP
+// Work split.  One wavefront = one stream of tiles of one KV head (wave s of S takes tiles s, s + S, ...),
+// with a ring of kPrefetch tiles in flight; a workgroup holds four such streams that never synchronise.  Document max = DPP
 // max over the C lanes of a document.  Top-k = threshold filter + per-(wave, query) candidate list in
 // LDS: accepted lanes get their slots from a ballot and a population count (no atomics, counters live
 // in registers), lists are pruned to the k best by rank counting on 64-bit (score, ~doc) keys, and
