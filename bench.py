@@ -204,8 +204,7 @@ def main():
                              token_pool=int(args.token_pool), bank_keys_rotated=1)
         pos0 = wl.k                                                      # Section 3.2.2: local positions start at k
         q_pos = (wl.q_pos - wl.pos0 + pos0).contiguous()
-        local_rows = wl.M * wl.Lloc if wl.M == 1 else wl.M * (wl.M + 1) // 2   # causal prefill: token m sees m + 1
-        ab["attend"] = wl.B * wl.Hkv * (wl.M * wl.k * wl.C + local_rows) * wl.d * 2 * 2
+        ab["attend"] = wl.B * wl.Hkv * (wl.M * wl.k * wl.C + wl.Lloc) * wl.d * 2 * 2   # local context read once
         ab["pool"] = 2 * wl.N * wl.Hkv * (wl.G + wl.C) * wl.d * 2
 
     # ---- online path: everything preallocated, nothing allocated inside the timed region --------

@@ -123,6 +123,6 @@ def algorithmic_bytes(wl):
     score_once = wl.Hkv * tiles * 16 * (wl.d * elem + 4)
     if wl.M == 1:
         attend = wl.B * wl.M * wl.Hkv * (wl.k * wl.G + wl.Lloc) * wl.d * elem * 2
-    else:   # causal prefill: token m reads k documents + m + 1 local rows (upper bound: no reuse between tokens)
-        attend = wl.B * wl.Hkv * (wl.M * wl.k * wl.G + wl.M * (wl.M + 1) // 2) * wl.d * elem * 2
+    else:   # prefill: every token gathers its own k documents; the local context is shared by the tokens (once)
+        attend = wl.B * wl.Hkv * (wl.M * wl.k * wl.G + wl.Lloc) * wl.d * elem * 2
     return dict(build=build, score=score_once, score_passes=n_pass, attend=attend)

@@ -598,7 +598,7 @@ AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_k
   // many query tokens sharing one selection: the tiled prefill kernel (raw keys, r a power of two)
   p.prefill = (dm.token_pool && M >= 8 && !bank_keys_rotated && dm.G % 32 == 0 &&
                (dm.r == 1 || dm.r == 2 || dm.r == 4 || dm.r == 8)) ? 1 : 0;
-  p.tpw = p.prefill ? 16 / dm.r : 0;
+  p.tpw = p.prefill ? 32 / dm.r : 0;
   p.n_ttiles = p.prefill ? (M + 4 * p.tpw - 1) / (4 * p.tpw) : 0;
   const long long pairs = p.prefill ? (long long)B * p.n_ttiles * dm.Hkv : (long long)BM * dm.Hkv;
   // aim at <= 512 blocks: two 256-thread blocks are resident per CU (register-limited), so 512 is
@@ -623,7 +623,7 @@ AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_k
   p.mem_splits = p.loc_splits = 0;
   p.mem_steps_per_split = p.loc_steps_per_split = 0;
   if (p.split_local) {
-    p.tpw = 16 / dm.r;
+    p.tpw = 32 / dm.r;
     p.n_ttiles = (M + 4 * p.tpw - 1) / (4 * p.tpw);
     p.mem_splits = split(p.steps_mem, (long long)BM * dm.Hkv, kAttWaves, kMaxAttSplits / 2, &p.mem_steps_per_split);
     p.loc_splits = split((Lloc + 31) / 32, (long long)B * p.n_ttiles * dm.Hkv, 1, kMaxAttSplits / 2,

@@ -6,19 +6,20 @@
 // with 64 / r query tokens x r heads on the matrix cores.
 //
 // Work split.  A workgroup owns a tile of 4 * TPW query tokens of one (batch row, KV head), TPW =
-// 16 / r tokens per wave, and a contiguous range of 32-key steps (split-K as in the decode path; the
+// 32 / r tokens per wave, and a contiguous range of 32-key steps (split-K as in the decode path; the
 // partials (max, sum, O) use the same layout and the same merge kernel).  Per step:
 //   all 256 threads  load the 32 key rows and 32 value rows (16-byte pieces), rotate the keys in
 //                    fp32 (thread = key x 8 rotation pairs, running (cos, sin) advanced by 32
 //                    positions per step), round to bf16 and write them to LDS in MFMA operand order;
 //                    values go to LDS as they are (padded rows for transposed 16-bit reads);
-//   every wave       S^T[32 keys][32 slots] = K~ Q~^T with v_mfma_f32_32x32x16_bf16; a slot is
-//                    (token, head, hi | lo): the rotated, scaled queries are carried as bf16 (hi, lo)
-//                    pairs in adjacent columns, exactly as in the decode kernel; online softmax per
-//                    column (16 keys per lane, the other 16 in lane ^ 32); the weights go back as
-//                    bf16 (hi, lo) and ARE the B operand of  O^T[dd][slot] += V^T[dd][key] P^T[key][slot]
-//                    (the contraction index runs over the lane's own 8 keys of each 16-key slice, and
-//                    V^T is read with 16-bit LDS reads in the same key order).
+//   every wave       S^T[32 keys][32 slots] = K~ Q~^T with v_mfma_f32_32x32x16_bf16; a slot (column) is a
+//                    (token, head) pair.  The rotated, scaled queries are carried as bf16 (hi, lo) pairs
+//                    laid along the CONTRACTION (two products per slice into one accumulator), so a
+//                    score exists in exactly one lane and the softmax work is not duplicated; online
+//                    softmax per column (16 keys per lane, the other 16 in lane ^ 32); the weights go
+//                    back as bf16 hi and lo parts, two B operands of  O^T[dd][slot] += V^T[dd][key] P^T[key][slot]
+//                    that share one A operand (the contraction index runs over the lane's own 8 keys of
+//                    each 16-key slice, and V^T is read with 16-bit LDS reads in the same key order).
 // Causality: local key t is visible to token m iff pos0 + t <= q_pos[m]; the mask is per column and
 // the workgroup stops at the last step any of its tokens can see.  LDS is double buffered, one
 // barrier per step.
@@ -67,7 +68,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   unsigned char* const kt0 = smem;                       // rotated keys [piece][key][8 bf16], two buffers
   uint16_t* const vt0 = reinterpret_cast<uint16_t*>(smem + 2 * KT_BYTES);  // value rows, two buffers
   __shared__ float2 bt[32][HALF];  // e^{i key theta_u}, key < 32
-  __shared__ int nvis_s[64];       // visible local tokens of each token of the tile
+  __shared__ int nvis_s[128];      // visible local tokens of each token of the tile (4 waves x 32 / r tokens)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -98,7 +99,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
       cur = cmul(cur, w);
     }
   }
-  if (tid < 64) {
+  if (tid < 128) {
     int nv = 0;
     const int m = m_tile + tid;
     if (tid < tile_tok && m < a.M) {
@@ -107,56 +108,69 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     }
     nvis_s[tid] = nv;
   }
-  // (cos, sin)(q_pos theta_u) of this wave's tokens, staged in the (still unused) key buffer
-  float2* ang = reinterpret_cast<float2*>(smem) + wave * (16 * HALF);  // [tpw][HALF]
-  for (int e = lane; e < tpw * HALF; e += 64) {
-    const int tl = e / HALF, u = e % HALF;
-    const int m = m_tile + wave * tpw + tl;
-    const int qp = (m < a.M) ? a.q_pos[(long long)b * a.M + m] : 0;
-    ang[e] = cis_pos(qp, th.th[u]);
-  }
   __syncthreads();
   int nvis_blk = 0;
   for (int i = 0; i < tile_tok; ++i) nvis_blk = nvis_s[i] > nvis_blk ? nvis_s[i] : nvis_blk;
 
-  // B operand of the score product: column = slot (pair col/2 = (token, head), hi for even, lo for odd)
-  const int pair = col >> 1;
-  const int tl = pair / r, hh = pair - tl * r;
+  // B operands of the score product: column = (token, head) pair; hi and lo parts of the rotated, scaled
+  // query are two operands that go into the same accumulator
+  const int tl = col / r, hh = col - tl * r;
   const int m_tok = m_tile + wave * tpw + tl;           // this column's query token
   const bool tok_ok = tl < tpw && m_tok < a.M;
   const int nvis_col = tok_ok ? nvis_s[wave * tpw + tl] : 0;
-  bf16x8_t bq[NS];
-  {
-    const uint16_t* qp = a.q + (((long long)b * a.M + (tok_ok ? m_tok : 0)) * a.Hq + g * r + hh) * D;
+  bf16x8_t bqh[NS], bql[NS];
 #pragma unroll
-    for (int s = 0; s < NS / 2; ++s) {
-      // dims 16 s + 8 h .. +8 (first half) and their partners + D/2 (slice s + NS/2)
-      const uint4 r1 = *reinterpret_cast<const uint4*>(qp + 16 * s + 8 * h);
-      const uint4 r2 = *reinterpret_cast<const uint4*>(qp + HALF + 16 * s + 8 * h);
-      const uint32_t w1[4] = {r1.x, r1.y, r1.z, r1.w}, w2[4] = {r2.x, r2.y, r2.z, r2.w};
-      uint32_t o1[4], o2[4];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        float y1[2], y2[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const float x1 = e ? bf16_hi(w1[jj]) : bf16_lo(w1[jj]);
-          const float x2 = e ? bf16_hi(w2[jj]) : bf16_lo(w2[jj]);
-          const float2 cs = ang[(tok_ok ? tl : 0) * HALF + 16 * s + 8 * h + 2 * jj + e];
-          y1[e] = tok_ok ? (x1 * cs.x - x2 * cs.y) * a.qscale : 0.f;
-          y2[e] = tok_ok ? (x2 * cs.x + x1 * cs.y) * a.qscale : 0.f;
-        }
-        float h0, l0, h1, l1;
-        split_bf16(y1[0], h0, l0);
-        split_bf16(y1[1], h1, l1);
-        o1[jj] = (col & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
-        split_bf16(y2[0], h0, l0);
-        split_bf16(y2[1], h1, l1);
-        o2[jj] = (col & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
-      }
-      bq[s] = as_bf16x8(make_uint4(o1[0], o1[1], o1[2], o1[3]));
-      bq[s + NS / 2] = as_bf16x8(make_uint4(o2[0], o2[1], o2[2], o2[3]));
+  for (int s = 0; s < NS; ++s) bqh[s] = bql[s] = as_bf16x8(make_uint4(0, 0, 0, 0));
+  // (cos, sin)(q_pos theta_u) of 16 of this wave's tokens at a time, staged in the wave's own part of
+  // the (still unused) key buffer
+  float2* ang = reinterpret_cast<float2*>(smem) + wave * (16 * HALF);  // [16][HALF]
+  for (int rd = 0; rd * 16 < tpw; ++rd) {
+    for (int e = lane; e < 16 * HALF; e += 64) {
+      const int t16 = e / HALF, u = e % HALF;
+      const int m = m_tile + wave * tpw + rd * 16 + t16;
+      const int qp = (rd * 16 + t16 < tpw && m < a.M) ? a.q_pos[(long long)b * a.M + m] : 0;
+      ang[e] = cis_pos(qp, th.th[u]);
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (tok_ok && (tl >> 4) == rd) {
+      const uint16_t* qp = a.q + (((long long)b * a.M + m_tok) * a.Hq + g * r + hh) * D;
+#pragma unroll
+      for (int s = 0; s < NS / 2; ++s) {
+        // dims 16 s + 8 h .. +8 (first half) and their partners + D/2 (slice s + NS/2)
+        const uint4 r1 = *reinterpret_cast<const uint4*>(qp + 16 * s + 8 * h);
+        const uint4 r2 = *reinterpret_cast<const uint4*>(qp + HALF + 16 * s + 8 * h);
+        const uint32_t w1[4] = {r1.x, r1.y, r1.z, r1.w}, w2[4] = {r2.x, r2.y, r2.z, r2.w};
+        uint32_t h1w[4], l1w[4], h2w[4], l2w[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          float y1[2], y2[2];
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const float x1 = e ? bf16_hi(w1[jj]) : bf16_lo(w1[jj]);
+            const float x2 = e ? bf16_hi(w2[jj]) : bf16_lo(w2[jj]);
+            const float2 cs = ang[(tl & 15) * HALF + 16 * s + 8 * h + 2 * jj + e];
+            y1[e] = (x1 * cs.x - x2 * cs.y) * a.qscale;
+            y2[e] = (x2 * cs.x + x1 * cs.y) * a.qscale;
+          }
+          float h0, l0, h1, l1;
+          split_bf16(y1[0], h0, l0);
+          split_bf16(y1[1], h1, l1);
+          h1w[jj] = pack_bf16(h0, h1);
+          l1w[jj] = pack_bf16(l0, l1);
+          split_bf16(y2[0], h0, l0);
+          split_bf16(y2[1], h1, l1);
+          h2w[jj] = pack_bf16(h0, h1);
+          l2w[jj] = pack_bf16(l0, l1);
+        }
+        bqh[s] = as_bf16x8(make_uint4(h1w[0], h1w[1], h1w[2], h1w[3]));
+        bql[s] = as_bf16x8(make_uint4(l1w[0], l1w[1], l1w[2], l1w[3]));
+        bqh[s + NS / 2] = as_bf16x8(make_uint4(h2w[0], h2w[1], h2w[2], h2w[3]));
+        bql[s + NS / 2] = as_bf16x8(make_uint4(l2w[0], l2w[1], l2w[2], l2w[3]));
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }
   __syncthreads();  // the angle staging area becomes the key buffer
 
@@ -313,21 +327,22 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     for (int s = 0; s < NS; ++s) {
       const bf16x8_t ak =
           as_bf16x8(*reinterpret_cast<const uint4*>(&kt0[buf * KT_BYTES + ((2 * s + h) * 32 + col) * 16]));
-      sacc = mfma32p(ak, bq[s], sacc);
+      sacc = mfma32p(ak, bqh[s], sacc);
+      sacc = mfma32p(ak, bql[s], sacc);
     }
     float sc[16];
     float mx = -INFINITY;
     if (is_mem && rows_valid == 32) {  // block-uniform: a whole step of document rows, nothing to mask
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        sc[i] = sacc[i] + dpp_f<kDppXor1>(sacc[i]);  // hi + lo column
+        sc[i] = sacc[i];
         mx = fmaxf(mx, sc[i]);
       }
     } else {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int krow = (i & 3) + 8 * (i >> 2) + 4 * h;
-        const float v = sacc[i] + dpp_f<kDppXor1>(sacc[i]);  // hi + lo column
+        const float v = sacc[i];
         const bool live = is_mem ? true : (t0 + krow < nvis_col);
         sc[i] = (krow < rows_valid && live) ? v : -INFINITY;
         mx = fmaxf(mx, sc[i]);
@@ -344,20 +359,19 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
         for (int i = 0; i < 16; ++i) o[t][i] *= alpha;
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-    uint32_t pw[8];
+    uint32_t pwh[8], pwl[8];
     float psum = 0.f;
 #pragma unroll
     for (int i2 = 0; i2 < 8; ++i2) {
-      float pv[2];
+      float ph2[2], pl2[2];
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const float p = __builtin_amdgcn_exp2f(sc[2 * i2 + e] - m_use);
         psum += p;
-        float hi, lo;
-        split_bf16(p, hi, lo);
-        pv[e] = (col & 1) ? lo : hi;
+        split_bf16(p, ph2[e], pl2[e]);
       }
-      pw[i2] = pack_bf16(pv[0], pv[1]);
+      pwh[i2] = pack_bf16(ph2[0], ph2[1]);
+      pwl[i2] = pack_bf16(pl2[0], pl2[1]);
     }
     l_run += psum;
 
@@ -366,7 +380,8 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     // score registers 8 sg .. 8 sg + 7
 #pragma unroll
     for (int sg = 0; sg < 2; ++sg) {
-      const bf16x8_t pb = as_bf16x8(make_uint4(pw[4 * sg], pw[4 * sg + 1], pw[4 * sg + 2], pw[4 * sg + 3]));
+      const bf16x8_t pbh = as_bf16x8(make_uint4(pwh[4 * sg], pwh[4 * sg + 1], pwh[4 * sg + 2], pwh[4 * sg + 3]));
+      const bf16x8_t pbl = as_bf16x8(make_uint4(pwl[4 * sg], pwl[4 * sg + 1], pwl[4 * sg + 2], pwl[4 * sg + 3]));
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         uint32_t w[4];
@@ -379,7 +394,9 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
           const uint32_t hi = vt0[buf * (VT_BYTES / 2) + r1 * VS2 + 32 * t + col];
           w[jj] = lo | (hi << 16);
         }
-        o[t] = mfma32p(as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])), pb, o[t]);
+        const bf16x8_t av = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+        o[t] = mfma32p(av, pbh, o[t]);
+        o[t] = mfma32p(av, pbl, o[t]);
       }
     }
     st = st_next;
@@ -389,17 +406,16 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
 
   // ---- partial results of this split ---------------------------------------------------------------
   const float l_tot = both_halves_sum(l_run);
-  if (tok_ok) {  // the same for both columns of a pair, so the lane exchange below stays inside the mask
+  if (tok_ok) {
     const long long ph = (((long long)b * a.M + m_tok) * a.Hq + g * r + hh) * a.ph_splits + a.split0 + sp;
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float v = o[t][i] + dpp_f<kDppXor1>(o[t][i]);  // hi + lo column
         const int dd = 32 * t + (i & 3) + 8 * (i >> 2) + 4 * h;
-        if ((col & 1) == 0) a.part_o[ph * D + dd] = v;
+        a.part_o[ph * D + dd] = o[t][i];
       }
-    if ((col & 1) == 0 && h == 0) a.part_ml[ph] = make_float2(m_run, l_tot);
+    if (h == 0) a.part_ml[ph] = make_float2(m_run, l_tot);
   }
 }
 

@@ -69,7 +69,7 @@ struct AttendPlan {
                          //    kernel, the local context (shared by the tokens) through attend_prefill_kernel
   int mem_splits, mem_steps_per_split;  // split_local: decode kernel over the documents
   int loc_splits, loc_steps_per_split;  // split_local: tiled kernel over the local context
-  int tpw, n_ttiles;     // prefill: tokens per wave (16 / r), token tiles (4 waves each) per batch row
+  int tpw, n_ttiles;     // prefill: tokens per wave (32 / r), token tiles (4 waves each) per batch row
   size_t off_ml;         // byte offset of the (m, l) pairs inside the workspace
   size_t ws_bytes;
 };
