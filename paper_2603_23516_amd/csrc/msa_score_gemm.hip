@@ -102,7 +102,7 @@ struct GemmArgs {
 };
 
 template <int D>
-__global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void score_gemm_kernel(GemmArgs a) {
   constexpr int NS8 = D / 16;            // 16-wide contraction slices per half (hi / lo)
   constexpr int SUB_BYTES = 32 * D * 2;  // one 32-key sub-tile
   constexpr int STAGE_BYTES = 2 * SUB_BYTES;  // a stage = two sub-tiles = 64 keys, one barrier
@@ -179,6 +179,45 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
       lsc[cb][p] = -INFINITY;
       ldoc[cb][p] = -1;
     }
+
+  // Accepted candidates wait in a two-deep per-lane buffer (newest at index 0) and enter the sorted
+  // lists only when some lane's buffer is full.  The sorted insertion costs the whole wave ~64 vector
+  // instructions however few lanes take part; run for every sub-tile in which ANY of the 64 lanes accepts
+  // a document it would run in most of them; run on full buffers it runs far less often (a deeper buffer
+  // would help more but does not fit the register budget of two waves per SIMD: three entries spill).  The
+  // acceptance test uses the list's last entry as it was at the last flush: a valid (if slightly stale)
+  // lower bound, so nothing that belongs in the list is ever turned away.
+  constexpr int kPend = 2;
+  float psc[2][kPend];
+  int pdoc[2][kPend];
+  int pcnt[2] = {0, 0};
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int q = 0; q < kPend; ++q) {
+      psc[cb][q] = -INFINITY;
+      pdoc[cb][q] = -1;
+    }
+  // oldest first, so that among equal scores the lower document stays ahead
+  auto flush = [&](int cb) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = kPend - 1; q >= 0; --q) {
+      const float sc = psc[cb][q];
+      const int doc = pdoc[cb][q];
+      const bool ok = q < pcnt[cb] && sc > lsc[cb][kGemmK - 1];
+      // branch-free insertion below every entry with score >= sc
+#pragma unroll
+      for (int p = kGemmK - 1; p >= 0; --p) {
+        const float above = (p > 0) ? lsc[cb][p - 1] : INFINITY;
+        const int above_d = (p > 0) ? ldoc[cb][p - 1] : -1;
+        const bool shift = ok && sc > above;            // entry p-1 moves down to p
+        const bool here = ok && !shift && sc > lsc[cb][p];
+        lsc[cb][p] = shift ? above : (here ? sc : lsc[cb][p]);
+        ldoc[cb][p] = shift ? above_d : (here ? doc : ldoc[cb][p]);
+      }
+    }
+    pcnt[cb] = 0;
+  };
 
   // ---- staging of key stages: global -> LDS directly (no registers), two stages ahead ---------
   // A 64-lane global_load_lds_dwordx4 lands at LDS base + 16 * lane, and a stage is contiguous in
@@ -270,17 +309,16 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
         const long long doc = st * 4 + 2 * h + jj;
         const bool ok = doc < a.N && sc > lsc[cb][kGemmK - 1];
         if (__any(ok)) {
-          // branch-free insertion below every entry with score >= sc (documents arrive in
-          // increasing order, so equal scores keep the lower document first)
+          // push onto the lane's pending buffer (documents arrive in increasing order)
 #pragma unroll
-          for (int p = kGemmK - 1; p >= 0; --p) {
-            const float above = (p > 0) ? lsc[cb][p - 1] : INFINITY;
-            const int above_d = (p > 0) ? ldoc[cb][p - 1] : -1;
-            const bool shift = ok && sc > above;            // entry p-1 moves down to p
-            const bool here = ok && !shift && sc > lsc[cb][p];
-            lsc[cb][p] = shift ? above : (here ? sc : lsc[cb][p]);
-            ldoc[cb][p] = shift ? above_d : (here ? (int)doc : ldoc[cb][p]);
+          for (int q = kPend - 1; q > 0; --q) {
+            psc[cb][q] = ok ? psc[cb][q - 1] : psc[cb][q];
+            pdoc[cb][q] = ok ? pdoc[cb][q - 1] : pdoc[cb][q];
           }
+          psc[cb][0] = ok ? sc : psc[cb][0];
+          pdoc[cb][0] = ok ? (int)doc : pdoc[cb][0];
+          pcnt[cb] += ok ? 1 : 0;
+          if (__any(pcnt[cb] == kPend)) flush(cb);
         }
       }
     }
@@ -312,6 +350,8 @@ __global__ __launch_bounds__(256) void score_gemm_kernel(GemmArgs a) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
+  flush(0);
+  flush(1);
   // ---- merge the two half-wave lists of every token, write sorted keys -----------------------
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb) {
