@@ -636,6 +636,14 @@ AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_k
   const size_t o_bytes = round_up256((size_t)BM * dm.Hq * p.n_splits * dm.d * sizeof(float));
   p.off_ml = o_bytes;
   p.ws_bytes = o_bytes + round_up256((size_t)BM * dm.Hq * p.n_splits * sizeof(float2));
+  // the tiled kernel reads keys that were rotated once per (batch row, KV head): all steps of a shared
+  // selection, or the local steps alone
+  p.off_krot = 0;
+  p.krot_steps = p.prefill ? p.steps_total : (p.split_local ? (Lloc + 31) / 32 : 0);
+  if (p.krot_steps > 0) {
+    p.off_krot = p.ws_bytes;
+    p.ws_bytes += round_up256((size_t)B * dm.Hkv * p.krot_steps * 32 * dm.d * 2);
+  }
   return p;
 }
 
@@ -652,6 +660,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.Vloc = (const uint16_t*)Vloc;
   a.q_pos = q_pos;
   a.lens = dm.lens;
+  a.Krot = pl.krot_steps > 0 ? (const uint16_t*)((char*)ws + pl.off_krot) : nullptr;
   a.part_o = (float*)ws;
   a.part_ml = (float2*)((char*)ws + pl.off_ml);
   a.M = M;

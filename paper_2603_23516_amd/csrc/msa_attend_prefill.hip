@@ -29,6 +29,11 @@ namespace msa {
 
 typedef float f32x16p_t __attribute__((ext_vector_type(16)));
 
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ s16x4_t lds_read_tr16(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)p);
+}
+
 __device__ __forceinline__ f32x16p_t mfma32p(bf16x8_t a, bf16x8_t b, f32x16p_t c) {
   // D(32x32) += A(32x16) * B(16x32).  Lane l: A[l%32][8(l/32)..+8], B[8(l/32)..+8][l%32],
   // D register i: row (i%4) + 8(i/4) + 4(l/32), column l%32.
@@ -47,6 +52,68 @@ __device__ __forceinline__ float both_halves_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// The keys of a (batch row, KV head) are the same for every token tile, so they are rotated ONCE, by
+// this kernel, and stored step by step in the order the tiled kernel keeps them in LDS
+// ([piece][key][8 bf16], 32 keys per step); the tiled kernel then copies a step global -> LDS
+// without touching a register or a vector instruction.  One workgroup per (step, KV head, batch row);
+// the step numbering and the row clamping are the tiled kernel's (all Lloc local rows are prepared,
+// whatever the tokens of a tile can see).  Angles come straight from a double-precision range
+// reduction: no recurrence, so these keys are if anything more accurate than in-kernel rotation.
+template <int D>
+__global__ __launch_bounds__(256) void rotate_steps_kernel(AttendArgs a, RopeTheta th, uint16_t* __restrict__ Krot) {
+  constexpr int HALF = D / 2;
+  constexpr int PPH = D / 16;
+  const int tid = threadIdx.x;
+  if (tid >= 32 * PPH) return;
+  const int kr = tid / PPH, pc = tid % PPH;
+  const int st = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const uint16_t* Kb;
+  int rows_valid, p_first;
+  if (st < a.steps_mem) {
+    const long long idx_row = (a.idx_rows_per_b == 1) ? b : (long long)b * a.M;
+    const int32_t* idx_g = a.idx + (idx_row * a.idx_sel + (a.idx_sel == 1 ? 0 : g)) * a.k;
+    const int tok = st * 32;
+    const int slot = tok / a.G;
+    const int pin = tok - slot * a.G;
+    const int doc = idx_g[slot];
+    if (doc < 0 || doc >= a.N) return;
+    int len = a.G;
+    if (a.lens != nullptr) {
+      len = a.lens[doc];
+      len = len < 1 ? 1 : (len > a.G ? a.G : len);
+    }
+    if (pin >= len) return;
+    Kb = a.K + (((long long)doc * a.Hkv + g) * a.G + pin) * D;
+    rows_valid = len - pin < 32 ? len - pin : 32;
+    p_first = pin;
+  } else {
+    const int t0 = (st - a.steps_mem) * 32;
+    if (t0 >= a.Lloc) return;
+    Kb = a.Kloc + (((long long)b * a.Hkv + g) * a.Lloc + t0) * D;
+    rows_valid = a.Lloc - t0 < 32 ? a.Lloc - t0 : 32;
+    p_first = a.pos0 + t0;
+  }
+  const int row = kr < rows_valid ? kr : rows_valid - 1;
+  const uint16_t* rp = Kb + (long long)row * D + pc * 8;
+  const uint4 k1 = *reinterpret_cast<const uint4*>(rp);
+  const uint4 k2 = *reinterpret_cast<const uint4*>(rp + HALF);
+  const uint32_t w1[4] = {k1.x, k1.y, k1.z, k1.w}, w2[4] = {k2.x, k2.y, k2.z, k2.w};
+  uint32_t y1[4], y2[4];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const float2 c0 = cis_pos(p_first + row, th.th[8 * pc + 2 * jj]);
+    const float2 c1 = cis_pos(p_first + row, th.th[8 * pc + 2 * jj + 1]);
+    const float p0 = bf16_lo(w1[jj]), p1 = bf16_hi(w1[jj]);
+    const float q0 = bf16_lo(w2[jj]), q1 = bf16_hi(w2[jj]);
+    y1[jj] = pack_bf16(p0 * c0.x - q0 * c0.y, p1 * c1.x - q1 * c1.y);
+    y2[jj] = pack_bf16(q0 * c0.x + p0 * c0.y, q1 * c1.x + p1 * c1.y);
+  }
+  unsigned char* blk = reinterpret_cast<unsigned char*>(Krot) +
+                       (((long long)b * a.Hkv + g) * a.steps_total + st) * (32 * D * 2);
+  *reinterpret_cast<uint4*>(&blk[(pc * 32 + kr) * 16]) = make_uint4(y1[0], y1[1], y1[2], y1[3]);
+  *reinterpret_cast<uint4*>(&blk[((pc + PPH) * 32 + kr) * 16]) = make_uint4(y2[0], y2[1], y2[2], y2[3]);
+}
+
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
@@ -55,19 +122,16 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   constexpr int NP = D / 8;          // 16-byte pieces per row
   constexpr int NS = D / 16;         // 16-wide contraction slices of the score product
   constexpr int NT = D / 32;         // 32-row tiles of the output product
-  constexpr int PPH = D / 16;        // rotating threads per key (8 rotation pairs each)
-  constexpr int VSTRIDE = D * 2 + 8; // bytes per staged value row (+8: conflict-free 16-bit reads)
-  constexpr int VS2 = VSTRIDE / 2;
   constexpr int KT_BYTES = 32 * D * 2;
-  constexpr int VT_BYTES = 32 * VSTRIDE;
-  constexpr int NVL = 32 * NP / 256 > 0 ? 32 * NP / 256 : 1;  // value pieces per thread per step
+  constexpr int VT_BYTES = 32 * D * 2;
+  constexpr int NCP = 32 * NP / 256;  // 16-byte copies per thread, step and operand
+  static_assert(NCP >= 1 && NCP * 256 == 32 * NP, "a step is a whole number of 256-thread copies");
 
   constexpr int ANG_BYTES = 4 * 16 * HALF * 8;  // prologue only: (cos, sin)(q_pos theta_u), 16 tokens x 4 waves
   constexpr int STAGE_BYTES = 2 * KT_BYTES + 2 * VT_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char smem[STAGE_BYTES > ANG_BYTES ? STAGE_BYTES : ANG_BYTES];
-  unsigned char* const kt0 = smem;                       // rotated keys [piece][key][8 bf16], two buffers
-  uint16_t* const vt0 = reinterpret_cast<uint16_t*>(smem + 2 * KT_BYTES);  // value rows, two buffers
-  __shared__ float2 bt[32][HALF];  // e^{i key theta_u}, key < 32
+  unsigned char* const kt0 = smem;                 // rotated keys [piece][key][8 bf16], two buffers
+  unsigned char* const vt0 = smem + 2 * KT_BYTES;  // value rows [key][piece ^ 4 (key & 1)][8 bf16], two buffers
   __shared__ int nvis_s[128];      // visible local tokens of each token of the tile (4 waves x 32 / r tokens)
 
   const int tid = threadIdx.x;
@@ -84,21 +148,6 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   const int r = a.r;
 
   // ---- prologue ---------------------------------------------------------------------------------
-  // bt[key][u] = e^{i key theta_u} by repeated multiplication with the host's e^{i theta_u}
-  for (int e = tid; e < 4 * HALF; e += 256) {
-    const int u = e % HALF, q8 = e / HALF;  // this thread fills keys 8 q8 .. 8 q8 + 7
-    const float2 w = th.e1[u];
-    const float2 w2 = cmul(w, w);
-    const float2 w4 = cmul(w2, w2);
-    const float2 w8 = cmul(w4, w4);
-    float2 cur = make_float2(1.f, 0.f);
-    for (int i = 0; i < q8; ++i) cur = cmul(cur, w8);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      bt[8 * q8 + i][u] = cur;
-      cur = cmul(cur, w);
-    }
-  }
   if (tid < 128) {
     int nv = 0;
     const int m = m_tile + tid;
@@ -184,10 +233,11 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   struct StepSrc {
     const uint16_t* Kb;
     const uint16_t* Vb;
-    int rows_valid, p_first, t0;
+    int rows_valid, p_first, t0, st;
     bool is_mem;
   };
   auto locate = [&](int st, StepSrc& ss) -> bool {  // block-uniform
+    ss.st = st;
     if (st < a.steps_mem) {
       const int tok = st * 32;
       const int slot = tok / a.G;
@@ -225,38 +275,38 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     return st;
   };
 
-  // loader / rotator role of this thread: key row kr, rotation pairs u = 8 pc + e and partners u + D/2
-  const int kr = tid / PPH;
-  const int pc = tid % PPH;
-  const bool rot_thread = tid < 32 * PPH;
-  uint4 kreg[2];
-  uint4 vreg[NVL];
-  auto issue_loads = [&](const StepSrc& ss) {
-    if (rot_thread) {
-      const int row = kr < ss.rows_valid ? kr : ss.rows_valid - 1;
-      const uint16_t* rp = ss.Kb + (long long)row * D + pc * 8;
-      kreg[0] = *reinterpret_cast<const uint4*>(rp);
-      kreg[1] = *reinterpret_cast<const uint4*>(rp + HALF);
-    }
+  // Global -> LDS copies of a step, 16 bytes per lane: a wave's 64 pieces land side by side.  Keys are
+  // stored in operand order already.  Value row `key` keeps its piece c at place c ^ 4 (key & 1): rows
+  // that the transposing reads below fetch together then start 64 bytes apart in the banks.
+  auto issue_loads = [&](const StepSrc& ss, int into) {
+    const unsigned char* ksrc = reinterpret_cast<const unsigned char*>(a.Krot) +
+                                (((long long)b * a.Hkv + g) * a.steps_total + ss.st) * KT_BYTES;
 #pragma unroll
-    for (int i = 0; i < NVL; ++i) {
-      const int f = i * 256 + tid;
-      if (f < 32 * NP) {
-        int row = f / NP;
-        row = row < ss.rows_valid ? row : ss.rows_valid - 1;
-        vreg[i] = *reinterpret_cast<const uint4*>(ss.Vb + (long long)row * D + (f % NP) * 8);
-      }
+    for (int i = 0; i < NCP; ++i)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(ksrc + (i * 256 + tid) * 16),
+          (__attribute__((address_space(3))) void*)(kt0 + into * KT_BYTES + (i * 256 + wave * 64) * 16), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < NCP; ++i) {
+      const int x = i * 256 + tid;
+      const int key = x / NP;
+      const int c = (x % NP) ^ (4 * (key & 1));
+      const int row = key < ss.rows_valid ? key : ss.rows_valid - 1;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(ss.Vb + (long long)row * D + c * 8),
+          (__attribute__((address_space(3))) void*)(vt0 + into * VT_BYTES + (i * 256 + wave * 64) * 16), 16, 0, 0);
     }
   };
-
-  float2 cs[8];     // (cos, sin)((cur_p + kr) theta_u), u = 8 pc + e
-  int cur_p = -1;   // position of key row 0 the state is valid for; -1 = invalid
-  float2 st32[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float2 w16 = th.e16[(8 * pc + e) % HALF];
-    st32[e] = cmul(w16, w16);
-  }
+  // Transposing 64-bit LDS read (ds_read_b64_tr_b16): among 16 lanes, lane j hands in the address of
+  // elements 4 (j % 4) .. + 3 of row j / 4 and receives element j of rows 0 .. 3.  Lane l of the second
+  // product needs V[keys 16 sg + 4 h + {0..3, 8..11}][32 t + col]: two such reads per operand.
+  const int j16 = lane & 15, q16 = (lane >> 4) & 1;
+  const int vrow = 4 * h + (j16 >> 2);                      // + 16 sg + 8 (second read)
+  const int vodd = vrow & 1;                                // rows of odd number hold their pieces swapped by 4
+  const int vcolb = (16 * q16 + 4 * (j16 & 3)) * 2;          // byte inside the 64-byte group of 32 t
+  // byte offset of (vrow, 32 t + ...) for even and for odd t: the swap moves tile t to place t ^ 1
+  const int voff_e = vrow * (D * 2) + vcolb + 64 * vodd;
+  const int voff_o = vrow * (D * 2) + vcolb - 64 * vodd;
 
   float m_run = -INFINITY, l_run = 0.f;
   f32x16p_t o[NT];
@@ -267,57 +317,20 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
 
   StepSrc cur_src;
   int st = next_valid(sb, cur_src);
-  if (st < se) issue_loads(cur_src);
+  if (st < se) issue_loads(cur_src, 0);
   int buf = 0;
   while (st < se) {
-    // ---- (a) rotate this step's keys into LDS, stage its values -------------------------------
-    if (rot_thread) {
-      if (cur_p != cur_src.p_first) {
-        if (cur_src.p_first == 0) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) cs[e] = bt[kr][8 * pc + e];
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) cs[e] = cis_pos(cur_src.p_first + kr, th.th[8 * pc + e]);
-        }
-        cur_p = cur_src.p_first;
-      }
-      const uint32_t w1[4] = {kreg[0].x, kreg[0].y, kreg[0].z, kreg[0].w};
-      const uint32_t w2[4] = {kreg[1].x, kreg[1].y, kreg[1].z, kreg[1].w};
-      uint32_t y1[4], y2[4];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const float2 c0 = cs[2 * jj], c1 = cs[2 * jj + 1];
-        const float p0 = bf16_lo(w1[jj]), p1 = bf16_hi(w1[jj]);
-        const float q0 = bf16_lo(w2[jj]), q1 = bf16_hi(w2[jj]);
-        y1[jj] = pack_bf16(p0 * c0.x - q0 * c0.y, p1 * c1.x - q1 * c1.y);
-        y2[jj] = pack_bf16(q0 * c0.x + p0 * c0.y, q1 * c1.x + p1 * c1.y);
-      }
-      unsigned char* ktb = kt0 + buf * KT_BYTES;
-      *reinterpret_cast<uint4*>(&ktb[(pc * 32 + kr) * 16]) = make_uint4(y1[0], y1[1], y1[2], y1[3]);
-      *reinterpret_cast<uint4*>(&ktb[((pc + PPH) * 32 + kr) * 16]) = make_uint4(y2[0], y2[1], y2[2], y2[3]);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) cs[e] = cmul(cs[e], st32[e]);
-      cur_p += 32;
-    }
-#pragma unroll
-    for (int i = 0; i < NVL; ++i) {
-      const int f = i * 256 + tid;
-      if (f < 32 * NP) {
-        uint2* dst = reinterpret_cast<uint2*>(&vt0[buf * (VT_BYTES / 2) + (f / NP) * VS2 + (f % NP) * 8]);
-        dst[0] = make_uint2(vreg[i].x, vreg[i].y);
-        dst[1] = make_uint2(vreg[i].z, vreg[i].w);
-      }
-    }
+    // ---- (a) this step's copies have been under way since the previous step ---------------------
     const int rows_valid = cur_src.rows_valid;
     const int t0 = cur_src.t0;
     const bool is_mem = cur_src.is_mem;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's part of the copies has landed
     __syncthreads();  // (b) this step is staged; everyone is done with the other buffer's previous step
 
     // ---- (c) request the next step ---------------------------------------------------------------
     StepSrc nxt_src = cur_src;
     const int st_next = next_valid(st + 1, nxt_src);
-    if (st_next < se) issue_loads(nxt_src);
+    if (st_next < se) issue_loads(nxt_src, buf ^ 1);
 
     // ---- (d) scores of 32 keys x 32 slots ------------------------------------------------------
     f32x16p_t sacc;
@@ -384,17 +397,10 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
       const bf16x8_t pbl = as_bf16x8(make_uint4(pwl[4 * sg], pwl[4 * sg + 1], pwl[4 * sg + 2], pwl[4 * sg + 3]));
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        uint32_t w[4];
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const int j0 = 2 * jj, j1 = 2 * jj + 1;
-          const int r0 = 16 * sg + (j0 & 3) + 8 * (j0 >> 2) + 4 * h;
-          const int r1 = 16 * sg + (j1 & 3) + 8 * (j1 >> 2) + 4 * h;
-          const uint32_t lo = vt0[buf * (VT_BYTES / 2) + r0 * VS2 + 32 * t + col];
-          const uint32_t hi = vt0[buf * (VT_BYTES / 2) + r1 * VS2 + 32 * t + col];
-          w[jj] = lo | (hi << 16);
-        }
-        const bf16x8_t av = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+        const unsigned char* vp = vt0 + buf * VT_BYTES + ((t & 1) ? voff_o : voff_e) + 16 * sg * (D * 2) + 64 * t;
+        const s16x4_t v03 = lds_read_tr16(vp);
+        const s16x4_t v8b = lds_read_tr16(vp + 8 * (D * 2));
+        const bf16x8_t av = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v03, v8b, 0, 1, 2, 3, 4, 5, 6, 7));
         o[t] = mfma32p(av, pbh, o[t]);
         o[t] = mfma32p(av, pbl, o[t]);
       }
@@ -421,6 +427,15 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
 
 int launch_attend_prefill_partial(const Dims& dm, const AttendPlan& pl, const AttendArgs& a,
                                   const RopeTheta& th, int B, hipStream_t st) {
+  if (a.Krot == nullptr) return MSA_ERR_INVALID_ARG;  // the plan always reserves the rotated keys
+  {
+    dim3 rgrid(a.steps_total, dm.Hkv, B);
+    if (dm.d == 128)
+      hipLaunchKernelGGL(rotate_steps_kernel<128>, rgrid, dim3(256), 0, st, a, th, const_cast<uint16_t*>(a.Krot));
+    else
+      hipLaunchKernelGGL(rotate_steps_kernel<64>, rgrid, dim3(256), 0, st, a, th, const_cast<uint16_t*>(a.Krot));
+    if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+  }
   dim3 grid(pl.n_splits, dm.Hkv, B * pl.n_ttiles), block(256);
   if (dm.d == 128)
     hipLaunchKernelGGL(attend_prefill_kernel<128>, grid, block, 0, st, a, th, pl.tpw, pl.n_ttiles);

@@ -71,6 +71,8 @@ struct AttendPlan {
   int loc_splits, loc_steps_per_split;  // split_local: tiled kernel over the local context
   int tpw, n_ttiles;     // prefill: tokens per wave (32 / r), token tiles (4 waves each) per batch row
   size_t off_ml;         // byte offset of the (m, l) pairs inside the workspace
+  size_t off_krot;       // tiled kernel: byte offset of the once-rotated keys (0 = none)
+  int krot_steps;        // steps per (batch row, KV head) held there
   size_t ws_bytes;
 };
 AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_keys_rotated);
