@@ -132,6 +132,8 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   __shared__ __attribute__((aligned(16))) unsigned char smem[STAGE_BYTES > ANG_BYTES ? STAGE_BYTES : ANG_BYTES];
   unsigned char* const kt0 = smem;                 // rotated keys [piece][key][8 bf16], two buffers
   unsigned char* const vt0 = smem + 2 * KT_BYTES;  // value rows [key][piece ^ 4 (key & 1)][8 bf16], two buffers
+  constexpr int kSelCache = 128;
+  __shared__ int sel_doc[kSelCache], sel_len[kSelCache];
   __shared__ int nvis_s[128];      // visible local tokens of each token of the tile (4 waves x 32 / r tokens)
 
   const int tid = threadIdx.x;
@@ -230,49 +232,96 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   const long long idx_row = (a.idx_rows_per_b == 1) ? b : (long long)b * a.M;  // shared selection: row of b
   const int32_t* idx_g = a.idx + (idx_row * a.idx_sel + (a.idx_sel == 1 ? 0 : g)) * a.k;
 
-  struct StepSrc {
-    const uint16_t* Kb;
-    const uint16_t* Vb;
-    int rows_valid, p_first, t0, st;
-    bool is_mem;
-  };
-  auto locate = [&](int st, StepSrc& ss) -> bool {  // block-uniform
-    ss.st = st;
-    if (st < a.steps_mem) {
-      const int tok = st * 32;
-      const int slot = tok / a.G;
-      const int pin = tok - slot * a.G;
-      const int doc = idx_g[slot];
-      if (doc < 0 || doc >= a.N) return false;  // -1 pads, and ids outside the bank, are skipped
-      int len = a.G;
+  // The selection of this split's documents, read once: (document, rows that exist) of the first kSelCache
+  // slots from the split's first one; pads and ids outside the bank get 0 rows.  Slots beyond the cache
+  // are looked up in global memory.
+  const int slot0 = (int)(((long long)sb * 32) / a.G);
+  {
+    const int n_mem_slots = sb < a.steps_mem ? a.k - slot0 : 0;
+    if (tid < kSelCache && tid < n_mem_slots) {
+      const int doc = idx_g[slot0 + tid];
+      int len = 0;
+      if (doc >= 0 && doc < a.N) {
+        len = a.G;
+        if (a.lens != nullptr) {
+          len = a.lens[doc];
+          len = len < 1 ? 1 : (len > a.G ? a.G : len);
+        }
+      }
+      sel_doc[tid] = doc;
+      sel_len[tid] = len;
+    }
+  }
+  __syncthreads();
+  auto lookup = [&](int slot, int& doc, int& len) {  // block-uniform
+    const int i = slot - slot0;
+    if (i < kSelCache) {
+      doc = __builtin_amdgcn_readfirstlane(sel_doc[i]);
+      len = __builtin_amdgcn_readfirstlane(sel_len[i]);
+      return;
+    }
+    doc = idx_g[slot];
+    len = 0;
+    if (doc >= 0 && doc < a.N) {
+      len = a.G;
       if (a.lens != nullptr) {
         len = a.lens[doc];
         len = len < 1 ? 1 : (len > a.G ? a.G : len);
       }
-      if (pin >= len) return false;             // past the document's last token
-      const long long off = (((long long)doc * a.Hkv + g) * a.G + pin) * D;
-      ss.Kb = a.K + off;
-      ss.Vb = a.V + off;
-      ss.rows_valid = len - pin < 32 ? len - pin : 32;
-      ss.p_first = pin;
-      ss.t0 = 0;
-      ss.is_mem = true;
-      return true;
     }
-    const int t0 = (st - a.steps_mem) * 32;
-    if (t0 >= nvis_blk) return false;
-    const long long off = (((long long)b * a.Hkv + g) * a.Lloc + t0) * D;
-    ss.Kb = a.Kloc + off;
-    ss.Vb = a.Vloc + off;
-    ss.rows_valid = nvis_blk - t0 < 32 ? nvis_blk - t0 : 32;
-    ss.p_first = a.pos0 + t0;
-    ss.t0 = t0;
-    ss.is_mem = false;
-    return true;
   };
-  auto next_valid = [&](int st, StepSrc& ss) -> int {
-    while (st < se && !locate(st, ss)) ++st;
-    return st;
+
+  struct StepSrc {
+    const uint16_t* Vb;  // first value row of the step
+    int rows_valid, p_first, t0, st, len;
+    bool is_mem;
+  };
+  // first step >= st of this split that holds rows (se if none); block-uniform
+  auto locate = [&](int st, StepSrc& ss) -> int {
+    while (st < se) {
+      if (st < a.steps_mem) {
+        const int tok = st * 32;
+        const int slot = tok / a.G;
+        const int pin = tok - slot * a.G;
+        int doc, len;
+        lookup(slot, doc, len);
+        if (pin >= len) {  // a pad, or past the document's last token: on to the next slot (G % 32 == 0)
+          st = (slot + 1) * (a.G / 32);
+          continue;
+        }
+        ss.Vb = a.V + (((long long)doc * a.Hkv + g) * a.G + pin) * D;
+        ss.rows_valid = len - pin < 32 ? len - pin : 32;
+        ss.p_first = pin;
+        ss.t0 = 0;
+        ss.len = len;
+        ss.is_mem = true;
+      } else {
+        const int t0 = (st - a.steps_mem) * 32;
+        if (t0 >= nvis_blk) return se;
+        ss.Vb = a.Vloc + (((long long)b * a.Hkv + g) * a.Lloc + t0) * D;
+        ss.rows_valid = nvis_blk - t0 < 32 ? nvis_blk - t0 : 32;
+        ss.p_first = a.pos0 + t0;
+        ss.t0 = t0;
+        ss.len = 0;
+        ss.is_mem = false;
+      }
+      ss.st = st;
+      return st;
+    }
+    return se;
+  };
+  // the step after ss: inside a document it is the next 32 rows, no lookup
+  auto advance = [&](StepSrc& ss) -> int {
+    const int st = ss.st + 1;
+    if (st >= se) return se;
+    if (ss.is_mem && ss.p_first + 32 < ss.len) {
+      ss.Vb += 32 * D;
+      ss.p_first += 32;
+      ss.rows_valid = ss.len - ss.p_first < 32 ? ss.len - ss.p_first : 32;
+      ss.st = st;
+      return st;
+    }
+    return locate(st, ss);
   };
 
   // Global -> LDS copies of a step, 16 bytes per lane: a wave's 64 pieces land side by side.  Keys are
@@ -316,7 +365,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     for (int i = 0; i < 16; ++i) o[t][i] = 0.f;
 
   StepSrc cur_src;
-  int st = next_valid(sb, cur_src);
+  int st = locate(sb, cur_src);
   if (st < se) issue_loads(cur_src, 0);
   int buf = 0;
   while (st < se) {
@@ -329,7 +378,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
 
     // ---- (c) request the next step ---------------------------------------------------------------
     StepSrc nxt_src = cur_src;
-    const int st_next = next_valid(st + 1, nxt_src);
+    const int st_next = advance(nxt_src);
     if (st_next < se) issue_loads(nxt_src, buf ^ 1);
 
     // ---- (d) scores of 32 keys x 32 slots ------------------------------------------------------
