@@ -127,18 +127,19 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   constexpr int NCP = 32 * NP / 256;  // 16-byte copies per thread, step and operand
   static_assert(NCP >= 1 && NCP * 256 == 32 * NP, "a step is a whole number of 256-thread copies");
 
+  constexpr int NBUF = 3;             // stages in LDS: one in use, two on their way
   constexpr int ANG_BYTES = 4 * 16 * HALF * 8;  // prologue only: (cos, sin)(q_pos theta_u), 16 tokens x 4 waves
-  constexpr int STAGE_BYTES = 2 * KT_BYTES + 2 * VT_BYTES;
+  constexpr int STAGE_BYTES = NBUF * (KT_BYTES + VT_BYTES);
   __shared__ __attribute__((aligned(16))) unsigned char smem[STAGE_BYTES > ANG_BYTES ? STAGE_BYTES : ANG_BYTES];
-  unsigned char* const kt0 = smem;                 // rotated keys [piece][key][8 bf16], two buffers
-  unsigned char* const vt0 = smem + 2 * KT_BYTES;  // value rows [key][piece ^ 4 (key & 1)][8 bf16], two buffers
+  unsigned char* const kt0 = smem;                    // rotated keys [piece][key][8 bf16], NBUF stages
+  unsigned char* const vt0 = smem + NBUF * KT_BYTES;  // value rows [key][piece ^ 4 (key & 1)][8 bf16], NBUF stages
   constexpr int kSelCache = 128;
   __shared__ int sel_doc[kSelCache], sel_len[kSelCache];
   __shared__ int nvis_s[128];      // visible local tokens of each token of the tile (4 waves x 32 / r tokens)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int h = lane >> 5;
   const int col = lane & 31;
   const int sp = blockIdx.x;
@@ -327,22 +328,27 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   // Global -> LDS copies of a step, 16 bytes per lane: a wave's 64 pieces land side by side.  Keys are
   // stored in operand order already.  Value row `key` keeps its piece c at place c ^ 4 (key & 1): rows
   // that the transposing reads below fetch together then start 64 bytes apart in the banks.
+  const unsigned char* const ksrc0 = reinterpret_cast<const unsigned char*>(a.Krot) +
+                                     ((long long)b * a.Hkv + g) * a.steps_total * KT_BYTES + tid * 16;
+  int vkey[NCP], vcol[NCP];  // this thread's value pieces: row of the step, element of the row
+#pragma unroll
+  for (int i = 0; i < NCP; ++i) {
+    const int x = i * 256 + tid;
+    vkey[i] = x / NP;
+    vcol[i] = ((x % NP) ^ (4 * (vkey[i] & 1))) * 8;
+  }
   auto issue_loads = [&](const StepSrc& ss, int into) {
-    const unsigned char* ksrc = reinterpret_cast<const unsigned char*>(a.Krot) +
-                                (((long long)b * a.Hkv + g) * a.steps_total + ss.st) * KT_BYTES;
+    const unsigned char* ksrc = ksrc0 + (long long)ss.st * KT_BYTES;
 #pragma unroll
     for (int i = 0; i < NCP; ++i)
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(ksrc + (i * 256 + tid) * 16),
+          (const __attribute__((address_space(1))) void*)(ksrc + i * 4096),
           (__attribute__((address_space(3))) void*)(kt0 + into * KT_BYTES + (i * 256 + wave * 64) * 16), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < NCP; ++i) {
-      const int x = i * 256 + tid;
-      const int key = x / NP;
-      const int c = (x % NP) ^ (4 * (key & 1));
-      const int row = key < ss.rows_valid ? key : ss.rows_valid - 1;
+      const int row = vkey[i] < ss.rows_valid ? vkey[i] : ss.rows_valid - 1;
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(ss.Vb + (long long)row * D + c * 8),
+          (const __attribute__((address_space(1))) void*)(ss.Vb + row * D + vcol[i]),
           (__attribute__((address_space(3))) void*)(vt0 + into * VT_BYTES + (i * 256 + wave * 64) * 16), 16, 0, 0);
     }
   };
@@ -364,22 +370,35 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[t][i] = 0.f;
 
-  StepSrc cur_src;
+  // Three stages: while step i is multiplied, the copies of steps i + 1 and i + 2 are under way.
+  StepSrc cur_src, nxt_src;
   int st = locate(sb, cur_src);
-  if (st < se) issue_loads(cur_src, 0);
+  int st_next = se;
+  if (st < se) {
+    issue_loads(cur_src, 0);
+    nxt_src = cur_src;
+    st_next = advance(nxt_src);
+    if (st_next < se) issue_loads(nxt_src, 1);
+  }
   int buf = 0;
   while (st < se) {
-    // ---- (a) this step's copies have been under way since the previous step ---------------------
+    // ---- (a) this step's copies have landed (the next step's, issued after them, may be on their way)
     const int rows_valid = cur_src.rows_valid;
     const int t0 = cur_src.t0;
     const bool is_mem = cur_src.is_mem;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's part of the copies has landed
-    __syncthreads();  // (b) this step is staged; everyone is done with the other buffer's previous step
+    if (st_next < se)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NCP) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();  // (b) this step is staged for everyone; everyone is done with the previous step's stage
 
-    // ---- (c) request the next step ---------------------------------------------------------------
-    StepSrc nxt_src = cur_src;
-    const int st_next = advance(nxt_src);
-    if (st_next < se) issue_loads(nxt_src, buf ^ 1);
+    // ---- (c) request the step after the next into the stage the previous step used ----------------
+    StepSrc nx2_src = nxt_src;
+    int st_nx2 = se;
+    if (st_next < se) {
+      st_nx2 = advance(nx2_src);
+      if (st_nx2 < se) issue_loads(nx2_src, buf >= 1 ? buf - 1 : NBUF - 1);
+    }
 
     // ---- (d) scores of 32 keys x 32 slots ------------------------------------------------------
     f32x16p_t sacc;
@@ -456,7 +475,9 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     }
     st = st_next;
     cur_src = nxt_src;
-    buf ^= 1;
+    st_next = st_nx2;
+    nxt_src = nx2_src;
+    buf = buf + 1 < NBUF ? buf + 1 : 0;
   }
 
   // ---- partial results of this split ---------------------------------------------------------------
