@@ -341,15 +341,11 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     const unsigned char* ksrc = ksrc0 + (long long)ss.st * KT_BYTES;
 #pragma unroll
     for (int i = 0; i < NCP; ++i)
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(ksrc + i * 4096),
-          (__attribute__((address_space(3))) void*)(kt0 + into * KT_BYTES + (i * 256 + wave * 64) * 16), 16, 0, 0);
+      copy16_to_lds_async(ksrc + i * 4096, kt0 + into * KT_BYTES + (i * 256 + wave * 64) * 16);
 #pragma unroll
     for (int i = 0; i < NCP; ++i) {
       const int row = vkey[i] < ss.rows_valid ? vkey[i] : ss.rows_valid - 1;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(ss.Vb + row * D + vcol[i]),
-          (__attribute__((address_space(3))) void*)(vt0 + into * VT_BYTES + (i * 256 + wave * 64) * 16), 16, 0, 0);
+      copy16_to_lds_async(ss.Vb + row * D + vcol[i], vt0 + into * VT_BYTES + (i * 256 + wave * 64) * 16);
     }
   };
   // Transposing 64-bit LDS read (ds_read_b64_tr_b16): among 16 lanes, lane j hands in the address of
@@ -387,10 +383,13 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     const int t0 = cur_src.t0;
     const bool is_mem = cur_src.is_mem;
     if (st_next < se)
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NCP) : "memory");
+      wait_copies_but<2 * NCP>();
     else
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // (b) this step is staged for everyone; everyone is done with the previous step's stage
+      wait_copies_but<0>();
+    // (b) this step is staged for everyone; everyone is done with the previous step's stage (its LDS reads
+    // went into matrix products that were issued before this point).  A bare barrier: the fences of
+    // __syncthreads would wait for the copies that are meant to stay in flight.
+    __builtin_amdgcn_s_barrier();
 
     // ---- (c) request the step after the next into the stage the previous step used ----------------
     StepSrc nx2_src = nxt_src;

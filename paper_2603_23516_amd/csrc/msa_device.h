@@ -12,6 +12,27 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
 
+// ---- asynchronous copies global -> LDS ---------------------------------------------------------
+// One 64-lane copy of 16 bytes per lane: lane l's 16 bytes from its own global address land at LDS
+// byte lds_base + 16 l (lds_base: the same value in every lane).  Nothing waits here: the caller counts
+// the copy in s_waitcnt vmcnt like any load and orders it against the readers of that LDS itself.
+// Written as assembly because for the builtin of the same instruction the compiler, unable to tell
+// which LDS bytes a copy fills, waits for EVERY outstanding copy before the next LDS read of any kind,
+// which turns a multi-stage pipeline into a synchronous load.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"  // m0 is reserved: the compiler keeps nothing in it across statements
+__device__ __forceinline__ void copy16_to_lds_async(const void* gsrc, const void* lds_base) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(size_t)(const __attribute__((address_space(3))) void*)lds_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(gsrc), "s"(base) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+template <int N>
+__device__ __forceinline__ void wait_copies_but() {  // until at most the N newest loads / copies are outstanding
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
 // ---- bf16 <-> fp32 ---------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
