@@ -329,7 +329,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   // stored in operand order already.  Value row `key` keeps its piece c at place c ^ 4 (key & 1): rows
   // that the transposing reads below fetch together then start 64 bytes apart in the banks.
   const unsigned char* const ksrc0 = reinterpret_cast<const unsigned char*>(a.Krot) +
-                                     ((long long)b * a.Hkv + g) * a.steps_total * KT_BYTES + tid * 16;
+                                     ((long long)b * a.Hkv + g) * a.steps_total * KT_BYTES;
   int vkey[NCP], vcol[NCP];  // this thread's value pieces: row of the step, element of the row
 #pragma unroll
   for (int i = 0; i < NCP; ++i) {
@@ -341,11 +341,11 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     const unsigned char* ksrc = ksrc0 + (long long)ss.st * KT_BYTES;
 #pragma unroll
     for (int i = 0; i < NCP; ++i)
-      copy16_to_lds_async(ksrc + i * 4096, kt0 + into * KT_BYTES + (i * 256 + wave * 64) * 16);
+      copy16_to_lds_async(ksrc, i * 4096 + tid * 16, kt0 + into * KT_BYTES + (i * 256 + wave * 64) * 16);
 #pragma unroll
     for (int i = 0; i < NCP; ++i) {
       const int row = vkey[i] < ss.rows_valid ? vkey[i] : ss.rows_valid - 1;
-      copy16_to_lds_async(ss.Vb + row * D + vcol[i], vt0 + into * VT_BYTES + (i * 256 + wave * 64) * 16);
+      copy16_to_lds_async(ss.Vb, (row * D + vcol[i]) * 2, vt0 + into * VT_BYTES + (i * 256 + wave * 64) * 16);
     }
   };
   // Transposing 64-bit LDS read (ds_read_b64_tr_b16): among 16 lanes, lane j hands in the address of

@@ -14,18 +14,26 @@ constexpr int kWave = 64;
 
 // ---- asynchronous copies global -> LDS ---------------------------------------------------------
 // One 64-lane copy of 16 bytes per lane: lane l's 16 bytes from its own global address land at LDS
-// byte lds_base + 16 l (lds_base: the same value in every lane).  Nothing waits here: the caller counts
+// byte lds_base + 16 l (lds_base: the same value in every lane; goff < 2^31).  Nothing waits here: the caller counts
 // the copy in s_waitcnt vmcnt like any load and orders it against the readers of that LDS itself.
 // Written as assembly because for the builtin of the same instruction the compiler, unable to tell
 // which LDS bytes a copy fills, waits for EVERY outstanding copy before the next LDS read of any kind,
 // which turns a multi-stage pipeline into a synchronous load.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"  // m0 is reserved: the compiler keeps nothing in it across statements
-__device__ __forceinline__ void copy16_to_lds_async(const void* gsrc, const void* lds_base) {
+__device__ __forceinline__ void copy16_to_lds_async(const void* gbase, uint32_t goff, const void* lds_base) {
+  // source of lane l: gbase (the same in every lane) + goff (the lane's own byte offset)
   const uint32_t base = __builtin_amdgcn_readfirstlane(
       (uint32_t)(size_t)(const __attribute__((address_space(3))) void*)lds_base);
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(gsrc), "s"(base) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(goff), "s"(gbase), "s"(base) : "memory", "m0");
+}
+// The same with 4 bytes per lane: lane l's word lands at lds_base + 4 l.
+__device__ __forceinline__ void copy4_to_lds_async(const void* gbase, uint32_t goff, const void* lds_base) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(size_t)(const __attribute__((address_space(3))) void*)lds_base);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :: "v"(goff), "s"(gbase), "s"(base) : "memory", "m0");
 }
 #pragma clang diagnostic pop
 template <int N>

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int h = lane >> 5;   // half of the wave
   const int c = lane & 31;   // token column / key row
   const int g = blockIdx.x % a.Hkv;
@@ -226,26 +226,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   // wave issues exactly LOADS + 1 memory operations per stage and can wait on its own counter).
   const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS;
   const float* ing = a.inv_norm ? a.inv_norm + (long long)g * a.tiles * 16 : nullptr;
+  // Copy i of a thread covers bytes [4096 i, 4096 (i + 1)) of the stage = TPC whole tiles, the same
+  // tiles for every thread: the source is a scalar base plus the thread's constant offset.
+  constexpr int TILE_BYTES = TILE_ELEMS * 2;
+  constexpr int TPC = 4096 / TILE_BYTES;
+  const uint32_t goff_full = tid * 16;                 // all TPC tiles of the copy exist
+  const uint32_t goff_wrap = (tid * 16) % TILE_BYTES;  // only the first does: the others repeat it (masked)
   auto fetch = [&](long long sg, unsigned char* kdst, float* idst) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int off = (i * 256 + tid) * 16;            // byte offset inside the stage
-      long long tile = 4 * sg + off / (TILE_ELEMS * 2);
+      long long tile = 4 * sg + TPC * i;
       if (tile >= a.tiles) tile = a.tiles - 1;         // past the end: repeat the last tile (masked)
-      const unsigned char* src = reinterpret_cast<const unsigned char*>(KRg) + tile * (TILE_ELEMS * 2) +
-                                 off % (TILE_ELEMS * 2);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)src,
-          (__attribute__((address_space(3))) void*)(kdst + (i * 256 + wave * 64) * 16), 16, 0, 0);
+      uint32_t goff = goff_full;
+      if constexpr (TPC > 1) goff = (tile + TPC <= a.tiles) ? goff_full : goff_wrap;
+      copy16_to_lds_async(reinterpret_cast<const unsigned char*>(KRg) + tile * TILE_BYTES, goff,
+                          kdst + (i * 256 + wave * 64) * 16);
     }
     {
-      long long key = sg * 64 + lane;
-      if (key >= a.tiles * 16) key = a.tiles * 16 - 1;
       // dot product: no norms; the copy still runs (from the index itself) to keep the counts equal,
       // and the multiply below reads the constant ones instead
-      const float* src = ing ? ing + key : reinterpret_cast<const float*>(KRg) + lane;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)idst, 4, 0, 0);
+      long long key0 = sg * 64;
+      const long long last = a.tiles * 16 - 1;
+      if (key0 > last) key0 = last;
+      const int room = (int)(last - key0 < 63 ? last - key0 : 63);  // lanes beyond it repeat the last key
+      const float* src = ing ? ing + key0 : reinterpret_cast<const float*>(KRg);
+      copy4_to_lds_async(src, (uint32_t)((ing && lane > room) ? room : lane) * 4, idst);
     }
   };
   // wait until at most the copies of the newest stage are outstanding
