@@ -24,6 +24,8 @@ struct AttendArgs {
   const uint16_t* Vloc;
   const int32_t* q_pos;  // [BM]
   const int32_t* lens;   // [N] document lengths (rows of a bank slot that exist), or null = G everywhere
+  uint16_t* out;         // tiled kernel with a single split: the final output and (or null) log-sum-exp,
+  float* lse;            // written directly instead of partials; null = partials
   const uint16_t* Krot;  // tiled kernel: keys of every step, rotated once, [B][Hkv][steps_total][D/8][32][8]; or null
   float* part_o;         // [BM][Hq][n_splits][D]   unnormalised partial outputs
   float2* part_ml;       // [BM][Hq][n_splits]      (running max in log2 units, sum)

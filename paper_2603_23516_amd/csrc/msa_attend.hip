@@ -660,6 +660,10 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.Vloc = (const uint16_t*)Vloc;
   a.q_pos = q_pos;
   a.lens = dm.lens;
+  // a shared selection that is not split: the tiled kernel writes the result itself, no merge
+  const bool direct = pl.prefill && pl.n_splits == 1;
+  a.out = direct ? (uint16_t*)out : nullptr;
+  a.lse = direct ? lse : nullptr;
   a.Krot = pl.krot_steps > 0 ? (const uint16_t*)((char*)ws + pl.off_krot) : nullptr;
   a.part_o = (float*)ws;
   a.part_ml = (float2*)((char*)ws + pl.off_ml);
@@ -697,6 +701,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   if (pl.split_local) {
     // local context through the tiled kernel (it never touches the bank or the selection: no memory steps) ...
     AttendArgs al = a;
+    al.out = nullptr;
     al.steps_mem = 0;
     al.steps_total = (Lloc + 31) / 32;
     al.steps_per_split = pl.loc_steps_per_split;
@@ -731,6 +736,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
 #undef MSA_LAUNCH_ATTEND
   }
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+  if (direct) return MSA_OK;
   if (dm.d == 128)
     hipLaunchKernelGGL(attend_merge_kernel<128>, dim3(BM * dm.Hq), dim3(128), 0, st,
                        (const float*)a.part_o, (const float2*)a.part_ml, (uint16_t*)out, lse,

@@ -481,7 +481,24 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
 
   // ---- partial results of this split ---------------------------------------------------------------
   const float l_tot = both_halves_sum(l_run);
-  if (tok_ok) {
+  if (tok_ok && a.out != nullptr) {
+    // the only split of its (token, head): normalise and write the result itself, with the merge
+    // kernel's arithmetic for one partial
+    const long long qh = ((long long)b * a.M + m_tok) * a.Hq + g * r + hh;
+    const float inv_on = l_tot > 0.f ? 1.f : 0.f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = inv_on != 0.f ? o[t][4 * i4 + e] / l_tot : 0.f;
+        *reinterpret_cast<uint2*>(&a.out[qh * D + 32 * t + 8 * i4 + 4 * h]) =
+            make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+      }
+    if (h == 0 && a.lse != nullptr)
+      a.lse[qh] = (l_tot > 0.f) ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+  } else if (tok_ok) {
     const long long ph = (((long long)b * a.M + m_tok) * a.Hq + g * r + hh) * a.ph_splits + a.split0 + sp;
 #pragma unroll
     for (int t = 0; t < NT; ++t)

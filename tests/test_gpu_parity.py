@@ -276,6 +276,7 @@ CASES = {
     "batch33_d64": (11000, 500, 1, 2, 32, 64, 8, 33, 1, 0, 1e4, 24),
     "prefill100_gemm": (13000, 301, 2, 4, 64, 128, 8, 1, 100, 100, 1e6, 8),
     "prefill300_gemm_d64": (14000, 77, 2, 2, 64, 64, 8, 2, 150, 150, 1e4, 5),
+    "prefill140_r8_local_in_eight_wave_tiles": (15000, 60, 2, 8, 64, 128, 8, 1, 140, 90, 1e6, 6),
 }
 
 
@@ -680,6 +681,9 @@ PREFILL_ATT_CASES = {
     "r1_d64_wide_tile": (53000, 25, 3, 1, 96, 64, 2, 100, 33, 1e4, 7),
     "r2_d64_long_context_few_tokens": (54000, 40, 2, 2, 512, 64, 1, 9, 300, 1e4, 12),
     "r4_d128_no_local": (55000, 16, 2, 4, 256, 128, 1, 24, 0, 1e6, 4),
+    # enough tokens for workgroups of eight waves (M >= 16 * 32 / r)
+    "r8_d128_eight_waves": (56000, 24, 2, 8, 64, 128, 2, 75, 50, 1e6, 5),
+    "r4_d64_eight_waves_ragged_tail": (57000, 18, 1, 4, 96, 64, 1, 150, 70, 1e4, 6),
 }
 
 
