@@ -127,7 +127,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   constexpr int NCP = 32 * NP / 256;  // 16-byte copies per thread, step and operand
   static_assert(NCP >= 1 && NCP * 256 == 32 * NP, "a step is a whole number of 256-thread copies");
 
-  constexpr int NBUF = 3;             // stages in LDS: one in use, two on their way
+  constexpr int NBUF = 4;             // stages in LDS: two in use (values of step i, keys of step i + 1), two on their way
   constexpr int ANG_BYTES = 4 * 16 * HALF * 8;  // prologue only: (cos, sin)(q_pos theta_u), 16 tokens x 4 waves
   constexpr int STAGE_BYTES = NBUF * (KT_BYTES + VT_BYTES);
   __shared__ __attribute__((aligned(16))) unsigned char smem[STAGE_BYTES > ANG_BYTES ? STAGE_BYTES : ANG_BYTES];
@@ -366,50 +366,73 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[t][i] = 0.f;
 
-  // Three stages: while step i is multiplied, the copies of steps i + 1 and i + 2 are under way.
-  StepSrc cur_src, nxt_src;
-  int st = locate(sb, cur_src);
-  int st_next = se;
-  if (st < se) {
-    issue_loads(cur_src, 0);
-    nxt_src = cur_src;
-    st_next = advance(nxt_src);
-    if (st_next < se) issue_loads(nxt_src, 1);
+  // Four stages in LDS.  The loop is software pipelined: iteration i holds the scores of step i (made in
+  // iteration i - 1), issues the score products of step i + 1 next to the softmax arithmetic of step i so
+  // that matrix and vector units of the wave work at the same time, then the second product of step i;
+  // meanwhile the copies of steps i + 2 and i + 3 are under way.
+  auto scores = [&](int stage) __attribute__((always_inline)) -> f32x16p_t {
+    f32x16p_t acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const bf16x8_t ak =
+          as_bf16x8(*reinterpret_cast<const uint4*>(&kt0[stage * KT_BYTES + ((2 * s + h) * 32 + col) * 16]));
+      acc = mfma32p(ak, bqh[s], acc);
+      acc = mfma32p(ak, bql[s], acc);
+    }
+    return acc;
+  };
+  StepSrc q0 = {}, q1 = {}, q2 = {};  // steps i, i + 1, i + 2
+  int s0 = locate(sb, q0), s1 = se, s2 = se;
+  if (s0 < se) {
+    issue_loads(q0, 0);
+    q1 = q0;
+    s1 = advance(q1);
+    if (s1 < se) {
+      issue_loads(q1, 1);
+      q2 = q1;
+      s2 = advance(q2);
+      if (s2 < se) issue_loads(q2, 2);
+    }
   }
-  int buf = 0;
-  while (st < se) {
-    // ---- (a) this step's copies have landed (the next step's, issued after them, may be on their way)
-    const int rows_valid = cur_src.rows_valid;
-    const int t0 = cur_src.t0;
-    const bool is_mem = cur_src.is_mem;
-    if (st_next < se)
+  f32x16p_t sacc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+  if (s0 < se) {
+    if (s2 < se)
+      wait_copies_but<4 * NCP>();
+    else if (s1 < se)
       wait_copies_but<2 * NCP>();
     else
       wait_copies_but<0>();
-    // (b) this step is staged for everyone; everyone is done with the previous step's stage (its LDS reads
+    __builtin_amdgcn_s_barrier();  // step s0 is staged for everyone
+    sacc = scores(0);
+  }
+  int buf = 0;
+  while (s0 < se) {
+    const int rows_valid = q0.rows_valid;
+    const int t0 = q0.t0;
+    const bool is_mem = q0.is_mem;
+    // ---- (a) the keys of step i + 1 have landed (the copies of step i + 2 may be on their way) -----
+    if (s2 < se)
+      wait_copies_but<2 * NCP>();
+    else
+      wait_copies_but<0>();
+    // (b) step i + 1 is staged for everyone; everyone is done with the stage of step i - 1 (its LDS reads
     // went into matrix products that were issued before this point).  A bare barrier: the fences of
     // __syncthreads would wait for the copies that are meant to stay in flight.
     __builtin_amdgcn_s_barrier();
 
-    // ---- (c) request the step after the next into the stage the previous step used ----------------
-    StepSrc nx2_src = nxt_src;
-    int st_nx2 = se;
-    if (st_next < se) {
-      st_nx2 = advance(nx2_src);
-      if (st_nx2 < se) issue_loads(nx2_src, buf >= 1 ? buf - 1 : NBUF - 1);
+    // ---- (c) request step i + 3 into the stage that step i - 1 used ---------------------------------
+    StepSrc q3 = q2;
+    int s3 = se;
+    if (s2 < se) {
+      s3 = advance(q3);
+      if (s3 < se) issue_loads(q3, (buf + 3) & 3);
     }
 
-    // ---- (d) scores of 32 keys x 32 slots ------------------------------------------------------
-    f32x16p_t sacc;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const bf16x8_t ak =
-          as_bf16x8(*reinterpret_cast<const uint4*>(&kt0[buf * KT_BYTES + ((2 * s + h) * 32 + col) * 16]));
-      sacc = mfma32p(ak, bqh[s], sacc);
-      sacc = mfma32p(ak, bql[s], sacc);
-    }
+    // ---- (d) scores of step i: mask, running maximum ------------------------------------------------
     float sc[16];
     float mx = -INFINITY;
     if (is_mem && rows_valid == 32) {  // block-uniform: a whole step of document rows, nothing to mask
@@ -439,6 +462,10 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
         for (int i = 0; i < 16; ++i) o[t][i] *= alpha;
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+
+    // ---- (e) score products of step i + 1 (after the last step: of a stage nobody waits for, unused)
+    // next to the weights of step i ------------------------------------------------------------------
+    const f32x16p_t snext = scores((buf + 1) & 3);
     uint32_t pwh[8], pwl[8];
     float psum = 0.f;
 #pragma unroll
@@ -455,7 +482,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     }
     l_run += psum;
 
-    // ---- second product: O^T[dd][slot] += V^T[dd][key] P^T[key][slot] ---------------------------
+    // ---- (f) second product: O^T[dd][slot] += V^T[dd][key] P^T[key][slot] ---------------------------
     // contraction slot j of slice sg and half h is key 16 sg + (j % 4) + 8 (j / 4) + 4 h: the lane's own
     // score registers 8 sg .. 8 sg + 7
 #pragma unroll
@@ -472,11 +499,11 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
         o[t] = mfma32p(av, pbl, o[t]);
       }
     }
-    st = st_next;
-    cur_src = nxt_src;
-    st_next = st_nx2;
-    nxt_src = nx2_src;
-    buf = buf + 1 < NBUF ? buf + 1 : 0;
+    sacc = snext;
+    s0 = s1; q0 = q1;
+    s1 = s2; q1 = q2;
+    s2 = s3; q2 = q3;
+    buf = (buf + 1) & 3;
   }
 
   // ---- partial results of this split ---------------------------------------------------------------
