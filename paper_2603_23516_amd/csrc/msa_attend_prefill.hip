@@ -1,28 +1,32 @@
 // msa_sparse_attend for MANY query tokens that SHARE one selection (token_pool = 1: the routing of
 // Eq. 2 as printed picks the documents once per question, so all M tokens of a batch row attend the
-// same k documents, Eq. 3-4).  Then the gathered keys and values are common to a whole tile of query
-// tokens and attention is a dense contraction: this kernel reads, rotates (Section 3.2.2: positions
-// restart at 0 in every document) and stages every 32-key step ONCE per workgroup and multiplies it
-// with 64 / r query tokens x r heads on the matrix cores.
+// same k documents, Eq. 3-4).  Then the gathered keys and values are common to every tile of query
+// tokens and attention is a dense contraction on the matrix cores.
 //
-// Work split.  A workgroup owns a tile of 4 * TPW query tokens of one (batch row, KV head), TPW =
-// 32 / r tokens per wave, and a contiguous range of 32-key steps (split-K as in the decode path; the
-// partials (max, sum, O) use the same layout and the same merge kernel).  Per step:
-//   all 256 threads  load the 32 key rows and 32 value rows (16-byte pieces), rotate the keys in
-//                    fp32 (thread = key x 8 rotation pairs, running (cos, sin) advanced by 32
-//                    positions per step), round to bf16 and write them to LDS in MFMA operand order;
-//                    values go to LDS as they are (padded rows for transposed 16-bit reads);
-//   every wave       S^T[32 keys][32 slots] = K~ Q~^T with v_mfma_f32_32x32x16_bf16; a slot (column) is a
-//                    (token, head) pair.  The rotated, scaled queries are carried as bf16 (hi, lo) pairs
-//                    laid along the CONTRACTION (two products per slice into one accumulator), so a
-//                    score exists in exactly one lane and the softmax work is not duplicated; online
-//                    softmax per column (16 keys per lane, the other 16 in lane ^ 32); the weights go
-//                    back as bf16 hi and lo parts, two B operands of  O^T[dd][slot] += V^T[dd][key] P^T[key][slot]
-//                    that share one A operand (the contraction index runs over the lane's own 8 keys of
-//                    each 16-key slice, and V^T is read with 16-bit LDS reads in the same key order).
+// Two kernels.
+//   rotate_steps_kernel    rotates the keys of every 32-key step ONCE per (batch row, KV head) (Section
+//                          3.2.2: positions restart at 0 in every document; the local context continues
+//                          at pos0), rounds them to bf16 and stores them in MFMA operand order.
+//   attend_prefill_kernel  a workgroup owns a tile of 4 * TPW query tokens of one (batch row, KV head),
+//                          TPW = 32 / r tokens per wave, and a contiguous range of steps (split-K as in
+//                          the decode path: same partials, same merge kernel; a range that is the only one
+//                          writes the final output itself).  Per step:
+//     copies     the step's rotated keys and its value rows go global -> LDS asynchronously, 16 bytes per
+//                lane, two steps ahead of their use (four stages); value rows land with their 16-byte
+//                pieces swizzled so that the transposing reads below are conflict free.  No registers,
+//                no vector instructions.
+//     scores     S^T[32 keys][32 slots] = K~ Q~^T with v_mfma_f32_32x32x16_bf16; a slot (column) is a
+//                (token, head) pair.  The rotated, scaled queries stay in registers as bf16 (hi, lo) pairs
+//                laid along the CONTRACTION (two products per slice into one accumulator), so a score
+//                exists in exactly one lane and the softmax work is not duplicated.
+//     softmax    online, per column (16 keys per lane, the other 16 in lane ^ 32); the weights go back as
+//                bf16 hi and lo parts, two B operands of  O^T[dd][slot] += V^T[dd][key] P^T[key][slot]
+//                that share one A operand: V^T comes from ds_read_b64_tr_b16 (16 lanes exchange 4 x 4
+//                elements on the way out of LDS) in the order of the lane's own score registers.
+//   The loop is software pipelined: the score products of step i + 1 are issued next to the softmax
+//   arithmetic of step i.  One bare barrier per step.
 // Causality: local key t is visible to token m iff pos0 + t <= q_pos[m]; the mask is per column and
-// the workgroup stops at the last step any of its tokens can see.  LDS is double buffered, one
-// barrier per step.
+// the workgroup stops at the last step any of its tokens can see.
 #include "msa_attend.h"
 
 namespace msa {
