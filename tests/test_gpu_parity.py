@@ -793,6 +793,47 @@ def test_fetch_selected_from_host_bank(scope, pool):
     assert e.value.status == msa.MSA_ERR_INVALID_ARG
 
 
+def test_fetch_selected_from_pooled_host_bank():
+    """Section 3.4.2 as the paper runs it: the POOLED content bank (K-bar, V-bar) lives in host memory and only the
+    selected documents' pooled rows are fetched; attention over the staging bank equals attention over the same
+    pooled bank in device memory bit for bit, and the oracle within the attention tolerances."""
+    seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k = 72000, 90, 2, 4, 256, 128, 32, 3, 2, 50, 1e6, 7
+    say(f"tiered pooled bank: N={N} Hkv={Hkv} r={r} G={G} P={P} d={d} B={B} M={M} Lloc={Lloc} k={k}")
+    case = Case(seed, N, Hkv, r, G, d, P, B, M, Lloc, base).to_device()
+    Gp = G // P
+    Kbar, Vbar = msa.msa_pool_kv(case.cfg(), case.dK, case.dV)
+    torch.cuda.synchronize()
+    acfg = msa.MsaConfig(N, Gp, Gp, case.Hq, Hkv, d, base, bank_keys_rotated=1)
+    Kh = torch.empty(Kbar.shape, dtype=torch.bfloat16, pin_memory=True)
+    Vh = torch.empty(Vbar.shape, dtype=torch.bfloat16, pin_memory=True)
+    Kh.copy_(Kbar)
+    Vh.copy_(Vbar)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(seed)
+    sel = np.stack([rng.permutation(N)[:k] for _ in range(B * M * Hkv)]).reshape(B, M, Hkv, k)
+    sel[1, 0, 1, 2] = -1
+    didx = torch.from_numpy(sel.astype(np.int32)).cuda()
+    pos0 = k                                                        # Section 3.2.2: local positions start at k
+    q_pos = np.array([[pos0 + (Lloc - 1 - (3 * m + b) % Lloc) for m in range(M)] for b in range(B)])
+    dpos = torch.from_numpy(q_pos.astype(np.int32)).cuda()
+    Ks, Vs, idx_s, scfg = msa.msa_fetch_selected(acfg, Kh, Vh, didx, B, M)
+    torch.cuda.synchronize()
+    assert scfg.bank_keys_rotated == 1 and scfg.doc_len == Gp and scfg.n_docs == B * M * k
+    out_t, lse_t = msa.msa_sparse_attend(scfg, case.dq, Ks, Vs, idx_s, case.dKl, case.dVl, pos0, dpos)
+    out_d, lse_d = msa.msa_sparse_attend(acfg, case.dq, Kbar, Vbar, didx, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    assert torch.equal(out_t.view(torch.int16), out_d.view(torch.int16)) and torch.equal(lse_t, lse_d)
+    Kb = S.bf16_bits_to_f64(Kbar.view(torch.int16).cpu().numpy().view(np.uint16))
+    Vb = S.bf16_bits_to_f64(Vbar.view(torch.int16).cpu().numpy().view(np.uint16))
+    oo, ol = O.sparse_attend(case.q, Kb, Vb, sel, case.Kl, case.Vl, pos0, q_pos, base, mem_rotated=True)
+    go = out_t.float().cpu().numpy().astype(np.float64)
+    err = np.abs(go - oo)
+    rel = np.linalg.norm(err) / max(np.linalg.norm(oo), 1e-30)
+    say(f"   attend over fetched pooled rows: max-abs {err.max():.3e}  rel-L2 {rel:.3e}")
+    assert err.max() <= 2e-2 and rel <= 5e-3
+    assert np.allclose(lse_t.cpu().numpy().astype(np.float64), ol, rtol=0, atol=5e-3)
+
+
 def test_all_scores_equal_more_than_on_chip_survivors():
     """3000 documents with all-zero keys: every score ties at 0, so every document survives any
     threshold (more than the row top-k keeps on chip): the in-memory path, and the tie-break by index."""
