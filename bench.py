@@ -7,9 +7,13 @@ RoPE + attention) with every input already resident in HBM.  The routing index i
 the timed region by msa_build_routing_keys -- the paper's Stage 1 is offline, once per bank version
 (Section 3.4.1) -- and its own time and bandwidth are reported in the "build" object.
 
-Prints ONE JSON line: metric value = routed decode queries/s; "roofline" = achieved HBM GB/s of the
-dominant kernel family (the routing scan) from HIP events on the launch stream; "cpu_baseline" = the
-float64 oracle timed on this machine's host cores on a bounded sample of the same workload.
+Prints ONE JSON line: metric value = routed decode queries/s from the wall clock around the K timed
+steps; "roofline" = achieved HBM GB/s (or MFMA TFLOP/s) of the dominant kernel (the routing scan / the
+scoring GEMM), its duration taken from HIP events that the library records on the launch stream
+immediately around that kernel (msa_profile_dominant_kernel) in a second run of the same K steps, next
+to "entry_point_ms", the whole msa_score_topk call from events inside the timed steps; "attend" the same
+for msa_sparse_attend; "cpu_baseline" = the float64 oracle timed on this machine's host cores on a bounded
+sample of the same workload.
 """
 import argparse
 import json
@@ -253,9 +257,14 @@ def main():
     ws_s = torch.empty(msa.score_topk_workspace_bytes(cfg, B, M, k), dtype=torch.uint8, device="cuda")
     ws_a = torch.empty(msa.sparse_attend_workspace_bytes(acfg, B, M, k, wl.Lloc), dtype=torch.uint8, device="cuda")
 
-    def step(ev=None):
+    def step(ev=None, kev=None):
+        # ev: [before score, between, after attend] around the entry points; kev: (start, stop) pairs that the
+        # library records immediately around the dominant kernel of each entry point
         if ev:
             ev[0].record(stream)
+        if kev:
+            msa.msa_profile_dominant_kernel(0, kev[0], kev[1])
+            msa.msa_profile_dominant_kernel(1, kev[2], kev[3])
         msa.msa_score_topk(cfg, wl.q, KR, inv, k, idx, val, ws_s, stream=stream)
         if ev:
             ev[1].record(stream)
@@ -280,6 +289,19 @@ def main():
         step(events[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    # The same K steps once more with events recorded by the library around the dominant kernel of each entry
+    # point (four more event records per step cost ~10 us of stream time, so they stay out of the steps that
+    # `value` is taken from).
+    kevents = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for e in kevents:                     # torch creates the underlying event at its first record
+        for x in e:
+            x.record(stream)
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        step(None, kevents[i])
+    torch.cuda.synchronize()
+    msa.msa_profile_dominant_kernel(0, None, None)
+    msa.msa_profile_dominant_kernel(1, None, None)
     eager_ms = wall * 1e3 / args.steps
     if args.graph:      # same work, launched as one graph: the library only enqueues kernels on the given stream
         cap = torch.cuda.Stream()
@@ -300,6 +322,10 @@ def main():
 
     score_all = sorted(e[0].elapsed_time(e[1]) for e in events)
     attend_all = sorted(e[1].elapsed_time(e[2]) for e in events)
+    score_call_ms = sum(score_all) / args.steps      # whole entry points (small kernels around the dominant one)
+    attend_call_ms = sum(attend_all) / args.steps
+    score_all = sorted(e[0].elapsed_time(e[1]) for e in kevents)    # the dominant kernels alone
+    attend_all = sorted(e[2].elapsed_time(e[3]) for e in kevents)
     score_ms = sum(score_all) / args.steps
     attend_ms = sum(attend_all) / args.steps
 
@@ -363,21 +389,25 @@ def main():
                    "memory_tokens": wl.N * wl.G, "docs": wl.N, "doc_len": wl.G,
                    "chunk": wl.P, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.d, "batch": B,
                    "query_tokens": M, "top_k": k, "local_tokens": wl.Lloc, "rope_base": wl.base},
-        "roofline": ({"bound": "hbm", "kernel": "msa_score_topk = prep + score_scan_kernel (dominant) + score_merge",
+        "roofline": ({"bound": "hbm", "kernel": "score_scan_kernel (inside msa_score_topk = prep + scan + merge)",
+                      "entry_point_ms": score_call_ms,
                       "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                       "frac": score_gbs / HBM_PEAK_GBS, "traffic": MEASURED_SCORE_TRAFFIC.get(wl.name),
                       "algorithmic_bytes_per_launch": ab["score"], "avg_ms": score_ms,
                       "median_ms": score_all[args.steps // 2], "min_ms": score_all[0]} if flops is None else
-                     {"bound": "mfma", "kernel": "msa_score_topk = fold + score_gemm_kernel (dominant) + score_merge",
+                     {"bound": "mfma", "kernel": "score_gemm_kernel (inside msa_score_topk = fold + GEMM + merge)",
+                      "entry_point_ms": score_call_ms,
                       "achieved": flops / (score_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                       "unit": "TFLOP/s", "frac": flops / (score_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                       "traffic": None, "flops_issued_per_launch": flops, "avg_ms": score_ms,
                       "median_ms": score_all[args.steps // 2], "min_ms": score_all[0]}),
-        "attend": ({"bound": "hbm", "achieved": attend_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "attend": ({"bound": "hbm", "kernel": "attend_partial_kernel (inside msa_sparse_attend)",
+                    "entry_point_ms": attend_call_ms, "achieved": attend_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": attend_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": ab["attend"],
                     "avg_ms": attend_ms, "median_ms": attend_all[args.steps // 2], "min_ms": attend_all[0]}
                    if att_flops is None else
-                   {"bound": "mfma", "kernel": "attend_prefill_kernel (shared selection) + attend_merge",
+                   {"bound": "mfma", "kernel": "attend_prefill_kernel (shared selection)",
+                    "entry_point_ms": attend_call_ms,
                     "achieved": att_flops / (attend_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": att_flops / (attend_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                     "flops_issued_per_launch": att_flops, "avg_ms": attend_ms,

@@ -235,6 +235,18 @@ int msa_fetch_selected(const msa_config_t* cfg, const void* K_host, const void* 
                        int32_t B, int32_t M, int32_t k, void* K_stage, void* V_stage, int32_t* idx_stage,
                        int32_t* lens_stage, msa_stream_t stream);
 
+/* ---- timing aid -------------------------------------------------------------------------------
+ * For benchmarks that must time the DOMINANT KERNEL of an entry point and not the small kernels around it
+ * (operand preparation, list merges): while a pair of events is set for `which`, every call of that entry point
+ * records `start_event` on its stream immediately before the dominant kernel and `stop_event` immediately after it.
+ *   which = 0  msa_score_topk:    the scan over the routing index (all of its passes) or the scoring GEMM
+ *   which = 1  msa_sparse_attend: the gather-attention kernel, or the tiled kernel of a shared selection
+ * Both events are hipEvent_t created by the caller with timing enabled and stay the caller's; (NULL, NULL)
+ * switches the recording off (the state at load).  Process-wide and not thread-safe: set it, make the call,
+ * clear it.  Do not leave it set while a stream is being captured into a graph.
+ * Returns MSA_OK, or MSA_ERR_INVALID_ARG for another `which` or when only one of the two events is NULL. */
+int msa_profile_dominant_kernel(int32_t which, void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ MSA_OK, MSA_ERR_INVALID_ARG, MSA_ERR_UNSUPPORTED, MSA_ERR_WORKSPACE, MSA_ERR_MIS
 EXPORTS = ("msa_version", "msa_status_string", "msa_routing_keys_bytes", "msa_inv_norm_bytes",
            "msa_pooled_bank_bytes", "msa_score_topk_workspace_bytes",
            "msa_sparse_attend_workspace_bytes", "msa_build_routing_keys", "msa_pool_kv", "msa_score_topk",
-           "msa_sparse_attend", "msa_fetch_slots", "msa_fetch_selected")
+           "msa_sparse_attend", "msa_fetch_slots", "msa_fetch_selected", "msa_profile_dominant_kernel")
 
 
 class MsaConfig(ctypes.Structure):
@@ -103,6 +103,8 @@ def load_library():
     lib.msa_fetch_slots.argtypes = [cfgp, i32, i32, i32]
     lib.msa_fetch_selected.restype = ctypes.c_int
     lib.msa_fetch_selected.argtypes = [cfgp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.msa_profile_dominant_kernel.restype = ctypes.c_int
+    lib.msa_profile_dominant_kernel.argtypes = [i32, vp, vp]
     lib.msa_score_topk.restype = ctypes.c_int
     lib.msa_score_topk.argtypes = [cfgp, vp, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.msa_sparse_attend.restype = ctypes.c_int
@@ -258,6 +260,15 @@ def msa_sparse_attend(cfg, q, K, V, idx, Kloc, Vloc, local_pos0, q_pos, out=None
 
 def fetch_slots(cfg, B, M, k):
     return load_library().msa_fetch_slots(ctypes.byref(cfg), B, M, k)
+
+
+def msa_profile_dominant_kernel(which, start_event=None, stop_event=None):
+    """which: 0 = msa_score_topk, 1 = msa_sparse_attend.  start_event / stop_event: torch.cuda.Event objects with
+    timing enabled that have been recorded once (torch creates the underlying event at the first record), or both
+    None to switch the recording off."""
+    h0 = None if start_event is None else ctypes.c_void_p(start_event.cuda_event)
+    h1 = None if stop_event is None else ctypes.c_void_p(stop_event.cuda_event)
+    _check(load_library().msa_profile_dominant_kernel(which, h0, h1), "msa_profile_dominant_kernel")
 
 
 def msa_fetch_selected(cfg, K_host, V_host, idx, B, M, K_stage=None, V_stage=None, idx_stage=None,

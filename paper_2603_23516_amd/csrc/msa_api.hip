@@ -3,6 +3,8 @@
 
 namespace msa {
 
+ProfileEvents g_profile[2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 // Returns MSA_OK and fills dm, or the status that describes what is wrong with cfg.  The limits on
@@ -64,7 +66,15 @@ using namespace msa;
 
 extern "C" {
 
-int msa_version(void) { return 102; }
+int msa_version(void) { return 103; }
+
+int msa_profile_dominant_kernel(int32_t which, void* start_event, void* stop_event) {
+  if (which < 0 || which > 1) return MSA_ERR_INVALID_ARG;
+  if ((start_event == nullptr) != (stop_event == nullptr)) return MSA_ERR_INVALID_ARG;
+  msa::g_profile[which].start = (hipEvent_t)start_event;
+  msa::g_profile[which].stop = (hipEvent_t)stop_event;
+  return MSA_OK;
+}
 
 const char* msa_status_string(int status) {
   switch (status) {

@@ -41,6 +41,6 @@ struct AttendArgs {
 // Shared-selection prefill: unnormalised partials of every (token, head, split) in the layout the
 // decode path writes, merged by the same attend_merge_kernel.
 int launch_attend_prefill_partial(const Dims& dm, const AttendPlan& pl, const AttendArgs& a,
-                                  const RopeTheta& th, int B, hipStream_t st);
+                                  const RopeTheta& th, int B, hipStream_t st, bool dominant);
 
 }  // namespace msa

@@ -709,7 +709,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     al.split0 = pl.mem_splits;
     AttendPlan pll = pl;
     pll.n_splits = pl.loc_splits;
-    const int rc = launch_attend_prefill_partial(dm, pll, al, th, B, st);
+    const int rc = launch_attend_prefill_partial(dm, pll, al, th, B, st, false);
     if (rc != MSA_OK) return rc;
     // ... and the selected documents through the decode kernel below, which sees no local context
     a.Lloc = 0;
@@ -718,9 +718,10 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     a.n_splits = pl.mem_splits;
   }
   if (pl.prefill) {
-    const int rc = launch_attend_prefill_partial(dm, pl, a, th, B, st);
+    const int rc = launch_attend_prefill_partial(dm, pl, a, th, B, st, true);
     if (rc != MSA_OK) return rc;
   } else {
+    profile_mark(1, false, st);
     dim3 grid(a.n_splits, dm.Hkv, BM), block(256);
 #define MSA_LAUNCH_ATTEND(DD, MM) \
   hipLaunchKernelGGL((attend_partial_kernel<DD, MM>), grid, block, 0, st, a, th)
@@ -734,6 +735,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
       else MSA_LAUNCH_ATTEND(64, 2);
     }
 #undef MSA_LAUNCH_ATTEND
+    profile_mark(1, true, st);
   }
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   if (direct) return MSA_OK;

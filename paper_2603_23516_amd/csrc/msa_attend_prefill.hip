@@ -543,7 +543,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
 }
 
 int launch_attend_prefill_partial(const Dims& dm, const AttendPlan& pl, const AttendArgs& a,
-                                  const RopeTheta& th, int B, hipStream_t st) {
+                                  const RopeTheta& th, int B, hipStream_t st, bool dominant) {
   if (a.Krot == nullptr) return MSA_ERR_INVALID_ARG;  // the plan always reserves the rotated keys
   {
     dim3 rgrid(a.steps_total, dm.Hkv, B);
@@ -554,10 +554,12 @@ int launch_attend_prefill_partial(const Dims& dm, const AttendPlan& pl, const At
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
   dim3 grid(pl.n_splits, dm.Hkv, B * pl.n_ttiles), block(256);
+  if (dominant) profile_mark(1, false, st);
   if (dm.d == 128)
     hipLaunchKernelGGL(attend_prefill_kernel<128>, grid, block, 0, st, a, th, pl.tpw, pl.n_ttiles);
   else
     hipLaunchKernelGGL(attend_prefill_kernel<64>, grid, block, 0, st, a, th, pl.tpw, pl.n_ttiles);
+  if (dominant) profile_mark(1, true, st);
   return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
 }
 

@@ -59,6 +59,16 @@ struct ScorePlan {
 };
 ScorePlan plan_score(const Dims& dm, int BM, int k);
 
+// events recorded around the dominant kernel of msa_score_topk (0) and msa_sparse_attend (1); null = off
+struct ProfileEvents {
+  hipEvent_t start, stop;
+};
+extern ProfileEvents g_profile[2];
+inline void profile_mark(int which, bool stop, hipStream_t st) {
+  hipEvent_t e = stop ? g_profile[which].stop : g_profile[which].start;
+  if (e != nullptr) (void)hipEventRecord(e, st);
+}
+
 struct AttendPlan {
   int steps_mem;         // 32-key steps over the selected documents, ceil(k * G / 32)
   int steps_total;       // + ceil(Lloc / 32)

@@ -33,9 +33,17 @@ def test_exports_match_header(lib):
     assert declared == set(msa.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.msa_version() == 102
+    assert lib.msa_version() == 103
     for st in (0, -1, -2, -3, -4, -5, -99):
         assert len(msa.status_string(st)) > 0
+
+
+def test_profile_hook_validation(lib):
+    f = lib.msa_profile_dominant_kernel
+    assert f(0, None, None) == msa.MSA_OK and f(1, None, None) == msa.MSA_OK
+    assert f(2, None, None) == msa.MSA_ERR_INVALID_ARG and f(-1, None, None) == msa.MSA_ERR_INVALID_ARG
+    assert f(0, ctypes.c_void_p(16), None) == msa.MSA_ERR_INVALID_ARG     # one event without the other
+    assert f(0, None, ctypes.c_void_p(16)) == msa.MSA_ERR_INVALID_ARG
 
 
 def test_sizes_and_paper_estimate(lib):

@@ -834,6 +834,48 @@ def test_fetch_selected_from_pooled_host_bank():
     assert np.allclose(lse_t.cpu().numpy().astype(np.float64), ol, rtol=0, atol=5e-3)
 
 
+def test_profile_events_bracket_the_dominant_kernels():
+    """The timing aid records the caller's events inside the entry points: the bracketed time is positive and not
+    longer than the whole call's, results do not change, and clearing it stops the recording."""
+    seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k = CASES["d128_batch16"]
+    case = Case(seed, N, Hkv, r, G, d, P, B, M, Lloc, base).to_device()
+    cfg = case.cfg()
+    KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+    idx0, val0 = msa.msa_score_topk(cfg, case.dq, KR, inv, k)
+    pos0 = G
+    dpos = torch.full((B, M), pos0 + Lloc - 1, dtype=torch.int32, device="cuda")
+    out0, lse0 = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx0, case.dKl, case.dVl, pos0, dpos)
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+    for e in ev:
+        e.record(st)
+    torch.cuda.synchronize()
+    msa.msa_profile_dominant_kernel(0, ev[3], ev[4])
+    msa.msa_profile_dominant_kernel(1, ev[5], ev[6])
+    ev[0].record(st)
+    idx1, val1 = msa.msa_score_topk(cfg, case.dq, KR, inv, k)
+    ev[1].record(st)
+    out1, lse1 = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx1, case.dKl, case.dVl, pos0, dpos)
+    ev[2].record(st)
+    torch.cuda.synchronize()
+    msa.msa_profile_dominant_kernel(0, None, None)
+    msa.msa_profile_dominant_kernel(1, None, None)
+    assert torch.equal(idx1, idx0) and torch.equal(val1, val0)
+    assert torch.equal(out1.view(torch.int16), out0.view(torch.int16)) and torch.equal(lse1, lse0)
+    s_in, s_out = ev[3].elapsed_time(ev[4]), ev[0].elapsed_time(ev[1])
+    a_in, a_out = ev[5].elapsed_time(ev[6]), ev[1].elapsed_time(ev[2])
+    say(f"   score kernel {s_in * 1e3:.1f} us of {s_out * 1e3:.1f} us, attend kernel {a_in * 1e3:.1f} us of {a_out * 1e3:.1f} us")
+    assert 0 < s_in <= s_out and 0 < a_in <= a_out
+    # the score kernel's start lies inside the call: after the call's first event, before its last
+    assert ev[0].elapsed_time(ev[3]) >= 0 and ev[4].elapsed_time(ev[1]) >= 0
+    # cleared: a later call leaves the events alone
+    t_before = ev[3].elapsed_time(ev[4])
+    msa.msa_score_topk(cfg, case.dq, KR, inv, k)
+    torch.cuda.synchronize()
+    assert ev[3].elapsed_time(ev[4]) == t_before
+
+
 def test_all_scores_equal_more_than_on_chip_survivors():
     """3000 documents with all-zero keys: every score ties at 0, so every document survives any
     threshold (more than the row top-k keeps on chip): the in-memory path, and the tie-break by index."""
