@@ -137,7 +137,7 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   __shared__ __attribute__((aligned(16))) unsigned char smem[STAGE_BYTES > ANG_BYTES ? STAGE_BYTES : ANG_BYTES];
   unsigned char* const kt0 = smem;                    // rotated keys [piece][key][8 bf16], NBUF stages
   unsigned char* const vt0 = smem + NBUF * KT_BYTES;  // value rows [key][piece ^ 4 (key & 1)][8 bf16], NBUF stages
-  constexpr int kSelCache = 128;
+  constexpr int kSelCache = MSA_MAX_TOPK;  // a selection has at most this many slots
   __shared__ int sel_doc[kSelCache], sel_len[kSelCache];
   __shared__ int nvis_s[128];      // visible local tokens of each token of the tile (4 waves x 32 / r tokens)
 
@@ -237,9 +237,8 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
   const long long idx_row = (a.idx_rows_per_b == 1) ? b : (long long)b * a.M;  // shared selection: row of b
   const int32_t* idx_g = a.idx + (idx_row * a.idx_sel + (a.idx_sel == 1 ? 0 : g)) * a.k;
 
-  // The selection of this split's documents, read once: (document, rows that exist) of the first kSelCache
-  // slots from the split's first one; pads and ids outside the bank get 0 rows.  Slots beyond the cache
-  // are looked up in global memory.
+  // The selection of this split's documents, read once: (document, rows that exist) of the slots from the
+  // split's first one on; pads and ids outside the bank get 0 rows.
   const int slot0 = (int)(((long long)sb * 32) / a.G);
   {
     const int n_mem_slots = sb < a.steps_mem ? a.k - slot0 : 0;
@@ -258,22 +257,10 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     }
   }
   __syncthreads();
-  auto lookup = [&](int slot, int& doc, int& len) {  // block-uniform
+  auto lookup = [&](int slot, int& doc, int& len) {  // block-uniform; slot < k <= kSelCache
     const int i = slot - slot0;
-    if (i < kSelCache) {
-      doc = __builtin_amdgcn_readfirstlane(sel_doc[i]);
-      len = __builtin_amdgcn_readfirstlane(sel_len[i]);
-      return;
-    }
-    doc = idx_g[slot];
-    len = 0;
-    if (doc >= 0 && doc < a.N) {
-      len = a.G;
-      if (a.lens != nullptr) {
-        len = a.lens[doc];
-        len = len < 1 ? 1 : (len > a.G ? a.G : len);
-      }
-    }
+    doc = __builtin_amdgcn_readfirstlane(sel_doc[i]);
+    len = __builtin_amdgcn_readfirstlane(sel_len[i]);
   };
 
   struct StepSrc {
