@@ -891,20 +891,25 @@ def test_all_scores_equal_more_than_on_chip_survivors():
     assert np.all(val.cpu().numpy() == 0)
 
 
-def test_hip_graph_replays_match_eager():
+@pytest.mark.parametrize("kind", ["decode", "prefill_shared_selection"])
+def test_hip_graph_replays_match_eager(kind):
     """The online step (score + top-k, then attention) captured once into a HIP graph on the caller's side --
     the library only enqueues kernels on the stream it is given and allocates nothing -- and replayed with
-    new queries: every replay must equal the eager result bit for bit, with eager work between replays."""
-    say("case HIP graph: capture score_topk + sparse_attend, replay with new queries")
-    case = Case(81000, 700, 2, 4, 64, 128, 16, 3, 1, 50, 1e6).to_device()
-    cfg = case.cfg()
-    N, G, k, B, M, Lloc = 700, 64, 6, 3, 1, 50
+    new queries: every replay must equal the eager result bit for bit, with eager work between replays.
+    decode: the scan and the gather-attention kernels; prefill_shared_selection: the scoring GEMM, the pooling over
+    tokens, the once-rotated keys and the tiled attention kernel with its asynchronous LDS copies."""
+    say(f"case HIP graph ({kind}): capture score_topk + sparse_attend, replay with new queries")
+    N, G, k, B, Lloc = 700, 64, 6, 3, 50
+    M, P, pool = (1, 16, 0) if kind == "decode" else (40, 8, 1)
+    case = Case(81000, N, 2, 4, G, 128, P, B, M, Lloc, 1e6).to_device()
+    cfg = case.cfg(token_pool=pool)
     KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
     pos0 = G
-    dpos = torch.full((B, M), pos0 + Lloc - 1, dtype=torch.int32, device="cuda")
+    dpos = (pos0 + (torch.arange(B * M, device="cuda", dtype=torch.int32) * 7) % Lloc).reshape(B, M).contiguous()
     q_static = case.dq.clone()
-    idx = torch.empty((B, M, 2, k), dtype=torch.int32, device="cuda")
-    val = torch.empty((B, M, 2, k), dtype=torch.float32, device="cuda")
+    Mi = 1 if pool else M
+    idx = torch.empty((B, Mi, 2, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((B, Mi, 2, k), dtype=torch.float32, device="cuda")
     out = torch.empty_like(q_static)
     lse = torch.empty((B, M, case.Hq), dtype=torch.float32, device="cuda")
     ws_s = torch.empty(msa.score_topk_workspace_bytes(cfg, B, M, k), dtype=torch.uint8, device="cuda")
