@@ -461,15 +461,10 @@ void attend_prefill_kernel(AttendArgs a, RopeTheta th, int tpw,
     float psum = 0.f;
 #pragma unroll
     for (int i2 = 0; i2 < 8; ++i2) {
-      float ph2[2], pl2[2];
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const float p = __builtin_amdgcn_exp2f(sc[2 * i2 + e] - m_use);
-        psum += p;
-        split_bf16(p, ph2[e], pl2[e]);
-      }
-      pwh[i2] = pack_bf16(ph2[0], ph2[1]);
-      pwl[i2] = pack_bf16(pl2[0], pl2[1]);
+      const float p0 = __builtin_amdgcn_exp2f(sc[2 * i2] - m_use);
+      const float p1 = __builtin_amdgcn_exp2f(sc[2 * i2 + 1] - m_use);
+      psum += p0 + p1;
+      split_pack_bf16(p0, p1, pwh[i2], pwl[i2]);
     }
     l_run += psum;
 

@@ -57,6 +57,12 @@ __device__ __forceinline__ void split_bf16(float x, float& hi, float& lo) {
   lo = x - hi;
 }
 
+// The same for a pair, straight to packed words: hi_w = (bf16(x0), bf16(x1)), lo_w = (bf16(x0 - hi0), bf16(x1 - hi1)).
+__device__ __forceinline__ void split_pack_bf16(float x0, float x1, uint32_t& hi_w, uint32_t& lo_w) {
+  hi_w = pack_bf16(x0, x1);
+  lo_w = pack_bf16(x0 - bf16_lo(hi_w), x1 - bf16_hi(hi_w));
+}
+
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 
 // D(16x16, fp32) += A(16x32, bf16) * B(32x16, bf16).
