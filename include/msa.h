@@ -24,7 +24,8 @@
  *     so); bf16 = bfloat16 bit patterns (uint16_t).  The config struct is a HOST pointer and is read
  *     before the call returns.
  *   - Ownership: the caller owns every buffer, workspace included.  The library allocates nothing,
- *     frees nothing and keeps no state between calls.
+ *     frees nothing and keeps no state between calls (the one exception is the optional timing aid at
+ *     the end of this file, which is off unless the caller sets it).
  *   - Asynchrony: work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream); no call synchronises.  Outputs are valid once the stream reaches that point.
  *   - Errors: 0 on success, a negative msa_status otherwise.  Arguments are validated on the host
@@ -117,7 +118,9 @@ size_t msa_inv_norm_bytes(const msa_config_t* cfg);
 uint64_t msa_pooled_bank_bytes(uint64_t tokens, uint32_t chunk, uint32_t heads, uint32_t head_dim,
                                uint32_t n_layers, uint32_t bytes_per_elem, uint32_t n_tensors);
 
-/* Workspace requirements (bytes, multiple of 256).  0 if the arguments are invalid. */
+/* Workspace requirements (bytes, multiple of 256).  0 if the arguments are invalid.  The attention workspace
+ * holds the split-K partials and, where many query tokens share keys (token_pool = 1 with M >= 8, or the local
+ * context with M >= 16), those keys rotated once: B * Hkv * ceil((k*G or 0) + Lloc, 32 rows) * d * 2 bytes more. */
 size_t msa_score_topk_workspace_bytes(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k);
 size_t msa_sparse_attend_workspace_bytes(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k,
                                          int32_t Lloc);
