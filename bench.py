@@ -58,7 +58,7 @@ def parse():
                     help="documents of different lengths: seeded lengths in [G/8, G] passed as cfg.doc_lens (the "
                          "bank keeps its G-row slots); byte counts then follow the lengths")
     ap.add_argument("--local-tokens", type=int, default=None,
-                    help="decode workloads: local-context length instead of the workload's (BASELINE does not state "
+                    help="decode workloads: local-context length instead of the workload's (the benchmark definition does not state "
                          "it for configs 3 and 5; 2048 is used, 0 is the other case asked for)")
     ap.add_argument("--cold", action="store_true",
                     help="additionally time the step with nothing left in the 256 MB Infinity Cache from the step "

@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (same workload
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times (same workload
 builder, same B / M / k, same entry points).  The banks (2 GiB .. 191 GiB of K/V) are generated on the
 device; the oracle works on documents regenerated on the host bit-for-bit, so it can check SAMPLED
 outputs one by one:
@@ -202,7 +202,7 @@ def test_fullsize_sampled_parity(name, plant, a):
 
 
 def test_fullsize_cfg4_question_level_routing():
-    """BASELINE config 4 with Eq. 2 as printed over the tokens (token_pool = 1): one selection per KV head
+    """benchmark config 4 with Eq. 2 as printed over the tokens (token_pool = 1): one selection per KV head
     for the whole 2048-token question (GEMM scoring + token pooling), then the tiled shared-selection
     attention kernel.  Sampled checks against the oracle as above."""
     name = "cfg4_prefill_16m"
@@ -262,7 +262,7 @@ def test_fullsize_cfg4_question_level_routing():
 
 
 def test_fullsize_cfg3_documents_of_different_lengths():
-    """BASELINE config 3 with seeded document lengths in [G/8, G] (cfg.doc_lens): sampled checks of the index,
+    """benchmark config 3 with seeded document lengths in [G/8, G] (cfg.doc_lens): sampled checks of the index,
     the selection and the attention against the oracle's lens / valid arguments."""
     name = "cfg3_batch32_4m"
     say(f"workload {name} with document lengths")
