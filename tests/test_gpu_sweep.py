@@ -3,6 +3,8 @@ k, local context, similarity, selection scope, token pooling and document length
 the documented limits, and every draw runs the whole chain (index build, score + top-k, attention) against
 the float64 oracle with the tolerances of test_gpu_parity.py.  The draws are fixed by the seed, so a failure
 names its case."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -14,7 +16,9 @@ from test_gpu_ragged import attend_err, make_lens
 
 pytestmark = pytest.mark.gpu
 
-N_DRAWS = 96
+# 96 draws by default; MSA_SWEEP_FIRST / MSA_SWEEP_DRAWS select another range of the same seeded sequence
+FIRST_DRAW = int(os.environ.get("MSA_SWEEP_FIRST", "0"))
+N_DRAWS = int(os.environ.get("MSA_SWEEP_DRAWS", "96"))
 
 
 def draw(i):
@@ -50,7 +54,7 @@ def draw(i):
                 ragged=bool(rng.integers(0, 2)), base=float(rng.choice([1e4, 1e6])), seed=91000 + 17 * i)
 
 
-@pytest.mark.parametrize("i", range(N_DRAWS))
+@pytest.mark.parametrize("i", range(FIRST_DRAW, FIRST_DRAW + N_DRAWS))
 def test_random_configuration(i):
     c = draw(i)
     say(f"draw {i}: {c}")
