@@ -25,7 +25,8 @@
  *     before the call returns.
  *   - Ownership: the caller owns every buffer, workspace included.  The library allocates nothing,
  *     frees nothing and keeps no state between calls (the one exception is the optional timing aid at
- *     the end of this file, which is off unless the caller sets it).
+ *     the end of this file, which is off unless the caller sets it; msa_score_topk_noalloc brings its
+ *     own fixed scratch buffer in place of a workspace).
  *   - Asynchrony: work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream); no call synchronises.  Outputs are valid once the stream reaches that point.
  *   - Errors: 0 on success, a negative msa_status otherwise.  Arguments are validated on the host
@@ -181,6 +182,22 @@ int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t d
 int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
                    const void* KR, const float* inv_norm, int32_t k, int32_t* out_idx,
                    float* out_score, void* workspace, size_t workspace_bytes, msa_stream_t stream);
+
+/*
+ * msa_score_topk for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results; the workspace is a buffer of msa_noalloc_scratch_bytes() (32 MiB) built into
+ * the library's device code (one copy per GPU, held until the process ends).  The call allocates and
+ * frees nothing.  A request whose msa_score_topk_workspace_bytes() exceeds the built-in buffer returns
+ * MSA_ERR_WORKSPACE before anything is enqueued (all five benchmark configurations fit).  The stream must
+ * belong to the CURRENT device.  Every call on a GPU shares that GPU's buffer: calls that overlap on one GPU
+ * (two streams, two threads) race -- serialise them or use msa_score_topk with separate workspaces.
+ * The buffer keeps the previous call's contents; nothing in it needs to start at zero.
+ */
+size_t msa_noalloc_scratch_bytes(void);
+int msa_score_topk_noalloc(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
+                           const void* KR, const float* inv_norm, int32_t k, int32_t* out_idx,
+                           float* out_score, msa_stream_t stream);
 
 /*
  * Sparse attention (Eq. 3-4 with the position scheme of Section 3.2.2).  For query (b,m), head h of

@@ -20,7 +20,8 @@ MSA_OK, MSA_ERR_INVALID_ARG, MSA_ERR_UNSUPPORTED, MSA_ERR_WORKSPACE, MSA_ERR_MIS
 EXPORTS = ("msa_version", "msa_status_string", "msa_routing_keys_bytes", "msa_inv_norm_bytes",
            "msa_pooled_bank_bytes", "msa_score_topk_workspace_bytes",
            "msa_sparse_attend_workspace_bytes", "msa_build_routing_keys", "msa_pool_kv", "msa_score_topk",
-           "msa_sparse_attend", "msa_fetch_slots", "msa_fetch_selected", "msa_profile_dominant_kernel")
+           "msa_sparse_attend", "msa_fetch_slots", "msa_fetch_selected", "msa_profile_dominant_kernel",
+           "msa_noalloc_scratch_bytes", "msa_score_topk_noalloc")
 
 
 class MsaConfig(ctypes.Structure):
@@ -107,6 +108,10 @@ def load_library():
     lib.msa_profile_dominant_kernel.argtypes = [i32, vp, vp]
     lib.msa_score_topk.restype = ctypes.c_int
     lib.msa_score_topk.argtypes = [cfgp, vp, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.msa_noalloc_scratch_bytes.restype = sz
+    lib.msa_noalloc_scratch_bytes.argtypes = []
+    lib.msa_score_topk_noalloc.restype = ctypes.c_int
+    lib.msa_score_topk_noalloc.argtypes = [cfgp, vp, i32, i32, vp, vp, i32, vp, vp, vp]
     lib.msa_sparse_attend.restype = ctypes.c_int
     lib.msa_sparse_attend.argtypes = [cfgp, vp, i32, i32, vp, vp, vp, i32, vp, vp, i32, i32, vp, vp,
                                       vp, vp, sz, vp]
@@ -230,6 +235,22 @@ def msa_score_topk(cfg, q_route, KR, inv_norm, k, out_idx=None, out_score=None, 
                                        _ptr(out_idx), _ptr(out_score), _ptr(workspace), workspace.numel(),
                                        _stream(stream, dev))
     _check(rc, "msa_score_topk")
+    return out_idx, out_score
+
+
+def noalloc_scratch_bytes():
+    return load_library().msa_noalloc_scratch_bytes()
+
+
+def msa_score_topk_noalloc(cfg, q_route, KR, inv_norm, k, out_idx, out_score, stream=None):
+    """msa_score_topk on the library's built-in scratch buffer: the caller passes every output, nothing is
+    allocated here or in the library."""
+    _need(q_route, torch.bfloat16, "q_route")
+    _need(out_idx, torch.int32, "out_idx")
+    B, M = q_route.shape[0], q_route.shape[1]
+    rc = load_library().msa_score_topk_noalloc(ctypes.byref(cfg), _ptr(q_route), B, M, _ptr(KR), _ptr(inv_norm),
+                                               k, _ptr(out_idx), _ptr(out_score), _stream(stream, q_route.device))
+    _check(rc, "msa_score_topk_noalloc")
     return out_idx, out_score
 
 

@@ -1,6 +1,8 @@
 // C-ABI layer: argument validation (host only, before anything is enqueued), work plans, launches.
 #include "msa_host.h"
 
+#include <mutex>
+
 namespace msa {
 
 ProfileEvents g_profile[2] = {{nullptr, nullptr}, {nullptr, nullptr}};
@@ -60,13 +62,44 @@ static bool attend_doc_len_ok(const msa_config_t* cfg) {
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 static bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
 
+// ---- scratch memory of msa_score_topk_noalloc ---------------------------------------------------
+// A file-scope device array takes the place of the caller's workspace for callers that cannot
+// allocate.  Every device the library runs on holds its own copy at its own address; in host code the
+// array's name is only a handle for hipGetSymbolAddress, never an address to hand to a kernel.
+constexpr size_t kNoAllocScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices];  // per device, filled at the first call on that device
+
+// Address of `scratch` on the CURRENT device (looked up once per device, with that device current).
+static int scratch_on_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return MSA_ERR_HIP;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return MSA_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MSA_OK;
+}
+
 }  // namespace msa
 
 using namespace msa;
 
 extern "C" {
 
-int msa_version(void) { return 103; }
+int msa_version(void) { return 104; }
 
 int msa_profile_dominant_kernel(int32_t which, void* start_event, void* stop_event) {
   if (which < 0 || which > 1) return MSA_ERR_INVALID_ARG;
@@ -215,6 +248,33 @@ int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int3
   const ScorePlan pl = plan_score(dm, B * M, k);
   if (workspace_bytes < pl.ws_bytes) return MSA_ERR_WORKSPACE;
   return launch_score(dm, pl, q_route, B, M, KR, inv_norm, k, out_idx, out_score, workspace,
+                      (hipStream_t)stream);
+}
+
+size_t msa_noalloc_scratch_bytes(void) { return kNoAllocScratchBytes; }
+
+int msa_score_topk_noalloc(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
+                           const void* KR, const float* inv_norm, int32_t k, int32_t* out_idx,
+                           float* out_score, msa_stream_t stream) {
+  Dims dm;
+  const int rc = make_dims(cfg, &dm);
+  if (rc != MSA_OK) return rc;
+  if (q_route == nullptr || KR == nullptr || out_idx == nullptr) return MSA_ERR_INVALID_ARG;
+  if (inv_norm == nullptr && dm.cos) return MSA_ERR_INVALID_ARG;
+  if (B < 1 || M < 1 || (int64_t)B * M > (1 << 20)) return MSA_ERR_INVALID_ARG;
+  if (k < 1 || k > dm.N) return MSA_ERR_INVALID_ARG;
+  if (k > MSA_MAX_TOPK) return MSA_ERR_UNSUPPORTED;
+  if (misaligned(q_route) || misaligned(KR) || misaligned(inv_norm) || misaligned(out_idx) ||
+      misaligned(out_score))
+    return MSA_ERR_MISALIGNED;
+  const ScorePlan pl = plan_score(dm, B * M, k);
+  if (pl.ws_bytes > kNoAllocScratchBytes) return MSA_ERR_WORKSPACE;  // beyond the built-in scratch
+  void* ws = nullptr;
+  const int rs = scratch_on_current_device(&ws);
+  if (rs != MSA_OK) return rs;
+  // The kernels take the scratch address exactly as they take a caller's workspace; nothing in it has
+  // to start at zero (every buffer of the plan is written before it is read within the call).
+  return launch_score(dm, pl, q_route, B, M, KR, inv_norm, k, out_idx, out_score, ws,
                       (hipStream_t)stream);
 }
 

@@ -33,7 +33,7 @@ def test_exports_match_header(lib):
     assert declared == set(msa.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.msa_version() == 103
+    assert lib.msa_version() == 104
     for st in (0, -1, -2, -3, -4, -5, -99):
         assert len(msa.status_string(st)) > 0
 
@@ -166,6 +166,33 @@ def test_argument_validation_before_launch(lib):
     assert lib.msa_pool_kv(cb, p, odd, 0, 1, p, p, None, None) == E.MSA_ERR_MISALIGNED
     assert lib.msa_pool_kv(cb, p, p, 0, 0, p, p, None, None) == E.MSA_OK                      # nothing to do, nothing launched
     assert lib.msa_pool_kv(ctypes.byref(_cfg(head_dim=96)), p, p, 0, 1, p, p, None, None) == E.MSA_ERR_UNSUPPORTED
+
+
+def test_noalloc_entry_point_validation(lib):
+    """The entry point on the built-in scratch buffer validates like msa_score_topk and refuses a request
+    beyond its buffer before it touches a device."""
+    E = msa
+    c = _cfg()
+    cb = ctypes.byref(c)
+    p = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x10008)
+    f = lib.msa_score_topk_noalloc
+    assert msa.noalloc_scratch_bytes() == 32 << 20
+    assert f(cb, None, 1, 1, p, p, 4, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, 1, 1, p, None, 4, p, p, None) == E.MSA_ERR_INVALID_ARG       # cosine needs inv_norm
+    assert f(cb, p, 1, 1, p, p, 4, None, p, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, 0, 1, p, p, 4, p, p, None) == E.MSA_ERR_INVALID_ARG
+    assert f(cb, p, 1, 1, p, p, 65, p, p, None) == E.MSA_ERR_INVALID_ARG         # k > N
+    assert f(cb, p, 1, 1, odd, p, 4, p, p, None) == E.MSA_ERR_MISALIGNED
+    assert f(None, p, 1, 1, p, p, 4, p, p, None) == E.MSA_ERR_INVALID_ARG
+    # 8192 query tokens against 64K documents: folded queries plus candidate lists exceed 32 MiB
+    big = _cfg(n_docs=65536, n_q_heads=32, n_kv_heads=8, head_dim=128)
+    assert msa.score_topk_workspace_bytes(big, 1, 8192, 8) > msa.noalloc_scratch_bytes()
+    assert f(ctypes.byref(big), p, 1, 8192, p, p, 8, p, p, None) == E.MSA_ERR_WORKSPACE
+    # the five benchmark configurations fit
+    for N, B, M, k in ((2048, 1, 1, 16), (8192, 32, 1, 16), (32768, 1, 2048, 8), (97656, 8, 1, 32)):
+        cc = _cfg(n_docs=N, n_q_heads=32, n_kv_heads=8, head_dim=128)
+        assert 0 < msa.score_topk_workspace_bytes(cc, B, M, k) <= msa.noalloc_scratch_bytes(), N
 
 
 def test_fetch_validation(lib):
