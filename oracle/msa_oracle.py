@@ -144,13 +144,15 @@ def pool_values(V, P, lens=None):
 # Section 3.2.1, Eq. 2: relevance scores
 # --------------------------------------------------------------------------------------------
 def similarity(x, Y, sim="cos"):
-    """sim(x, Y[c]) for every row c of Y.  cos(x,y) = x.y / (max(|x|,eps) * max(|y|,eps))."""
-    dots = Y @ x
+    """sim(x, Y[c]) for every row c of Y.  cos(x,y) = x.y / (max(|x|,eps) * max(|y|,eps)).
+    x [d] -> [NC]; a matrix of queries x [n, d] -> [n, NC] (one matrix product)."""
+    x = np.asarray(x, dtype=np.float64)
+    dots = Y @ x if x.ndim == 1 else x @ Y.T
     if sim == "dot":
         return dots
-    nx = max(np.sqrt(x @ x), EPS_NORM)
+    nx = np.maximum(np.sqrt((x * x).sum(axis=-1)), EPS_NORM)
     ny = np.maximum(np.sqrt((Y * Y).sum(axis=-1)), EPS_NORM)
-    return dots / (nx * ny)
+    return dots / (nx * ny) if x.ndim == 1 else dots / (nx[:, None] * ny[None, :])
 
 
 def chunk_scores(qr, KRb, sim="cos", select_scope="group", token_pool=False, valid=None):
@@ -168,10 +170,9 @@ def chunk_scores(qr, KRb, sim="cos", select_scope="group", token_pool=False, val
     assert Hq % Hkv == 0
     r = Hq // Hkv
     per_head = np.empty((B, M, Hq, NC), dtype=np.float64)
-    for b in range(B):
-        for m in range(M):
-            for h in range(Hq):
-                per_head[b, m, h, :] = similarity(qr[b, m, h], KRb[h // r], sim)
+    for g in range(Hkv):          # the r heads of group g, all query tokens at once, against that group's keys
+        heads = qr[:, :, g * r:(g + 1) * r, :].reshape(B * M * r, d)
+        per_head[:, :, g * r:(g + 1) * r, :] = similarity(heads, KRb[g], sim).reshape(B, M, r, NC)
     if select_scope == "group":
         Sc = per_head.reshape(B, M, Hkv, r, NC).sum(axis=3) / r
     elif select_scope == "all":
