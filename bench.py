@@ -10,7 +10,7 @@ the timed region by msa_build_routing_keys -- the paper's Stage 1 is offline, on
 Prints ONE JSON line: metric value = routed decode queries/s from the wall clock around the K timed
 steps; "roofline" = achieved HBM GB/s (or MFMA TFLOP/s) of the dominant kernel (the routing scan / the
 scoring GEMM), its duration taken from HIP events that the library records on the launch stream
-immediately around that kernel (msa_profile_dominant_kernel) in a second run of the same K steps, next
+immediately around that kernel (the per-call profile events of msa_config_t) in a second run of the same K steps, next
 to "entry_point_ms", the whole msa_score_topk call from events inside the timed steps; "attend" the same
 for msa_sparse_attend; "cpu_baseline" = the float64 oracle timed on this machine's host cores on a bounded
 sample of the same workload.
@@ -257,18 +257,20 @@ def main():
     ws_s = torch.empty(msa.score_topk_workspace_bytes(cfg, B, M, k), dtype=torch.uint8, device="cuda")
     ws_a = torch.empty(msa.sparse_attend_workspace_bytes(acfg, B, M, k, wl.Lloc), dtype=torch.uint8, device="cuda")
 
+    cfg_prof, acfg_prof = cfg.replace(), acfg.replace()    # copies that carry the per-call profile events
+
     def step(ev=None, kev=None):
         # ev: [before score, between, after attend] around the entry points; kev: (start, stop) pairs that the
         # library records immediately around the dominant kernel of each entry point
         if ev:
             ev[0].record(stream)
+        c_s, c_a = cfg, acfg
         if kev:
-            msa.msa_profile_dominant_kernel(0, kev[0], kev[1])
-            msa.msa_profile_dominant_kernel(1, kev[2], kev[3])
-        msa.msa_score_topk(cfg, wl.q, KR, inv, k, idx, val, ws_s, stream=stream)
+            c_s, c_a = cfg_prof.set_profile_events(kev[0], kev[1]), acfg_prof.set_profile_events(kev[2], kev[3])
+        msa.msa_score_topk(c_s, wl.q, KR, inv, k, idx, val, ws_s, stream=stream)
         if ev:
             ev[1].record(stream)
-        msa.msa_sparse_attend(acfg, wl.q, bank_K, bank_V, idx, wl.Kloc, wl.Vloc, pos0, q_pos, out, lse,
+        msa.msa_sparse_attend(c_a, wl.q, bank_K, bank_V, idx, wl.Kloc, wl.Vloc, pos0, q_pos, out, lse,
                               ws_a, stream=stream)
         if ev:
             ev[2].record(stream)
@@ -300,8 +302,6 @@ def main():
     for i in range(args.steps):
         step(None, kevents[i])
     torch.cuda.synchronize()
-    msa.msa_profile_dominant_kernel(0, None, None)
-    msa.msa_profile_dominant_kernel(1, None, None)
     eager_ms = wall * 1e3 / args.steps
     if args.graph:      # same work, launched as one graph: the library only enqueues kernels on the given stream
         cap = torch.cuda.Stream()

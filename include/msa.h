@@ -24,9 +24,8 @@
  *     so); bf16 = bfloat16 bit patterns (uint16_t).  The config struct is a HOST pointer and is read
  *     before the call returns.
  *   - Ownership: the caller owns every buffer, workspace included.  The library allocates nothing,
- *     frees nothing and keeps no state between calls (the one exception is the optional timing aid at
- *     the end of this file, which is off unless the caller sets it; msa_score_topk_noalloc brings its
- *     own fixed scratch buffer in place of a workspace).
+ *     frees nothing and keeps no state between calls (msa_score_topk_noalloc brings its own fixed
+ *     scratch buffer in place of a workspace).
  *   - Asynchrony: work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
  *     stream); no call synchronises.  Outputs are valid once the stream reaches that point.
  *   - Errors: 0 on success, a negative msa_status otherwise.  Arguments are validated on the host
@@ -86,6 +85,14 @@ typedef struct msa_config {
                            value to [1, G].  Read by msa_build_routing_keys, msa_pool_kv,
                            msa_sparse_attend and msa_fetch_selected; msa_score_topk does not need it (the
                            index already accounts for the lengths)                                    */
+  void* profile_start_event; /* Optional per-call timing aid for benchmarks; NULL (both) = off.  A pair of   */
+  void* profile_stop_event;  /* the caller's hipEvent_t (timing enabled): msa_score_topk / msa_sparse_attend
+                           called with this config record start on the call's stream immediately before their
+                           DOMINANT kernel (the scan over the routing index, all passes, or the scoring GEMM;
+                           the gather-attention kernel, or the tiled kernel of a shared selection) and stop
+                           immediately after it, so that its duration can be told from the small kernels
+                           around it.  Nothing is kept after the call returns; other entry points ignore the
+                           fields; exactly one of the two being NULL is MSA_ERR_INVALID_ARG                */
 } msa_config_t;
 
 /* Library version (major * 100 + minor). */
@@ -254,18 +261,6 @@ int64_t msa_fetch_slots(const msa_config_t* cfg, int32_t B, int32_t M, int32_t k
 int msa_fetch_selected(const msa_config_t* cfg, const void* K_host, const void* V_host, const int32_t* idx,
                        int32_t B, int32_t M, int32_t k, void* K_stage, void* V_stage, int32_t* idx_stage,
                        int32_t* lens_stage, msa_stream_t stream);
-
-/* ---- timing aid -------------------------------------------------------------------------------
- * For benchmarks that must time the DOMINANT KERNEL of an entry point and not the small kernels around it
- * (operand preparation, list merges): while a pair of events is set for `which`, every call of that entry point
- * records `start_event` on its stream immediately before the dominant kernel and `stop_event` immediately after it.
- *   which = 0  msa_score_topk:    the scan over the routing index (all of its passes) or the scoring GEMM
- *   which = 1  msa_sparse_attend: the gather-attention kernel, or the tiled kernel of a shared selection
- * Both events are hipEvent_t created by the caller with timing enabled and stay the caller's; (NULL, NULL)
- * switches the recording off (the state at load).  Process-wide and not thread-safe: set it, make the call,
- * clear it.  Do not leave it set while a stream is being captured into a graph.
- * Returns MSA_OK, or MSA_ERR_INVALID_ARG for another `which` or when only one of the two events is NULL. */
-int msa_profile_dominant_kernel(int32_t which, void* start_event, void* stop_event);
 
 #ifdef __cplusplus
 }

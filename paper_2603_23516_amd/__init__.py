@@ -20,7 +20,7 @@ MSA_OK, MSA_ERR_INVALID_ARG, MSA_ERR_UNSUPPORTED, MSA_ERR_WORKSPACE, MSA_ERR_MIS
 EXPORTS = ("msa_version", "msa_status_string", "msa_routing_keys_bytes", "msa_inv_norm_bytes",
            "msa_pooled_bank_bytes", "msa_score_topk_workspace_bytes",
            "msa_sparse_attend_workspace_bytes", "msa_build_routing_keys", "msa_pool_kv", "msa_score_topk",
-           "msa_sparse_attend", "msa_fetch_slots", "msa_fetch_selected", "msa_profile_dominant_kernel",
+           "msa_sparse_attend", "msa_fetch_slots", "msa_fetch_selected",
            "msa_noalloc_scratch_bytes", "msa_score_topk_noalloc")
 
 
@@ -30,7 +30,8 @@ class MsaConfig(ctypes.Structure):
                 ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("rope_base", ctypes.c_float), ("sim", ctypes.c_int32),
                 ("select_scope", ctypes.c_int32), ("token_pool", ctypes.c_int32),
-                ("bank_keys_rotated", ctypes.c_int32), ("doc_lens", ctypes.c_void_p)]
+                ("bank_keys_rotated", ctypes.c_int32), ("doc_lens", ctypes.c_void_p),
+                ("profile_start_event", ctypes.c_void_p), ("profile_stop_event", ctypes.c_void_p)]
 
     def __init__(self, n_docs, doc_len, chunk, n_q_heads, n_kv_heads, head_dim, rope_base=1e6,
                  sim=MSA_SIM_COS, select_scope=MSA_SCOPE_GROUP, token_pool=0, bank_keys_rotated=0,
@@ -43,7 +44,17 @@ class MsaConfig(ctypes.Structure):
         self.doc_lens_tensor = doc_lens
         super().__init__(n_docs, doc_len, chunk, n_q_heads, n_kv_heads, head_dim, rope_base, sim,
                          select_scope, token_pool, bank_keys_rotated,
-                         None if doc_lens is None else doc_lens.data_ptr())
+                         None if doc_lens is None else doc_lens.data_ptr(), None, None)
+        self._profile_events = None
+
+    def set_profile_events(self, start_event=None, stop_event=None):
+        """Per-call timing aid: torch.cuda.Event objects with timing enabled that have been recorded once (torch
+        creates the underlying event at the first record), recorded by msa_score_topk / msa_sparse_attend around
+        their dominant kernel when called with this config; (None, None) switches it off."""
+        self._profile_events = (start_event, stop_event)           # kept alive by this object
+        self.profile_start_event = None if start_event is None else start_event.cuda_event
+        self.profile_stop_event = None if stop_event is None else stop_event.cuda_event
+        return self
 
     def replace(self, **kw):
         """A copy with some fields changed (doc_lens: a tensor or None)."""
@@ -104,8 +115,6 @@ def load_library():
     lib.msa_fetch_slots.argtypes = [cfgp, i32, i32, i32]
     lib.msa_fetch_selected.restype = ctypes.c_int
     lib.msa_fetch_selected.argtypes = [cfgp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp]
-    lib.msa_profile_dominant_kernel.restype = ctypes.c_int
-    lib.msa_profile_dominant_kernel.argtypes = [i32, vp, vp]
     lib.msa_score_topk.restype = ctypes.c_int
     lib.msa_score_topk.argtypes = [cfgp, vp, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     lib.msa_noalloc_scratch_bytes.restype = sz
@@ -281,15 +290,6 @@ def msa_sparse_attend(cfg, q, K, V, idx, Kloc, Vloc, local_pos0, q_pos, out=None
 
 def fetch_slots(cfg, B, M, k):
     return load_library().msa_fetch_slots(ctypes.byref(cfg), B, M, k)
-
-
-def msa_profile_dominant_kernel(which, start_event=None, stop_event=None):
-    """which: 0 = msa_score_topk, 1 = msa_sparse_attend.  start_event / stop_event: torch.cuda.Event objects with
-    timing enabled that have been recorded once (torch creates the underlying event at the first record), or both
-    None to switch the recording off."""
-    h0 = None if start_event is None else ctypes.c_void_p(start_event.cuda_event)
-    h1 = None if stop_event is None else ctypes.c_void_p(stop_event.cuda_event)
-    _check(load_library().msa_profile_dominant_kernel(which, h0, h1), "msa_profile_dominant_kernel")
 
 
 def msa_fetch_selected(cfg, K_host, V_host, idx, B, M, K_stage=None, V_stage=None, idx_stage=None,

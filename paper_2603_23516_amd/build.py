@@ -15,8 +15,6 @@ LIBMSA_SRC = [os.path.join(HERE, "csrc", f) for f in
               ("msa_api.hip", "msa_build.hip", "msa_pool.hip", "msa_score.hip", "msa_score_gemm.hip", "msa_attend.hip", "msa_attend_prefill.hip", "msa_fetch.hip")]
 LIBSYNTH = os.path.join(ROOT, "msa_synth", "libmsa_synth.so")
 LIBSYNTH_SRC = [os.path.join(ROOT, "msa_synth", "csrc", "synth_fill.hip")]
-LIBPROBE = os.path.join(ROOT, "tests", "libmsa_probe.so")
-LIBPROBE_SRC = [os.path.join(ROOT, "tests", "csrc", "probe.hip")]
 
 
 def _run(cmd):
@@ -28,14 +26,12 @@ def _run(cmd):
 
 
 def build_all(verbose=False):
-    """Compile libmsa.so (the product), libmsa_synth.so (the input generator's device fill) and
-    the test-only probe library."""
+    """Compile libmsa.so (the product) and libmsa_synth.so (the input generator's device fill)."""
     out = _run([HIPCC] + COMMON + ["-I", os.path.join(ROOT, "include")] + LIBMSA_SRC + ["-o", LIBMSA])
     out += _run([HIPCC] + COMMON + LIBSYNTH_SRC + ["-o", LIBSYNTH])
-    out += _run([HIPCC] + COMMON + LIBPROBE_SRC + ["-o", LIBPROBE])
     if verbose and out.strip():
         print(out)
-    return [LIBMSA, LIBSYNTH, LIBPROBE]
+    return [LIBMSA, LIBSYNTH]
 
 
 if __name__ == "__main__":

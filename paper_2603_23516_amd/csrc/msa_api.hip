@@ -5,8 +5,6 @@
 
 namespace msa {
 
-ProfileEvents g_profile[2] = {{nullptr, nullptr}, {nullptr, nullptr}};
-
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 // Returns MSA_OK and fills dm, or the status that describes what is wrong with cfg.  The limits on
@@ -26,6 +24,7 @@ static int make_dims(const msa_config_t* cfg, Dims* dm, DimsFor use = kForRoutin
   if (cfg->token_pool != 0 && cfg->token_pool != 1) return MSA_ERR_INVALID_ARG;
   if (cfg->bank_keys_rotated != 0 && cfg->bank_keys_rotated != 1) return MSA_ERR_INVALID_ARG;
   if (!(cfg->rope_base > 1.0f)) return MSA_ERR_INVALID_ARG;
+  if ((cfg->profile_start_event == nullptr) != (cfg->profile_stop_event == nullptr)) return MSA_ERR_INVALID_ARG;
   if (cfg->head_dim != 64 && cfg->head_dim != 128) return MSA_ERR_UNSUPPORTED;
   const int C = cfg->doc_len / cfg->chunk;
   if (use != kForAttend && cfg->chunk % 8 != 0) return MSA_ERR_UNSUPPORTED;
@@ -47,6 +46,8 @@ static int make_dims(const msa_config_t* cfg, Dims* dm, DimsFor use = kForRoutin
   dm->token_pool = cfg->token_pool;
   dm->base = cfg->rope_base;
   dm->lens = cfg->doc_lens;
+  dm->prof_start = (hipEvent_t)cfg->profile_start_event;
+  dm->prof_stop = (hipEvent_t)cfg->profile_stop_event;
   dm->NC = (int64_t)dm->N * C;
   dm->tiles = (dm->NC + 15) / 16;
   return MSA_OK;
@@ -99,15 +100,7 @@ using namespace msa;
 
 extern "C" {
 
-int msa_version(void) { return 104; }
-
-int msa_profile_dominant_kernel(int32_t which, void* start_event, void* stop_event) {
-  if (which < 0 || which > 1) return MSA_ERR_INVALID_ARG;
-  if ((start_event == nullptr) != (stop_event == nullptr)) return MSA_ERR_INVALID_ARG;
-  msa::g_profile[which].start = (hipEvent_t)start_event;
-  msa::g_profile[which].stop = (hipEvent_t)stop_event;
-  return MSA_OK;
-}
+int msa_version(void) { return 105; }
 
 const char* msa_status_string(int status) {
   switch (status) {

@@ -721,7 +721,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     const int rc = launch_attend_prefill_partial(dm, pl, a, th, B, st, true);
     if (rc != MSA_OK) return rc;
   } else {
-    profile_mark(1, false, st);
+    profile_mark(dm, false, st);
     dim3 grid(a.n_splits, dm.Hkv, BM), block(256);
 #define MSA_LAUNCH_ATTEND(DD, MM) \
   hipLaunchKernelGGL((attend_partial_kernel<DD, MM>), grid, block, 0, st, a, th)
@@ -735,7 +735,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
       else MSA_LAUNCH_ATTEND(64, 2);
     }
 #undef MSA_LAUNCH_ATTEND
-    profile_mark(1, true, st);
+    profile_mark(dm, true, st);
   }
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   if (direct) return MSA_OK;

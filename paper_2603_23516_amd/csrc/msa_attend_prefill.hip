@@ -536,12 +536,12 @@ int launch_attend_prefill_partial(const Dims& dm, const AttendPlan& pl, const At
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
   dim3 grid(pl.n_splits, dm.Hkv, B * pl.n_ttiles), block(256);
-  if (dominant) profile_mark(1, false, st);
+  if (dominant) profile_mark(dm, false, st);
   if (dm.d == 128)
     hipLaunchKernelGGL(attend_prefill_kernel<128>, grid, block, 0, st, a, th, pl.tpw, pl.n_ttiles);
   else
     hipLaunchKernelGGL(attend_prefill_kernel<64>, grid, block, 0, st, a, th, pl.tpw, pl.n_ttiles);
-  if (dominant) profile_mark(1, true, st);
+  if (dominant) profile_mark(dm, true, st);
   return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
 }
 

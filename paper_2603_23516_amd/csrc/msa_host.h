@@ -16,6 +16,7 @@ struct Dims {
   int token_pool; // 1 = document score is the max over the M tokens of a batch row (literal Eq. 2)
   float base;
   const int32_t* lens;  // device [N] document lengths, or null (every document holds G tokens)
+  hipEvent_t prof_start, prof_stop;  // the caller's events around the dominant kernel of this call, or null
   int64_t NC;     // N * C routing keys per KV head
   int64_t tiles;  // ceil(NC / 16) tiles of 16 keys per KV head
 };
@@ -59,13 +60,9 @@ struct ScorePlan {
 };
 ScorePlan plan_score(const Dims& dm, int BM, int k);
 
-// events recorded around the dominant kernel of msa_score_topk (0) and msa_sparse_attend (1); null = off
-struct ProfileEvents {
-  hipEvent_t start, stop;
-};
-extern ProfileEvents g_profile[2];
-inline void profile_mark(int which, bool stop, hipStream_t st) {
-  hipEvent_t e = stop ? g_profile[which].stop : g_profile[which].start;
+// record the caller's per-call events (msa_config_t.profile_*_event) around the dominant kernel; null = off
+inline void profile_mark(const Dims& dm, bool stop, hipStream_t st) {
+  hipEvent_t e = stop ? dm.prof_stop : dm.prof_start;
   if (e != nullptr) (void)hipEventRecord(e, st);
 }
 

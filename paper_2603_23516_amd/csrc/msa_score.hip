@@ -1140,7 +1140,7 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
   }
   const int wpb = pl.all_heads ? kAllWaves : kScanWaves;
   dim3 grid((pl.n_splits + wpb - 1) / wpb, pl.all_heads ? 1 : dm.Hkv), block(64 * wpb);
-  profile_mark(0, false, st);
+  profile_mark(dm, false, st);
   for (int pass = 0; pass < pl.n_pass; ++pass) {
     a.q0 = pass * pl.q_per_pass;
     if (pl.all_heads) {
@@ -1181,7 +1181,7 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
 #undef MSA_SCAN
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
-  profile_mark(0, true, st);
+  profile_mark(dm, true, st);
   if (pl.mode == 2) {
     hipLaunchKernelGGL(topk_rows_kernel, dim3(BM * pl.n_sel), dim3(256), 0, st, (const float*)a.mat, out_idx,
                        out_score, tok_keys, BM, pl.n_sel, dm.N, k);

@@ -431,12 +431,12 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
   a.n_splits = pl.n_splits;
   a.stages_per_split = pl.stages_per_split;
   const unsigned blocks = (unsigned)(dm.Hkv * pl.n_qblocks * pl.n_splits);
-  profile_mark(0, false, st);
+  profile_mark(dm, false, st);
   if (dm.d == 128)
     hipLaunchKernelGGL(score_gemm_kernel<128>, dim3(blocks), dim3(256), 0, st, a);
   else
     hipLaunchKernelGGL(score_gemm_kernel<64>, dim3(blocks), dim3(256), 0, st, a);
-  profile_mark(0, true, st);
+  profile_mark(dm, true, st);
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   return MSA_OK;
 }

@@ -33,17 +33,24 @@ def test_exports_match_header(lib):
     assert declared == set(msa.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.msa_version() == 104
+    assert lib.msa_version() == 105
     for st in (0, -1, -2, -3, -4, -5, -99):
         assert len(msa.status_string(st)) > 0
 
 
-def test_profile_hook_validation(lib):
-    f = lib.msa_profile_dominant_kernel
-    assert f(0, None, None) == msa.MSA_OK and f(1, None, None) == msa.MSA_OK
-    assert f(2, None, None) == msa.MSA_ERR_INVALID_ARG and f(-1, None, None) == msa.MSA_ERR_INVALID_ARG
-    assert f(0, ctypes.c_void_p(16), None) == msa.MSA_ERR_INVALID_ARG     # one event without the other
-    assert f(0, None, ctypes.c_void_p(16)) == msa.MSA_ERR_INVALID_ARG
+def test_profile_events_are_per_call_config_fields(lib):
+    """The timing aid is a pair of fields of the per-call config (no library state): one event without the other is
+    refused by every entry point that reads the config, before anything is enqueued."""
+    p = ctypes.c_void_p(0x10000)
+    c = _cfg()
+    c.profile_start_event = 16
+    assert lib.msa_score_topk(ctypes.byref(c), p, 1, 1, p, p, 4, p, p, p, 1 << 30, None) == msa.MSA_ERR_INVALID_ARG
+    c.profile_start_event, c.profile_stop_event = None, 16
+    assert lib.msa_score_topk(ctypes.byref(c), p, 1, 1, p, p, 4, p, p, p, 1 << 30, None) == msa.MSA_ERR_INVALID_ARG
+    assert msa.score_topk_workspace_bytes(c, 1, 1, 4) == 0
+    c.profile_start_event = 32
+    assert msa.score_topk_workspace_bytes(c, 1, 1, 4) > 0          # a complete pair is a valid config
+    assert not hasattr(lib, "msa_profile_dominant_kernel") or "msa_profile_dominant_kernel" not in msa.EXPORTS
 
 
 def test_sizes_and_paper_estimate(lib):
@@ -238,3 +245,39 @@ def test_binding_refuses_cpu_tensors(lib):
     c = _cfg()
     with pytest.raises(ValueError):
         msa.msa_build_routing_keys(c, torch.zeros((64, 2, 512, 64), dtype=torch.bfloat16))
+
+
+def test_host_sanitizers_on_extreme_sizes():
+    """The C-ABI layer's host code (validation, work plans, workspace-size arithmetic) compiled with
+    AddressSanitizer + UndefinedBehaviorSanitizer + the integer sanitizer (host side only) and driven by
+    tests/csrc/boundary_sanitize.cpp with sizes at the limits: N*C just below 2^31 keys per head, B*M = 2^20,
+    k = 64, local contexts of 2^24 tokens.  No device is visible to the driver, so nothing can launch; a valid
+    request must come back as MSA_ERR_HIP from the launch stage with no sanitizer report on the way."""
+    import glob
+    import subprocess
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out_dir = os.path.join(ROOT, "tests", "_build")
+    os.makedirs(out_dir, exist_ok=True)
+    lib_san = os.path.join(out_dir, "libmsa_san.so")
+    exe = os.path.join(out_dir, "boundary_sanitize")
+    srcs = sorted(glob.glob(os.path.join(ROOT, "paper_2603_23516_amd", "csrc", "*.hip")))
+    deps = srcs + glob.glob(os.path.join(ROOT, "paper_2603_23516_amd", "csrc", "*.h")) + \
+        [os.path.join(ROOT, "include", "msa.h"), os.path.join(ROOT, "tests", "csrc", "boundary_sanitize.cpp")]
+    san = []
+    for f in ("-fsanitize=address", "-fsanitize=undefined", "-fsanitize=integer", "-fno-sanitize-recover=all"):
+        san += ["-Xarch_host", f]
+    newest = max(os.path.getmtime(f) for f in deps)
+    if not (os.path.exists(exe) and os.path.exists(lib_san) and
+            min(os.path.getmtime(exe), os.path.getmtime(lib_san)) >= newest):
+        common = [hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                  "-packed-fp32-ops", "-Wno-unused-command-line-argument"] + san + ["-I", os.path.join(ROOT, "include")]
+        r = subprocess.run(common + ["-fPIC", "-shared"] + srcs + ["-o", lib_san], stdout=subprocess.PIPE,
+                           stderr=subprocess.STDOUT, text=True, timeout=900)
+        assert r.returncode == 0, r.stdout[-3000:]
+        r = subprocess.run(common + [os.path.join(ROOT, "tests", "csrc", "boundary_sanitize.cpp"), "-L", out_dir,
+                                     "-lmsa_san", "-Wl,-rpath," + out_dir, "-o", exe], stdout=subprocess.PIPE,
+                           stderr=subprocess.STDOUT, text=True, timeout=300)
+        assert r.returncode == 0, r.stdout[-3000:]
+    env = dict(os.environ, HIP_VISIBLE_DEVICES="-1", ROCR_VISIBLE_DEVICES="", ASAN_OPTIONS="detect_leaks=0")
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300, env=env)
+    assert r.returncode == 0 and "boundary_sanitize: ok" in r.stdout, r.stdout[-3000:]

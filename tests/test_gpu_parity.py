@@ -89,7 +89,8 @@ class Case:
 # ------------------------------------------------------------------------------------------------
 @pytest.fixture(scope="module")
 def probe():
-    return ctypes.CDLL(os.path.join(HERE, "libmsa_probe.so"))
+    from probe_build import build_probe
+    return ctypes.CDLL(build_probe(force=False))
 
 
 def test_probe_mfma_layout(probe):
@@ -835,8 +836,9 @@ def test_fetch_selected_from_pooled_host_bank():
 
 
 def test_profile_events_bracket_the_dominant_kernels():
-    """The timing aid records the caller's events inside the entry points: the bracketed time is positive and not
-    longer than the whole call's, results do not change, and clearing it stops the recording."""
+    """The per-call timing aid (config fields) records the caller's events inside the entry points: the bracketed
+    time is positive and not longer than the whole call's, results do not change, and a config without events
+    leaves them alone."""
     seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k = CASES["d128_batch16"]
     case = Case(seed, N, Hkv, r, G, d, P, B, M, Lloc, base).to_device()
     cfg = case.cfg()
@@ -851,16 +853,14 @@ def test_profile_events_bracket_the_dominant_kernels():
     for e in ev:
         e.record(st)
     torch.cuda.synchronize()
-    msa.msa_profile_dominant_kernel(0, ev[3], ev[4])
-    msa.msa_profile_dominant_kernel(1, ev[5], ev[6])
+    cfg_s = case.cfg().set_profile_events(ev[3], ev[4])
+    cfg_a = case.cfg().set_profile_events(ev[5], ev[6])
     ev[0].record(st)
-    idx1, val1 = msa.msa_score_topk(cfg, case.dq, KR, inv, k)
+    idx1, val1 = msa.msa_score_topk(cfg_s, case.dq, KR, inv, k)
     ev[1].record(st)
-    out1, lse1 = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx1, case.dKl, case.dVl, pos0, dpos)
+    out1, lse1 = msa.msa_sparse_attend(cfg_a, case.dq, case.dK, case.dV, idx1, case.dKl, case.dVl, pos0, dpos)
     ev[2].record(st)
     torch.cuda.synchronize()
-    msa.msa_profile_dominant_kernel(0, None, None)
-    msa.msa_profile_dominant_kernel(1, None, None)
     assert torch.equal(idx1, idx0) and torch.equal(val1, val0)
     assert torch.equal(out1.view(torch.int16), out0.view(torch.int16)) and torch.equal(lse1, lse0)
     s_in, s_out = ev[3].elapsed_time(ev[4]), ev[0].elapsed_time(ev[1])
@@ -869,11 +869,106 @@ def test_profile_events_bracket_the_dominant_kernels():
     assert 0 < s_in <= s_out and 0 < a_in <= a_out
     # the score kernel's start lies inside the call: after the call's first event, before its last
     assert ev[0].elapsed_time(ev[3]) >= 0 and ev[4].elapsed_time(ev[1]) >= 0
-    # cleared: a later call leaves the events alone
+    # a call with a config that carries no events leaves them alone
     t_before = ev[3].elapsed_time(ev[4])
     msa.msa_score_topk(cfg, case.dq, KR, inv, k)
     torch.cuda.synchronize()
     assert ev[3].elapsed_time(ev[4]) == t_before
+
+
+def test_two_streams_profile_concurrently():
+    """Two callers on two streams, each with its own config and event pair, at the same time: every pair brackets
+    its own call (it lies between that stream's own events around the call), and the results are those of the
+    un-profiled calls.  There is no library state for them to share."""
+    say("case two streams profiling concurrently")
+    case = Case(82500, 3000, 2, 4, 64, 128, 16, 4, 1, 40, 1e6).to_device()
+    N, G, k, B, M, Lloc = 3000, 64, 9, 4, 1, 40
+    cfg = case.cfg()
+    KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+    qs = [case.dq, dev(S.normal_bf16(82501, (B, M, case.Hq, 128))[0])]
+    ref = [msa.msa_score_topk(cfg, q, KR, inv, k) for q in qs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(2)]
+    for st, e4 in zip(streams, evs):
+        for e in e4:
+            e.record(st)
+    torch.cuda.synchronize()
+    cfgs = [case.cfg().set_profile_events(e4[1], e4[2]) for e4 in evs]
+    outs = [(torch.empty_like(ref[0][0]), torch.empty_like(ref[0][1])) for _ in range(2)]
+    wss = [torch.empty(msa.score_topk_workspace_bytes(cfg, B, M, k), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    for rep in range(5):
+        for j in (0, 1):
+            evs[j][0].record(streams[j])
+            msa.msa_score_topk(cfgs[j], qs[j], KR, inv, k, outs[j][0], outs[j][1], wss[j], stream=streams[j])
+            evs[j][3].record(streams[j])
+        torch.cuda.synchronize()
+        for j in (0, 1):
+            assert torch.equal(outs[j][0], ref[j][0]) and torch.equal(outs[j][1], ref[j][1])
+            inner = evs[j][1].elapsed_time(evs[j][2])
+            assert inner > 0
+            assert evs[j][0].elapsed_time(evs[j][1]) >= 0 and evs[j][2].elapsed_time(evs[j][3]) >= 0
+            assert inner <= evs[j][0].elapsed_time(evs[j][3])
+    say("   5 concurrent rounds: every event pair lies inside its own call")
+
+
+GUARD = 4096
+
+
+def guarded(shape, dtype):
+    """A tensor whose storage sits between two guard bands of GUARD bytes filled with 0xA5: (tensor, check)."""
+    n = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+    pad = (-n) % 256
+    raw = torch.full((GUARD + n + pad + GUARD,), 0xA5, dtype=torch.uint8, device="cuda")
+    t = raw[GUARD:GUARD + n].view(dtype).reshape(shape)
+
+    def check(what):
+        assert bool((raw[:GUARD] == 0xA5).all()), f"{what}: bytes before the buffer were written"
+        assert bool((raw[GUARD + n:] == 0xA5).all()), f"{what}: bytes after the buffer were written"
+    return t, check
+
+
+@pytest.mark.parametrize("name", ["d128_ragged", "batch40_c4", "prefill100_gemm"])
+def test_guard_bands_around_outputs_and_workspaces(name):
+    """Every output and both workspaces sit between guard bands; after each call the bands are intact (nothing is
+    written outside what the size helpers and the header promise) and the results equal the un-guarded run's."""
+    seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k = CASES[name]
+    say(f"guard bands, case {name}")
+    case = Case(seed, N, Hkv, r, G, d, P, B, M, Lloc, base).to_device()
+    cfg = case.cfg()
+    pos0 = G
+    dpos = torch.full((B, M), pos0 + max(Lloc, 1) - 1, dtype=torch.int32, device="cuda")
+    KR0, inv0 = msa.msa_build_routing_keys(cfg, case.dK)
+    idx0, val0 = msa.msa_score_topk(cfg, case.dq, KR0, inv0, k)
+    out0, lse0 = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx0, case.dKl, case.dVl, pos0, dpos)
+    Kb0, Vb0 = msa.msa_pool_kv(cfg, case.dK, case.dV)
+    torch.cuda.synchronize()
+    KR, c_kr = guarded(tuple(KR0.shape), torch.bfloat16)
+    inv, c_inv = guarded(tuple(inv0.shape), torch.float32)
+    msa.msa_build_routing_keys(cfg, case.dK, KR=KR, inv_norm=inv)
+    torch.cuda.synchronize()
+    c_kr("KR"), c_inv("inv_norm")
+    assert torch.equal(KR.view(torch.int16), KR0.view(torch.int16)) and torch.equal(inv, inv0)
+    idx, c_idx = guarded(tuple(idx0.shape), torch.int32)
+    val, c_val = guarded(tuple(val0.shape), torch.float32)
+    ws_s, c_ws = guarded((msa.score_topk_workspace_bytes(cfg, B, M, k),), torch.uint8)
+    msa.msa_score_topk(cfg, case.dq, KR, inv, k, idx, val, ws_s)
+    torch.cuda.synchronize()
+    c_idx("out_idx"), c_val("out_score"), c_ws("score workspace")
+    assert torch.equal(idx, idx0) and torch.equal(val, val0)
+    out, c_out = guarded(tuple(out0.shape), torch.bfloat16)
+    lse, c_lse = guarded(tuple(lse0.shape), torch.float32)
+    ws_a, c_wa = guarded((msa.sparse_attend_workspace_bytes(cfg, B, M, k, Lloc),), torch.uint8)
+    msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, idx, case.dKl, case.dVl, pos0, dpos, out, lse, ws_a)
+    torch.cuda.synchronize()
+    c_out("out"), c_lse("lse"), c_wa("attend workspace")
+    assert torch.equal(out.view(torch.int16), out0.view(torch.int16)) and torch.equal(lse, lse0)
+    Kb, c_kb = guarded(tuple(Kb0.shape), torch.bfloat16)
+    Vb, c_vb = guarded(tuple(Vb0.shape), torch.bfloat16)
+    msa.msa_pool_kv(cfg, case.dK, case.dV, Kbar=Kb, Vbar=Vb)
+    torch.cuda.synchronize()
+    c_kb("Kbar"), c_vb("Vbar")
+    assert torch.equal(Kb.view(torch.int16), Kb0.view(torch.int16)) and torch.equal(Vb.view(torch.int16), Vb0.view(torch.int16))
 
 
 def test_all_scores_equal_more_than_on_chip_survivors():

@@ -284,3 +284,38 @@ def test_ragged_fetch_from_host_bank():
     assert torch.equal(out_t.view(torch.int16), out_d.view(torch.int16)) and torch.equal(lse_t, lse_d)
     oo, ol = O.sparse_attend(case.q, case.K, case.V, sel, case.Kl, case.Vl, pos0, q_pos, base, lens=lens)
     attend_err(out_t, lse_t, oo, ol)
+
+
+def test_length_zero_is_clamped_to_one_token():
+    """The library has no empty documents: doc_lens values are clamped to [1, G] (a document holds at least one
+    token), so an entry of 0 (or below, or above G) behaves exactly like 1 (or G) in every stage.  The oracle's
+    lens = 0 (a document that never scores and contributes no rows) has no library counterpart; this pins the
+    documented behaviour instead."""
+    say("case doc_lens with 0, negative and too large entries: clamped to [1, G]")
+    seed, N, Hkv, r, G, d, P, B, M, Lloc, base, k = 69000, 40, 2, 4, 128, 64, 32, 2, 1, 20, 1e4, 6
+    case = Case(seed, N, Hkv, r, G, d, P, B, M, Lloc, base).to_device()
+    lens = make_lens(seed + 9, N, G, P)
+    raw = lens.copy()
+    raw[[3, 11]] = 0
+    raw[17] = -5
+    raw[23] = G + 1000
+    clamped = np.clip(raw, 1, G)
+    res = []
+    for l in (raw, clamped):
+        dl = torch.from_numpy(l.astype(np.int32)).cuda()
+        cfg = case.cfg(doc_lens=dl)
+        KR, inv = msa.msa_build_routing_keys(cfg, case.dK)
+        idx, val = msa.msa_score_topk(cfg, case.dq, KR, inv, k)
+        sel = idx.clone()
+        sel[0, 0, 0, :4] = torch.tensor([3, 11, 17, 23], dtype=torch.int32)     # attend the clamped documents
+        dpos = torch.full((B, M), G + Lloc - 1, dtype=torch.int32, device="cuda")
+        out, lse = msa.msa_sparse_attend(cfg, case.dq, case.dK, case.dV, sel, case.dKl, case.dVl, G, dpos)
+        Kbar, Vbar, plens = msa.msa_pool_kv(cfg, case.dK, case.dV)
+        torch.cuda.synchronize()
+        res.append((KR, inv, idx, val, out.view(torch.int16), lse, Kbar.view(torch.int16), Vbar.view(torch.int16), plens))
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+    # and the clamped reading is the oracle's reading of those lengths
+    oo, ol = O.sparse_attend(case.q, case.K, case.V, sel.cpu().numpy().astype(np.int64), case.Kl, case.Vl, G,
+                             np.full((B, M), G + Lloc - 1), base, lens=clamped)
+    attend_err(out, lse, oo, ol)

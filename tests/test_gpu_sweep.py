@@ -3,7 +3,6 @@ k, local context, similarity, selection scope, token pooling and document length
 the documented limits, and every draw runs the whole chain (index build, score + top-k, attention) against
 the float64 oracle with the tolerances of test_gpu_parity.py.  The draws are fixed by the seed, so a failure
 names its case."""
-import os
 
 import numpy as np
 import pytest
@@ -16,9 +15,7 @@ from test_gpu_ragged import attend_err, make_lens
 
 pytestmark = pytest.mark.gpu
 
-# 96 draws by default; MSA_SWEEP_FIRST / MSA_SWEEP_DRAWS select another range of the same seeded sequence
-FIRST_DRAW = int(os.environ.get("MSA_SWEEP_FIRST", "0"))
-N_DRAWS = int(os.environ.get("MSA_SWEEP_DRAWS", "96"))
+FIRST_DRAW, N_DRAWS = 0, 96
 
 
 def draw(i):
