@@ -28,11 +28,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-# HBM traffic per msa_score_topk call (bytes) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
-# scaled by the same counter's reading for a plain copy of known size (FETCH_SIZE reads 0.5 KiB per KiB
-# copied -> x2; WRITE_SIZE reads 1.0 -> x1); see profiles/pmc_traffic_cfg5_decode_50m.txt.
-MEASURED_SCORE_TRAFFIC = {"cfg5_decode_50m": 1660.7e6,   # prep + scan + merge, read + write
-                          "cfg3_batch32_4m": 155.2e6}    # prep + scan (score matrix) + row top-k; profiles/pmc_traffic_cfg3_batch32_4m.txt
+# HBM traffic per entry-point call (bytes, read + write, all kernels of the call) from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this file, each counter scaled by its reading for a plain copy of known size; the summaries, with
+# the kernel signatures and the commit they were measured at, are profiles/pmc_traffic_<workload>.txt.  Only with the
+# default flags (un-pooled bank, per-group selection); None where no such run exists.
+MEASURED_TRAFFIC = {}
 
 
 def parse():
@@ -70,19 +70,31 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture the step once into a HIP graph and time replays (the per-stage times still come "
                          "from an eager pass with HIP events); pays off where the step is launch-bound (config 2)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="additionally time the per-token loop over this many routed layers (the paper's model routes in "
+                         "18, Section 3.2.1 / 3.4.2): per layer its own routing index and pooled content bank (needs "
+                         "--bank pooled; with --tier host the pooled banks live in pinned host memory), score -> (fetch) "
+                         "-> attention in every layer, routing of layer l + 1 overlapped with fetch + attention of layer "
+                         "l on a second stream; reported in \"layers\", never in value (it runs after the one-layer "
+                         "step, whose bank is freed first: one layer's K or V at a time is staged to build the banks)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-docs", type=int, default=1024)
     return ap.parse_args()
 
 
-def cpu_baseline(wl, sample_docs):
-    """Time the oracle, as it stands, on a bounded sample of the workload:
-      routing  : all B*M queries over the first `sample_docs` documents (regenerated on the host),
-                 scaled linearly to N documents -- the scan is O(N) (paper, Section 5.1);
-      attention: one query, one KV group (its r heads) over its k selected documents + the local
-                 context, scaled by Hkv -- independent of N."""
+def cpu_baseline(wl, cfg, KR, sample_docs):
+    """Time the oracle, as it stands, on a bounded sample of the workload (10-30 s of CPU work):
+      routing  : Eq. 2, document max and top-k over ALL N documents of the routing index, one KV head at a time, for
+                 every query of a decode batch (prefill: 64 evenly spaced query tokens).  The index values are the
+                 GPU-built index copied back -- input data for the timing, nothing is compared here;
+      attention: one query, all its KV groups, over its k selected documents (regenerated on the host) + the
+                 local context;
+      pooling  : `sample_docs` documents through the oracle's chunk pooling (offline stage, not in value).
+    value = 1 / (routing seconds per query + attention seconds per query)."""
     import numpy as np
     import msa_synth as S
+    import paper_2603_23516_amd as msa
+    from msa_synth import device as SD
     from msa_synth import workloads as W
     from oracle import msa_oracle as O
     try:
@@ -90,35 +102,45 @@ def cpu_baseline(wl, sample_docs):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count()
+    bits = SD.torch_to_bits(msa.untile_routing_keys(cfg, KR))          # [Hkv, N*C, d]
+    nq = wl.B * wl.M
+    q_all = wl.q_host.reshape(nq, 1, wl.Hq, wl.d)
+    sel_q = np.arange(nq) if wl.M == 1 else np.linspace(0, nq - 1, 64).astype(np.int64)
+    q = q_all[sel_q]
+    t_route = 0.0
+    idx = None
+    for g in range(wl.Hkv):
+        KRb = S.bf16_bits_to_f64(bits[g])[None]
+        t0 = time.perf_counter()
+        oi, _, _ = O.score_topk(q[:, :, g * wl.r:(g + 1) * wl.r], KRb, wl.C, wl.k)
+        t_route += time.perf_counter() - t0
+        idx = oi if idx is None else np.concatenate([idx, oi], axis=2)
+        del KRb
     n_s = min(sample_docs, wl.N)
     Ks = np.stack([W.host_doc(wl, "K", i)[1] for i in range(n_s)])
-    q = wl.q_host
     t0 = time.perf_counter()
-    KRb, _ = O.routing_keys(Ks, wl.P)
+    O.routing_keys(Ks, wl.P)
     t_build = time.perf_counter() - t0
-    kk = min(wl.k, n_s)
-    reps = 10
+    del Ks
+    sel = idx[0, 0]                                                     # [Hkv, k]: the first query's documents
+    docs = sorted(set(sel.reshape(-1).tolist()))
+    pos = {dd: i for i, dd in enumerate(docs)}
+    K_sel = np.stack([W.host_doc(wl, "K", int(i))[1] for i in docs])    # [n, Hkv, G, d]
+    V_sel = np.stack([W.host_doc(wl, "V", int(i))[1] for i in docs])
+    local = np.array([[[pos[int(dd)] for dd in sel[g]] for g in range(wl.Hkv)]])[None]      # [1, 1, Hkv, k]
+    Kl = S.normal_bf16(wl.seeds["Kloc"], (1, wl.Hkv, wl.Lloc, wl.d))[1] if wl.Lloc else None
+    Vl = S.normal_bf16(wl.seeds["Vloc"], (1, wl.Hkv, wl.Lloc, wl.d))[1] if wl.Lloc else None
+    b0, m0 = divmod(int(sel_q[0]), wl.M)
     t0 = time.perf_counter()
-    for _ in range(reps):
-        idx, val, _ = O.score_topk(q, KRb, wl.C, kk)
-    t_score = (time.perf_counter() - t0) / reps
-    sel = idx[0, 0, 0]
-    K_sel = Ks[sel][:, :1]
-    V_sel = np.stack([W.host_doc(wl, "V", int(i))[1][:1] for i in sel])
-    Kl = S.normal_bf16(wl.seeds["Kloc"], (1, 1, wl.Lloc, wl.d))[1] if wl.Lloc else None
-    Vl = S.normal_bf16(wl.seeds["Vloc"], (1, 1, wl.Lloc, wl.d))[1] if wl.Lloc else None
-    t0 = time.perf_counter()
-    O.sparse_attend(q[:1, :1, :wl.r], K_sel, V_sel, np.arange(kk)[None, None, None], Kl, Vl, wl.pos0,
-                    wl.q_pos_host[:1, :1], wl.base)
+    O.sparse_attend(q[:1], K_sel, V_sel, local, Kl, Vl, wl.pos0, wl.q_pos_host[b0:b0 + 1, m0:m0 + 1], wl.base)
     t_att = time.perf_counter() - t0
-    nq = wl.B * wl.M
-    per_query = t_score * (wl.N / n_s) / nq + t_att * wl.Hkv * (wl.k / kk)
+    per_query = t_route / len(sel_q) + t_att
     return {
         "value": 1.0 / per_query, "unit": "queries/s", "cores": int(threads), "kind": "oracle",
-        "sample": (f"float64 NumPy oracle, {os.cpu_count()} host cpus visible: routing of {nq} queries over "
-                   f"{n_s} of {wl.N} documents {t_score:.3f}s (scaled x{wl.N / n_s:.1f}: extrapolated); attention "
-                   f"of 1 query, 1 of {wl.Hkv} KV groups over {kk} documents + {wl.Lloc} local tokens "
-                   f"{t_att:.3f}s (scaled x{wl.Hkv}); pooling {n_s} documents {t_build:.3f}s (offline, not in value)"),
+        "sample": (f"float64 NumPy oracle, {os.cpu_count()} host cpus visible: routing (Eq. 2, document max, top-k) of "
+                   f"{len(sel_q)} of {nq} queries over all {wl.N} documents of the routing index {t_route:.2f}s; "
+                   f"attention of 1 query (all {wl.Hkv} KV groups, {wl.k} documents each + {wl.Lloc} local tokens) "
+                   f"{t_att:.2f}s; pooling {n_s} documents {t_build:.2f}s (offline, not in value)"),
     }
 
 
@@ -193,6 +215,71 @@ def host_tier(msa, wl, cfg, acfg, bank_K, bank_V, pos0, q_pos, KR, inv, idx, val
                     "fetch with the other's scoring on a second stream"}
 
 
+def layer_loop(args, msa, wl, cfg):
+    """The routed layers of the tiered engine (Section 3.4.2; routing in the latter half of the layers, Section
+    3.2.1): n_layers routing indices in HBM, n_layers pooled banks K-bar / V-bar in HBM or pinned host memory, and per
+    token batch score -> (fetch) -> attention in every layer."""
+    import torch
+    import msa_synth as S
+    from msa_synth import device as SD
+    from paper_2603_23516_amd.layers import LayerStack
+    L, B, M, k = args.layers, wl.B, wl.M, wl.k
+    t0 = time.perf_counter()
+    stack = LayerStack(cfg, L, B, M, k, wl.Lloc, tier=args.tier)
+    buf = torch.empty(wl.shape_bank, dtype=torch.bfloat16, device="cuda")      # one layer's K, then its V
+    qs, Klocs, Vlocs = [], [], []
+    for l in range(L):
+        sd = {t: S.seed_for(wl.cfg_id, 100 + 5 * l + i) for i, t in enumerate(("K", "V", "q", "Kloc", "Vloc"))}
+        SD.fill_normal_(buf, sd["K"])
+        stack.set_layer_keys(l, buf)
+        SD.fill_normal_(buf, sd["V"])
+        stack.set_layer_values(l, buf)
+        qs.append(SD.bits_to_torch(S.normal_bf16(sd["q"], (B, M, wl.Hq, wl.d))[0], "cuda"))
+        kl = torch.empty((B, wl.Hkv, wl.Lloc, wl.d), dtype=torch.bfloat16, device="cuda")
+        vl = torch.empty_like(kl)
+        SD.fill_normal_(kl, sd["Kloc"])
+        SD.fill_normal_(vl, sd["Vloc"])
+        Klocs.append(kl)
+        Vlocs.append(vl)
+    torch.cuda.synchronize()
+    del buf
+    torch.cuda.empty_cache()
+    setup_s = time.perf_counter() - t0
+    pos0 = k                                                        # Section 3.2.2: local positions start at k
+    q_pos = (wl.q_pos - wl.pos0 + pos0).contiguous()
+    outs = [torch.empty_like(qs[0]) for _ in range(L)]
+    lses = [torch.empty((B, M, wl.Hq), dtype=torch.float32, device="cuda") for _ in range(L)]
+
+    def timed(overlap):
+        for _ in range(max(2, args.warmup // 4)):
+            stack.step(qs, Klocs, Vlocs, pos0, q_pos, outs, lses, overlap=overlap)
+        torch.cuda.synchronize()
+        n = max(5, args.steps // 4)
+        t0 = time.perf_counter()
+        for _ in range(n):
+            stack.step(qs, Klocs, Vlocs, pos0, q_pos, outs, lses, overlap=overlap)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n, n
+    serial_ms, n = timed(False)
+    ref = [o.clone() for o in outs]
+    overlap_ms, _ = timed(True)
+    same = all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(ref, outs))
+    index_bytes, bank_bytes = stack.bytes()
+    nq = B * M
+    return {"n_layers": L, "tier": args.tier, "routing_index_bytes": index_bytes, "pooled_bank_bytes": bank_bytes,
+            "pooled_bank_in": "pinned host memory" if args.tier == "host" else "HBM",
+            "distinct_pooled_banks": stack.n_banks,
+            "memory_tokens_per_layer": wl.N * wl.G, "batch": nq, "timed_steps": n,
+            "ms_per_token_batch_one_stream": serial_ms, "ms_per_token_batch_overlapped": overlap_ms,
+            "ms_per_layer_overlapped": overlap_ms / L,
+            "token_batches_per_s": 1e3 / overlap_ms, "tokens_per_s": nq * 1e3 / overlap_ms,
+            "overlap_gain": 1.0 - overlap_ms / serial_ms, "overlapped_equals_serial_bitwise": bool(same),
+            "setup_s": setup_s,
+            "note": "score+top-k -> (fetch) -> attention over the pooled bank + local context in every routed layer; "
+                    "routing of layer l+1 runs on a second stream while layer l is fetched and attended; the other "
+                    "layers of the model (local attention only) and its projections are outside this path"}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -206,6 +293,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     msa.load_library()
     torch.cuda.set_device(0)
+    if args.layers > 0:
+        assert args.bank == "pooled" and not args.ragged, "--layers runs over the pooled bank (add --bank pooled)"
     wl = W.make(args.workload, Lloc=args.local_tokens)
     scope = msa.MSA_SCOPE_ALL if args.scope == "all" else msa.MSA_SCOPE_GROUP
     n_sel = 1 if args.scope == "all" else wl.Hkv
@@ -370,16 +459,24 @@ def main():
     attend_gbs = ab["attend"] / (attend_ms * 1e-3) / 1e9
     build_gbs = ab["build"] / (build_ms * 1e-3) / 1e9
 
-    flops = None
-    if nq >= 64 and k <= 8 and args.scope == "group":      # the MFMA GEMM path: flops issued = 2 * tokens * keys * (hi + lo) * d per head
+    # the MFMA GEMM path (many query tokens).  Algorithmic flops: the folded form of Eq. 2, one routing query per (token,
+    # KV group): 2 * tokens * Hkv * keys * d.  Issued: twice that, the query travels as a bf16 (hi, lo) pair
+    flops = flops_issued = None
+    if nq >= 64 and args.scope == "group":
         tiles = (wl.N * wl.C + 15) // 16
-        flops = 2.0 * nq * wl.Hkv * tiles * 16 * 2 * wl.d
-    # shared selection and many tokens: attention is a dense contraction on the matrix cores.  Flops issued: two
-    # products (QK, PV) of 2 flops per multiply-add, each doubled by the bf16 (hi, lo) pairs of Q and P
-    att_flops = None
+        flops = 2.0 * nq * wl.Hkv * wl.N * wl.C * wl.d
+        flops_issued = 2.0 * nq * wl.Hkv * tiles * 16 * 2 * wl.d
+    # shared selection and many tokens: attention is a dense contraction on the matrix cores.  Algorithmic flops: two
+    # products (QK, PV) of 2 flops per multiply-add over the keys each token sees; issued: twice that (bf16 (hi, lo) pairs
+    # of Q and P)
+    att_flops = att_flops_issued = None
     if args.token_pool and M >= 8 and args.bank == "full":
         keys = M * k * wl.G + M * (M + 1) // 2           # memory rows + causal local rows, summed over the tokens
-        att_flops = 8.0 * B * wl.Hq * keys * wl.d
+        att_flops = 4.0 * B * wl.Hq * keys * wl.d
+        att_flops_issued = 2 * att_flops
+    default_flags = (args.bank == "full" and args.scope == "group" and not args.token_pool and not args.ragged and
+                     args.local_tokens is None)
+    TRAFFIC = MEASURED_TRAFFIC.get(wl.name, {}) if default_flags else {}
     res = {
         "metric": "routed decode queries/sec (score+top-k then sparse attend, one MSA layer)",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -390,28 +487,37 @@ def main():
                    "chunk": wl.P, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.d, "batch": B,
                    "query_tokens": M, "top_k": k, "local_tokens": wl.Lloc, "rope_base": wl.base},
         "roofline": ({"bound": "hbm", "kernel": "score_scan_kernel (inside msa_score_topk = prep + scan + merge)",
-                      "entry_point_ms": score_call_ms,
                       "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                      "frac": score_gbs / HBM_PEAK_GBS, "traffic": MEASURED_SCORE_TRAFFIC.get(wl.name),
+                      "frac": score_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC.get("score"),
                       "algorithmic_bytes_per_launch": ab["score"], "avg_ms": score_ms,
-                      "median_ms": score_all[args.steps // 2], "min_ms": score_all[0]} if flops is None else
-                     {"bound": "mfma", "kernel": "score_gemm_kernel (inside msa_score_topk = fold + GEMM + merge)",
+                      "median_ms": score_all[args.steps // 2], "min_ms": score_all[0],
                       "entry_point_ms": score_call_ms,
+                      "entry_point_frac": ab["score"] / (score_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS} if flops is None else
+                     {"bound": "mfma", "kernel": "score_gemm_kernel (inside msa_score_topk = fold + GEMM + merge)",
                       "achieved": flops / (score_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                       "unit": "TFLOP/s", "frac": flops / (score_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                      "traffic": None, "flops_issued_per_launch": flops, "avg_ms": score_ms,
-                      "median_ms": score_all[args.steps // 2], "min_ms": score_all[0]}),
+                      "traffic": TRAFFIC.get("score"),
+                      "algorithmic_flops_per_launch": flops, "flops_issued_per_launch": flops_issued,
+                      "frac_issued": flops_issued / (score_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                      "avg_ms": score_ms, "median_ms": score_all[args.steps // 2], "min_ms": score_all[0],
+                      "entry_point_ms": score_call_ms,
+                      "entry_point_frac": flops / (score_call_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}),
         "attend": ({"bound": "hbm", "kernel": "attend_partial_kernel (inside msa_sparse_attend)",
-                    "entry_point_ms": attend_call_ms, "achieved": attend_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": attend_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": ab["attend"],
-                    "avg_ms": attend_ms, "median_ms": attend_all[args.steps // 2], "min_ms": attend_all[0]}
+                    "achieved": attend_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": attend_gbs / HBM_PEAK_GBS, "traffic": TRAFFIC.get("attend"),
+                    "algorithmic_bytes_per_launch": ab["attend"],
+                    "avg_ms": attend_ms, "median_ms": attend_all[args.steps // 2], "min_ms": attend_all[0],
+                    "entry_point_ms": attend_call_ms,
+                    "entry_point_frac": ab["attend"] / (attend_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
                    if att_flops is None else
                    {"bound": "mfma", "kernel": "attend_prefill_kernel (shared selection)",
-                    "entry_point_ms": attend_call_ms,
                     "achieved": att_flops / (attend_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": att_flops / (attend_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                    "flops_issued_per_launch": att_flops, "avg_ms": attend_ms,
-                    "median_ms": attend_all[args.steps // 2], "min_ms": attend_all[0]}),
+                    "algorithmic_flops_per_launch": att_flops, "flops_issued_per_launch": att_flops_issued,
+                    "frac_issued": att_flops_issued / (attend_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "avg_ms": attend_ms, "median_ms": attend_all[args.steps // 2], "min_ms": attend_all[0],
+                    "entry_point_ms": attend_call_ms,
+                    "entry_point_frac": att_flops / (attend_call_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}),
         "build": {"bound": "hbm", "achieved": build_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                   "frac": build_gbs / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": ab["build"],
                   "ms": build_ms, "note": "offline Stage 1, once per bank version; outside the timed steps"},
@@ -455,7 +561,13 @@ def main():
                        "algorithmic_bytes_per_launch": ab["pool"], "ms": pool_ms,
                        "note": "msa_pool_kv, offline Stage 1; outside the timed steps"}
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_docs)
+        res["cpu_baseline"] = cpu_baseline(wl, cfg, KR, args.cpu_sample_docs)
+    if args.layers > 0:
+        # free the one-layer bank (2 x 95 GiB at config 5) before the per-layer banks are built
+        bank_K = bank_V = KR = inv = ws_s = ws_a = idx = val = out = lse = None
+        wl.K = wl.V = None
+        torch.cuda.empty_cache()
+        res["layers"] = layer_loop(args, msa, wl, cfg)
     print(json.dumps(res))
 
 

@@ -41,10 +41,11 @@ def planted_chunk(q_b, r, g, noise, a):
     return S.f64_to_bf16_bits(a * u[None, :] + noise)
 
 
-def make(name, device="cuda", plant_per_query=0, plant_a=0.12, plant_chunk=3, Lloc=None):
+def make(name, device="cuda", plant_per_query=0, plant_a=0.12, plant_chunk=3, Lloc=None, alloc_bank=True):
     """Allocate and fill the workload `name` on the device.  Returns a Workload with the shapes,
     device tensors (K, V, q, Kloc, Vloc, q_pos) and, if plant_per_query > 0, the planted documents
-    (wl.planted[(b, j)] = doc id; their K slices are in wl.planted_K[doc] as bits [Hkv, G, d])."""
+    (wl.planted[(b, j)] = doc id; their K slices are in wl.planted_K[doc] as bits [Hkv, G, d]).
+    alloc_bank=False leaves out the K / V bank (wl.K = wl.V = None) for callers that fill their own buffers."""
     p = WORKLOADS[name]
     wl = Workload()
     wl.name = name
@@ -59,10 +60,15 @@ def make(name, device="cuda", plant_per_query=0, plant_a=0.12, plant_chunk=3, Ll
     seeds = {t: S.seed_for(wl.cfg_id, i) for i, t in enumerate(("K", "V", "q", "Kloc", "Vloc"))}
     wl.seeds = seeds
     shape_bank = (wl.N, wl.Hkv, wl.G, wl.d)
-    wl.K = torch.empty(shape_bank, dtype=torch.bfloat16, device=device)
-    wl.V = torch.empty(shape_bank, dtype=torch.bfloat16, device=device)
-    SD.fill_normal_(wl.K, seeds["K"])
-    SD.fill_normal_(wl.V, seeds["V"])
+    wl.shape_bank = shape_bank
+    wl.K = wl.V = None
+    if alloc_bank:
+        wl.K = torch.empty(shape_bank, dtype=torch.bfloat16, device=device)
+        wl.V = torch.empty(shape_bank, dtype=torch.bfloat16, device=device)
+        SD.fill_normal_(wl.K, seeds["K"])
+        SD.fill_normal_(wl.V, seeds["V"])
+    else:
+        assert plant_per_query == 0
     wl.q_bits, wl.q_host = S.normal_bf16(seeds["q"], (wl.B, wl.M, wl.Hq, wl.d))
     wl.q = SD.bits_to_torch(wl.q_bits, device)
     if wl.Lloc > 0:

@@ -205,22 +205,32 @@ def msa_build_routing_keys(cfg, K, doc_begin=0, doc_count=None, KR=None, inv_nor
 
 def msa_pool_kv(cfg, K, V, doc_begin=0, doc_count=None, Kbar=None, Vbar=None, pooled_lens=None, stream=None):
     """K, V bf16 [N][Hkv][G][d] -> pooled bank (Kbar, Vbar) bf16 [N][Hkv][C][d]; Kbar is the chunk mean of the
-    position-encoded keys.  Read it with a config whose doc_len = C and bank_keys_rotated = 1.  When cfg carries
-    doc_lens the result is (Kbar, Vbar, pooled_lens int32 [N]), pooled_lens being the pooled bank's doc_lens."""
-    _need(K, torch.bfloat16, "K")
-    _need(V, torch.bfloat16, "V")
+    position-encoded keys.  Read it with a config whose doc_len = C and bank_keys_rotated = 1.  K or V may be None:
+    that half is skipped and comes back as None.  When cfg carries doc_lens the result is (Kbar, Vbar, pooled_lens
+    int32 [N]), pooled_lens being the pooled bank's doc_lens."""
+    if K is None and V is None:
+        raise ValueError("msa_pool_kv: K and V are both None")
+    src = K if K is not None else V
+    if K is not None:
+        _need(K, torch.bfloat16, "K")
+    if V is not None:
+        _need(V, torch.bfloat16, "V")
     if doc_count is None:
         doc_count = cfg.n_docs - doc_begin
     shape = (cfg.n_docs, cfg.n_kv_heads, cfg.chunks_per_doc, cfg.head_dim)
-    if Kbar is None:
-        Kbar = torch.empty(shape, dtype=torch.bfloat16, device=K.device)
-    if Vbar is None:
-        Vbar = torch.empty(shape, dtype=torch.bfloat16, device=K.device)
+    if Kbar is None and K is not None:
+        Kbar = torch.empty(shape, dtype=torch.bfloat16, device=src.device)
+    if Vbar is None and V is not None:
+        Vbar = torch.empty(shape, dtype=torch.bfloat16, device=src.device)
+    if K is None:
+        Kbar = None
+    if V is None:
+        Vbar = None
     ragged = cfg.doc_lens_tensor is not None
     if ragged and pooled_lens is None:
-        pooled_lens = torch.empty(cfg.n_docs, dtype=torch.int32, device=K.device)
+        pooled_lens = torch.empty(cfg.n_docs, dtype=torch.int32, device=src.device)
     rc = load_library().msa_pool_kv(ctypes.byref(cfg), _ptr(K), _ptr(V), doc_begin, doc_count, _ptr(Kbar),
-                                    _ptr(Vbar), _ptr(pooled_lens), _stream(stream, K.device))
+                                    _ptr(Vbar), _ptr(pooled_lens), _stream(stream, src.device))
     _check(rc, "msa_pool_kv")
     return (Kbar, Vbar, pooled_lens) if ragged else (Kbar, Vbar)
 

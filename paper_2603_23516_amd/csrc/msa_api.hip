@@ -1,11 +1,23 @@
 // C-ABI layer: argument validation (host only, before anything is enqueued), work plans, launches.
 #include "msa_host.h"
 
+#include <chrono>
 #include <mutex>
 
 namespace msa {
 
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// (the mixer multiplies modulo 2^64 on purpose)
+__attribute__((no_sanitize("unsigned-integer-overflow"))) unsigned long long launch_nonce48() {
+  unsigned long long z = (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count();
+  z += 0x9E3779B97F4A7C15ull;  // splitmix64 finaliser
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  z &= 0xFFFFFFFFFFFFull;
+  return z ? z : 1ull;
+}
 
 // Returns MSA_OK and fills dm, or the status that describes what is wrong with cfg.  The limits on
 // the chunking belong to those who read it: routing needs whole 16-byte pieces per chunk and a

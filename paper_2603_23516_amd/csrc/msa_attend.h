@@ -36,6 +36,10 @@ struct AttendArgs {
   int steps_mem, steps_total, steps_per_split, n_splits;
   int ph_splits, split0;  // partial slots per (query, head) in the workspace, and this launch's first slot
   float qscale;          // log2(e) / sqrt(d)
+  unsigned long long* tickets;  // decode kernel: arrival counters [BM][Hkv], or null = a separate merge launch
+  unsigned long long nonce;     // this launch's tag of the counters (48 bits, non-zero)
+  uint16_t* final_out;          // with tickets: the merged output [BM][Hq][D] and (or null) log-sum-exp
+  float* final_lse;
 };
 
 // Shared-selection prefill: unnormalised partials of every (token, head, split) in the layout the

@@ -519,9 +519,89 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       }
     }
     const long long ph = ((long long)bm * a.Hq + g * a.r + hh) * a.ph_splits + a.split0 + sp;
-    a.part_o[ph * D + dd] = osum;
-    if (dd == 0) a.part_ml[ph] = make_float2(mx, lsum);
+    // device-scope stores: the merging workgroup may run on another XCD
+    store_dev(&a.part_o[ph * D + dd], osum);
+    if (dd == 0) {
+      const float2 mlv = make_float2(mx, lsum);
+      store_dev(reinterpret_cast<unsigned long long*>(a.part_ml + ph), __builtin_bit_cast(unsigned long long, mlv));
+    }
   }
+  if (a.tickets == nullptr) return;  // a separate launch merges the splits
+
+  // ---- the workgroup that arrives last at this (query, KV head) merges its splits -------------------
+  // Every workgroup of the launch gets here (one without keys wrote empty partials above).  A thread's partial
+  // stores are complete before the workgroup's arrival is counted, so whoever counts the last arrival can read
+  // all partials with device-scope loads.
+  __shared__ int last_s;
+  wait_stores_done();
+  __syncthreads();
+  if (tid == 0) {
+    unsigned long long* word = a.tickets + (long long)bm * a.Hkv + g;
+    const uint32_t before = arrive_at(word, a.nonce);
+    last_s = (before + 1u == (uint32_t)gridDim.x) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!last_s) return;
+  // (m, l) of every (head, split), all loads independent; the staging area is free again (every wave passed the
+  // barriers above after its last use)
+  const int ns = a.ph_splits;
+  float2* mls = reinterpret_cast<float2*>(&stage[0][0]);  // [r][ns]: (max, sum), then (weight, sum)
+  for (int t = tid; t < a.r * ns; t += 256) {
+    const int hh = t / ns, s = t - hh * ns;
+    const long long qh = (long long)bm * a.Hq + g * a.r + hh;
+    mls[t] = __builtin_bit_cast(float2, load_dev(reinterpret_cast<const unsigned long long*>(a.part_ml + qh * ns + s)));
+  }
+  __syncthreads();
+  for (int hh = wave; hh < a.r; hh += kAttWaves) {  // one wave per head: maximum, weights, normaliser
+    float mx = -INFINITY;
+    for (int s = lane; s < ns; s += 64) mx = fmaxf(mx, mls[hh * ns + s].x);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    float lsum = 0.f;
+    for (int s = lane; s < ns; s += 64) {
+      const float2 v = mls[hh * ns + s];
+      const float f = (v.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(v.x - mx);
+      mls[hh * ns + s].x = f;
+      lsum += f * v.y;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off, 64);
+    if (lane == 0) {
+      wm[0][hh] = mx;
+      wl[0][hh] = lsum;
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < a.r * (D / 2); e += 256) {  // a thread owns two adjacent output elements of one head
+    const int hh = e / (D / 2), d2 = e % (D / 2);
+    const long long qh = (long long)bm * a.Hq + g * a.r + hh;
+    const unsigned long long* po = reinterpret_cast<const unsigned long long*>(a.part_o + qh * ns * D) + d2;
+    const float2* w = mls + hh * ns;
+    float o0 = 0.f, o1 = 0.f;
+    int s = 0;
+    for (; s + 8 <= ns; s += 8) {
+      unsigned long long v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = load_dev(po + (long long)(s + u) * (D / 2));
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float2 x = __builtin_bit_cast(float2, v[u]);
+        o0 += w[s + u].x * x.x;
+        o1 += w[s + u].x * x.y;
+      }
+    }
+    for (; s < ns; ++s) {
+      const float2 x = __builtin_bit_cast(float2, load_dev(po + (long long)s * (D / 2)));
+      o0 += w[s].x * x.x;
+      o1 += w[s].x * x.y;
+    }
+    const float lsum = wl[0][hh], mx = wm[0][hh];
+    const float r0 = (lsum > 0.f) ? o0 / lsum : 0.f, r1 = (lsum > 0.f) ? o1 / lsum : 0.f;
+    reinterpret_cast<uint32_t*>(a.final_out + qh * D)[d2] = pack_bf16(r0, r1);
+    if (a.final_lse != nullptr && d2 == 0)
+      a.final_lse[qh] = (lsum > 0.f) ? (mx + log2f(lsum)) * 0.6931471805599453f : -INFINITY;
+  }
+  if (tid == 0) store_dev(a.tickets + (long long)bm * a.Hkv + g, 0ull);  // ready for a replay of this launch
 }
 
 // Log-sum-exp merge of the split partials of one (query, head); one thread per output element.
@@ -636,6 +716,11 @@ AttendPlan plan_attend(const Dims& dm, int B, int M, int k, int Lloc, int bank_k
   const size_t o_bytes = round_up256((size_t)BM * dm.Hq * p.n_splits * dm.d * sizeof(float));
   p.off_ml = o_bytes;
   p.ws_bytes = o_bytes + round_up256((size_t)BM * dm.Hq * p.n_splits * sizeof(float2));
+  // decode kernel alone: its last-arriving workgroup per (query, KV head) merges the splits, no merge launch
+  // (few splits only: with many, the separate merge launch, one workgroup per head, is the faster way to read them)
+  p.fused_merge = (!p.prefill && !p.split_local && p.n_splits <= 16) ? 1 : 0;
+  p.off_tickets = p.ws_bytes;
+  if (p.fused_merge) p.ws_bytes += round_up256((size_t)BM * dm.Hkv * sizeof(unsigned long long));
   // the tiled kernel reads keys that were rotated once per (batch row, KV head): all steps of a shared
   // selection, or the local steps alone
   p.off_krot = 0;
@@ -687,6 +772,10 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
   a.ph_splits = pl.n_splits;
   a.split0 = 0;
   a.qscale = (float)(1.4426950408889634 / sqrt((double)dm.d));
+  a.tickets = pl.fused_merge ? (unsigned long long*)((char*)ws + pl.off_tickets) : nullptr;
+  a.nonce = launch_nonce48();
+  a.final_out = (uint16_t*)out;
+  a.final_lse = lse;
   RopeTheta th;
   for (int u = 0; u < kMaxHalf; ++u) {
     th.th[u] = (u < dm.d / 2) ? pow((double)dm.base, -2.0 * (double)u / (double)dm.d) : 0.0;
@@ -738,7 +827,7 @@ int launch_attend(const Dims& dm, const AttendPlan& pl, const void* q, int B, in
     profile_mark(dm, true, st);
   }
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
-  if (direct) return MSA_OK;
+  if (direct || pl.fused_merge) return MSA_OK;
   if (dm.d == 128)
     hipLaunchKernelGGL(attend_merge_kernel<128>, dim3(BM * dm.Hq), dim3(128), 0, st,
                        (const float*)a.part_o, (const float2*)a.part_ml, (uint16_t*)out, lse,

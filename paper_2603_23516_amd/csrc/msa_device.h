@@ -122,4 +122,56 @@ __device__ __forceinline__ uint64_t make_key(float score, uint32_t doc) {
 __device__ __forceinline__ uint32_t key_doc(uint64_t key) { return 0xffffffffu - (uint32_t)key; }
 __device__ __forceinline__ float key_score(uint64_t key) { return unorderable((uint32_t)(key >> 32)); }
 
+// ---- device-coherent accesses ----------------------------------------------------------------------
+// Every XCD has its own L2, so data that one workgroup writes and a workgroup on another XCD reads within the same
+// launch must not linger in (or be served from) an L2.  These accesses carry device scope: the store is written
+// through to memory, the load is not served from a stale line.  Once a thread's stores are complete
+// (wait_stores_done) they are visible to device-scope loads anywhere on the chip; no cache-wide write-back or
+// invalidate (which every wave of a launch would have to pay for) is involved.
+__device__ __forceinline__ void store_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_dev(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long load_dev(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// ---- arrival counter that needs no initialisation ------------------------------------------------
+// Workgroups that produced parts of one result count themselves in; the one that arrives last combines the
+// parts.  The 64-bit word holds (nonce << 16 | arrivals); a word whose upper 48 bits are not this call's nonce
+// is a leftover (the caller's workspace has undefined contents) and counts as zero arrivals, so nothing has
+// to be cleared before the launch.  The first arrival installs the nonce with a compare-exchange; every later
+// one sees the nonce and counts itself with a plain fetch-add (arrivals that come together are then served by
+// the memory's atomic unit back to back instead of retrying one after the other).  Returns the number of
+// arrivals BEFORE this one.  Every path ends: an exchange fails only because another arrival installed the
+// nonce, after which the fetch-add path is taken.  The last arrival stores 0 when it is done, which keeps
+// replays of a captured launch (same nonce every time) correct.  nonce48 != 0; fewer than 65536 participants.
+__device__ __forceinline__ uint32_t arrive_at(unsigned long long* word, unsigned long long nonce48) {
+  unsigned long long old = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if ((old >> 16) != nonce48) {
+    const unsigned long long first = (nonce48 << 16) | 1ull;
+    if (__hip_atomic_compare_exchange_strong(word, &old, first, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT))
+      return 0u;
+    if ((old >> 16) != nonce48) {
+      // the word changed between the load and the exchange without the nonce appearing: it can only have been
+      // a foreign write (the workspace is shared with something else); fall back to the exchange loop
+      for (;;) {
+        const uint32_t cnt = ((old >> 16) == nonce48) ? (uint32_t)(old & 0xffffull) : 0u;
+        if (__hip_atomic_compare_exchange_strong(word, &old, (nonce48 << 16) | (unsigned long long)(cnt + 1u),
+                                                 __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+          return cnt;
+      }
+    }
+  }
+  old = __hip_atomic_fetch_add(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return (uint32_t)(old & 0xffffull);
+}
+
 }  // namespace msa

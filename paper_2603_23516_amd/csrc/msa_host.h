@@ -78,6 +78,8 @@ struct AttendPlan {
   int loc_splits, loc_steps_per_split;  // split_local: tiled kernel over the local context
   int tpw, n_ttiles;     // prefill: tokens per wave (32 / r), token tiles (4 waves each) per batch row
   size_t off_ml;         // byte offset of the (m, l) pairs inside the workspace
+  int fused_merge;       // 1: the decode kernel's last-arriving workgroup of a (query, KV head) merges the splits
+  size_t off_tickets;    // byte offset of the arrival counters [B*M][Hkv] (64-bit)
   size_t off_krot;       // tiled kernel: byte offset of the once-rotated keys (0 = none)
   int krot_steps;        // steps per (batch row, KV head) held there
   size_t ws_bytes;
@@ -101,5 +103,10 @@ int launch_fetch(const Dims& dm, const void* K_dev_view, const void* V_dev_view,
                  int32_t* lens_stage, hipStream_t st);
 
 inline size_t round_up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// A 48-bit non-zero value that differs from call to call (clock ticks through a 64-bit mixer): the tag of the
+// arrival counters of one launch (arrive_at in msa_device.h).  It only has to differ from whatever the
+// caller's workspace happens to hold.
+unsigned long long launch_nonce48();
 
 }  // namespace msa
