@@ -462,7 +462,7 @@ def main():
     # the MFMA GEMM path (many query tokens).  Algorithmic flops: the folded form of Eq. 2, one routing query per (token,
     # KV group): 2 * tokens * Hkv * keys * d.  Issued: twice that, the query travels as a bf16 (hi, lo) pair
     flops = flops_issued = None
-    if nq >= 64 and args.scope == "group":
+    if nq >= 64 and k <= 16 and wl.C == 8:          # both selection scopes do the same matrix work
         tiles = (wl.N * wl.C + 15) // 16
         flops = 2.0 * nq * wl.Hkv * wl.N * wl.C * wl.d
         flops_issued = 2.0 * nq * wl.Hkv * tiles * 16 * 2 * wl.d
@@ -493,7 +493,8 @@ def main():
                       "median_ms": score_all[args.steps // 2], "min_ms": score_all[0],
                       "entry_point_ms": score_call_ms,
                       "entry_point_frac": ab["score"] / (score_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS} if flops is None else
-                     {"bound": "mfma", "kernel": "score_gemm_kernel (inside msa_score_topk = fold + GEMM + merge)",
+                     {"bound": "mfma", "kernel": ("score_gemm_all_kernel" if args.scope == "all" else "score_gemm_kernel") +
+                      " (inside msa_score_topk = fold + GEMM + merge)",
                       "achieved": flops / (score_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                       "unit": "TFLOP/s", "frac": flops / (score_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                       "traffic": TRAFFIC.get("score"),

@@ -23,9 +23,10 @@ struct Dims {
 
 // Work split of the MFMA-bound scoring path for many query tokens (msa_score_gemm.hip).
 struct GemmPlan {
-  int n_qblocks;         // blocks of 256 query tokens
+  int all_heads;         // 1: head mean over every head (select_scope = ALL): score_gemm_all_kernel
+  int n_qblocks;         // blocks of 256 (128: k > 8, or all heads) query tokens
   int n_splits;          // key-range splits per (head, token block)
-  int stages_per_split;  // 64-key stages per split
+  int stages_per_split;  // 64-key stages per split (all heads: ranges of stages per split)
   size_t off_lists;      // byte offset of the candidate lists (after the folded fp32 queries)
   size_t ws_bytes;
 };

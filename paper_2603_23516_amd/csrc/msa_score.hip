@@ -1005,7 +1005,7 @@ ScorePlan plan_score(const Dims& dm, int BM, int k) {
   // one selection per KV group, or (literal Eq. 2 head mean, more than one group) one for all heads
   p.all_heads = (dm.scope_all && dm.Hkv > 1) ? 1 : 0;
   p.n_sel = dm.scope_all ? 1 : dm.Hkv;
-  p.use_gemm = (!p.all_heads && gemm_path_applies(dm, BM, k)) ? 1 : 0;
+  p.use_gemm = gemm_path_applies(dm, BM, k) ? 1 : 0;
   if (p.use_gemm) {
     p.gemm = plan_score_gemm(dm, BM, k);
     p.n_splits = p.gemm.n_splits;

@@ -15,7 +15,7 @@
 //     the A operand of v_mfma_f32_32x32x16_bf16: D[key][token].
 //     Keys are the ROWS of the product, so the 8 chunks of a document sit in two lanes (l, l ^ 32)
 //     as four accumulator registers each: document max = 3 in-lane max + one half-wave swap.
-//     Each lane keeps a private sorted top-8 list (score, document) per token block in registers;
+//     Each lane keeps a private sorted top-8 (or top-16) list (score, document) per token block in registers;
 //     the lower half of the wave serves documents 0,1 of a sub-tile, the upper half documents 2,3.
 //     Lists are merged per token at the end and written as sorted 64-bit keys, the same format the
 //     streaming scan writes, so score_merge_kernel combines the key-range splits.
@@ -26,8 +26,10 @@ namespace msa {
 
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kGemmTokens = 256;  // tokens per workgroup (4 waves x 64)
-constexpr int kGemmK = 8;         // per-lane list length (k <= 8)
+constexpr int kGemmMaxK = 16;     // longest per-lane list (k <= 16)
+// Two shapes of the kernel: k <= 8 keeps two 32-token blocks per wave (256 tokens per workgroup) with 8-entry
+// per-lane lists; 8 < k <= 16 keeps one block per wave (128 tokens per workgroup) with 16-entry lists -- the longer
+// lists take the registers of the second block's query operands.
 
 __device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
   // D(32x32) += A(32x16) * B(16x32).  Lane l: A[l%32][8(l/32)..+8], B[8(l/32)..+8][l%32],
@@ -101,14 +103,16 @@ struct GemmArgs {
   int n_qblocks, n_splits, stages_per_split;
 };
 
-template <int D>
+template <int D, int TB, int KL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void score_gemm_kernel(GemmArgs a) {
+  constexpr int kGemmK = KL;               // per-lane list length
+  constexpr int kGemmTokens = 128 * TB;    // tokens per workgroup (4 waves x TB blocks of 32)
   constexpr int NS8 = D / 16;            // 16-wide contraction slices per half (hi / lo)
   constexpr int SUB_BYTES = 32 * D * 2;  // one 32-key sub-tile
   constexpr int STAGE_BYTES = 2 * SUB_BYTES;  // a stage = two sub-tiles = 64 keys, one barrier
   constexpr int TILE_ELEMS = 16 * D;
   constexpr int LOADS = STAGE_BYTES / (256 * 16);  // 16-byte copies per thread per stage (4 at d=128)
-  constexpr int MRG_BYTES = 4 * 64 * 2 * kGemmK * 8;
+  constexpr int MRG_BYTES = 4 * 32 * TB * 2 * kGemmK * 8;
   constexpr int RING_BYTES = 3 * STAGE_BYTES;
   // ring of three stages (two copies in flight while one is multiplied); the end-of-kernel merge of
   // the two half-wave lists reuses the same memory once the ring is drained
@@ -119,7 +123,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   unsigned char* const kbuf1 = smem + STAGE_BYTES;
   unsigned char* const kbuf2 = smem + 2 * STAGE_BYTES;
   typedef unsigned long long mrg_row_t[2 * kGemmK];
-  mrg_row_t* const mrg = reinterpret_cast<mrg_row_t*>(smem);  // [4 waves * 64 tokens][2 * kGemmK]
+  mrg_row_t* const mrg = reinterpret_cast<mrg_row_t*>(smem);  // [4 waves * 32 TB tokens][2 * kGemmK]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -138,10 +142,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   if (tid < 64) ones[tid] = 1.0f;
 
   // ---- B operands: this wave's 64 tokens, hi and lo halves, resident for the whole kernel -----
-  const int tok0 = qb * kGemmTokens + wave * 64;
-  bf16x8_t Bhi[2][NS8], Blo[2][NS8];
+  const int tok0 = qb * kGemmTokens + wave * 32 * TB;
+  bf16x8_t Bhi[TB][NS8], Blo[TB][NS8];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) {
+  for (int cb = 0; cb < TB; ++cb) {
     const int tok = tok0 + 32 * cb + c;
 #pragma unroll
     for (int s = 0; s < NS8; ++s) {
@@ -170,10 +174,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   }
 
   // per-lane sorted lists: [token block][rank]
-  float lsc[2][kGemmK];
-  int ldoc[2][kGemmK];
+  float lsc[TB][kGemmK];
+  int ldoc[TB][kGemmK];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb)
+  for (int cb = 0; cb < TB; ++cb)
 #pragma unroll
     for (int p = 0; p < kGemmK; ++p) {
       lsc[cb][p] = -INFINITY;
@@ -188,11 +192,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   // acceptance test uses the list's last entry as it was at the last flush: a valid (if slightly stale)
   // lower bound, so nothing that belongs in the list is ever turned away.
   constexpr int kPend = 2;
-  float psc[2][kPend];
-  int pdoc[2][kPend];
-  int pcnt[2] = {0, 0};
+  float psc[TB][kPend];
+  int pdoc[TB][kPend];
+  int pcnt[TB];
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb)
+  for (int cb = 0; cb < TB; ++cb) pcnt[cb] = 0;
+#pragma unroll
+  for (int cb = 0; cb < TB; ++cb)
 #pragma unroll
     for (int q = 0; q < kPend; ++q) {
       psc[cb][q] = -INFINITY;
@@ -263,9 +269,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 
   // 32 keys x 64 tokens, contraction over [hi | lo], then the epilogue for these four documents
   auto sub_tile = [&](long long st, const unsigned char* kcur, const float* icur) __attribute__((always_inline)) {
-    f32x16_t acc[2];
+    f32x16_t acc[TB];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < TB; ++cb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
     // A operand: key row c -> tile c/16, slot c%16; dims 16s + 8h .. +8 = piece 2s + h.  All slices
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 #pragma unroll
     for (int s = 0; s < NS8; ++s) {
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
+      for (int cb = 0; cb < TB; ++cb) {
         acc[cb] = mfma32(av[s], Bhi[cb][s], acc[cb]);
         acc[cb] = mfma32(av[s], Blo[cb][s], acc[cb]);
       }
@@ -295,7 +301,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 
     // ---- epilogue: document max, insertion into the per-lane lists ------------------------------
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int cb = 0; cb < TB; ++cb) {
       float m0, m1, m2, m3;
       {
         float m[4];
@@ -355,22 +361,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  flush(0);
-  flush(1);
+#pragma unroll
+  for (int cb = 0; cb < TB; ++cb) flush(cb);
   // ---- merge the two half-wave lists of every token, write sorted keys -----------------------
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) {
+  for (int cb = 0; cb < TB; ++cb) {
 #pragma unroll
     for (int p = 0; p < kGemmK; ++p)
-      mrg[wave * 64 + 32 * cb + c][h * kGemmK + p] =
+      mrg[wave * 32 * TB + 32 * cb + c][h * kGemmK + p] =
           (ldoc[cb][p] >= 0) ? make_key(lsc[cb][p], (uint32_t)ldoc[cb][p]) : 0ull;
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
 #pragma unroll
-  for (int cb = 0; cb < 2; ++cb) {
+  for (int cb = 0; cb < TB; ++cb) {
     const int tok = tok0 + 32 * cb + c;
-    const unsigned long long* both = mrg[wave * 64 + 32 * cb + c];
+    const unsigned long long* both = mrg[wave * 32 * TB + 32 * cb + c];
 #pragma unroll
     for (int p = 0; p < kGemmK; ++p) {
       const unsigned long long key = both[h * kGemmK + p];
@@ -385,14 +391,283 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   }
 }
 
+// ---- Eq. 2 as printed for many query tokens: head mean over EVERY head (select_scope = ALL) -----------
+// The chunk score is the mean over the KV groups g of  inv_norm_g(key) * (qf_g(token) . key_g):  every group
+// has its own keys and its own reciprocal norms, so the groups' products cannot share one accumulator; each is
+// scaled by its group's 1/|key| and added to a running total, and the document max and the top-k run ONCE on the
+// total -- eight times the matrix work per selection of the per-group kernel above, and an epilogue that is
+// amortised over the groups.
+//
+// A workgroup owns 128 query tokens (4 waves x 32) and a range of key stages.  The stages are walked in RANGES of
+// R stages (R x 64 keys): for each group in turn the wave loads that group's folded queries of its 32 tokens
+// (fp32 from the workspace, split into bf16 hi + lo operands in registers) and multiplies them with the group's
+// keys of the range, streamed through the same three-buffer ring of asynchronous global -> LDS copies (entry e of
+// the stream = range e / (HKV R), group (e / R) % HKV, stage e % R of the range); the totals of the range's
+// 2 R sub-tiles stay in registers until the last group has been added.
+constexpr int kAllRange = 2;  // stages per range
+
+template <int D, int KL, int HKV>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void score_gemm_all_kernel(GemmArgs a) {
+  constexpr int NS8 = D / 16;
+  constexpr int SUB_BYTES = 32 * D * 2;
+  constexpr int STAGE_BYTES = 2 * SUB_BYTES;
+  constexpr int TILE_ELEMS = 16 * D;
+  constexpr int LOADS = STAGE_BYTES / (256 * 16);
+  constexpr int R = kAllRange;
+  constexpr int MRG_BYTES = 4 * 32 * 2 * KL * 8;
+  constexpr int RING_BYTES = 3 * STAGE_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[RING_BYTES > MRG_BYTES ? RING_BYTES : MRG_BYTES];
+  __shared__ __attribute__((aligned(16))) float ibuf[3][64];
+  __shared__ __attribute__((aligned(16))) float ones[64];
+  typedef unsigned long long mrg_row_t[2 * KL];
+  mrg_row_t* const mrg = reinterpret_cast<mrg_row_t*>(smem);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int h = lane >> 5;
+  const int c = lane & 31;
+  const int qb = blockIdx.x % a.n_qblocks;
+  const int ks = blockIdx.x / a.n_qblocks;
+  const long long n_sub = (a.tiles + 1) / 2;
+  const long long n_stage = (n_sub + 1) / 2;
+  const long long n_range = (n_stage + R - 1) / R;
+  const long long r0 = (long long)ks * a.stages_per_split;  // ranges per split
+  long long r1 = r0 + a.stages_per_split;
+  if (r1 > n_range) r1 = n_range;
+  if (tid < 64) ones[tid] = 1.0f;
+  const int tok = qb * 128 + wave * 32 + c;
+  const long long n_entries = (r1 > r0) ? (r1 - r0) * HKV * R : 0;
+
+  float lsc[KL];
+  int ldoc[KL];
+#pragma unroll
+  for (int p = 0; p < KL; ++p) {
+    lsc[p] = -INFINITY;
+    ldoc[p] = -1;
+  }
+  constexpr int kPend = 2;
+  float psc[kPend];
+  int pdoc[kPend];
+  int pcnt = 0;
+#pragma unroll
+  for (int q = 0; q < kPend; ++q) {
+    psc[q] = -INFINITY;
+    pdoc[q] = -1;
+  }
+  auto flush = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = kPend - 1; q >= 0; --q) {  // oldest first: among equal scores the lower document stays ahead
+      const float sc = psc[q];
+      const int doc = pdoc[q];
+      const bool ok = q < pcnt && sc > lsc[KL - 1];
+#pragma unroll
+      for (int p = KL - 1; p >= 0; --p) {
+        const float above = (p > 0) ? lsc[p - 1] : INFINITY;
+        const int above_d = (p > 0) ? ldoc[p - 1] : -1;
+        const bool shift = ok && sc > above;
+        const bool here = ok && !shift && sc > lsc[p];
+        lsc[p] = shift ? above : (here ? sc : lsc[p]);
+        ldoc[p] = shift ? above_d : (here ? doc : ldoc[p]);
+      }
+    }
+    pcnt = 0;
+  };
+
+  constexpr int TILE_BYTES = TILE_ELEMS * 2;
+  constexpr int TPC = 4096 / TILE_BYTES;
+  const uint32_t goff_full = tid * 16;
+  const uint32_t goff_wrap = (tid * 16) % TILE_BYTES;
+  // entry e of this workgroup's stream -> (group, stage); past the end the last entry is fetched again
+  auto entry_at = [&](long long e, int& g, long long& sg) __attribute__((always_inline)) {
+    if (e >= n_entries) e = n_entries - 1;
+    const long long rg = r0 + e / (HKV * R);
+    g = (int)((e / R) % HKV);
+    sg = rg * R + e % R;  // may lie past the last stage of the index: fetched clamped, its documents masked
+  };
+  auto fetch = [&](long long e, unsigned char* kdst, float* idst) __attribute__((always_inline)) {
+    int g;
+    long long sg;
+    entry_at(e, g, sg);
+    const unsigned char* KRg = reinterpret_cast<const unsigned char*>(a.KR) + (long long)g * a.tiles * TILE_BYTES;
+    const float* ing = a.inv_norm ? a.inv_norm + (long long)g * a.tiles * 16 : nullptr;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      long long tile = 4 * sg + TPC * i;
+      if (tile >= a.tiles) tile = a.tiles - 1;
+      uint32_t goff = goff_full;
+      if constexpr (TPC > 1) goff = (tile + TPC <= a.tiles) ? goff_full : goff_wrap;
+      copy16_to_lds_async(KRg + tile * TILE_BYTES, goff, kdst + (i * 256 + wave * 64) * 16);
+    }
+    {
+      long long key0 = sg * 64;
+      const long long last = a.tiles * 16 - 1;
+      if (key0 > last) key0 = last;
+      const int room = (int)(last - key0 < 63 ? last - key0 : 63);
+      const float* src = ing ? ing + key0 : reinterpret_cast<const float*>(KRg);
+      copy4_to_lds_async(src, (uint32_t)((ing && lane > room) ? room : lane) * 4, idst);
+    }
+  };
+  auto wait_oldest_copy = [&]() __attribute__((always_inline)) {
+    if constexpr (LOADS == 4)
+      asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+  };
+  auto ring_k = [&](long long e) -> unsigned char* { return smem + (e % 3) * STAGE_BYTES; };
+  auto ring_i = [&](long long e) -> float* { return ibuf[e % 3]; };
+
+  if (n_entries > 0) {
+    fetch(0, ring_k(0), ring_i(0));
+    fetch(1, ring_k(1), ring_i(1));
+    wait_oldest_copy();
+  }
+  __syncthreads();
+  const float inv_groups = 1.0f / (float)HKV;
+  long long e = 0;
+  for (long long rg = r0; rg < r1; ++rg) {  // block-uniform
+    f32x16_t tot[2 * R];
+#pragma unroll
+    for (int t = 0; t < 2 * R; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) tot[t][i] = 0.f;
+    for (int g = 0; g < HKV; ++g) {
+      // this group's folded queries of the wave's 32 tokens: hi and lo operands
+      bf16x8_t Bhi[NS8], Blo[NS8];
+#pragma unroll
+      for (int s = 0; s < NS8; ++s) {
+        float x[8];
+        if (tok < a.BM) {
+          const float4* src =
+              reinterpret_cast<const float4*>(a.qf + ((long long)tok * HKV + g) * D + 16 * s + 8 * h);
+          const float4 u0 = src[0], u1 = src[1];
+          x[0] = u0.x; x[1] = u0.y; x[2] = u0.z; x[3] = u0.w;
+          x[4] = u1.x; x[5] = u1.y; x[6] = u1.z; x[7] = u1.w;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) x[i] = 0.f;
+        }
+        uint32_t wh[4], wl[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) split_pack_bf16(x[2 * jj], x[2 * jj + 1], wh[jj], wl[jj]);
+        Bhi[s] = as_bf16x8(make_uint4(wh[0], wh[1], wh[2], wh[3]));
+        Blo[s] = as_bf16x8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
+      }
+#pragma unroll
+      for (int st = 0; st < R; ++st, ++e) {
+        fetch(e + 2, ring_k(e + 2), ring_i(e + 2));  // always issued (past the end: the last entry again)
+        const unsigned char* kcur = ring_k(e);
+        const float* icur = a.inv_norm ? ring_i(e) : ones;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+          const unsigned char* kc = kcur + sub * SUB_BYTES;
+          bf16x8_t av[NS8];
+#pragma unroll
+          for (int s = 0; s < NS8; ++s)
+            av[s] = as_bf16x8(*reinterpret_cast<const uint4*>(
+                &kc[(c >> 4) * (TILE_ELEMS * 2) + ((2 * s + h) * 16 + (c & 15)) * 16]));
+          f32x16_t acc;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+          for (int s = 0; s < NS8; ++s) {
+            acc = mfma32(av[s], Bhi[s], acc);
+            acc = mfma32(av[s], Blo[s], acc);
+          }
+          const float* ic = a.inv_norm ? icur + 32 * sub : ones;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float4 v = *reinterpret_cast<const float4*>(&ic[8 * j + 4 * h]);
+            tot[2 * st + sub][4 * j] += acc[4 * j] * v.x;
+            tot[2 * st + sub][4 * j + 1] += acc[4 * j + 1] * v.y;
+            tot[2 * st + sub][4 * j + 2] += acc[4 * j + 2] * v.z;
+            tot[2 * st + sub][4 * j + 3] += acc[4 * j + 3] * v.w;
+          }
+        }
+        wait_oldest_copy();
+        __syncthreads();
+      }
+    }
+    // ---- the range's totals are complete: head mean, document max, per-lane lists ----------------------
+#pragma unroll
+    for (int t = 0; t < 2 * R; ++t) {
+      const long long sub_tile = (rg * R + t / 2) * 2 + (t & 1);  // 32 keys = 4 documents
+      float m[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        m[j] = max_with_other_half(fmaxf(fmaxf(tot[t][4 * j], tot[t][4 * j + 1]),
+                                         fmaxf(tot[t][4 * j + 2], tot[t][4 * j + 3]))) * inv_groups;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        const float sc = h ? (jj ? m[3] : m[2]) : (jj ? m[1] : m[0]);
+        const long long doc = sub_tile * 4 + 2 * h + jj;
+        const bool ok = doc < a.N && sc > lsc[KL - 1];
+        if (__any(ok)) {
+#pragma unroll
+          for (int q = kPend - 1; q > 0; --q) {
+            psc[q] = ok ? psc[q - 1] : psc[q];
+            pdoc[q] = ok ? pdoc[q - 1] : pdoc[q];
+          }
+          psc[0] = ok ? sc : psc[0];
+          pdoc[0] = ok ? (int)doc : pdoc[0];
+          pcnt += ok ? 1 : 0;
+          if (__any(pcnt == kPend)) flush();
+        }
+      }
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  flush();
+#pragma unroll
+  for (int p = 0; p < KL; ++p)
+    mrg[wave * 32 + c][h * KL + p] = (ldoc[p] >= 0) ? make_key(lsc[p], (uint32_t)ldoc[p]) : 0ull;
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  {
+    const unsigned long long* both = mrg[wave * 32 + c];
+#pragma unroll
+    for (int p = 0; p < KL; ++p) {
+      const unsigned long long key = both[h * KL + p];
+      int rank = p;
+#pragma unroll
+      for (int o = 0; o < KL; ++o) rank += (both[(1 - h) * KL + o] > key) ? 1 : 0;
+      if (tok < a.BM && rank < a.k) {
+        unsigned long long* dst = a.ws + ((long long)tok * a.n_splits + ks) * a.k;
+        dst[rank] = key;
+      }
+    }
+  }
+}
+
 // ---- host side -----------------------------------------------------------------------------------
 bool gemm_path_applies(const Dims& dm, int BM, int k) {
-  return dm.C == 8 && k <= kGemmK && BM >= 64;
+  // (one group with select_scope = ALL is the per-group kernel's case)
+  return dm.C == 8 && k <= kGemmMaxK && BM >= 64;
 }
 
 GemmPlan plan_score_gemm(const Dims& dm, int BM, int k) {
   GemmPlan p;
-  p.n_qblocks = (BM + kGemmTokens - 1) / kGemmTokens;
+  p.all_heads = (dm.scope_all && dm.Hkv > 1) ? 1 : 0;
+  if (p.all_heads) {
+    // one workgroup per (128 tokens, range of key stages); the per-token lists are [BM][n_splits][k]
+    p.n_qblocks = (BM + 127) / 128;
+    const long long n_stage = ((dm.tiles + 1) / 2 + 1) / 2;
+    const long long n_range = (n_stage + kAllRange - 1) / kAllRange;
+    long long want = (2 * 256) / (long long)p.n_qblocks;
+    if (want < 1) want = 1;
+    long long by_len = (n_range + 3) / 4;                            // at least 4 ranges per split
+    long long ns = want < by_len ? want : by_len;
+    if (ns < 1) ns = 1;
+    if (ns > 64) ns = 64;
+    p.stages_per_split = (int)((n_range + ns - 1) / ns);             // RANGES per split on this path
+    p.n_splits = (int)((n_range + p.stages_per_split - 1) / p.stages_per_split);
+    p.off_lists = round_up256((size_t)BM * dm.Hkv * dm.d * sizeof(float));
+    p.ws_bytes = p.off_lists + round_up256((size_t)BM * p.n_splits * k * sizeof(unsigned long long));
+    return p;
+  }
+  const int tokens_per_wg = (k <= 8) ? 256 : 128;
+  p.n_qblocks = (BM + tokens_per_wg - 1) / tokens_per_wg;
   const long long n_stage = ((dm.tiles + 1) / 2 + 1) / 2;           // stages of 64 keys
   long long want = (2 * 256) / ((long long)dm.Hkv * p.n_qblocks);  // ~2 workgroups per CU
   if (want < 1) want = 1;
@@ -430,12 +705,36 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
   a.n_qblocks = pl.n_qblocks;
   a.n_splits = pl.n_splits;
   a.stages_per_split = pl.stages_per_split;
+  if (pl.all_heads) {
+    const unsigned nb = (unsigned)(pl.n_qblocks * pl.n_splits);
+    profile_mark(dm, false, st);
+#define MSA_GEMM_ALL(DD, HH) \
+  do { \
+    if (k <= 8) hipLaunchKernelGGL((score_gemm_all_kernel<DD, 8, HH>), dim3(nb), dim3(256), 0, st, a); \
+    else hipLaunchKernelGGL((score_gemm_all_kernel<DD, 16, HH>), dim3(nb), dim3(256), 0, st, a); \
+  } while (0)
+    if (dm.d == 128) {
+      if (dm.Hkv == 2) MSA_GEMM_ALL(128, 2); else if (dm.Hkv == 4) MSA_GEMM_ALL(128, 4); else MSA_GEMM_ALL(128, 8);
+    } else {
+      if (dm.Hkv == 2) MSA_GEMM_ALL(64, 2); else if (dm.Hkv == 4) MSA_GEMM_ALL(64, 4); else MSA_GEMM_ALL(64, 8);
+    }
+#undef MSA_GEMM_ALL
+    profile_mark(dm, true, st);
+    return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
+  }
   const unsigned blocks = (unsigned)(dm.Hkv * pl.n_qblocks * pl.n_splits);
   profile_mark(dm, false, st);
-  if (dm.d == 128)
-    hipLaunchKernelGGL(score_gemm_kernel<128>, dim3(blocks), dim3(256), 0, st, a);
-  else
-    hipLaunchKernelGGL(score_gemm_kernel<64>, dim3(blocks), dim3(256), 0, st, a);
+  if (k <= 8) {
+    if (dm.d == 128)
+      hipLaunchKernelGGL((score_gemm_kernel<128, 2, 8>), dim3(blocks), dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL((score_gemm_kernel<64, 2, 8>), dim3(blocks), dim3(256), 0, st, a);
+  } else {
+    if (dm.d == 128)
+      hipLaunchKernelGGL((score_gemm_kernel<128, 1, 16>), dim3(blocks), dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL((score_gemm_kernel<64, 1, 16>), dim3(blocks), dim3(256), 0, st, a);
+  }
   profile_mark(dm, true, st);
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   return MSA_OK;

@@ -278,6 +278,8 @@ CASES = {
     "prefill100_gemm": (13000, 301, 2, 4, 64, 128, 8, 1, 100, 100, 1e6, 8),
     "prefill300_gemm_d64": (14000, 77, 2, 2, 64, 64, 8, 2, 150, 150, 1e4, 5),
     "prefill140_r8_local_in_eight_wave_tiles": (15000, 60, 2, 8, 64, 128, 8, 1, 140, 90, 1e6, 6),
+    "prefill96_gemm_k16": (16000, 400, 2, 4, 64, 128, 8, 1, 96, 96, 1e6, 16),
+    "prefill200_gemm_k12_d64": (17000, 150, 2, 2, 64, 64, 8, 2, 100, 100, 1e4, 12),
 }
 
 
@@ -620,7 +622,40 @@ EQ2_CASES = {
     "hkv1_d64": (34000, 80, 1, 4, 128, 64, 32, 2, 3, 16, 1e4, 7, "cos"),
     "hkv8_d64_c16": (35000, 41, 8, 1, 256, 64, 16, 1, 11, 20, 1e4, 9, "cos"),
     "prefill80_gemm_pool": (36000, 150, 2, 4, 64, 128, 8, 2, 80, 80, 1e6, 8, "cos"),
+    # the paper's own setting on the matrix cores: head mean over every head, k = 16, many query tokens
+    "prefill70_all_heads_gemm_k16_hkv8": (37000, 300, 8, 2, 64, 128, 8, 1, 70, 70, 1e6, 16, "cos"),
+    "prefill130_all_heads_gemm_hkv4_d64_dot": (38000, 222, 4, 2, 64, 64, 8, 1, 130, 0, 1e4, 12, "dot"),
 }
+
+
+@pytest.mark.parametrize("k", [8, 16])
+def test_prefill_scoring_all_heads_long_splits(k):
+    """select_scope = ALL with many query tokens: the all-heads scoring GEMM over key ranges long enough for many
+    ring rotations, several key-range splits and token blocks with a ragged tail (M = 300), Hkv = 8, with an exact
+    tie between two documents planted in every head; the oracle scores 100 tokens at a time."""
+    N, C, d, Hkv, r, B, M = 5000, 8, 128, 8, 1, 1, 300
+    say(f"case all-heads prefill scoring: N={N} docs, C={C}, d={d}, Hkv={Hkv}, M={M}, k={k}")
+    cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e6, select_scope=msa.MSA_SCOPE_ALL)
+    _, KRb = S.normal_bf16(42000, (Hkv, N * C, d))
+    qb, q = S.normal_bf16(42001, (B, M, Hkv * r, d))
+    KRb[:, 7 * C + 1] = KRb[:, 4500 * C + 6]                      # documents 7 and 4500 tie wherever that chunk is their best
+    inv = 1.0 / np.maximum(np.linalg.norm(KRb, axis=-1), O.EPS_NORM)
+    dKR, dinv = upload_oracle_index(cfg, KRb, inv)
+    idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    assert tuple(idx.shape) == (B, M, 1, k)
+    n_band = 0
+    for m0 in range(0, M, 100):
+        sl = slice(m0, min(M, m0 + 100))
+        _, nb = check_topk_generic(q[:, sl], KRb, C, N, idx[:, sl], val[:, sl], k, "cos", "all", False)
+        n_band += nb
+    say(f"   top-k ok ({n_band} inside the tie band)")
+    # and pooled over the tokens (Eq. 2 as printed): one selection for the whole question
+    cfg_p = cfg.replace(token_pool=1)
+    idx, val = msa.msa_score_topk(cfg_p, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    _, nb = check_topk_generic(q, KRb, C, N, idx, val, k, "cos", "all", True)
+    say(f"   pooled top-k ok ({nb} inside the tie band)")
 
 
 @pytest.mark.parametrize("name", list(EQ2_CASES))
