@@ -28,8 +28,10 @@ constexpr int kPrefetch = 4;         // tiles in flight per wave
 constexpr int kListBytes = 16384;    // LDS per wave for candidate lists
 
 struct ScoreArgs {
-  const uint4* qop;         // [Hkv][n_qtiles][D/32][64] A operands (bf16 hi/lo rows) of 8-query tiles
+  const uint4* qop;         // [Hkv][n_qtiles][D/32][64] A operands (bf16 hi/lo rows) of 8-query tiles, prepared by
+                            // prep_scan_operands_kernel (all-heads scan; per-group scan with the threshold exchange)
   int n_qtiles;
+  const uint16_t* q_route;  // [BM][Hq][D] routing queries: a per-group scan without the exchange folds them itself
   const uint16_t* KR;       // tiled
   const float* inv_norm;    // may be null (dot)
   unsigned long long* ws;   // [Hkv][BM][n_splits][k] candidate keys, each list sorted descending
@@ -113,6 +115,65 @@ __device__ __forceinline__ float group_sum(float x) {
 // Independent streams (waves) per workgroup: measured 3-5 % faster than single-wave workgroups.
 constexpr int kScanWaves = 4;
 
+// One wave folds the r heads of KV group g of the 8 queries of tile qt into one fp32 routing query per token,
+//     qf = (1/r) sum_h q_h / max(|q_h|, 1e-12)        (plain mean for the dot product),
+// splits it into bf16 hi + lo and leaves the MFMA A operands of the tile in aop[s][lane]: lane 16q + n holds row n
+// (query n/2, hi for even n, lo for odd n), dims 32s + 8q .. +8 of slice s.  qf: 8 * D floats of the wave's own LDS.
+template <int D>
+__device__ __forceinline__ void fold_query_tile(const uint16_t* __restrict__ q_route, long long qt, int g, int BM,
+                                                int Hq, int r, int cos, float* qf, uint4 (*aop)[64], int lane) {
+  constexpr int NS = D / 32, LPH = D / 8, HPL = 64 / LPH;
+  // Lane = (query lane / LPH, 16-byte piece lane % LPH): a lane loads the same piece of all r heads of
+  // its query, so the head sum stays in the lane and the norms need only DPP sums over LPH <= 16 lanes.
+  const int piece = lane % LPH;
+#pragma unroll
+  for (int pass = 0; pass < 8 / HPL; ++pass) {
+    const int qi = pass * HPL + lane / LPH;
+    const long long qg = qt * 8 + qi;
+    uint4 v[8];
+#pragma unroll
+    for (int hh = 0; hh < 8; ++hh) {
+      v[hh] = make_uint4(0, 0, 0, 0);
+      if (qg < BM && hh < r)
+        v[hh] = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hh) * D + piece * 8);
+    }
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = 0.f;
+#pragma unroll
+    for (int hh = 0; hh < 8; ++hh) {
+      if (hh < r) {  // wave-uniform
+        const float x[8] = {bf16_lo(v[hh].x), bf16_hi(v[hh].x), bf16_lo(v[hh].y), bf16_hi(v[hh].y),
+                            bf16_lo(v[hh].z), bf16_hi(v[hh].z), bf16_lo(v[hh].w), bf16_hi(v[hh].w)};
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+        ss = group_sum<LPH>(ss);
+        const float w = cos ? 1.0f / fmaxf(sqrtf(ss), 1e-12f) : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] += x[e] * w;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qf[qi * D + piece * 8 + e] = f[e] / (float)r;
+  }
+  wave_sync();
+  const int rr = lane >> 4, n = lane & 15;
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    uint32_t w[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      float h0, l0, h1, l1;
+      split_bf16(qf[(n >> 1) * D + 32 * s + 8 * rr + 2 * jj], h0, l0);
+      split_bf16(qf[(n >> 1) * D + 32 * s + 8 * rr + 2 * jj + 1], h1, l1);
+      w[jj] = (n & 1) ? pack_bf16(l0, l1) : pack_bf16(h0, h1);
+    }
+    aop[s][lane] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  wave_sync();
+}
+
 // MODE 0  filter: thresholds, candidate lists, pruning (long streams).
 // MODE 1  dense lists: a wave's whole stream holds no more documents than a list has slots, so every
 //         document score goes straight to slot (iteration, document-in-tile) of its query's list and
@@ -121,7 +182,11 @@ constexpr int kScanWaves = 4;
 //         sorting, writes the fp32 document scores of every query as one coalesced run of the row
 //         mat[g][query][:]; topk_rows_kernel then selects per row.  For short streams (small banks,
 //         many queries) the per-wave sorts and the list merge cost more than the stream itself.
-template <int D, int NQT, bool COS, int MODE>
+// FOLD: the workgroup folds its queries into MFMA operands itself (wave t folds tile t, one workgroup barrier) instead
+//       of reading operands that prep_scan_operands_kernel prepared: one launch less, which is what short streams
+//       are made of.  Scans with the threshold exchange keep the prepared operands: that launch also resets the
+//       exchange buffer, and their waves never synchronise.
+template <int D, int NQT, bool COS, int MODE, bool FOLD>
 __global__ __launch_bounds__(64 * kScanWaves) __attribute__((amdgpu_waves_per_eu(2)))
 void score_scan_kernel(ScoreArgs a) {
   constexpr bool DENSE = MODE != 0;
@@ -145,7 +210,10 @@ void score_scan_kernel(ScoreArgs a) {
   const int n = lane & 15;   // A row / B column / D column
   const int sp = blockIdx.x * kScanWaves + wave;
   const int g = blockIdx.y;
-  if (sp >= a.n_splits) return;  // wave-uniform; the waves of a workgroup never synchronise
+  // wave-uniform; with FOLD a wave without a stream (the tail of the last workgroup) still takes part in the
+  // workgroup barriers of the prologue, otherwise the waves of a workgroup never synchronise
+  const bool active = sp < a.n_splits;
+  if (!FOLD && !active) return;
 
   // ---- start streaming at once: the first kPrefetch tiles are requested before the prologue ----
   // Wave sp takes tiles sp, sp + n_splits, sp + 2 n_splits, ...: at any moment the waves of a head
@@ -153,32 +221,53 @@ void score_scan_kernel(ScoreArgs a) {
   // always issued, so the number of loads in flight is the same on every path.
   const long long S = a.n_splits;
   const long long t0 = (long long)sp * a.tiles_per_wave;  // MODE 2: first tile of this wave
-  const long long n_it = (MODE == 2) ? ((a.tiles - t0 < a.tiles_per_wave) ? a.tiles - t0 : a.tiles_per_wave)
-                                     : (a.tiles - sp + S - 1) / S;  // >= 1 by construction of n_splits
+  const long long n_it = !active ? 0
+                         : (MODE == 2) ? ((a.tiles - t0 < a.tiles_per_wave) ? a.tiles - t0 : a.tiles_per_wave)
+                                       : (a.tiles - sp + S - 1) / S;  // >= 1 by construction of n_splits
   const long long i_last = n_it - 1;
   auto tile_at = [&](long long it) { return (MODE == 2) ? t0 + it : sp + it * S; };
   const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS + lane * 8;
   const float* ing = COS ? a.inv_norm + (long long)g * a.tiles * 16 + n : nullptr;
   uint4 buf[kPrefetch][NS];
   float binv[kPrefetch];
+  if (active) {
 #pragma unroll
-  for (int u = 0; u < kPrefetch; ++u) {
-    const long long t = tile_at((u < n_it) ? u : i_last);
+    for (int u = 0; u < kPrefetch; ++u) {
+      const long long t = tile_at((u < n_it) ? u : i_last);
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
-      buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512);
-    binv[u] = COS ? ing[t * 16] : 1.0f;
+      for (int s = 0; s < NS; ++s)
+        buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512);
+      binv[u] = COS ? ing[t * 16] : 1.0f;
+    }
   }
 
-  // ---- A operands (prepared once per call by prep_scan_operands_kernel): row n of query tile t is
-  // query 8t + n/2, hi (even n) or lo (odd n) half of the folded fp32 routing query -----------------
+  // ---- A operands: row n of query tile t is query 8t + n/2, hi (even n) or lo (odd n) half of the folded fp32
+  // routing query ------------------------------------------------------------------------------------------
   bf16x8_t A[NQT][NS];
+  if constexpr (FOLD) {
+    // wave t folds tile t; the operands pass through the candidate areas, which are free until the stream starts:
+    // tile t in the second half of area t, the folding wave's scratch in the first half of its own
+    static_assert(NQT <= kScanWaves && 8 * D * 4 <= kListBytes / 2 && NS * 64 * 16 <= kListBytes / 2, "prologue scratch");
+    typedef uint4 aop_tile_t[64];
+    if (wave < NQT)
+      fold_query_tile<D>(a.q_route, a.q0 / 8 + wave, g, a.BM, a.Hq, a.r, COS ? 1 : 0, reinterpret_cast<float*>(smem[wave]),
+                         reinterpret_cast<aop_tile_t*>(smem[wave] + kListBytes / 2), lane);
+    __syncthreads();
 #pragma unroll
-  for (int t = 0; t < NQT; ++t) {
-    const long long qt = a.q0 / 8 + t;
+    for (int t = 0; t < NQT; ++t)
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
-      A[t][s] = as_bf16x8(a.qop[(((long long)g * a.n_qtiles + qt) * NS + s) * 64 + lane]);
+      for (int s = 0; s < NS; ++s)
+        A[t][s] = as_bf16x8(reinterpret_cast<const aop_tile_t*>(smem[t] + kListBytes / 2)[s][lane]);
+    __syncthreads();  // every wave has its operands: the candidate areas are the streams' from here on
+    if (!active) return;
+  } else {
+#pragma unroll
+    for (int t = 0; t < NQT; ++t) {
+      const long long qt = a.q0 / 8 + t;
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+        A[t][s] = as_bf16x8(a.qop[(((long long)g * a.n_qtiles + qt) * NS + s) * 64 + lane]);
+    }
   }
 
   // This lane sees queries 8t + 2rr + e (e = 0, 1) of every tile; all 16 lanes of a row keep
@@ -1125,7 +1214,9 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
   a.mat = (pl.mode == 2) ? (float*)((char*)ws + pl.off_mat) : nullptr;
   a.tiles_per_wave = pl.tiles_per_wave;
   a.n_qtiles = pl.n_qtiles;
-  {
+  a.q_route = (const uint16_t*)q_route;
+  const bool fold_in_scan = !pl.all_heads && !pl.exchange;
+  if (!fold_in_scan) {
     const long long n_gmax = pl.exchange ? (long long)dm.Hkv * BM * pl.n_splits : 0;
     const unsigned blocks = (unsigned)(pl.n_qtiles * dm.Hkv);
     if (dm.d == 128)
@@ -1161,9 +1252,10 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
     const int nqt = pl.q_per_pass / 8;  // 1, 2 or 4
 #define MSA_SCAN(DD, QQ, CC) \
   do { \
-    if (pl.mode == 2) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 2>), grid, block, 0, st, a); \
-    else if (pl.mode == 1) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 1>), grid, block, 0, st, a); \
-    else hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 0>), grid, block, 0, st, a); \
+    if (pl.mode == 2) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 2, true>), grid, block, 0, st, a); \
+    else if (pl.mode == 1) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 1, true>), grid, block, 0, st, a); \
+    else if (fold_in_scan) hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 0, true>), grid, block, 0, st, a); \
+    else hipLaunchKernelGGL((score_scan_kernel<DD, QQ, CC, 0, false>), grid, block, 0, st, a); \
   } while (0)
     if (dm.d == 128) {
       if (dm.cos) {
