@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 // keys of the range, streamed through the same three-buffer ring of asynchronous global -> LDS copies (entry e of
 // the stream = range e / (HKV R), group (e / R) % HKV, stage e % R of the range); the totals of the range's
 // 2 R sub-tiles stay in registers until the last group has been added.
-constexpr int kAllRange = 2;  // stages per range
+constexpr int all_range(int KL) { return KL <= 8 ? 3 : 2; }  // stages per range (what the registers hold)
 
 template <int D, int KL, int HKV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void score_gemm_all_kernel(GemmArgs a) {
@@ -413,7 +413,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   constexpr int STAGE_BYTES = 2 * SUB_BYTES;
   constexpr int TILE_ELEMS = 16 * D;
   constexpr int LOADS = STAGE_BYTES / (256 * 16);
-  constexpr int R = kAllRange;
+  constexpr int R = all_range(KL);
   constexpr int MRG_BYTES = 4 * 32 * 2 * KL * 8;
   constexpr int RING_BYTES = 3 * STAGE_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char smem[RING_BYTES > MRG_BYTES ? RING_BYTES : MRG_BYTES];
@@ -653,7 +653,8 @@ GemmPlan plan_score_gemm(const Dims& dm, int BM, int k) {
     // one workgroup per (128 tokens, range of key stages); the per-token lists are [BM][n_splits][k]
     p.n_qblocks = (BM + 127) / 128;
     const long long n_stage = ((dm.tiles + 1) / 2 + 1) / 2;
-    const long long n_range = (n_stage + kAllRange - 1) / kAllRange;
+    const int R = all_range(k <= 8 ? 8 : 16);
+    const long long n_range = (n_stage + R - 1) / R;
     long long want = (2 * 256) / (long long)p.n_qblocks;
     if (want < 1) want = 1;
     long long by_len = (n_range + 3) / 4;                            // at least 4 ranges per split
