@@ -68,7 +68,9 @@ def test_random_configuration(i):
     KRo, _ = O.routing_keys(case.K, P, lens)
     valid = None if lens is None else O.chunk_valid(lens, G, P)
     # chained on the GPU's own index: a tie-adjacent rounding of a key moves a score by up to ~1e-3 relative
-    atol = 2e-4 if c["sim"] == "cos" else 2e-2
+    # chained on the GPU-built index: a key one bf16 step off (next to a rounding tie) moves a cosine by <= 1e-4 and an
+    # un-normalised dot product (|q| ~ 11, |q_i k_i| up to ~1) by up to 2^-8 |q_i k_i| ~ 4e-3
+    atol = 2e-4 if c["sim"] == "cos" else 5e-3
     oi, n_band = check_topk_generic(case.q, KRo, C, N, idx, val, k, c["sim"], c["scope"], c["pool"], atol=atol,
                                     valid=valid)
     say(f"   top-k ok, shape {tuple(idx.shape)} ({n_band} inside the tie band)")
