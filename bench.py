@@ -127,25 +127,30 @@ def cpu_baseline(wl, cfg, KR, sample_docs):
     O.routing_keys(Ks, wl.P)
     t_build = time.perf_counter() - t0
     del Ks
-    sel = idx[0, 0]                                                     # [Hkv, k]: the first query's documents
-    docs = sorted(set(sel.reshape(-1).tolist()))
-    pos = {dd: i for i, dd in enumerate(docs)}
-    K_sel = np.stack([W.host_doc(wl, "K", int(i))[1] for i in docs])    # [n, Hkv, G, d]
-    V_sel = np.stack([W.host_doc(wl, "V", int(i))[1] for i in docs])
-    local = np.array([[[pos[int(dd)] for dd in sel[g]] for g in range(wl.Hkv)]])[None]      # [1, 1, Hkv, k]
-    Kl = S.normal_bf16(wl.seeds["Kloc"], (1, wl.Hkv, wl.Lloc, wl.d))[1] if wl.Lloc else None
-    Vl = S.normal_bf16(wl.seeds["Vloc"], (1, wl.Hkv, wl.Lloc, wl.d))[1] if wl.Lloc else None
-    b0, m0 = divmod(int(sel_q[0]), wl.M)
-    t0 = time.perf_counter()
-    O.sparse_attend(q[:1], K_sel, V_sel, local, Kl, Vl, wl.pos0, wl.q_pos_host[b0:b0 + 1, m0:m0 + 1], wl.base)
-    t_att = time.perf_counter() - t0
+    n_att = min(len(sel_q), 8)                                          # queries whose attention the oracle computes
+    t_att = 0.0
+    for j in range(n_att):
+        sel = idx[j, 0]                                                 # [Hkv, k]: this query's documents
+        docs = sorted(set(sel.reshape(-1).tolist()))
+        pos = {dd: i for i, dd in enumerate(docs)}
+        K_sel = np.stack([W.host_doc(wl, "K", int(i))[1] for i in docs])    # [n, Hkv, G, d]
+        V_sel = np.stack([W.host_doc(wl, "V", int(i))[1] for i in docs])
+        local = np.array([[[pos[int(dd)] for dd in sel[g]] for g in range(wl.Hkv)]])[None]      # [1, 1, Hkv, k]
+        b0, m0 = divmod(int(sel_q[j]), wl.M)
+        per_b = wl.Hkv * wl.Lloc * wl.d
+        Kl = S.normal_bf16(wl.seeds["Kloc"], (1, wl.Hkv, wl.Lloc, wl.d), start=b0 * per_b)[1] if wl.Lloc else None
+        Vl = S.normal_bf16(wl.seeds["Vloc"], (1, wl.Hkv, wl.Lloc, wl.d), start=b0 * per_b)[1] if wl.Lloc else None
+        t0 = time.perf_counter()
+        O.sparse_attend(q[j:j + 1], K_sel, V_sel, local, Kl, Vl, wl.pos0, wl.q_pos_host[b0:b0 + 1, m0:m0 + 1], wl.base)
+        t_att += time.perf_counter() - t0
+    t_att /= n_att
     per_query = t_route / len(sel_q) + t_att
     return {
         "value": 1.0 / per_query, "unit": "queries/s", "cores": int(threads), "kind": "oracle",
         "sample": (f"float64 NumPy oracle, {os.cpu_count()} host cpus visible: routing (Eq. 2, document max, top-k) of "
                    f"{len(sel_q)} of {nq} queries over all {wl.N} documents of the routing index {t_route:.2f}s; "
-                   f"attention of 1 query (all {wl.Hkv} KV groups, {wl.k} documents each + {wl.Lloc} local tokens) "
-                   f"{t_att:.2f}s; pooling {n_s} documents {t_build:.2f}s (offline, not in value)"),
+                   f"attention of {n_att} queries (all {wl.Hkv} KV groups, {wl.k} documents each + {wl.Lloc} local tokens) "
+                   f"{t_att:.2f}s per query; pooling {n_s} documents {t_build:.2f}s (offline, not in value)"),
     }
 
 
