@@ -367,6 +367,49 @@ void score_scan_kernel(ScoreArgs a) {
               if (a.q0 + 8 * tq + 2 * rr + e < a.BM)
                 thr[tq][e] = fmaxf(thr[tq][e], thr_s[8 * tq + 2 * rr + e]);
           wave_sync();
+          // Candidates accepted before the bound was known and now below it can never be among the k best: drop
+          // them at once.  What is left is a handful of entries per list, so the final sort of the stream (which
+          // every wave runs while the memory system idles) has next to nothing to do.
+          if (n == 0) {
+#pragma unroll
+            for (int tq = 0; tq < NQT; ++tq)
+#pragma unroll
+              for (int e = 0; e < 2; ++e) {
+                cnt_s[8 * tq + 2 * rr + e] = cnt[tq][e];
+                thr_s[8 * tq + 2 * rr + e] = thr[tq][e];
+              }
+          }
+          wave_sync();
+          for (int qi = 0; qi < NQ; ++qi) {
+            constexpr int PER = (CAP + 63) / 64;
+            const int c = cnt_s[qi];
+            const float th = thr_s[qi];
+            unsigned long long* cl = cand + qi * CAP;
+            unsigned long long x[PER];
+            bool kp[PER];
+#pragma unroll
+            for (int p = 0; p < PER; ++p) {
+              const int j = lane + 64 * p;
+              x[p] = (j < c) ? cl[j] : 0ull;
+              kp[p] = j < c && key_score(x[p]) >= th;
+            }
+            wave_sync();  // every entry is in a register before the list is rewritten
+            int kept = 0;
+#pragma unroll
+            for (int p = 0; p < PER; ++p) {
+              const unsigned long long m = __ballot(kp[p]);
+              if (kp[p]) cl[kept + __popcll(m & ((1ull << lane) - 1ull))] = x[p];
+              kept += __popcll(m);
+            }
+            if (lane == 0) cnt_s[qi] = kept;
+          }
+          wave_sync();
+#pragma unroll
+          for (int tq = 0; tq < NQT; ++tq) {
+            cnt[tq][0] = cnt_s[8 * tq + 2 * rr];
+            cnt[tq][1] = cnt_s[8 * tq + 2 * rr + 1];
+          }
+          wave_sync();
         }
       }
 #pragma unroll
@@ -935,18 +978,42 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
   }
   __syncthreads();
   const unsigned long long theta = theta_s;
-  for (int i0 = 0; i0 < T; i0 += 256 * 8) {  // eight independent loads per thread in flight
-    unsigned long long x[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int i = i0 + u * 256 + tid;
-      x[u] = (i < T) ? src[i] : 0ull;
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (x[u] != 0ull && x[u] >= theta) {
+  if (n_lists * depth <= kMaxSub) {
+    // The heads of all lists are in LDS already, and the lists are sorted: a list holds further survivors only if
+    // the last entry seen of it is still >= theta, and then only as far as its entries stay >= theta.  After the
+    // streams' thresholds have converged that is a handful of entries per (query, head) instead of n_lists * k.
+    for (int l = tid; l < n_lists; l += 256) {
+      bool more = true;
+      for (int j = 0; j < depth; ++j) {
+        const unsigned long long x = sub[l * depth + j];
+        more = x != 0ull && x >= theta;
+        if (!more) break;
         const int slot = atomicAdd(&n_surv, 1);
-        if (slot < kMaxSurv) surv[slot] = x[u];
+        if (slot < kMaxSurv) surv[slot] = x;
+      }
+      for (int j = depth; more && j < k; ++j) {
+        const unsigned long long x = src[l * k + j];
+        more = x != 0ull && x >= theta;
+        if (more) {
+          const int slot = atomicAdd(&n_surv, 1);
+          if (slot < kMaxSurv) surv[slot] = x;
+        }
+      }
+    }
+  } else {
+    for (int i0 = 0; i0 < T; i0 += 256 * 8) {  // eight independent loads per thread in flight
+      unsigned long long x[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * 256 + tid;
+        x[u] = (i < T) ? src[i] : 0ull;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (x[u] != 0ull && x[u] >= theta) {
+          const int slot = atomicAdd(&n_surv, 1);
+          if (slot < kMaxSurv) surv[slot] = x[u];
+        }
       }
     }
   }
