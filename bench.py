@@ -472,7 +472,7 @@ def main():
     # the MFMA GEMM path (many query tokens).  Algorithmic flops: the folded form of Eq. 2, one routing query per (token,
     # KV group): 2 * tokens * Hkv * keys * d.  Issued: twice that, the query travels as a bf16 (hi, lo) pair
     flops = flops_issued = None
-    if nq >= 64 and k <= 16 and wl.C == 8:          # both selection scopes do the same matrix work
+    if nq >= 64 and k <= 16 and wl.C in (4, 8, 16):          # both selection scopes do the same matrix work
         tiles = (wl.N * wl.C + 15) // 16
         flops = 2.0 * nq * wl.Hkv * wl.N * wl.C * wl.d
         flops_issued = 2.0 * nq * wl.Hkv * tiles * 16 * 2 * wl.d

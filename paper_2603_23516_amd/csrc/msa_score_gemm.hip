@@ -94,6 +94,7 @@ __global__ __launch_bounds__(64) void fold_queries_kernel(const uint16_t* __rest
 }
 
 struct GemmArgs {
+  int C;                    // chunks per document: 4, 8 or 16
   const float* qf;          // [BM][Hkv][D]
   const uint16_t* KR;       // tiled
   const float* inv_norm;    // may be null (dot)
@@ -103,7 +104,9 @@ struct GemmArgs {
   int n_qblocks, n_splits, stages_per_split;
 };
 
-template <int D, int TB, int KL>
+// C8: eight chunks per document, the benchmark shape, known at compile time (it fills the register file exactly; the
+// general epilogue for C = 4 / 16 is a second instantiation).
+template <int D, int TB, int KL, bool C8>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void score_gemm_kernel(GemmArgs a) {
   constexpr int kGemmK = KL;               // per-lane list length
   constexpr int kGemmTokens = 128 * TB;    // tokens per workgroup (4 waves x TB blocks of 32)
@@ -302,25 +305,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
     // ---- epilogue: document max, insertion into the per-lane lists ------------------------------
 #pragma unroll
     for (int cb = 0; cb < TB; ++cb) {
-      float m0, m1, m2, m3;
-      {
-        float m[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float x0 = acc[cb][4 * j] * inv[4 * j], x1 = acc[cb][4 * j + 1] * inv[4 * j + 1];
-          const float x2 = acc[cb][4 * j + 2] * inv[4 * j + 2], x3 = acc[cb][4 * j + 3] * inv[4 * j + 3];
-          m[j] = max_with_other_half(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
-        }
-        m0 = m[0]; m1 = m[1]; m2 = m[2]; m3 = m[3];
-      }
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        const float lo_half = jj ? m1 : m0, hi_half = jj ? m3 : m2;
-        const float sc = h ? hi_half : lo_half;
-        const long long doc = st * 4 + 2 * h + jj;
+      // a candidate document of this lane: onto the pending buffer (documents arrive in increasing order)
+      auto push = [&](float sc, long long doc) __attribute__((always_inline)) {
         const bool ok = doc < a.N && sc > lsc[cb][kGemmK - 1];
         if (__any(ok)) {
-          // push onto the lane's pending buffer (documents arrive in increasing order)
 #pragma unroll
           for (int q = kPend - 1; q > 0; --q) {
             psc[cb][q] = ok ? psc[cb][q - 1] : psc[cb][q];
@@ -330,6 +318,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
           pdoc[cb][0] = ok ? (int)doc : pdoc[cb][0];
           pcnt[cb] += ok ? 1 : 0;
           if (__any(pcnt[cb] == kPend)) flush(cb);
+        }
+      };
+      // m4[j]: max over the lane's four rows 8j + 4h .. + 3 of the sub-tile
+      float m4[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float x0 = acc[cb][4 * j] * inv[4 * j], x1 = acc[cb][4 * j + 1] * inv[4 * j + 1];
+        const float x2 = acc[cb][4 * j + 2] * inv[4 * j + 2], x3 = acc[cb][4 * j + 3] * inv[4 * j + 3];
+        m4[j] = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
+      }
+      if (C8 || a.C == 8) {
+        // a document = rows 8j .. 8j + 7: the lane's four and the other half's four; the lower half of the wave
+        // takes documents 0, 1 of the sub-tile, the upper half documents 2, 3
+        float m[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m[j] = max_with_other_half(m4[j]);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) push(h ? (jj ? m[3] : m[2]) : (jj ? m[1] : m[0]), st * 4 + 2 * h + jj);
+      } else if constexpr (!C8) {
+        if (a.C == 4) {
+          // a document = the lane's four rows: document 2j + h of the sub-tile's eight, no exchange
+#pragma unroll
+          for (int j = 0; j < 4; ++j) push(m4[j], st * 8 + 2 * j + h);
+        } else {
+          // C == 16: a document = half of the sub-tile (rows 0..15 / 16..31, both halves of the wave); half h takes
+          // document h
+          const float d0 = max_with_other_half(fmaxf(m4[0], m4[1])), d1 = max_with_other_half(fmaxf(m4[2], m4[3]));
+          push(h ? d1 : d0, st * 2 + h);
         }
       }
     }
@@ -591,16 +607,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
     // ---- the range's totals are complete: head mean, document max, per-lane lists ----------------------
 #pragma unroll
     for (int t = 0; t < 2 * R; ++t) {
-      const long long sub_tile = (rg * R + t / 2) * 2 + (t & 1);  // 32 keys = 4 documents
-      float m[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        m[j] = max_with_other_half(fmaxf(fmaxf(tot[t][4 * j], tot[t][4 * j + 1]),
-                                         fmaxf(tot[t][4 * j + 2], tot[t][4 * j + 3]))) * inv_groups;
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        const float sc = h ? (jj ? m[3] : m[2]) : (jj ? m[1] : m[0]);
-        const long long doc = sub_tile * 4 + 2 * h + jj;
+      const long long sub_tile = (rg * R + t / 2) * 2 + (t & 1);  // 32 keys
+      auto push = [&](float sc, long long doc) __attribute__((always_inline)) {
         const bool ok = doc < a.N && sc > lsc[KL - 1];
         if (__any(ok)) {
 #pragma unroll
@@ -613,6 +621,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
           pcnt += ok ? 1 : 0;
           if (__any(pcnt == kPend)) flush();
         }
+      };
+      float m4[4];  // max over the lane's four rows 8j + 4h .. + 3, head mean applied
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        m4[j] = fmaxf(fmaxf(tot[t][4 * j], tot[t][4 * j + 1]), fmaxf(tot[t][4 * j + 2], tot[t][4 * j + 3])) * inv_groups;
+      if (a.C == 8) {
+        float m[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m[j] = max_with_other_half(m4[j]);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) push(h ? (jj ? m[3] : m[2]) : (jj ? m[1] : m[0]), sub_tile * 4 + 2 * h + jj);
+      } else if (a.C == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) push(m4[j], sub_tile * 8 + 2 * j + h);
+      } else {  // C == 16
+        const float d0 = max_with_other_half(fmaxf(m4[0], m4[1])), d1 = max_with_other_half(fmaxf(m4[2], m4[3]));
+        push(h ? d1 : d0, sub_tile * 2 + h);
       }
     }
   }
@@ -643,7 +668,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 // ---- host side -----------------------------------------------------------------------------------
 bool gemm_path_applies(const Dims& dm, int BM, int k) {
   // (one group with select_scope = ALL is the per-group kernel's case)
-  return dm.C == 8 && k <= kGemmMaxK && BM >= 64;
+  return (dm.C == 4 || dm.C == 8 || dm.C == 16) && k <= kGemmMaxK && BM >= 64;
 }
 
 GemmPlan plan_score_gemm(const Dims& dm, int BM, int k) {
@@ -699,6 +724,7 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
   a.inv_norm = dm.cos ? inv_norm : nullptr;
   a.ws = (unsigned long long*)((char*)ws + pl.off_lists);
   a.BM = BM;
+  a.C = dm.C;
   a.Hkv = dm.Hkv;
   a.N = dm.N;
   a.k = k;
@@ -725,17 +751,17 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
   }
   const unsigned blocks = (unsigned)(dm.Hkv * pl.n_qblocks * pl.n_splits);
   profile_mark(dm, false, st);
+#define MSA_GEMM(DD, TT, KK) \
+  do { \
+    if (dm.C == 8) hipLaunchKernelGGL((score_gemm_kernel<DD, TT, KK, true>), dim3(blocks), dim3(256), 0, st, a); \
+    else hipLaunchKernelGGL((score_gemm_kernel<DD, TT, KK, false>), dim3(blocks), dim3(256), 0, st, a); \
+  } while (0)
   if (k <= 8) {
-    if (dm.d == 128)
-      hipLaunchKernelGGL((score_gemm_kernel<128, 2, 8>), dim3(blocks), dim3(256), 0, st, a);
-    else
-      hipLaunchKernelGGL((score_gemm_kernel<64, 2, 8>), dim3(blocks), dim3(256), 0, st, a);
+    if (dm.d == 128) MSA_GEMM(128, 2, 8); else MSA_GEMM(64, 2, 8);
   } else {
-    if (dm.d == 128)
-      hipLaunchKernelGGL((score_gemm_kernel<128, 1, 16>), dim3(blocks), dim3(256), 0, st, a);
-    else
-      hipLaunchKernelGGL((score_gemm_kernel<64, 1, 16>), dim3(blocks), dim3(256), 0, st, a);
+    if (dm.d == 128) MSA_GEMM(128, 1, 16); else MSA_GEMM(64, 1, 16);
   }
+#undef MSA_GEMM
   profile_mark(dm, true, st);
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   return MSA_OK;

@@ -280,6 +280,9 @@ CASES = {
     "prefill140_r8_local_in_eight_wave_tiles": (15000, 60, 2, 8, 64, 128, 8, 1, 140, 90, 1e6, 6),
     "prefill96_gemm_k16": (16000, 400, 2, 4, 64, 128, 8, 1, 96, 96, 1e6, 16),
     "prefill200_gemm_k12_d64": (17000, 150, 2, 2, 64, 64, 8, 2, 100, 100, 1e4, 12),
+    # the scoring GEMM with four and sixteen chunks per document
+    "prefill90_gemm_c4": (18000, 301, 2, 4, 32, 128, 8, 1, 90, 90, 1e6, 7),
+    "prefill70_gemm_c16_k12": (19000, 99, 2, 2, 128, 64, 8, 1, 70, 70, 1e4, 12),
 }
 
 
@@ -625,6 +628,8 @@ EQ2_CASES = {
     # the paper's own setting on the matrix cores: head mean over every head, k = 16, many query tokens
     "prefill70_all_heads_gemm_k16_hkv8": (37000, 300, 8, 2, 64, 128, 8, 1, 70, 70, 1e6, 16, "cos"),
     "prefill130_all_heads_gemm_hkv4_d64_dot": (38000, 222, 4, 2, 64, 64, 8, 1, 130, 0, 1e4, 12, "dot"),
+    "prefill64_all_heads_gemm_c4": (39000, 261, 4, 2, 32, 128, 8, 1, 64, 64, 1e6, 8, "cos"),
+    "prefill100_all_heads_gemm_c16_k16": (39500, 91, 2, 4, 128, 128, 8, 1, 100, 100, 1e6, 16, "cos"),
 }
 
 
