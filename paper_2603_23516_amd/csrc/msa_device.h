@@ -142,6 +142,15 @@ __device__ __forceinline__ unsigned long long load_dev(const unsigned long long*
 }
 __device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads also fences global memory, i.e. waits
+// for every global load the wave has in flight; a stream that was started before the barrier should stay in
+// flight across it.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 // ---- arrival counter that needs no initialisation ------------------------------------------------
 // Workgroups that produced parts of one result count themselves in; the one that arrives last combines the
 // parts.  The 64-bit word holds (nonce << 16 | arrivals); a word whose upper 48 bits are not this call's nonce

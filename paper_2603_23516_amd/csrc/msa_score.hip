@@ -119,32 +119,53 @@ constexpr int kScanWaves = 4;
 //     qf = (1/r) sum_h q_h / max(|q_h|, 1e-12)        (plain mean for the dot product),
 // splits it into bf16 hi + lo and leaves the MFMA A operands of the tile in aop[s][lane]: lane 16q + n holds row n
 // (query n/2, hi for even n, lo for odd n), dims 32s + 8q .. +8 of slice s.  qf: 8 * D floats of the wave's own LDS.
+// Two steps, so that a caller can put other loads between the request for the queries and their use:
+// fold_query_load asks for the queries, fold_query_tile folds them.
+// Lane = (query lane / LPH, 16-byte piece lane % LPH): a lane loads the same piece of all r heads of
+// its query, so the head sum stays in the lane and the norms need only DPP sums over LPH <= 16 lanes.
 template <int D>
-__device__ __forceinline__ void fold_query_tile(const uint16_t* __restrict__ q_route, long long qt, int g, int BM,
-                                                int Hq, int r, int cos, float* qf, uint4 (*aop)[64], int lane) {
-  constexpr int NS = D / 32, LPH = D / 8, HPL = 64 / LPH;
-  // Lane = (query lane / LPH, 16-byte piece lane % LPH): a lane loads the same piece of all r heads of
-  // its query, so the head sum stays in the lane and the norms need only DPP sums over LPH <= 16 lanes.
+struct FoldRegs {
+  static constexpr int LPH = D / 8, HPL = 64 / LPH, PASSES = 8 / HPL;
+  uint4 v[PASSES][8];
+};
+
+template <int D>
+__device__ __forceinline__ void fold_query_load(const uint16_t* __restrict__ q_route, long long qt, int g, int BM,
+                                                int Hq, int r, FoldRegs<D>& fr, int lane) {
+  constexpr int LPH = FoldRegs<D>::LPH, HPL = FoldRegs<D>::HPL;
   const int piece = lane % LPH;
+  // No branch around a load (rows past the end re-read the last query, heads past r the last head; the fold
+  // ignores both): the loads then sit in straight-line code and the wait before the fold can leave the loads
+  // that were issued after them in flight.
 #pragma unroll
-  for (int pass = 0; pass < 8 / HPL; ++pass) {
-    const int qi = pass * HPL + lane / LPH;
-    const long long qg = qt * 8 + qi;
-    uint4 v[8];
+  for (int pass = 0; pass < FoldRegs<D>::PASSES; ++pass) {
+    long long qg = qt * 8 + pass * HPL + lane / LPH;
+    if (qg > BM - 1) qg = BM - 1;
 #pragma unroll
     for (int hh = 0; hh < 8; ++hh) {
-      v[hh] = make_uint4(0, 0, 0, 0);
-      if (qg < BM && hh < r)
-        v[hh] = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hh) * D + piece * 8);
+      const int hc = hh < r ? hh : r - 1;
+      fr.v[pass][hh] = *reinterpret_cast<const uint4*>(q_route + (qg * Hq + g * r + hc) * D + piece * 8);
     }
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void fold_query_tile(const FoldRegs<D>& fr, long long qt, int BM, int r, int cos, float* qf,
+                                                uint4 (*aop)[64], int lane) {
+  constexpr int NS = D / 32, LPH = FoldRegs<D>::LPH, HPL = FoldRegs<D>::HPL;
+  const int piece = lane % LPH;
+#pragma unroll
+  for (int pass = 0; pass < FoldRegs<D>::PASSES; ++pass) {
+    const int qi = pass * HPL + lane / LPH;
     float f[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) f[e] = 0.f;
 #pragma unroll
     for (int hh = 0; hh < 8; ++hh) {
       if (hh < r) {  // wave-uniform
-        const float x[8] = {bf16_lo(v[hh].x), bf16_hi(v[hh].x), bf16_lo(v[hh].y), bf16_hi(v[hh].y),
-                            bf16_lo(v[hh].z), bf16_hi(v[hh].z), bf16_lo(v[hh].w), bf16_hi(v[hh].w)};
+        const uint4 v = fr.v[pass][hh];
+        const float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                            bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
         float ss = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
@@ -155,7 +176,7 @@ __device__ __forceinline__ void fold_query_tile(const uint16_t* __restrict__ q_r
       }
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) qf[qi * D + piece * 8 + e] = f[e] / (float)r;
+    for (int e = 0; e < 8; ++e) qf[qi * D + piece * 8 + e] = (qt * 8 + qi < BM) ? f[e] / (float)r : 0.f;
   }
   wave_sync();
   const int rr = lane >> 4, n = lane & 15;
@@ -215,6 +236,13 @@ void score_scan_kernel(ScoreArgs a) {
   const bool active = sp < a.n_splits;
   if (!FOLD && !active) return;
 
+  // ---- the queries this wave folds are requested first: a wave's loads return in order, and behind the first tiles
+  // of every wave of the grid (tens of MB at once) they would arrive only when that burst has been served ----
+  FoldRegs<D> fr;
+  if constexpr (FOLD) {
+    if (wave < NQT) fold_query_load<D>(a.q_route, a.q0 / 8 + wave, g, a.BM, a.Hq, a.r, fr, lane);
+  }
+
   // ---- start streaming at once: the first kPrefetch tiles are requested before the prologue ----
   // Wave sp takes tiles sp, sp + n_splits, sp + 2 n_splits, ...: at any moment the waves of a head
   // read one contiguous window of the index.  Loads past the end re-read the last tile: they are
@@ -225,15 +253,22 @@ void score_scan_kernel(ScoreArgs a) {
                          : (MODE == 2) ? ((a.tiles - t0 < a.tiles_per_wave) ? a.tiles - t0 : a.tiles_per_wave)
                                        : (a.tiles - sp + S - 1) / S;  // >= 1 by construction of n_splits
   const long long i_last = n_it - 1;
-  auto tile_at = [&](long long it) { return (MODE == 2) ? t0 + it : sp + it * S; };
+  // MODE 2: the wave walks its range starting rot tiles in and wraps around, so that waves that run in step do
+  // not all ask for the same 4 KB position of their 16-tile ranges (the same memory channels) at the same moment
+  const long long rot = (MODE == 2 && n_it > 0) ? sp % n_it : 0;
+  auto tile_at = [&](long long it) {
+    if (MODE != 2) return sp + it * S;
+    const long long x = it + rot;
+    return t0 + (x >= n_it ? x - n_it : x);
+  };
   const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS + lane * 8;
   const float* ing = COS ? a.inv_norm + (long long)g * a.tiles * 16 + n : nullptr;
   uint4 buf[kPrefetch][NS];
   float binv[kPrefetch];
-  if (active) {
+  {  // a wave without a stream loads tile 0 and drops it: no branch around the loads
 #pragma unroll
     for (int u = 0; u < kPrefetch; ++u) {
-      const long long t = tile_at((u < n_it) ? u : i_last);
+      const long long t = active ? tile_at((u < n_it) ? u : i_last) : 0;
 #pragma unroll
       for (int s = 0; s < NS; ++s)
         buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512);
@@ -250,15 +285,15 @@ void score_scan_kernel(ScoreArgs a) {
     static_assert(NQT <= kScanWaves && 8 * D * 4 <= kListBytes / 2 && NS * 64 * 16 <= kListBytes / 2, "prologue scratch");
     typedef uint4 aop_tile_t[64];
     if (wave < NQT)
-      fold_query_tile<D>(a.q_route, a.q0 / 8 + wave, g, a.BM, a.Hq, a.r, COS ? 1 : 0, reinterpret_cast<float*>(smem[wave]),
+      fold_query_tile<D>(fr, a.q0 / 8 + wave, a.BM, a.r, COS ? 1 : 0, reinterpret_cast<float*>(smem[wave]),
                          reinterpret_cast<aop_tile_t*>(smem[wave] + kListBytes / 2), lane);
-    __syncthreads();
+    lds_barrier();
 #pragma unroll
     for (int t = 0; t < NQT; ++t)
 #pragma unroll
       for (int s = 0; s < NS; ++s)
         A[t][s] = as_bf16x8(reinterpret_cast<const aop_tile_t*>(smem[t] + kListBytes / 2)[s][lane]);
-    __syncthreads();  // every wave has its operands: the candidate areas are the streams' from here on
+    lds_barrier();  // every wave has its operands: the candidate areas are the streams' from here on
     if (!active) return;
   } else {
 #pragma unroll
@@ -443,7 +478,7 @@ void score_scan_kernel(ScoreArgs a) {
           for (int e = 0; e < 2; ++e) {
             const float sc = group_max_rt((acc[2 * e] + acc[2 * e + 1]) * cinv, a.C);
             if (MODE == 2) {
-              if (lead) candf[(8 * tq + 2 * rr + e) * CAPF + (int)it * dpt + ndoc] = sc;
+              if (lead) candf[(8 * tq + 2 * rr + e) * CAPF + (int)(t - t0) * dpt + ndoc] = sc;
             } else if (MODE == 1) {
               if (lead) cand[(8 * tq + 2 * rr + e) * CAP + (int)it * dpt + ndoc] = make_key(sc, (uint32_t)doc);
             } else {
@@ -522,7 +557,7 @@ void score_scan_kernel(ScoreArgs a) {
   // last tile of the index can end early
   int c_dense = 0;
   if (DENSE) {
-    const long long left = (long long)a.N - tile_at(i_last) * dpt;
+    const long long left = (long long)a.N - ((MODE == 2) ? t0 + i_last : tile_at(i_last)) * dpt;
     c_dense = (int)i_last * dpt + (int)(left < dpt ? (left < 0 ? 0 : left) : dpt);
   }
   if (MODE == 2) {
