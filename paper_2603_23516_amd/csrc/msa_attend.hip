@@ -51,6 +51,9 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   __shared__ __attribute__((aligned(16))) uint16_t stage[kAttWaves][STAGE / 2];
   __shared__ float wm[kAttWaves][16], wl[kAttWaves][16];
   __shared__ float2 estart[kAttWaves][HALF];  // e^{i p theta_u} at a wave's (re)start position
+  // theta_u for the restarts inside the stream: read from LDS there, because a global load (which a
+  // lane-indexed kernel argument is) could only be awaited together with every prefetch in flight
+  __shared__ double theta_s[HALF];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -81,7 +84,10 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       cur = cmul(cur, w);
     }
   }
-  if (tid < HALF) step16[tid] = th.e16[tid];
+  if (tid < HALF) {
+    step16[tid] = th.e16[tid];
+    theta_s[tid] = th.th[tid];
+  }
   for (int e = tid; e < a.r * HALF; e += 256) {
     const int hh = e / HALF, u = e % HALF;
     const uint16_t* qp = a.q + ((long long)bm * a.Hq + g * a.r + hh) * D;
@@ -237,11 +243,11 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     while (st < we && !locate(st, ss)) ++st;
     return st;
   };
-  // Loads of one step.  The step's base addresses are wave-uniform (scalar registers) and every
-  // lane adds a fixed 32-bit byte offset, so a load costs no address arithmetic; only the ragged
-  // last step of the local context clamps its rows.
-  const unsigned kofs = (unsigned)(n * D * 2 + 16 * rr);  // key row n, 16-byte piece rr of a 64-byte slice
-  const unsigned vofs = (unsigned)(lane * 16);            // value rows are contiguous: piece `lane` of 1 KiB
+  // Loads of one step: values first, then keys (the order in which the loop consumes them).  The step's base
+  // addresses are wave-uniform (scalar registers) and every lane adds a 32-bit byte offset.  One form for full
+  // and ragged steps -- a row past the step's last valid row re-reads that row, its score is masked -- so no
+  // branch surrounds a load: with the same loads on every path the waits in the loop can name exactly the loads
+  // they need and leave the prefetch behind them in flight.
   auto issue_loads = [&](const StepSrc& ss, uint4 (&kr)[2][NS], uint4 (&vr)[NVL], bool do_k, bool do_v) {
     const unsigned long long kaddr = (unsigned long long)ss.Kb, vaddr = (unsigned long long)ss.Vb;
     typedef const __attribute__((address_space(1))) char* gptr_t;  // global memory, not generic
@@ -258,15 +264,6 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     gptr_t kb = (gptr_t)uni64(kaddr);
     gptr_t vb = (gptr_t)uni64(vaddr);
     if (MODE == 2 && ss.is_mem) {
-      if (do_k) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          long long off;
-          gather_row(ss.st, 16 * h + n, off);
-#pragma unroll
-          for (int s = 0; s < NS; ++s) kr[h][s] = ld((gvec_t)(kb + (off * 2 + 16 * rr + s * 64)));
-        }
-      }
       if (do_v) {
 #pragma unroll
         for (int i = 0; i < NVL; ++i) {
@@ -276,37 +273,39 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
           vr[i] = ld((gvec_t)(vb + (off * 2 + (f % (D / 8)) * 16)));
         }
       }
-    } else if (ss.rows_valid == 32) {
-      if (do_k) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int s = 0; s < NS; ++s)
-            kr[h][s] = ld((gvec_t)(kb + kofs + (h * 16 * D * 2 + s * 64)));
-      }
-      if (do_v) {
-#pragma unroll
-        for (int i = 0; i < NVL; ++i) vr[i] = ld((gvec_t)(vb + vofs + i * 1024));
-      }
-    } else {
       if (do_k) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          int row = 16 * h + n;
-          row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+          long long off;
+          gather_row(ss.st, 16 * h + n, off);
 #pragma unroll
-          for (int s = 0; s < NS; ++s)
-            kr[h][s] = ld((gvec_t)(kb + (unsigned)(row * D * 2 + 16 * rr + s * 64)));
+          for (int s = 0; s < NS; ++s) kr[h][s] = ld((gvec_t)(kb + (off * 2 + 16 * rr + s * 64)));
         }
       }
+    } else {
+      const int last = ss.rows_valid - 1;
+      // the lanes' offsets are worked out here, from an opaque copy of the lane number, every time: a few
+      // instructions, whereas offsets kept across the loop would cost ten registers the loop does not have
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
       if (do_v) {
 #pragma unroll
         for (int i = 0; i < NVL; ++i) {
-          const int f = i * 64 + lane;
+          const int f = i * 64 + ln;
           int row = f / (D / 8);
           const int piece = f % (D / 8);
-          row = row < ss.rows_valid ? row : ss.rows_valid - 1;
+          row = row < last ? row : last;
           vr[i] = ld((gvec_t)(vb + (unsigned)(row * D * 2 + piece * 16)));
+        }
+      }
+      if (do_k) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          int row = 16 * h + (ln & 15);
+          row = row < last ? row : last;
+#pragma unroll
+          for (int s = 0; s < NS; ++s)
+            kr[h][s] = ld((gvec_t)(kb + (unsigned)(row * D * 2 + 16 * (ln >> 4) + s * 64)));
         }
       }
     }
@@ -344,22 +343,28 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     // ---- rotation state for this step ----------------------------------------------------------
     const bool rot = (MODE == 0) || !cur_src.is_mem;  // wave-uniform: stored-as-rotated bank keys skip it
     if (rot && cur_p != p_first) {
+      // The LDS addresses of this rare block are derived here from an opaque copy of the lane number: computed
+      // ahead of the loop they would occupy registers across the whole stream, and the spills that follow are
+      // reloaded through the vector memory counter, i.e. only together with every prefetch in flight.
+      int ln = lane, wv = wave;
+      asm volatile("" : "+v"(ln), "+v"(wv));
+      const int n_ = ln & 15, rr_ = ln >> 4;
       if (p_first == 0) {
 #pragma unroll
         for (int s2 = 0; s2 < NS / 2; ++s2)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = base0[n][32 * s2 + 8 * rr + j];
+          for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = base0[n_][32 * s2 + 8 * rr_ + j];
       } else {
         // wave-cooperative: lane u evaluates e^{i p theta_u} once, everyone combines it with e^{i n theta_u}
-        if (lane < HALF) estart[wave][lane] = cis_pos(p_first, th.th[lane]);
+        if (ln < HALF) estart[wv][ln] = cis_pos(p_first, theta_s[ln]);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int s2 = 0; s2 < NS / 2; ++s2)
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            const int u = 32 * s2 + 8 * rr + j;
-            cs[8 * s2 + j] = cmul(estart[wave][u], base0[n][u]);
+            const int u = 32 * s2 + 8 * rr_ + j;
+            cs[8 * s2 + j] = cmul(estart[wv][u], base0[n_][u]);
           }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
