@@ -239,8 +239,19 @@ void score_scan_kernel(ScoreArgs a) {
   // ---- the queries this wave folds are requested first: a wave's loads return in order, and behind the first tiles
   // of every wave of the grid (tens of MB at once) they would arrive only when that burst has been served ----
   FoldRegs<D> fr;
+  bf16x8_t A[NQT][NS];
   if constexpr (FOLD) {
     if (wave < NQT) fold_query_load<D>(a.q_route, a.q0 / 8 + wave, g, a.BM, a.Hq, a.r, fr, lane);
+  } else {
+    // prepared operands: row n of query tile t is query 8t + n/2, hi (even n) or lo (odd n) half of the folded
+    // fp32 routing query
+#pragma unroll
+    for (int t = 0; t < NQT; ++t) {
+      const long long qt = a.q0 / 8 + t;
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+        A[t][s] = as_bf16x8(a.qop[(((long long)g * a.n_qtiles + qt) * NS + s) * 64 + lane]);
+    }
   }
 
   // ---- start streaming at once: the first kPrefetch tiles are requested before the prologue ----
@@ -278,7 +289,6 @@ void score_scan_kernel(ScoreArgs a) {
 
   // ---- A operands: row n of query tile t is query 8t + n/2, hi (even n) or lo (odd n) half of the folded fp32
   // routing query ------------------------------------------------------------------------------------------
-  bf16x8_t A[NQT][NS];
   if constexpr (FOLD) {
     // wave t folds tile t; the operands pass through the candidate areas, which are free until the stream starts:
     // tile t in the second half of area t, the folding wave's scratch in the first half of its own
@@ -296,13 +306,14 @@ void score_scan_kernel(ScoreArgs a) {
     lds_barrier();  // every wave has its operands: the candidate areas are the streams' from here on
     if (!active) return;
   } else {
+    // The operands were requested ahead of the tiles; they are awaited HERE, ahead of the loop.  A wait that is
+    // first needed inside the loop sits in the loop's first block and is paid on every round: there it has to
+    // cover the entry from here too, where the operands are the youngest loads, so it would wait for everything,
+    // i.e. drain the prefetch at the head of every round.
 #pragma unroll
-    for (int t = 0; t < NQT; ++t) {
-      const long long qt = a.q0 / 8 + t;
+    for (int t = 0; t < NQT; ++t)
 #pragma unroll
-      for (int s = 0; s < NS; ++s)
-        A[t][s] = as_bf16x8(a.qop[(((long long)g * a.n_qtiles + qt) * NS + s) * 64 + lane]);
-    }
+      for (int s = 0; s < NS; ++s) asm volatile("" : "+v"(A[t][s]));
   }
 
   // This lane sees queries 8t + 2rr + e (e = 0, 1) of every tile; all 16 lanes of a row keep
@@ -356,7 +367,7 @@ void score_scan_kernel(ScoreArgs a) {
             for (int e = 0; e < 2; ++e) {
               const float mrow = group_max<16>(qmax[tq][e]);
               const int qg = a.q0 + 8 * tq + 2 * rr + e;
-              if (n == 0 && qg < a.BM) a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp] = mrow;
+              if (n == 0 && qg < a.BM) store_dev_untracked(&a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp], mrow);
             }
         } else {
           // theta = k-th largest of the published maxima of one query: bitwise search on the
@@ -451,10 +462,23 @@ void score_scan_kernel(ScoreArgs a) {
       for (int u = 0; u < kPrefetch; ++u) {
         const long long it = base + u;
         const long long t = tile_at(it);
-        uint4 cur[NS];
+        // The products read the tile (and the scores its reciprocal norms) where they landed, and only then is
+        // the next tile of this slot requested into the same registers.  (Requested earlier, while this tile is
+        // still needed, the new tile would have to land in other registers; the slots would wander from one round
+        // of the loop to the next and be copied back at its end, and a copy of a register with a load in flight
+        // waits for that load, i.e. drains the prefetch.)
+        float sraw[NQT][2];
 #pragma unroll
-        for (int s = 0; s < NS; ++s) cur[s] = buf[u][s];
-        const float cinv = binv[u];
+        for (int tq = 0; tq < NQT; ++tq) {
+          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s = 0; s < NS; ++s) acc = mfma16(A[tq][s], as_bf16x8(buf[u][s]), acc);
+          sraw[tq][0] = (acc[0] + acc[1]) * binv[u];
+          sraw[tq][1] = (acc[2] + acc[3]) * binv[u];
+          // pinned here: left alone, the compiler sinks one of the two products below the requests (and hoists the
+          // requests above them), which keeps the old reciprocal norm alive and sends the new one elsewhere
+          asm volatile("" : "+v"(sraw[tq][0]), "+v"(sraw[tq][1])::"memory");
+        }
         {
           const long long tn = tile_at((it + kPrefetch < n_it) ? it + kPrefetch : i_last);
 #pragma unroll
@@ -471,12 +495,9 @@ void score_scan_kernel(ScoreArgs a) {
         bool any_pred = false;
 #pragma unroll
         for (int tq = 0; tq < NQT; ++tq) {
-          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int s = 0; s < NS; ++s) acc = mfma16(A[tq][s], as_bf16x8(cur[s]), acc);
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
-            const float sc = group_max_rt((acc[2 * e] + acc[2 * e + 1]) * cinv, a.C);
+            const float sc = group_max_rt(sraw[tq][e], a.C);
             if (MODE == 2) {
               if (lead) candf[(8 * tq + 2 * rr + e) * CAPF + (int)(t - t0) * dpt + ndoc] = sc;
             } else if (MODE == 1) {
