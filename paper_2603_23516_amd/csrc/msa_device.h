@@ -142,16 +142,6 @@ __device__ __forceinline__ unsigned long long load_dev(const unsigned long long*
 }
 __device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// A device-scope store the compiler's wait-count bookkeeping does not see, for a store inside a loop that keeps
-// loads in flight.  Loads and stores share one counter and complete out of order with respect to each other,
-// so once a store may be pending the compiler waits for the counter to reach zero wherever it needs a load --
-// in a streaming loop that is the whole prefetch, every time round.  An unseen store only ever makes the
-// counter read higher than the compiler assumes, so its waits stay sufficient (loads complete in order among
-// themselves); nothing in the launch may rely on this store being complete before the kernel ends.
-__device__ __forceinline__ void store_dev_untracked(float* p, float v) {
-  asm volatile("global_store_dword %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
-}
-
 // Workgroup barrier for data exchanged through LDS only.  __syncthreads also fences global memory, i.e. waits
 // for every global load the wave has in flight; a stream that was started before the barrier should stay in
 // flight across it.

@@ -348,7 +348,10 @@ void score_scan_kernel(ScoreArgs a) {
       // ---- threshold exchange (long streams only): every wave publishes the best score it has
       // seen per query; a little later it adopts theta = the k-th largest of all published maxima.
       // The maxima belong to distinct documents, so at least k documents score >= theta: a valid
-      // lower bound on the k-th best score whatever the other waves have written so far.
+      // lower bound on the k-th best score whatever the other waves have written so far.  (Plain stores and
+      // loads: a maximum published on another XCD may still sit in that XCD's L2 and read here as the -inf of
+      // the reset or not at all, which only weakens the bound; device-scope accesses were measured and cost
+      // more than the tighter bound saves.)
       if (!DENSE && kEarlyFetch && a.gmax != nullptr && base == a.it_adopt - kFetchLead * kPrefetch) {
 #pragma unroll
         for (int qi = 0; qi < (kEarlyFetch ? NQ : 1); ++qi) {
@@ -367,7 +370,7 @@ void score_scan_kernel(ScoreArgs a) {
             for (int e = 0; e < 2; ++e) {
               const float mrow = group_max<16>(qmax[tq][e]);
               const int qg = a.q0 + 8 * tq + 2 * rr + e;
-              if (n == 0 && qg < a.BM) store_dev_untracked(&a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp], mrow);
+              if (n == 0 && qg < a.BM) a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp] = mrow;
             }
         } else {
           // theta = k-th largest of the published maxima of one query: bitwise search on the
