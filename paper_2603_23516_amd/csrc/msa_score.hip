@@ -586,6 +586,30 @@ void score_scan_kernel(ScoreArgs a) {
   }
   if (MODE == 2) {
     const long long doc0 = t0 * dpt;  // the wave's documents are doc0 .. doc0 + c_dense - 1
+    int pw = 1;
+    while (pw < c_dense) pw <<= 1;  // wave-uniform
+    if (pw <= 64) {
+      // 64 / pw queries per wave-wide access (lane = query-in-group * pw + document), eight accesses read from
+      // LDS before the first is stored: the runs of one query are short, a loop over single queries would spend
+      // its time on one dependent LDS read after the other
+      const int qpi = 64 / pw;
+      const int j = lane & (pw - 1), qo = lane / pw;
+      for (int i0 = 0; i0 < NQ; i0 += 8 * qpi) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int qi = i0 + u * qpi + qo;
+          v[u] = (qi < NQ && j < c_dense) ? candf[qi * CAPF + j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int qi = i0 + u * qpi + qo;
+          if (qi < NQ && a.q0 + qi < a.BM && j < c_dense)
+            a.mat[((long long)g * a.BM + a.q0 + qi) * a.N + doc0 + j] = v[u];
+        }
+      }
+      return;
+    }
     for (int qi = 0; qi < NQ; ++qi) {
       const int qg = a.q0 + qi;
       if (qg >= a.BM) break;  // wave-uniform
@@ -875,12 +899,15 @@ __global__ __launch_bounds__(256) void pool_tokens_kernel(const unsigned long lo
 }
 
 // Top-k of one row of document scores (MODE 2 of the scan): mat[g][qg][0..N).  One workgroup per row.
-//   1. every thread takes the best key of its strided share of the row; the k-th best of these 256
-//      keys (rank counting) is a lower bound theta on the k-th best key of the row: they are k distinct
+//   1. every thread takes the best score of its strided share of the row; every wave finds (a lower bound
+//      on) the k-th best of its 64 lane maxima by a bitwise search with ballots, and the largest of the four
+//      waves' bounds is a lower bound theta on the k-th best score of the row: some wave holds k distinct
 //      documents scoring at least that much;
-//   2. every key >= theta goes to LDS (typically between k and 2k of them) and is ranked by counting.
-// Exact, ties included (keys are (score, ~doc): a total order).  If more survive than LDS holds
-// (adversarial order), k rounds of a block-wide arg-max over the row take over.
+//   2. every document scoring >= theta goes to LDS (a few k of them) and is ranked by counting on the full
+//      key.
+// Exact, ties included (keys are (score, ~doc): a total order; theta compares scores only, so equal scores
+// survive together).  If more survive than LDS holds (adversarial order), k rounds of a block-wide arg-max
+// over the row take over.
 constexpr int kRowSurv = 2048;
 constexpr int kRowRegs = 32;  // scores a thread keeps in registers between the two passes
 
@@ -889,10 +916,9 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
                                                         float* __restrict__ out_score,
                                                         unsigned long long* __restrict__ out_key, int BM,
                                                         int n_sel, int N, int k) {
-  __shared__ unsigned long long tmax[256];
   __shared__ unsigned long long surv[kRowSurv];
   __shared__ unsigned long long red[4];
-  __shared__ unsigned long long theta_s;
+  __shared__ uint32_t theta_w[4];
   __shared__ int n_surv;
   const int tid = threadIdx.x;
   const int qg = blockIdx.x % BM;
@@ -916,23 +942,24 @@ __global__ __launch_bounds__(256) void topk_rows_kernel(const float* __restrict_
     const unsigned long long x = make_key(row[i], (uint32_t)i);
     best = x > best ? x : best;
   }
-  tmax[tid] = best;
-  if (tid == 0) {
-    n_surv = 0;
-    theta_s = 0ull;
-  }
-  __syncthreads();
   {
-    const int have = N < 256 ? N : 256;  // threads that hold a document
-    const int kk = k < have ? k : have;
-    int rank = 0;
-    for (int j = 0; j < 256; ++j) rank += (tmax[j] > best) ? 1 : 0;
-    if (best != 0ull && rank == kk - 1) theta_s = best;  // keys are distinct
+    // the order-preserving image of this lane's best score (0: the lane holds no document); the largest value
+    // whose low 12 bits are clear and that at least k lanes of the wave reach, 0 if fewer than k lanes hold one
+    const uint32_t ob = (uint32_t)(best >> 32);
+    uint32_t prefix = 0u;
+    for (int bit = 31; bit >= 12; --bit) {
+      const uint32_t cnd = prefix | (1u << bit);
+      if (__popcll(__ballot(ob >= cnd)) >= k) prefix = cnd;  // wave-uniform
+    }
+    if ((tid & 63) == 0) theta_w[tid >> 6] = prefix;
   }
+  if (tid == 0) n_surv = 0;
   __syncthreads();
-  const unsigned long long theta = theta_s;
+  const uint32_t th01 = theta_w[0] > theta_w[1] ? theta_w[0] : theta_w[1];
+  const uint32_t th23 = theta_w[2] > theta_w[3] ? theta_w[2] : theta_w[3];
+  const uint32_t theta = th01 > th23 ? th01 : th23;
   auto keep = [&](unsigned long long x) {
-    if (x != 0ull && x >= theta) {
+    if (x != 0ull && (uint32_t)(x >> 32) >= theta) {
       const int slot = atomicAdd(&n_surv, 1);
       if (slot < kRowSurv) surv[slot] = x;
     }
