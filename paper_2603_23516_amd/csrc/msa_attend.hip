@@ -251,9 +251,9 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   auto issue_loads = [&](const StepSrc& ss, uint4 (&kr)[2][NS], uint4 (&vr)[NVL], bool do_k, bool do_v) {
     const unsigned long long kaddr = (unsigned long long)ss.Kb, vaddr = (unsigned long long)ss.Vb;
     typedef const __attribute__((address_space(1))) char* gptr_t;  // global memory, not generic
-    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
     typedef const __attribute__((address_space(1))) u32x4_t* gvec_t;
-    auto ld = [](gvec_t p) { const u32x4_t v = *p; return make_uint4(v.x, v.y, v.z, v.w); };
+    // every key and value row is read once per (query, KV head): streaming loads (load_stream16)
+    auto ld = [](gvec_t p) { const u32x4_t v = __builtin_nontemporal_load(p); return make_uint4(v.x, v.y, v.z, v.w); };
     // readfirstlane returns a signed int: both halves go through unsigned before widening, or a
     // low word with bit 31 set would sign-extend into the high word
     auto uni64 = [](unsigned long long v) {

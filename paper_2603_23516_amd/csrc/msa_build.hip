@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void build_routing_keys_kernel(
     for (int u = 0; u < 8; ++u) {
       const int it = it0 + u;
       if (it < iters && it * RPL + rowoff < n_rows) {
-        v[u] = *reinterpret_cast<const uint4*>(src + (long long)(it * RPL + rowoff) * D + piece * 8);
+        v[u] = load_stream16(src + (long long)(it * RPL + rowoff) * D + piece * 8);
       } else {
         v[u] = make_uint4(0, 0, 0, 0);
       }

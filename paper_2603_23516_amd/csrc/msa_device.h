@@ -41,6 +41,18 @@ __device__ __forceinline__ void wait_copies_but() {  // until at most the N newe
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
+// ---- streaming loads ---------------------------------------------------------------------------
+// Data that a launch reads exactly once (the routing index of a scan, the rows of a gathered document, the bank
+// under the index build) is loaded with the non-temporal hint: the line is not kept in the caches on its way
+// through.  A plain streaming read of a large buffer tops out near 6.2 TB/s on this chip; the same loads with the
+// hint reach 6.9-7.3 TB/s (measured with loads-only kernels over 1.6 GB and 8 GB, 2 to 16 waves per CU).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ float load_stream(const float* p) { return __builtin_nontemporal_load(p); }
+
 // ---- bf16 <-> fp32 ---------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

@@ -68,8 +68,8 @@ __global__ __launch_bounds__(256) void pool_chunks_kernel(const uint16_t* __rest
       const int row = (it0 + u) * RPL + rowoff;
       if (row < n_rows) {
         const uint16_t* rp = src + (long long)row * D + pc * 8;
-        v1[u] = *reinterpret_cast<const uint4*>(rp);
-        v2[u] = *reinterpret_cast<const uint4*>(rp + D / 2);
+        v1[u] = load_stream16(rp);
+        v2[u] = load_stream16(rp + D / 2);
       } else {
         v1[u] = v2[u] = make_uint4(0, 0, 0, 0);
       }

@@ -274,6 +274,11 @@ void score_scan_kernel(ScoreArgs a) {
   };
   const uint16_t* KRg = a.KR + (long long)g * a.tiles * TILE_ELEMS + lane * 8;
   const float* ing = COS ? a.inv_norm + (long long)g * a.tiles * 16 + n : nullptr;
+  // Long streams (MODE 0) read an index far larger than the caches exactly once: streaming loads.  The short
+  // streams of MODE 1 and 2 (an index of at most a few hundred MB) measured faster with plain loads.
+  auto load_tile16 = [](const uint16_t* p) {
+    return MODE == 0 ? load_stream16(p) : *reinterpret_cast<const uint4*>(p);
+  };
   uint4 buf[kPrefetch][NS];
   float binv[kPrefetch];
   {  // a wave without a stream loads tile 0 and drops it: no branch around the loads
@@ -282,7 +287,7 @@ void score_scan_kernel(ScoreArgs a) {
       const long long t = active ? tile_at((u < n_it) ? u : i_last) : 0;
 #pragma unroll
       for (int s = 0; s < NS; ++s)
-        buf[u][s] = *reinterpret_cast<const uint4*>(KRg + t * TILE_ELEMS + s * 512);
+        buf[u][s] = load_tile16(KRg + t * TILE_ELEMS + s * 512);
       binv[u] = COS ? ing[t * 16] : 1.0f;
     }
   }
@@ -348,10 +353,12 @@ void score_scan_kernel(ScoreArgs a) {
       // ---- threshold exchange (long streams only): every wave publishes the best score it has
       // seen per query; a little later it adopts theta = the k-th largest of all published maxima.
       // The maxima belong to distinct documents, so at least k documents score >= theta: a valid
-      // lower bound on the k-th best score whatever the other waves have written so far.  (Plain stores and
-      // loads: a maximum published on another XCD may still sit in that XCD's L2 and read here as the -inf of
-      // the reset or not at all, which only weakens the bound; device-scope accesses were measured and cost
-      // more than the tighter bound saves.)
+      // lower bound on the k-th best score whatever the other waves have written so far.  The maxima
+      // are published with device-scope stores and read with device-scope loads: the waves of a head sit on all
+      // eight XCDs, each with its own L2, and a plainly stored maximum becomes visible elsewhere only when its
+      // line happens to be evicted.  With plain index loads flooding the L2 that happened soon enough; the
+      // streaming loads used here leave the L2 alone, and the bound then came from one XCD's maxima only (the
+      // k-th largest of 32 instead of 256: scan 272 -> 283 us on the 50M-token index, 256 with these accesses).
       if (!DENSE && kEarlyFetch && a.gmax != nullptr && base == a.it_adopt - kFetchLead * kPrefetch) {
 #pragma unroll
         for (int qi = 0; qi < (kEarlyFetch ? NQ : 1); ++qi) {
@@ -359,7 +366,7 @@ void score_scan_kernel(ScoreArgs a) {
           const float* src = a.gmax + ((long long)g * a.BM + qg) * a.n_splits;
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            exq[qi][j] = (lane + 64 * j < a.n_splits) ? src[lane + 64 * j] : -INFINITY;
+            exq[qi][j] = (lane + 64 * j < a.n_splits) ? load_dev(src + lane + 64 * j) : -INFINITY;
         }
       }
       if (!DENSE && a.gmax != nullptr && (base == a.it_publish || base == a.it_adopt)) {
@@ -370,7 +377,7 @@ void score_scan_kernel(ScoreArgs a) {
             for (int e = 0; e < 2; ++e) {
               const float mrow = group_max<16>(qmax[tq][e]);
               const int qg = a.q0 + 8 * tq + 2 * rr + e;
-              if (n == 0 && qg < a.BM) a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp] = mrow;
+              if (n == 0 && qg < a.BM) store_dev(&a.gmax[((long long)g * a.BM + qg) * a.n_splits + sp], mrow);
             }
         } else {
           // theta = k-th largest of the published maxima of one query: bitwise search on the
@@ -403,7 +410,7 @@ void score_scan_kernel(ScoreArgs a) {
               uint32_t ord[4];
 #pragma unroll
               for (int j = 0; j < 4; ++j)
-                ord[j] = (lane + 64 * j < a.n_splits) ? orderable(src[lane + 64 * j]) : 0u;
+                ord[j] = (lane + 64 * j < a.n_splits) ? orderable(load_dev(src + lane + 64 * j)) : 0u;
               const float th = kth_largest(ord);
               if (lane == 0) thr_s[qi] = th;
             }
@@ -486,7 +493,7 @@ void score_scan_kernel(ScoreArgs a) {
           const long long tn = tile_at((it + kPrefetch < n_it) ? it + kPrefetch : i_last);
 #pragma unroll
           for (int s = 0; s < NS; ++s)
-            buf[u][s] = *reinterpret_cast<const uint4*>(KRg + tn * TILE_ELEMS + s * 512);
+            buf[u][s] = load_tile16(KRg + tn * TILE_ELEMS + s * 512);
           binv[u] = COS ? ing[tn * 16] : 1.0f;
         }
 
@@ -641,7 +648,9 @@ void score_scan_kernel(ScoreArgs a) {
 // already computes this).
 constexpr int kAllWaves = 4;
 
-template <int D, int HKV, bool COS>
+// STREAM: the index is far larger than the caches and read once per pass -> streaming loads (load_stream16); a small
+// index that several passes re-read is served partly from the caches and measured faster with plain loads.
+template <int D, int HKV, bool COS, bool STREAM>
 __global__ __launch_bounds__(64 * kAllWaves) void score_scan_all_kernel(ScoreArgs a) {
   constexpr int NS = D / 32;
   constexpr int NQ = 8;
@@ -676,6 +685,9 @@ __global__ __launch_bounds__(64 * kAllWaves) void score_scan_all_kernel(ScoreArg
   const float* inl = COS ? a.inv_norm + n : nullptr;
   auto tile_of = [&](long long it) { return sp + (it < n_it ? it : i_last) * S; };
 
+  auto load_tile16 = [](const uint16_t* p) {
+    return STREAM ? load_stream16(p) : *reinterpret_cast<const uint4*>(p);
+  };
   uint4 buf[kPrefetch][NS];
   float binv[kPrefetch];
 #pragma unroll
@@ -684,7 +696,7 @@ __global__ __launch_bounds__(64 * kAllWaves) void score_scan_all_kernel(ScoreArg
     const long long t = tile_of(u / HKV);
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-      buf[u][s] = *reinterpret_cast<const uint4*>(KRl + ((long long)h * a.tiles + t) * TILE_ELEMS + s * 512);
+      buf[u][s] = load_tile16(KRl + ((long long)h * a.tiles + t) * TILE_ELEMS + s * 512);
     binv[u] = COS ? inl[((long long)h * a.tiles + t) * 16] : 1.0f;
   }
 
@@ -722,8 +734,7 @@ __global__ __launch_bounds__(64 * kAllWaves) void score_scan_all_kernel(ScoreArg
           const long long tn = tile_of(base + en / HKV);
 #pragma unroll
           for (int s = 0; s < NS; ++s)
-            buf[slot][s] =
-                *reinterpret_cast<const uint4*>(KRl + ((long long)hn * a.tiles + tn) * TILE_ELEMS + s * 512);
+            buf[slot][s] = load_tile16(KRl + ((long long)hn * a.tiles + tn) * TILE_ELEMS + s * 512);
           binv[slot] = COS ? inl[((long long)hn * a.tiles + tn) * 16] : 1.0f;
         }
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -1382,6 +1393,8 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
                          dm.r, dm.cos, pl.n_qtiles, a.gmax, n_gmax);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   }
+  // an index of more than 512 MB outgrows the 256 MB of cache behind the L2s even across passes
+  const bool stream_index = (size_t)dm.Hkv * dm.tiles * 16 * dm.d * 2 > ((size_t)512 << 20);
   const int wpb = pl.all_heads ? kAllWaves : kScanWaves;
   dim3 grid((pl.n_splits + wpb - 1) / wpb, pl.all_heads ? 1 : dm.Hkv), block(64 * wpb);
   profile_mark(dm, false, st);
@@ -1390,8 +1403,10 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
     if (pl.all_heads) {
 #define MSA_SCAN_ALL(DD, HH) \
   do { \
-    if (dm.cos) hipLaunchKernelGGL((score_scan_all_kernel<DD, HH, true>), grid, block, 0, st, a); \
-    else hipLaunchKernelGGL((score_scan_all_kernel<DD, HH, false>), grid, block, 0, st, a); \
+    if (dm.cos && stream_index) hipLaunchKernelGGL((score_scan_all_kernel<DD, HH, true, true>), grid, block, 0, st, a); \
+    else if (dm.cos) hipLaunchKernelGGL((score_scan_all_kernel<DD, HH, true, false>), grid, block, 0, st, a); \
+    else if (stream_index) hipLaunchKernelGGL((score_scan_all_kernel<DD, HH, false, true>), grid, block, 0, st, a); \
+    else hipLaunchKernelGGL((score_scan_all_kernel<DD, HH, false, false>), grid, block, 0, st, a); \
   } while (0)
       if (dm.d == 128) {
         if (dm.Hkv == 2) MSA_SCAN_ALL(128, 2); else if (dm.Hkv == 4) MSA_SCAN_ALL(128, 4); else MSA_SCAN_ALL(128, 8);
