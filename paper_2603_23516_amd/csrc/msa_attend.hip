@@ -19,8 +19,11 @@
 // two shuffles; the weights go back as a bf16 (hi, lo) pair in the same two columns, which is exactly
 // the B-operand layout of the second product
 //   O^T[dd][slot] += V^T[dd][key] P^T[key][slot]       (8 MFMAs per 32 keys at d = 128)
-// whose A operand (V transposed) is read from an LDS copy of the 32 value rows with 16-bit reads.
+// whose A operand (V transposed) comes out of an LDS copy of the 32 value rows through transposing reads
+// (ds_read_b64_tr_b16); the rows get there by asynchronous global -> LDS copies, two stages per wave.
 // Every accumulator of a lane belongs to its own head slot, so the rescale needs no cross-lane data.
+// A wave keeps the keys of the next two steps in flight (two register sets, two steps per trip of the loop)
+// and the values of the next step (the stage the current step does not use).
 //
 // MODE selects how the memory bank is read (the local context is always rotated here):
 //   0  raw keys, rotated in the gather with positions 0..G-1 (G % 32 == 0);
@@ -40,10 +43,9 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   constexpr int HALF = D / 2;
   constexpr int NU = (NS / 2) * 8;  // rotation pairs per lane
   constexpr int NCB = D / 16;       // output column blocks
-  constexpr int VSTRIDE = D * 2 + 8;  // bytes per staged value row (+8: conflict-free 16-bit reads)
-  constexpr int VBYTES = 32 * VSTRIDE;
+  constexpr int VBYTES = 32 * D * 2;  // the 32 value rows of a step in LDS
   constexpr int OBYTES = 16 * D * 4;  // one wave's partial output in the merge
-  constexpr int STAGE = (VBYTES > OBYTES ? VBYTES : OBYTES);
+  constexpr int STAGE = (2 * VBYTES > OBYTES ? 2 * VBYTES : OBYTES);  // two value stages per wave
 
   __shared__ float2 base0[16][HALF];  // e^{i n theta_u}: positions 0..15
   __shared__ float2 step16[HALF];     // e^{i 16 theta_u}
@@ -128,8 +130,8 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   f32x4_t o[NCB];
 #pragma unroll
   for (int c = 0; c < NCB; ++c) o[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  constexpr int VS2 = VSTRIDE / 2;  // staged row stride in 16-bit elements
-  constexpr int NVL = 32 * D * 2 / 1024;  // wave-wide 16-byte loads covering 32 value rows
+  constexpr int NVL = 32 * D * 2 / 1024;  // wave-wide 16-byte copies covering 32 value rows
+  constexpr int PPR = D / 8;              // 16-byte pieces per row
 
   // selected documents of this (query, KV head): lane j holds idx[j] (k <= 64)
   const long long idx_row = (a.idx_rows_per_b == 1) ? b : bm;
@@ -166,7 +168,8 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
   int se = sb + steps_per_split;
   if (se > steps_total) se = steps_total;
   if (se < sb) se = sb;  // nothing left for this block
-  const int spw = (se - sb + kAttWaves - 1) / kAttWaves;
+  int spw = (se - sb + kAttWaves - 1) / kAttWaves;
+  spw = (spw + 1) & ~1;  // the loop takes two steps per trip
   const int wb = sb + wave * spw;
   int we = wb + spw;
   if (we > se) we = se;
@@ -243,106 +246,126 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     while (st < we && !locate(st, ss)) ++st;
     return st;
   };
-  // Loads of one step: values first, then keys (the order in which the loop consumes them).  The step's base
-  // addresses are wave-uniform (scalar registers) and every lane adds a 32-bit byte offset.  One form for full
-  // and ragged steps -- a row past the step's last valid row re-reads that row, its score is masked -- so no
-  // branch surrounds a load: with the same loads on every path the waits in the loop can name exactly the loads
-  // they need and leave the prefetch behind them in flight.
-  auto issue_loads = [&](const StepSrc& ss, uint4 (&kr)[2][NS], uint4 (&vr)[NVL], bool do_k, bool do_v) {
-    const unsigned long long kaddr = (unsigned long long)ss.Kb, vaddr = (unsigned long long)ss.Vb;
-    typedef const __attribute__((address_space(1))) char* gptr_t;  // global memory, not generic
-    typedef const __attribute__((address_space(1))) u32x4_t* gvec_t;
-    // every key and value row is read once per (query, KV head): streaming loads (load_stream16)
-    auto ld = [](gvec_t p) { const u32x4_t v = __builtin_nontemporal_load(p); return make_uint4(v.x, v.y, v.z, v.w); };
-    // readfirstlane returns a signed int: both halves go through unsigned before widening, or a
-    // low word with bit 31 set would sign-extend into the high word
-    auto uni64 = [](unsigned long long v) {
-      const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
-      const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
-      return ((unsigned long long)hi << 32) | (unsigned long long)lo;
-    };
-    gptr_t kb = (gptr_t)uni64(kaddr);
-    gptr_t vb = (gptr_t)uni64(vaddr);
+  // Requests of one step.  The step's base addresses are wave-uniform (scalar registers) and every lane adds a
+  // 32-bit byte offset, worked out here from an opaque copy of the lane number every time (a few instructions,
+  // whereas offsets kept across the loop would cost registers the loop does not have).  One form for full and
+  // ragged steps -- a row past the step's last valid row re-reads that row, its score is masked -- so no branch
+  // surrounds a request: with the same requests on every path the waits in the loop can name exactly what they
+  // need and leave the rest in flight.
+  typedef const __attribute__((address_space(1))) char* gptr_t;  // global memory, not generic
+  typedef const __attribute__((address_space(1))) u32x4_t* gvec_t;
+  // readfirstlane returns a signed int: both halves go through unsigned before widening, or a
+  // low word with bit 31 set would sign-extend into the high word
+  auto uni64 = [](unsigned long long v) {
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+    return ((unsigned long long)hi << 32) | (unsigned long long)lo;
+  };
+  // Keys: 16-byte pieces into registers, lane (rr, n) takes rows n and 16 + n.
+  auto issue_keys = [&](const StepSrc& ss, uint4 (&kr)[2][NS]) {
+    // Plain loads: a wave-wide key load takes 64 bytes of each of 16 rows, so every 128-byte line is touched by two
+    // loads; with the streaming hint the line is not kept for the second one (measured: 112 us per call of the 50M-
+    // token decode with the hint on these loads, 101 us without; the value copies below, whole lines, keep it).
+    auto ld = [](gvec_t p) { const u32x4_t v = *p; return make_uint4(v.x, v.y, v.z, v.w); };
+    gptr_t kb = (gptr_t)uni64((unsigned long long)ss.Kb);
     if (MODE == 2 && ss.is_mem) {
-      if (do_v) {
 #pragma unroll
-        for (int i = 0; i < NVL; ++i) {
-          const int f = i * 64 + lane;
-          long long off;
-          gather_row(ss.st, f / (D / 8), off);
-          vr[i] = ld((gvec_t)(vb + (off * 2 + (f % (D / 8)) * 16)));
-        }
-      }
-      if (do_k) {
+      for (int h = 0; h < 2; ++h) {
+        long long off;
+        gather_row(ss.st, 16 * h + n, off);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          long long off;
-          gather_row(ss.st, 16 * h + n, off);
-#pragma unroll
-          for (int s = 0; s < NS; ++s) kr[h][s] = ld((gvec_t)(kb + (off * 2 + 16 * rr + s * 64)));
-        }
+        for (int s = 0; s < NS; ++s) kr[h][s] = ld((gvec_t)(kb + (off * 2 + 16 * rr + s * 64)));
       }
     } else {
       const int last = ss.rows_valid - 1;
-      // the lanes' offsets are worked out here, from an opaque copy of the lane number, every time: a few
-      // instructions, whereas offsets kept across the loop would cost ten registers the loop does not have
       int ln = lane;
       asm volatile("" : "+v"(ln));
-      if (do_v) {
 #pragma unroll
-        for (int i = 0; i < NVL; ++i) {
-          const int f = i * 64 + ln;
-          int row = f / (D / 8);
-          const int piece = f % (D / 8);
-          row = row < last ? row : last;
-          vr[i] = ld((gvec_t)(vb + (unsigned)(row * D * 2 + piece * 16)));
-        }
-      }
-      if (do_k) {
+      for (int h = 0; h < 2; ++h) {
+        int row = 16 * h + (ln & 15);
+        row = row < last ? row : last;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          int row = 16 * h + (ln & 15);
-          row = row < last ? row : last;
-#pragma unroll
-          for (int s = 0; s < NS; ++s)
-            kr[h][s] = ld((gvec_t)(kb + (unsigned)(row * D * 2 + 16 * (ln >> 4) + s * 64)));
-        }
+        for (int s = 0; s < NS; ++s)
+          kr[h][s] = ld((gvec_t)(kb + (unsigned)(row * D * 2 + 16 * (ln >> 4) + s * 64)));
       }
     }
   };
-
-  StepSrc cur_src;
-  int st = next_valid(wb, cur_src);
-  uint4 kraw[2][NS];
-  uint4 vraw[NVL];
-  if (st < we) issue_loads(cur_src, kraw, vraw, true, true);
-
-  while (st < we) {
-    const int rows_valid = cur_src.rows_valid;
-    const int p_first = cur_src.p_first;
-
-    // ---- stage this step's value rows in LDS (frees their registers), then prefetch the next
-    //      step.  The prefetch is always issued (re-reading this step when there is no next one) so
-    //      that the number of loads in flight does not depend on the path taken.
+  // Values: copied global -> LDS without passing through registers, into one of the wave's two stages.  The 16-byte
+  // slot f = 16 row + c of a stage holds piece c ^ 2 (row & 3) of value row `row`: the transposing reads of the
+  // second product (four rows x 32 bytes per 16 lanes) then touch every bank once.  Rows that are masked (past the
+  // step's last row, or not a valid selection) hold some existing row: their weights are exactly zero.
+  auto issue_values = [&](const StepSrc& ss, int into) {
+    int ln = lane, wv = wave;
+    asm volatile("" : "+v"(ln), "+v"(wv));
+    // the stage's LDS address, in a scalar register (worked out here: see above)
+    const uint32_t dst = lds_addr_of(&stage[0][0]) + (uint32_t)__builtin_amdgcn_readfirstlane(wv) * STAGE + into * VBYTES;
+    if (MODE == 2 && ss.is_mem) {
 #pragma unroll
-    for (int i = 0; i < NVL; ++i) {
-      const int f = i * 64 + lane;
-      const int row = f / (D / 8);
-      const int piece = f % (D / 8);
-      uint2* dst = reinterpret_cast<uint2*>(&stage[wave][row * VS2 + piece * 8]);
-      uint4 vv = vraw[i];
-      if (MODE == 2 && !((cur_src.mask >> row) & 1u)) vv = make_uint4(0, 0, 0, 0);  // not a selected row
-      dst[0] = make_uint2(vv.x, vv.y);
-      dst[1] = make_uint2(vv.z, vv.w);
+      for (int i = 0; i < NVL; ++i) {
+        const int f = i * 64 + ln;
+        const int row = f / PPR;
+        const int piece = (f % PPR) ^ (2 * (row & 3));
+        long long off;
+        gather_row(ss.st, row, off);
+        copy16_to_lds_async_stream64(reinterpret_cast<const char*>(a.V) + (off * 2 + piece * 16), dst + i * 1024);
+      }
+    } else {
+      const void* vb = reinterpret_cast<const void*>(uni64((unsigned long long)ss.Vb));
+      const int last = ss.rows_valid - 1;
+#pragma unroll
+      for (int i = 0; i < NVL; ++i) {
+        const int f = i * 64 + ln;
+        const int row = f / PPR;
+        const int piece = (f % PPR) ^ (2 * (row & 3));
+        const int src_row = row < last ? row : last;
+        copy16_to_lds_async_stream(vb, (uint32_t)(src_row * D * 2 + piece * 16), dst + i * 1024);
+      }
     }
-    StepSrc nxt_src = cur_src;
-    const int st_next = next_valid(st + 1, nxt_src);
-    if (st_next >= we) nxt_src = cur_src;
-    issue_loads(nxt_src, kraw, vraw, false, true);  // values now; keys once this step's keys are consumed
+  };
+  // LDS byte of this lane's transposing reads inside a stage: rows 4 rr + (n >> 2) (first read) and 16 more
+  // (second read), elements 16 c + 4 (n & 3) .. + 3; column block c is applied with an exclusive or of 32 c
+  // (the swizzle above moves piece pair c of row `row` to pair c ^ (row & 3)).
+  const int vt_lane = (4 * rr + (n >> 2)) * (D * 2) + (n >> 2) * 32 + ((n >> 1) & 1) * 16 + (n & 1) * 8;
+
+  // The loop keeps three steps in view: s0 is worked on, the keys of s1 are in flight (requested one and a half
+  // steps before their use), the values of s1 are requested at the top of s0's turn into the stage that s0 does
+  // not use, the keys of s2 in the middle of it into the registers that s0's keys leave.  When there is no further
+  // step the requests repeat the last one (results unused), so the number of requests in flight never depends on
+  // the path.  Two turns per trip of the loop, so that the two sets of key registers have fixed names.
+  StepSrc s0, s1, s2;
+  int st0 = next_valid(wb, s0);
+  int st1 = we, st2 = we;
+  uint4 kA[2][NS], kB[2][NS];
+  if (st0 < we) {
+    s1 = s0;
+    st1 = next_valid(st0 + 1, s1);
+    if (st1 >= we) s1 = s0;
+    s2 = s1;
+    if (st1 < we) st2 = next_valid(st1 + 1, s2);
+    if (st2 >= we) s2 = s1;
+    issue_keys(s0, kA);
+    issue_values(s0, 0);
+    issue_keys(s1, kB);
+  }
+
+  auto turn = [&](uint4 (&kraw)[2][NS], const int cur_stage) __attribute__((always_inline)) {
+    const bool live = st0 < we;  // wave-uniform; false: the spare second turn of the last trip
+    const int rows_valid = live ? s0.rows_valid : 0;
+    const int p_first = s0.p_first;
+    const unsigned cur_mask = s0.mask;
+    const bool cur_is_mem = s0.is_mem;
+    // The keys of this step are awaited HERE, ahead of the value request below: the compiler's wait names the
+    // requests it knows (it leaves the next step's keys, the youngest, in flight); the copies are invisible to it,
+    // and issued first they would be the youngest requests and the next step's keys would be awaited too.
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int s = 0; s < NS; ++s) asm volatile("" : "+v"(kraw[h][s].x), "+v"(kraw[h][s].y), "+v"(kraw[h][s].z), "+v"(kraw[h][s].w));
+    issue_values(s1, cur_stage ^ 1);
 
     // ---- rotation state for this step ----------------------------------------------------------
-    const bool rot = (MODE == 0) || !cur_src.is_mem;  // wave-uniform: stored-as-rotated bank keys skip it
-    if (rot && cur_p != p_first) {
+    const bool rot = (MODE == 0) || !cur_is_mem;  // wave-uniform: stored-as-rotated bank keys skip it
+    if (live && rot && cur_p != p_first) {
       // The LDS addresses of this rare block are derived here from an opaque copy of the lane number: computed
       // ahead of the loop they would occupy registers across the whole stream, and the spills that follow are
       // reloaded through the vector memory counter, i.e. only together with every prefetch in flight.
@@ -351,20 +374,20 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
       const int n_ = ln & 15, rr_ = ln >> 4;
       if (p_first == 0) {
 #pragma unroll
-        for (int s2 = 0; s2 < NS / 2; ++s2)
+        for (int s2i = 0; s2i < NS / 2; ++s2i)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = base0[n_][32 * s2 + 8 * rr_ + j];
+          for (int j = 0; j < 8; ++j) cs[8 * s2i + j] = base0[n_][32 * s2i + 8 * rr_ + j];
       } else {
         // wave-cooperative: lane u evaluates e^{i p theta_u} once, everyone combines it with e^{i n theta_u}
         if (ln < HALF) estart[wv][ln] = cis_pos(p_first, theta_s[ln]);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int s2 = 0; s2 < NS / 2; ++s2)
+        for (int s2i = 0; s2i < NS / 2; ++s2i)
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            const int u = 32 * s2 + 8 * rr_ + j;
-            cs[8 * s2 + j] = cmul(estart[wv][u], base0[n_][u]);
+            const int u = 32 * s2i + 8 * rr_ + j;
+            cs[8 * s2i + j] = cmul(estart[wv][u], base0[n_][u]);
           }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -378,52 +401,52 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     for (int h = 0; h < 2; ++h) {
       uint32_t y1[NS / 2][4], y2[NS / 2][4];
 #pragma unroll
-      for (int s2 = 0; s2 < NS / 2; ++s2) {
-        const uint4 a1 = kraw[h][s2], a2 = kraw[h][s2 + NS / 2];
+      for (int s2i = 0; s2i < NS / 2; ++s2i) {
+        const uint4 a1 = kraw[h][s2i], a2 = kraw[h][s2i + NS / 2];
         const uint32_t w1[4] = {a1.x, a1.y, a1.z, a1.w};
         const uint32_t w2[4] = {a2.x, a2.y, a2.z, a2.w};
         if (rot) {
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
-            const float2 c0 = cs[8 * s2 + 2 * jj], c1 = cs[8 * s2 + 2 * jj + 1];
+            const float2 c0 = cs[8 * s2i + 2 * jj], c1 = cs[8 * s2i + 2 * jj + 1];
             const float p0 = bf16_lo(w1[jj]), p1 = bf16_hi(w1[jj]);
             const float q0 = bf16_lo(w2[jj]), q1 = bf16_hi(w2[jj]);
-            y1[s2][jj] = pack_bf16(p0 * c0.x - q0 * c0.y, p1 * c1.x - q1 * c1.y);
-            y2[s2][jj] = pack_bf16(q0 * c0.x + p0 * c0.y, q1 * c1.x + p1 * c1.y);
+            y1[s2i][jj] = pack_bf16(p0 * c0.x - q0 * c0.y, p1 * c1.x - q1 * c1.y);
+            y2[s2i][jj] = pack_bf16(q0 * c0.x + p0 * c0.y, q1 * c1.x + p1 * c1.y);
           }
         } else {
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
-            y1[s2][jj] = w1[jj];
-            y2[s2][jj] = w2[jj];
+            y1[s2i][jj] = w1[jj];
+            y2[s2i][jj] = w2[jj];
           }
         }
       }
       f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s2 = 0; s2 < NS / 2; ++s2) {
-        acc = mfma16(as_bf16x8(make_uint4(y1[s2][0], y1[s2][1], y1[s2][2], y1[s2][3])), bq[s2], acc);
-        acc = mfma16(as_bf16x8(make_uint4(y2[s2][0], y2[s2][1], y2[s2][2], y2[s2][3])),
-                     bq[s2 + NS / 2], acc);
+      for (int s2i = 0; s2i < NS / 2; ++s2i) {
+        acc = mfma16(as_bf16x8(make_uint4(y1[s2i][0], y1[s2i][1], y1[s2i][2], y1[s2i][3])), bq[s2i], acc);
+        acc = mfma16(as_bf16x8(make_uint4(y2[s2i][0], y2[s2i][1], y2[s2i][2], y2[s2i][3])),
+                     bq[s2i + NS / 2], acc);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float v = acc[i] + dpp_f<kDppXor1>(acc[i]);  // hi + lo column
         const int row = 16 * h + 4 * rr + i;
         bool live = row < rows_valid;
-        if (MODE == 2) live = live && ((cur_src.mask >> row) & 1u);
+        if (MODE == 2) live = live && ((cur_mask >> row) & 1u);
         sc[h][i] = live ? v : -INFINITY;
       }
       // advance the rotation state by 16 positions
       if (rot) {
 #pragma unroll
-        for (int s2 = 0; s2 < NS / 2; ++s2)
+        for (int s2i = 0; s2i < NS / 2; ++s2i)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) cs[8 * s2 + j] = cmul(cs[8 * s2 + j], step16[32 * s2 + 8 * rr + j]);
+          for (int j = 0; j < 8; ++j) cs[8 * s2i + j] = cmul(cs[8 * s2i + j], step16[32 * s2i + 8 * rr + j]);
       }
     }
     if (rot) cur_p += 32;
-    issue_loads(nxt_src, kraw, vraw, true, false);  // next step's keys (this step's are in the scores now)
+    issue_keys(s2, kraw);  // the keys of the step after next (this step's are in the scores now)
 
     // ---- online softmax (exp2 domain) ---------------------------------------------------------
     float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
@@ -466,29 +489,48 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     l_run += psum;
     const bf16x8_t pb = as_bf16x8(make_uint4(pw[0], pw[1], pw[2], pw[3]));
 
-    // ---- second product: value rows are read back from LDS transposed ------------------------
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    // ---- second product: V^T straight out of the stage through transposing reads ------------------
+    // This step's values were requested in the previous turn, ahead of the keys that the top of this turn left in
+    // flight, so they have landed; the wait here states the condition itself (everything but the requests issued
+    // since: keys of the next two steps, the next values) and costs nothing when it already holds.
+    wait_copies_but<NVL + 4 * NS>();
+    {
+      const unsigned char* vt = reinterpret_cast<const unsigned char*>(&stage[wave][0]) + cur_stage * VBYTES;
+      // (an opaque copy: the eight addresses of a stage, known ahead of the loop, would be kept in registers
+      // across it, which the loop does not have)
+      int vl = vt_lane;
+      asm volatile("" : "+v"(vl));
 #pragma unroll
-    for (int c = 0; c < NCB; ++c) {
-      uint32_t w[4];
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        // k-slots 2jj, 2jj+1 of this lane: keys 4rr + j (j < 4, first sub-tile), 16 + 4rr + j - 4
-        const int j0 = 2 * jj, j1 = 2 * jj + 1;
-        const int r0 = (j0 < 4) ? 4 * rr + j0 : 16 + 4 * rr + (j0 - 4);
-        const int r1 = (j1 < 4) ? 4 * rr + j1 : 16 + 4 * rr + (j1 - 4);
-        const uint32_t lo = stage[wave][r0 * VS2 + 16 * c + n];
-        const uint32_t hi = stage[wave][r1 * VS2 + 16 * c + n];
-        w[jj] = lo | (hi << 16);
+      for (int c = 0; c < NCB; ++c) {
+        const unsigned char* vp = vt + (vl ^ (32 * c));
+        const s16x4_t v0 = lds_read_tr16(vp);                   // keys 4 rr .. + 3
+        const s16x4_t v1 = lds_read_tr16(vp + 16 * (D * 2));    // keys 16 + 4 rr .. + 3
+        const bf16x8_t av = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+        o[c] = mfma16(av, pb, o[c]);
       }
-      o[c] = mfma16(as_bf16x8(make_uint4(w[0], w[1], w[2], w[3])), pb, o[c]);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    st = st_next;
-    cur_src = nxt_src;
+    // ---- next turn: s1 becomes the step at hand, a new s2 is located --------------------------------
+    st0 = st1;
+    s0 = s1;
+    st1 = st2;
+    s1 = s2;
+    if (st2 < we) {
+      StepSrc s3 = s2;
+      st2 = next_valid(st2 + 1, s3);
+      if (st2 < we) s2 = s3;
+    }
+  };
+  // Always two turns per trip: an exit between them would give the loop a second way back to its head (the exit
+  // is folded into the latch), on which the keys requested by the first turn are the youngest requests, and the
+  // waits of the first turn would be placed for that path, i.e. drain everything.  With an odd number of steps the
+  // second turn of the last trip works on a repeat of the last step with every row masked.
+  if (st0 < we) {
+    do {
+      turn(kA, 0);
+      turn(kB, 1);
+    } while (st0 < we);
   }
+  wait_copies_but<0>();  // the repeated requests of the last turns still write into the stages
 
   // ---- merge the four waves ----------------------------------------------------------------------
   l_run += __shfl_xor(l_run, 16, 64);

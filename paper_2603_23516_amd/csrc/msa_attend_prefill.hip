@@ -33,11 +33,6 @@ namespace msa {
 
 typedef float f32x16p_t __attribute__((ext_vector_type(16)));
 
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ s16x4_t lds_read_tr16(const unsigned char* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)p);
-}
-
 __device__ __forceinline__ f32x16p_t mfma32p(bf16x8_t a, bf16x8_t b, f32x16p_t c) {
   // D(32x32) += A(32x16) * B(16x32).  Lane l: A[l%32][8(l/32)..+8], B[8(l/32)..+8][l%32],
   // D register i: row (i%4) + 8(i/4) + 4(l/32), column l%32.

@@ -35,6 +35,21 @@ __device__ __forceinline__ void copy4_to_lds_async(const void* gbase, uint32_t g
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                :: "v"(goff), "s"(gbase), "s"(base) : "memory", "m0");
 }
+// 16 bytes per lane of data that is read once (streaming hint, see load_stream16); the destination is given as an
+// LDS byte address in a scalar register (lds_addr_of).  Source: scalar base + lane offset ...
+__device__ __forceinline__ void copy16_to_lds_async_stream(const void* gbase, uint32_t goff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+               :: "v"(goff), "s"(gbase), "s"(lds_addr) : "memory", "m0");
+}
+// ... or a full 64-bit address per lane (rows gathered from anywhere in a large allocation).
+__device__ __forceinline__ void copy16_to_lds_async_stream64(const void* gaddr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
+               :: "v"(gaddr), "s"(lds_addr) : "memory", "m0");
+}
+// LDS byte address of a __shared__ object
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
 #pragma clang diagnostic pop
 template <int N>
 __device__ __forceinline__ void wait_copies_but() {  // until at most the N newest loads / copies are outstanding
@@ -45,13 +60,23 @@ __device__ __forceinline__ void wait_copies_but() {  // until at most the N newe
 // Data that a launch reads exactly once (the routing index of a scan, the rows of a gathered document, the bank
 // under the index build) is loaded with the non-temporal hint: the line is not kept in the caches on its way
 // through.  A plain streaming read of a large buffer tops out near 6.2 TB/s on this chip; the same loads with the
-// hint reach 6.9-7.3 TB/s (measured with loads-only kernels over 1.6 GB and 8 GB, 2 to 16 waves per CU).
+// hint reach 6.9-7.3 TB/s (measured with loads-only kernels over 1.6 GB and 8 GB, 2 to 16 waves per CU).  Only for
+// accesses that take whole 128-byte lines in one instruction: a line that two instructions share is fetched again
+// for the second one, and the hint then costs more than it gives.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_stream16(const void* p) {
   const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ float load_stream(const float* p) { return __builtin_nontemporal_load(p); }
+
+// ---- transposing LDS read -------------------------------------------------------------------------
+// ds_read_b64_tr_b16: among 16 consecutive lanes, lane j hands in the address of elements 4 (j % 4) .. + 3 of row
+// j / 4 (four rows of 16 two-byte elements, anywhere in LDS) and receives element j of rows 0 .. 3.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ s16x4_t lds_read_tr16(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)p);
+}
 
 // ---- bf16 <-> fp32 ---------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
