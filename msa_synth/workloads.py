@@ -34,9 +34,9 @@ class Workload:
 def planted_chunk(q_b, r, g, noise, a):
     """Tokens of one planted chunk for KV group g of one query token.
     q_b [Hq, d] float64 query; noise [P, d] float64 (the chunk's original contents).
-    Returns bf16 bits [P, d] of a * u + noise, u = mean unit query of the group, unit per-dim variance."""
-    qh = q_b[g * r:(g + 1) * r]
-    u = (qh / np.linalg.norm(qh, axis=-1, keepdims=True)).mean(axis=0)
+    Returns bf16 bits [P, d] of a * u + noise, where u points along the plain sum of the group's query heads (an
+    input recipe: a direction that correlates with every head of the group) and has unit per-dim variance."""
+    u = q_b[g * r:(g + 1) * r].sum(axis=0)
     u = u / np.linalg.norm(u) * np.sqrt(u.shape[0])
     return S.f64_to_bf16_bits(a * u[None, :] + noise)
 

@@ -312,13 +312,15 @@ void attend_partial_kernel(AttendArgs a, RopeTheta th) {
     } else {
       const void* vb = reinterpret_cast<const void*>(uni64((unsigned long long)ss.Vb));
       const int last = ss.rows_valid - 1;
+      // slot f = 64 i + lane: row 64 i / PPR + lane / PPR, and the piece (with its swizzle) is the same for every i
+      constexpr int RPC = 64 / PPR;  // rows per copy (a multiple of 4)
+      const int lrow = (ln & 63) / PPR;
+      const int poff = (((ln & 63) % PPR) ^ (2 * (lrow & 3))) * 16;
 #pragma unroll
       for (int i = 0; i < NVL; ++i) {
-        const int f = i * 64 + ln;
-        const int row = f / PPR;
-        const int piece = (f % PPR) ^ (2 * (row & 3));
+        const int row = i * RPC + lrow;
         const int src_row = row < last ? row : last;
-        copy16_to_lds_async_stream(vb, (uint32_t)(src_row * D * 2 + piece * 16), dst + i * 1024);
+        copy16_to_lds_async_stream(vb, (uint32_t)(src_row * D * 2 + poff), dst + i * 1024);
       }
     }
   };

@@ -71,11 +71,12 @@ def test_pool_matches_reshape_mean_and_layout():
 
 
 def test_routing_keys_rounding_and_inv_norm():
+    import torch
     K = _bank(4, 4, 2, 16, 8)
     KRb, inv = O.routing_keys(K, 4)
     exact = O.pool_chunks(K, 4)
     assert np.all(np.abs(KRb - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-300)   # within half an ulp
-    assert np.array_equal(S.bf16_bits_to_f64(S.f64_to_bf16_bits(KRb)), KRb)   # representable
+    assert np.array_equal(torch.from_numpy(KRb).to(torch.bfloat16).to(torch.float64).numpy(), KRb)   # representable (PyTorch's cast)
     assert np.allclose(inv * np.linalg.norm(KRb, axis=-1), 1.0, rtol=1e-14)
     Kz = np.zeros((1, 1, 4, 4))
     assert O.routing_keys(Kz, 4)[1][0, 0] == 1.0 / O.EPS_NORM                  # zero key: guarded
