@@ -32,7 +32,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # WRITE_SIZE runs of this file, each counter scaled by its reading for a plain copy of known size; the summaries, with
 # the kernel signatures and the commit they were measured at, are profiles/pmc_traffic_<workload>.txt.  Only with the
 # default flags (un-pooled bank, per-group selection); None where no such run exists.
-MEASURED_TRAFFIC = {     # measured at commit e2b7106
+MEASURED_TRAFFIC = {     # measured at commit b048563
     "cfg5_decode_50m": {"score": 1641.9e6, "attend": 621.9e6},     # algorithmic 1625.0 / 604.0 MB: x1.010 / x1.030
     "cfg3_batch32_4m": {"score": 155.9e6, "attend": 1359.3e6},     # 136.3 / 1342.2 MB: x1.144 (score matrix round trip) / x1.013
     "cfg2_decode_1m": {"score": 34.8e6, "attend": 52.5e6},         # 34.1 / 41.9 MB: x1.020 / x1.251 (split partials)
