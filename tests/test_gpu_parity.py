@@ -283,6 +283,9 @@ CASES = {
     # the scoring GEMM with four and sixteen chunks per document
     "prefill90_gemm_c4": (18000, 301, 2, 4, 32, 128, 8, 1, 90, 90, 1e6, 7),
     "prefill70_gemm_c16_k12": (19000, 99, 2, 2, 128, 64, 8, 1, 70, 70, 1e4, 12),
+    # 512 (query, KV head) pairs: one split each, 37 steps per pair = 10, 10, 10, 7 per wave (the decode loop takes two
+    # steps per trip: an odd share ends with a masked spare turn), documents of 11 steps (rotation restarts mid-trip)
+    "batch64_odd_steps_per_wave": (20000, 40, 8, 4, 352, 128, 352, 64, 1, 100, 1e6, 3),
 }
 
 
@@ -499,6 +502,8 @@ POOLED_CASES = {
     "c4_d128": (25000, 50, 2, 4, 32, 128, 8, 3, 1, 20, 1e6, 9),
     "c32_whole_steps": (26000, 12, 2, 4, 256, 128, 8, 1, 2, 33, 1e6, 3),
     "c64_whole_steps_d64": (27000, 9, 1, 2, 512, 64, 8, 2, 1, 0, 1e4, 4),
+    # stored-rotated keys with whole steps, 512 (query, KV head) pairs of 37 steps: 10, 10, 10, 7 per wave
+    "c352_batch64_odd_steps_per_wave": (28000, 12, 8, 4, 2816, 128, 8, 64, 1, 100, 1e6, 3),
 }
 
 
