@@ -470,12 +470,16 @@ def main():
     build_gbs = ab["build"] / (build_ms * 1e-3) / 1e9
 
     # the MFMA GEMM path (many query tokens).  Algorithmic flops: the folded form of Eq. 2, one routing query per (token,
-    # KV group): 2 * tokens * Hkv * keys * d.  Issued: twice that, the query travels as a bf16 (hi, lo) pair
+    # KV group): 2 * tokens * Hkv * keys * d.  Issued: twice that where the query travels as a bf16 (hi, lo) pair (head
+    # mean over every head; d = 64; 4 or 16 chunks per document), once where the product runs on the hi parts alone and
+    # the few candidates inside the error band are scored again exactly (per-group selections, cosine, d = 128, C = 8)
     flops = flops_issued = None
+    one_pass = False
     if nq >= 64 and k <= 16 and wl.C in (4, 8, 16):          # both selection scopes do the same matrix work
         tiles = (wl.N * wl.C + 15) // 16
+        one_pass = args.scope == "group" and wl.d == 128 and wl.C == 8
         flops = 2.0 * nq * wl.Hkv * wl.N * wl.C * wl.d
-        flops_issued = 2.0 * nq * wl.Hkv * tiles * 16 * 2 * wl.d
+        flops_issued = 2.0 * nq * wl.Hkv * tiles * 16 * (1 if one_pass else 2) * wl.d
     # shared selection and many tokens: attention is a dense contraction on the matrix cores.  Algorithmic flops: two
     # products (QK, PV) of 2 flops per multiply-add over the keys each token sees; issued: twice that (bf16 (hi, lo) pairs
     # of Q and P)
@@ -504,7 +508,8 @@ def main():
                       "entry_point_ms": score_call_ms,
                       "entry_point_frac": ab["score"] / (score_call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS} if flops is None else
                      {"bound": "mfma", "kernel": ("score_gemm_all_kernel" if args.scope == "all" else "score_gemm_kernel") +
-                      " (inside msa_score_topk = fold + GEMM + merge)",
+                      (" on the hi parts of the queries (inside msa_score_topk = fold + one-pass GEMM + candidates and exact "
+                       "scores + gated two-pass GEMM and merge)" if one_pass else " (inside msa_score_topk = fold + GEMM + merge)"),
                       "achieved": flops / (score_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                       "unit": "TFLOP/s", "frac": flops / (score_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                       "traffic": TRAFFIC.get("score"),

@@ -184,7 +184,9 @@ int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t d
  *   out_score out  fp32  [B][M'][S][k], may be NULL
  *   workspace      >= msa_score_topk_workspace_bytes(cfg, B, M, k); contents undefined on entry/exit
  * Scores are accumulated in fp32; each query is carried as a bf16 (hi, lo) pair, so a score differs
- * from exact arithmetic by a few 1e-6 relative.
+ * from exact arithmetic by a few 1e-6 relative.  (With many query tokens, cosine, d = 128 and eight chunks per
+ * document the matrix product runs on the hi parts alone as a filter, and the reported scores of the winners are
+ * recomputed in fp32 from the fp32 folded query: the selection is the same as with exact scores.)
  */
 int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
                    const void* KR, const float* inv_norm, int32_t k, int32_t* out_idx,

@@ -38,11 +38,18 @@ def _compile(src):
 
 def build_all(verbose=False, only=None):
     """Compile libmsa.so (the product) and libmsa_synth.so (the input generator's device fill).  `only`: a list of
-    source base names to recompile (the other objects are reused as they are; for quick rebuilds by hand)."""
+    source base names to recompile (the other objects are reused unless their source or a header is newer; for quick
+    rebuilds by hand)."""
     os.makedirs(OBJDIR, exist_ok=True)
     srcs = LIBMSA_SRC + LIBSYNTH_SRC
-    todo = [s for s in srcs if only is None or os.path.basename(s) in only
-            or not os.path.exists(os.path.join(OBJDIR, os.path.basename(s) + ".o"))]
+    import glob
+    headers = glob.glob(os.path.join(HERE, "csrc", "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    newest_header = max(os.path.getmtime(h) for h in headers)
+
+    def stale(src):   # no object yet, or older than its source or than any header
+        obj = os.path.join(OBJDIR, os.path.basename(src) + ".o")
+        return not os.path.exists(obj) or os.path.getmtime(obj) < max(os.path.getmtime(src), newest_header)
+    todo = [s for s in srcs if only is None or os.path.basename(s) in only or stale(s)]
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         done = dict(zip(todo, ex.map(_compile, todo)))
     out = "".join(o for _, o in done.values())

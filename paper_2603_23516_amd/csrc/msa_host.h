@@ -28,12 +28,29 @@ struct GemmPlan {
   int n_splits;          // key-range splits per (head, token block)
   int stages_per_split;  // 64-key stages per split (all heads: ranges of stages per split)
   size_t off_lists;      // byte offset of the candidate lists (after the folded fp32 queries)
+  // One-pass filter (cosine, d = 128, eight chunks per document, one selection per KV group): the product runs on
+  // the bf16 hi parts of the folded queries alone; every document whose one-pass score lies within twice the error
+  // bound of the k-th best one-pass score is scored again exactly, and token blocks whose per-lane lists overflow
+  // inside that band are redone by the two-pass kernel.
+  int filter;            // 1: the filter applies
+  int list_len;          // entries per per-lane list (8: k <= 8, 16: k <= 16)
+  int tokens_per_wg;     // query tokens per workgroup = per fallback flag
+  size_t off_eps;        // fp32 [BM][Hkv]: bound on |one-pass score - exact score| per (token, KV group)
+  size_t off_flags;      // int32 [Hkv][n_qblocks]: 1 = this token block is redone by the two-pass kernel
+  size_t off_flists;     // 64-bit keys [Hkv][BM][n_splits][2][list_len]: the per-lane lists of the one-pass product
+                         // (the two-pass kernel's lists, off_lists, reuse this memory afterwards)
   size_t ws_bytes;
 };
+constexpr int kFilterMaxCand = 32;
 bool gemm_path_applies(const Dims& dm, int BM, int k);
 GemmPlan plan_score_gemm(const Dims& dm, int BM, int k);
+// Enqueues the scoring kernels.  Without the filter the per-split lists are left for score_merge_kernel.  With it
+// the exact winners of every token are written to out_idx / out_score (or out_key: sorted 64-bit keys, token pooling),
+// and the lists of the flagged token blocks are left for a merge that is gated by *gate_flags (device int32
+// [Hkv][n_qblocks], null without the filter).
 int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_route, int BM,
-                           const void* KR, const float* inv_norm, int k, void* ws, hipStream_t st);
+                           const void* KR, const float* inv_norm, int k, void* ws, hipStream_t st,
+                           int32_t* out_idx, float* out_score, unsigned long long* out_key, const int** gate_flags);
 
 // Work split of the routing scan (depends only on the problem size, so the workspace size is a
 // pure function of the arguments).

@@ -1041,7 +1041,8 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
                                                           float* __restrict__ out_score,
                                                           unsigned long long* __restrict__ out_key,
                                                           int BM, int Hkv, int n_lists_total, int k,
-                                                          int lpp, int parts) {
+                                                          int lpp, int parts, const int* __restrict__ gate,
+                                                          int gate_tokens, int gate_blocks) {
   __shared__ unsigned long long sub[kMaxSub];
   __shared__ unsigned long long surv[kMaxSurv];
   __shared__ unsigned long long red[4];
@@ -1051,6 +1052,8 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const unsigned long lo
   const int part = blockIdx.x % parts;
   const int qg = (blockIdx.x / parts) % BM;
   const int g = blockIdx.x / parts / BM;
+  // behind the one-pass filter of the scoring GEMM: only the token blocks it flagged have lists to merge
+  if (gate != nullptr && gate[g * gate_blocks + qg / gate_tokens] == 0) return;
   const int l0 = part * lpp;
   const int n_lists = (n_lists_total - l0 < lpp) ? n_lists_total - l0 : lpp;
   const int T = n_lists * k;
@@ -1337,23 +1340,27 @@ int launch_score(const Dims& dm, const ScorePlan& pl, const void* q_route, int B
     return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
   };
   // combine the per-split lists of every (query, selection): one level, or two for very many lists
+  const int* gate = nullptr;  // scoring GEMM with its one-pass filter: the token blocks whose lists are to be merged
+  const int gate_tokens = pl.use_gemm ? (pl.gemm.tokens_per_wg > 0 ? pl.gemm.tokens_per_wg : 1) : 1;
+  const int gate_blocks = pl.use_gemm ? pl.gemm.n_qblocks : 0;
   auto merge = [&](const unsigned long long* lists, int n_lists) -> int {
     if (pl.merge_parts > 1) {
       unsigned long long* part_keys = (unsigned long long*)((char*)ws + pl.off_part);
       hipLaunchKernelGGL(score_merge_kernel, dim3(BM * pl.n_sel * pl.merge_parts), dim3(256), 0, st, lists,
                          (int32_t*)nullptr, (float*)nullptr, part_keys, BM, pl.n_sel, n_lists, k,
-                         pl.merge_lpp, pl.merge_parts);
+                         pl.merge_lpp, pl.merge_parts, gate, gate_tokens, gate_blocks);
       if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
       lists = part_keys;
       n_lists = pl.merge_parts;
     }
     hipLaunchKernelGGL(score_merge_kernel, dim3(BM * pl.n_sel), dim3(256), 0, st, lists, out_idx, out_score,
-                       tok_keys, BM, pl.n_sel, n_lists, k, n_lists, 1);
+                       tok_keys, BM, pl.n_sel, n_lists, k, n_lists, 1, gate, gate_tokens, gate_blocks);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
     return pool_tokens();
   };
   if (pl.use_gemm) {
-    const int rc = launch_score_gemm_scan(dm, pl.gemm, q_route, BM, KR, inv_norm, k, ws, st);
+    const int rc = launch_score_gemm_scan(dm, pl.gemm, q_route, BM, KR, inv_norm, k, ws, st, out_idx, out_score,
+                                          tok_keys, &gate);
     if (rc != MSA_OK) return rc;
     return merge((const unsigned long long*)((const char*)ws + pl.gemm.off_lists), pl.gemm.n_splits);
   }

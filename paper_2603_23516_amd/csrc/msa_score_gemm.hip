@@ -55,10 +55,15 @@ __device__ __forceinline__ float gsum(float x) {
 
 // One wave per (token, KV group): qf[token][g][:] = (1/r) sum_h q_h / max(|q_h|, 1e-12)  (or the plain
 // mean for the dot product).
+// With eps != null (one-pass filter) it also writes, per (token, KV group), a bound on the difference between the
+// score of any document computed from the bf16 hi parts of qf alone and its exact score: for a unit key,
+// |(qf - hi(qf)) . key| <= |qf - hi(qf)|, plus the rounding of two fp32 accumulations over d products; and it clears
+// the fallback flags of the token blocks.
 template <int D>
 __global__ __launch_bounds__(64) void fold_queries_kernel(const uint16_t* __restrict__ q_route,
                                                           float* __restrict__ qf, int Hq, int Hkv,
-                                                          int r, int cos) {
+                                                          int r, int cos, float* __restrict__ eps,
+                                                          int* __restrict__ flags, int n_flags) {
   constexpr int LPH = D / 8, HPL = 64 / LPH;
   const int lane = threadIdx.x;
   const int g = blockIdx.x % Hkv;
@@ -86,10 +91,26 @@ __global__ __launch_bounds__(64) void fold_queries_kernel(const uint16_t* __rest
 #pragma unroll
     for (int e = 0; e < 8; ++e) f[e] += __shfl_xor(f[e], off, 64);
   }
+  float err2 = 0.f, n2 = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float x = f[e] / (float)r;
+    float hi, lo;
+    split_bf16(x, hi, lo);
+    err2 += lo * lo;
+    n2 += x * x;
+    f[e] = x;
+  }
   if (hs == 0) {
     float* dst = qf + (qg * Hkv + g) * D + piece * 8;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) dst[e] = f[e] / (float)r;
+    for (int e = 0; e < 8; ++e) dst[e] = f[e];
+  }
+  if (eps != nullptr) {
+    err2 = gsum<LPH>(err2);  // lanes 0 .. LPH-1 hold the D elements
+    n2 = gsum<LPH>(n2);
+    if (lane == 0) eps[qg * Hkv + g] = 1.01f * sqrtf(err2) + 2e-5f * sqrtf(n2) + 1e-7f;
+    if (lane == 0 && (int)blockIdx.x < n_flags) flags[blockIdx.x] = 0;
   }
 }
 
@@ -98,7 +119,8 @@ struct GemmArgs {
   const float* qf;          // [BM][Hkv][D]
   const uint16_t* KR;       // tiled
   const float* inv_norm;    // may be null (dot)
-  unsigned long long* ws;   // [Hkv][BM][n_splits][k]
+  unsigned long long* ws;   // [Hkv][BM][n_splits][k]   (one-pass filter: [Hkv][BM][n_splits][2][list length])
+  const int* flags;         // two-pass kernel behind the filter: [Hkv][n_qblocks], a workgroup runs only if its block's is set
   int BM, Hkv, N, k;
   long long tiles;          // 16-key tiles per head
   int n_qblocks, n_splits, stages_per_split;
@@ -106,7 +128,10 @@ struct GemmArgs {
 
 // C8: eight chunks per document, the benchmark shape, known at compile time (it fills the register file exactly; the
 // general epilogue for C = 4 / 16 is a second instantiation).
-template <int D, int TB, int KL, bool C8>
+// HIONLY: the one-pass filter.  Only the bf16 hi parts of the queries are multiplied (half the matrix work, half the
+// operand registers); the scores are approximate, within the bound that fold_queries_kernel writes, and both per-lane
+// lists of every token are written out whole, for score_filter_select_kernel.
+template <int D, int TB, int KL, bool C8, bool HIONLY>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void score_gemm_kernel(GemmArgs a) {
   constexpr int kGemmK = KL;               // per-lane list length
   constexpr int kGemmTokens = 128 * TB;    // tokens per workgroup (4 waves x TB blocks of 32)
@@ -137,6 +162,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   const int rest = blockIdx.x / a.Hkv;
   const int qb = rest % a.n_qblocks;
   const int ks = rest / a.n_qblocks;
+  if (!HIONLY && a.flags != nullptr && a.flags[g * a.n_qblocks + qb] == 0) return;  // block-uniform, ahead of any barrier
   const long long n_sub = (a.tiles + 1) / 2;
   const long long n_stage = (n_sub + 1) / 2;
   const long long s0 = (long long)ks * a.stages_per_split;
@@ -146,7 +172,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 
   // ---- B operands: this wave's 64 tokens, hi and lo halves, resident for the whole kernel -----
   const int tok0 = qb * kGemmTokens + wave * 32 * TB;
-  bf16x8_t Bhi[TB][NS8], Blo[TB][NS8];
+  bf16x8_t Bhi[TB][NS8], Blo[HIONLY ? 1 : TB][HIONLY ? 1 : NS8];
 #pragma unroll
   for (int cb = 0; cb < TB; ++cb) {
     const int tok = tok0 + 32 * cb + c;
@@ -172,7 +198,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
         wl[jj] = pack_bf16(l0, l1);
       }
       Bhi[cb][s] = as_bf16x8(make_uint4(wh[0], wh[1], wh[2], wh[3]));
-      Blo[cb][s] = as_bf16x8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
+      if constexpr (!HIONLY) Blo[cb][s] = as_bf16x8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
     }
   }
 
@@ -194,7 +220,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   // would help more but does not fit the register budget of two waves per SIMD: three entries spill).  The
   // acceptance test uses the list's last entry as it was at the last flush: a valid (if slightly stale)
   // lower bound, so nothing that belongs in the list is ever turned away.
-  constexpr int kPend = 2;
+  constexpr int kPend = HIONLY ? 4 : 2;  // the one-pass kernel has the registers of the lo operands to spare
   float psc[TB][kPend];
   int pdoc[TB][kPend];
   int pcnt[TB];
@@ -289,7 +315,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 #pragma unroll
       for (int cb = 0; cb < TB; ++cb) {
         acc[cb] = mfma32(av[s], Bhi[cb][s], acc[cb]);
-        acc[cb] = mfma32(av[s], Blo[cb][s], acc[cb]);
+        if constexpr (!HIONLY) acc[cb] = mfma32(av[s], Blo[cb][s], acc[cb]);
       }
     }
     float inv[16];
@@ -379,6 +405,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 
 #pragma unroll
   for (int cb = 0; cb < TB; ++cb) flush(cb);
+  if constexpr (HIONLY) {
+    // both lists of every token as they are (sorted, zero = empty slot): [Hkv][BM][n_splits][2][KL]
+#pragma unroll
+    for (int cb = 0; cb < TB; ++cb) {
+      const int tok = tok0 + 32 * cb + c;
+      if (tok < a.BM) {
+        unsigned long long* dst = a.ws + ((((long long)g * a.BM + tok) * a.n_splits + ks) * 2 + h) * kGemmK;
+#pragma unroll
+        for (int p = 0; p < kGemmK; ++p)
+          dst[p] = (ldoc[cb][p] >= 0) ? make_key(lsc[cb][p], (uint32_t)ldoc[cb][p]) : 0ull;
+      }
+    }
+    return;
+  }
   // ---- merge the two half-wave lists of every token, write sorted keys -----------------------
 #pragma unroll
   for (int cb = 0; cb < TB; ++cb) {
@@ -665,6 +705,158 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   }
 }
 
+// ---- one-pass filter: candidates, exact scores ----------------------------------------------------------
+// One wave per (token, KV group).  Input: the 2 * n_splits per-lane lists of the one-pass product (sorted, KL
+// entries each, zero = empty), whose scores s~ differ from the exact scores s by at most eps.  Let t~ be the k-th
+// largest s~.  The k documents with the largest s~ all have s >= t~ - eps, so the k-th largest exact score is at
+// least t~ - eps, and every document of the exact top-k has s~ >= s - eps >= t~ - 2 eps: the candidates are all
+// list entries with s~ >= t~ - 2 eps.  A lane's list holds the KL >= k best documents that lane saw; it can have
+// dropped a candidate only if it is full and its last entry is itself inside the band -- then, or with more than
+// kFilterMaxCand candidates, the token's block is flagged and redone by the two-pass kernel.
+//
+constexpr int kFilterMaxEntries = 1024;  // 2 * n_splits * KL
+
+// The exact scores of the candidates follow in the same wave: Eq. 2 in fp32 from the folded fp32 query and the bf16
+// routing keys (d = 128, eight chunks per document: eight lanes per chunk, 16 dims per lane), document max, then the k
+// best by (score descending, index ascending), written as the final selection (or, for token pooling, as the sorted
+// keys of the token).  Four (token, KV group) pairs per workgroup, one per wave; the waves never synchronise.
+__global__ __launch_bounds__(256) void score_filter_select_kernel(const unsigned long long* __restrict__ lists,
+                                                                  const float* __restrict__ eps,
+                                                                  const float* __restrict__ qf,
+                                                                  const uint16_t* __restrict__ KR,
+                                                                  const float* __restrict__ inv_norm,
+                                                                  int* __restrict__ flags, int32_t* __restrict__ out_idx,
+                                                                  float* __restrict__ out_score,
+                                                                  unsigned long long* __restrict__ out_key, int BM,
+                                                                  int Hkv, int n_splits, int KL, int k,
+                                                                  int tokens_per_wg, int n_qblocks, long long tiles) {
+  constexpr int PER = kFilterMaxEntries / 64;
+  constexpr int D = 128, C = 8;
+  __shared__ int32_t cand_s[4][kFilterMaxCand];
+  __shared__ unsigned long long keys_s[4][kFilterMaxCand];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const long long pair = (long long)blockIdx.x * 4 + wave;
+  if (pair >= (long long)BM * Hkv) return;  // wave-uniform; no workgroup barrier below
+  const int g = (int)(pair % Hkv);
+  const int tok = (int)(pair / Hkv);
+  int32_t* cand = cand_s[wave];
+  unsigned long long* keys = keys_s[wave];
+
+  // ---- candidates --------------------------------------------------------------------------------------
+  const int T = 2 * n_splits * KL;
+  const unsigned long long* src = lists + ((long long)g * BM + tok) * T;
+  const int per = (T + 63) / 64;  // wave-uniform: slots of x that hold entries
+  unsigned long long x[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int e = lane + 64 * i;
+    x[i] = (i < per && e < T) ? src[e] : 0ull;
+  }
+  // k-th largest one-pass score: bitwise search on the order-preserving image (the high word of a key)
+  uint32_t prefix = 0u;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cnd = prefix | (1u << bit);
+    int ge = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+      if (i < per) ge += __popcll(__ballot((uint32_t)(x[i] >> 32) >= cnd));
+    if (ge >= k) prefix = cnd;  // wave-uniform
+  }
+  // fewer than k entries in all (prefix == 0): every entry is a candidate
+  const float band = prefix ? unorderable(prefix) - 2.0f * eps[(long long)tok * Hkv + g] : -INFINITY;
+  int total = 0;
+  bool overflow = false;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    if (i < per) {  // wave-uniform
+      const int e = lane + 64 * i;
+      const bool is = x[i] != 0ull && key_score(x[i]) >= band;
+      overflow = overflow || (is && (e % KL) == KL - 1);  // a full list whose last entry is inside the band
+      const unsigned long long m = __ballot(is);
+      const int slot = total + __popcll(m & ((1ull << lane) - 1ull));
+      if (is && slot < kFilterMaxCand) cand[slot] = (int32_t)key_doc(x[i]);
+      total += __popcll(m);
+    }
+  }
+  overflow = __any(overflow) || total > kFilterMaxCand;
+  if (lane == 0 && overflow) flags[g * n_qblocks + tok / tokens_per_wg] = 1;
+  const int n = total < kFilterMaxCand ? total : kFilterMaxCand;
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+
+  // ---- exact scores ------------------------------------------------------------------------------------
+  const int ch = lane >> 3, part = lane & 7;  // chunk of the document, 16-dim part of the key
+  float q[16];
+  {
+    const float4* qs = reinterpret_cast<const float4*>(qf + ((long long)tok * Hkv + g) * D + 16 * part);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 v = qs[i];
+      q[4 * i] = v.x; q[4 * i + 1] = v.y; q[4 * i + 2] = v.z; q[4 * i + 3] = v.w;
+    }
+  }
+  const uint16_t* KRg = KR + (long long)g * tiles * (16 * D);
+  const float* ing = inv_norm + (long long)g * tiles * 16;
+  for (int j0 = 0; j0 < n; j0 += 4) {  // wave-uniform; four candidates at a time, all their loads in flight together
+    long long doc[4];
+    uint4 a0[4], a1[4];
+    float kinv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      doc[u] = cand[j0 + u < n ? j0 + u : n - 1];  // past the end: the last candidate again (not stored)
+      const long long key = doc[u] * C + ch;       // routing key of this lane's chunk
+      const long long tile = key >> 4;
+      const int slot = (int)(key & 15);
+      // tile layout [d / 8][16 keys][8 dims]: dims 16 part .. + 15 are pieces 2 part and 2 part + 1 of the key
+      const uint16_t* kp = KRg + tile * (16 * D) + (2 * part * 16 + slot) * 8;
+      a0[u] = *reinterpret_cast<const uint4*>(kp);
+      a1[u] = *reinterpret_cast<const uint4*>(kp + 16 * 8);
+      kinv[u] = ing[key];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t w[8] = {a0[u].x, a0[u].y, a0[u].z, a0[u].w, a1[u].x, a1[u].y, a1[u].z, a1[u].w};
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        acc = fmaf(q[2 * i], bf16_lo(w[i]), acc);
+        acc = fmaf(q[2 * i + 1], bf16_hi(w[i]), acc);
+      }
+      acc = gsum<8>(acc);                           // the chunk's dot product, in its eight lanes
+      float sc = acc * kinv[u];
+      sc = fmaxf(sc, __shfl_xor(sc, 8, 64));        // document max over the eight chunks
+      sc = fmaxf(sc, __shfl_xor(sc, 16, 64));
+      sc = fmaxf(sc, __shfl_xor(sc, 32, 64));
+      if (lane == 0 && j0 + u < n) keys[j0 + u] = make_key(sc, (uint32_t)doc[u]);
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const long long o_base = ((long long)tok * Hkv + g) * k;
+  if (lane < n) {
+    const unsigned long long mine = keys[lane];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) rank += (keys[j] > mine) ? 1 : 0;
+    if (rank < k) {
+      if (out_key) {
+        out_key[o_base + rank] = mine;
+      } else {
+        out_idx[o_base + rank] = (int32_t)key_doc(mine);
+        if (out_score) out_score[o_base + rank] = key_score(mine);
+      }
+    }
+  }
+  for (int i = n + lane; i < k; i += 64) {  // fewer than k candidates (k > number of documents cannot happen)
+    if (out_key) {
+      out_key[o_base + i] = 0ull;
+    } else {
+      out_idx[o_base + i] = -1;
+      if (out_score) out_score[o_base + i] = -INFINITY;
+    }
+  }
+}
+
 // ---- host side -----------------------------------------------------------------------------------
 bool gemm_path_applies(const Dims& dm, int BM, int k) {
   // (one group with select_scope = ALL is the per-group kernel's case)
@@ -690,6 +882,9 @@ GemmPlan plan_score_gemm(const Dims& dm, int BM, int k) {
     p.n_splits = (int)((n_range + p.stages_per_split - 1) / p.stages_per_split);
     p.off_lists = round_up256((size_t)BM * dm.Hkv * dm.d * sizeof(float));
     p.ws_bytes = p.off_lists + round_up256((size_t)BM * p.n_splits * k * sizeof(unsigned long long));
+    p.filter = 0;
+    p.list_len = p.tokens_per_wg = 0;
+    p.off_eps = p.off_flags = p.off_flists = 0;
     return p;
   }
   const int tokens_per_wg = (k <= 8) ? 256 : 128;
@@ -705,20 +900,43 @@ GemmPlan plan_score_gemm(const Dims& dm, int BM, int k) {
   p.n_splits = (int)((n_stage + p.stages_per_split - 1) / p.stages_per_split);
   p.off_lists = round_up256((size_t)BM * dm.Hkv * dm.d * sizeof(float));
   p.ws_bytes = p.off_lists + round_up256((size_t)dm.Hkv * BM * p.n_splits * k * sizeof(unsigned long long));
+  p.list_len = (k <= 8) ? 8 : 16;
+  p.tokens_per_wg = tokens_per_wg;
+  // The one-pass filter: cosine (the bound needs unit keys), the shape the exact-score kernel is written for, and
+  // few enough list entries per token for one wave.
+  p.filter = (dm.cos && dm.d == 128 && dm.C == 8 && 2 * p.n_splits * p.list_len <= kFilterMaxEntries) ? 1 : 0;
+  p.off_eps = p.off_flags = p.off_flists = 0;
+  if (p.filter) {
+    // the two-pass kernel's lists (fallback) reuse the memory of the one-pass lists, which are twice as long
+    p.off_flists = p.off_lists;
+    size_t end = p.off_flists +
+                 round_up256((size_t)dm.Hkv * BM * p.n_splits * 2 * p.list_len * sizeof(unsigned long long));
+    p.off_eps = end;
+    end += round_up256((size_t)BM * dm.Hkv * sizeof(float));
+    p.off_flags = end;
+    end += round_up256((size_t)dm.Hkv * p.n_qblocks * sizeof(int));
+    p.ws_bytes = end;
+  }
   return p;
 }
 
 int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_route, int BM, const void* KR,
-                           const float* inv_norm, int k, void* ws, hipStream_t st) {
+                           const float* inv_norm, int k, void* ws, hipStream_t st, int32_t* out_idx,
+                           float* out_score, unsigned long long* out_key, const int** gate_flags) {
   float* qf = (float*)ws;
+  float* eps = pl.filter ? (float*)((char*)ws + pl.off_eps) : nullptr;
+  int* flags = pl.filter ? (int*)((char*)ws + pl.off_flags) : nullptr;
+  const int n_flags = pl.filter ? dm.Hkv * pl.n_qblocks : 0;
+  *gate_flags = flags;
   if (dm.d == 128)
     hipLaunchKernelGGL(fold_queries_kernel<128>, dim3((unsigned)(BM * dm.Hkv)), dim3(64), 0, st,
-                       (const uint16_t*)q_route, qf, dm.Hq, dm.Hkv, dm.r, dm.cos);
+                       (const uint16_t*)q_route, qf, dm.Hq, dm.Hkv, dm.r, dm.cos, eps, flags, n_flags);
   else
     hipLaunchKernelGGL(fold_queries_kernel<64>, dim3((unsigned)(BM * dm.Hkv)), dim3(64), 0, st,
-                       (const uint16_t*)q_route, qf, dm.Hq, dm.Hkv, dm.r, dm.cos);
+                       (const uint16_t*)q_route, qf, dm.Hq, dm.Hkv, dm.r, dm.cos, eps, flags, n_flags);
   if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
   GemmArgs a;
+  a.flags = nullptr;
   a.qf = qf;
   a.KR = (const uint16_t*)KR;
   a.inv_norm = dm.cos ? inv_norm : nullptr;
@@ -750,11 +968,30 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
     return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
   }
   const unsigned blocks = (unsigned)(dm.Hkv * pl.n_qblocks * pl.n_splits);
+  if (pl.filter) {
+    // one-pass product -> candidates -> exact scores; then the two-pass kernel for the flagged token blocks only
+    a.ws = (unsigned long long*)((char*)ws + pl.off_flists);
+    profile_mark(dm, false, st);
+    if (k <= 8) hipLaunchKernelGGL((score_gemm_kernel<128, 2, 8, true, true>), dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((score_gemm_kernel<128, 1, 16, true, true>), dim3(blocks), dim3(256), 0, st, a);
+    profile_mark(dm, true, st);
+    if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+    hipLaunchKernelGGL(score_filter_select_kernel, dim3((unsigned)((BM * dm.Hkv + 3) / 4)), dim3(256), 0, st,
+                       (const unsigned long long*)a.ws, (const float*)eps, (const float*)qf, (const uint16_t*)KR,
+                       inv_norm, flags, out_idx, out_score, out_key, BM, dm.Hkv, pl.n_splits, pl.list_len, k,
+                       pl.tokens_per_wg, pl.n_qblocks, dm.tiles);
+    if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+    a.ws = (unsigned long long*)((char*)ws + pl.off_lists);
+    a.flags = flags;
+    if (k <= 8) hipLaunchKernelGGL((score_gemm_kernel<128, 2, 8, true, false>), dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((score_gemm_kernel<128, 1, 16, true, false>), dim3(blocks), dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
+  }
   profile_mark(dm, false, st);
 #define MSA_GEMM(DD, TT, KK) \
   do { \
-    if (dm.C == 8) hipLaunchKernelGGL((score_gemm_kernel<DD, TT, KK, true>), dim3(blocks), dim3(256), 0, st, a); \
-    else hipLaunchKernelGGL((score_gemm_kernel<DD, TT, KK, false>), dim3(blocks), dim3(256), 0, st, a); \
+    if (dm.C == 8) hipLaunchKernelGGL((score_gemm_kernel<DD, TT, KK, true, false>), dim3(blocks), dim3(256), 0, st, a); \
+    else hipLaunchKernelGGL((score_gemm_kernel<DD, TT, KK, false, false>), dim3(blocks), dim3(256), 0, st, a); \
   } while (0)
   if (k <= 8) {
     if (dm.d == 128) MSA_GEMM(128, 2, 8); else MSA_GEMM(64, 2, 8);

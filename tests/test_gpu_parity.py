@@ -717,6 +717,71 @@ def test_prefill_scoring_long_splits():
     say(f"   top-k ok ({n_band} inside the tie band)")
 
 
+@pytest.mark.parametrize("k", [8, 16])
+def test_prefill_scoring_one_pass_filter(k):
+    """d = 128, eight chunks per document, cosine: the scoring GEMM multiplies the hi parts of the queries only and
+    the candidates inside the error band are scored again exactly.  Long key-range splits, token blocks with a
+    ragged tail, r = 2 heads folded per group, an exact tie between two documents; the oracle scores 100 tokens
+    at a time."""
+    N, C, d, Hkv, r, B, M = 6144, 8, 128, 4, 2, 1, 700
+    say(f"case prefill scoring, one-pass filter: N={N} docs, C={C}, d={d}, Hkv={Hkv}, r={r}, M={M}, k={k}")
+    cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e6)
+    _, KRb = S.normal_bf16(42000, (Hkv, N * C, d))
+    qb, q = S.normal_bf16(42001, (B, M, Hkv * r, d))
+    KRb[:, 5 * C + 2] = KRb[:, 4000 * C + 5]                      # an exact tie between two documents' best chunks
+    inv = 1.0 / np.maximum(np.linalg.norm(KRb, axis=-1), O.EPS_NORM)
+    dKR, dinv = upload_oracle_index(cfg, KRb, inv)
+    idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    n_band = 0
+    for m0 in range(0, M, 100):
+        sl = slice(m0, min(M, m0 + 100))
+        _, nb = check_topk_generic(q[:, sl], KRb, C, N, idx[:, sl], val[:, sl], k, "cos", "group", False)
+        n_band += nb
+    say(f"   top-k ok ({n_band} inside the tie band)")
+    # the same with token pooling (the exact winners go to the pooling kernel as keys)
+    cfg_p = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e6, token_pool=1)
+    ip, vp = msa.msa_score_topk(cfg_p, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    _, nb = check_topk_generic(q, KRb, C, N, ip, vp, k, "cos", "group", True)
+    say(f"   token-pooled top-k ok ({nb} inside the tie band)")
+
+
+def test_prefill_one_pass_filter_overflow_is_redone_exactly():
+    """Ties that no per-lane list can hold: 400 copies of one document, then a bank of identical documents.  The
+    one-pass lists overflow inside the error band, the token blocks are flagged and redone by the two-pass kernel, and
+    the exact tie-break (lowest index first) decides."""
+    N, C, d, Hkv, r, B, M, k = 700, 8, 128, 2, 4, 1, 300, 8
+    say(f"case prefill scoring, one-pass filter overflowing: N={N} docs, 400 of them copies of document 7, M={M}")
+    cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e6)
+    _, KRb = S.normal_bf16(43000, (Hkv, N * C, d))
+    qb, q = S.normal_bf16(43001, (B, M, Hkv * r, d))
+    for i in range(300, 700):
+        KRb[:, i * C:(i + 1) * C] = KRb[:, 7 * C:8 * C]
+    inv = 1.0 / np.maximum(np.linalg.norm(KRb, axis=-1), O.EPS_NORM)
+    dKR, dinv = upload_oracle_index(cfg, KRb, inv)
+    idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    oi, n_band = check_topk_generic(q, KRb, C, N, idx, val, k, "cos", "group", False)
+    gi = idx.cpu().numpy()
+    n_tied = 0
+    for b, m, g in np.ndindex(B, M, Hkv):
+        got = gi[b, m, g].tolist()
+        if 7 in got:                       # the copies follow document 7 at once, lowest index first
+            j = got.index(7)
+            assert got[j + 1:] == list(range(300, 300 + k - 1 - j)), got
+            n_tied += 1
+    assert n_tied > 0
+    say(f"   top-k ok ({n_band} inside the tie band; document 7 and its copies selected {n_tied} times)")
+    KRb[:] = np.tile(KRb[:, :C], (1, N, 1))   # every document the same
+    inv = 1.0 / np.maximum(np.linalg.norm(KRb, axis=-1), O.EPS_NORM)
+    dKR, dinv = upload_oracle_index(cfg, KRb, inv)
+    idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), np.broadcast_to(np.arange(k), (B, M, Hkv, k)))
+    say("   a bank of identical documents: documents 0 .. k-1 for every token")
+
+
 # ------------------------------------------------------------------------------------------------
 # shared-selection prefill attention (token_pool = 1, many tokens): the tiled MFMA kernel
 # ------------------------------------------------------------------------------------------------
