@@ -462,7 +462,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 // 2 R sub-tiles stay in registers until the last group has been added.
 constexpr int all_range(int KL) { return KL <= 8 ? 3 : 2; }  // stages per range (what the registers hold)
 
-template <int D, int KL, int HKV>
+// HIONLY: the one-pass filter, as in score_gemm_kernel (hi parts only, both per-lane lists written out whole:
+// [BM][n_splits][2][KL]); the two-pass form behind it runs only for the token blocks flagged in a.flags.
+template <int D, int KL, int HKV, bool HIONLY>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void score_gemm_all_kernel(GemmArgs a) {
   constexpr int NS8 = D / 16;
   constexpr int SUB_BYTES = 32 * D * 2;
@@ -483,8 +485,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int h = lane >> 5;
   const int c = lane & 31;
-  const int qb = blockIdx.x % a.n_qblocks;
-  const int ks = blockIdx.x / a.n_qblocks;
+  // Workgroups go to the eight XCDs in turn (blockIdx % 8), each XCD with an L2 of its own: the token blocks of one
+  // key split are kept on one XCD, so that XCD streams only its splits' part of the index from memory and the
+  // other token blocks find it in the L2.
+  int vb = blockIdx.x;
+  {
+    const int total = a.n_qblocks * a.n_splits;
+    if (total % 8 == 0) vb = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
+  }
+  const int qb = vb % a.n_qblocks;
+  const int ks = vb / a.n_qblocks;
+  if (!HIONLY && a.flags != nullptr && a.flags[qb] == 0) return;  // block-uniform, ahead of any barrier
   const long long n_sub = (a.tiles + 1) / 2;
   const long long n_stage = (n_sub + 1) / 2;
   const long long n_range = (n_stage + R - 1) / R;
@@ -589,7 +600,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
       for (int i = 0; i < 16; ++i) tot[t][i] = 0.f;
     for (int g = 0; g < HKV; ++g) {
       // this group's folded queries of the wave's 32 tokens: hi and lo operands
-      bf16x8_t Bhi[NS8], Blo[NS8];
+      bf16x8_t Bhi[NS8], Blo[HIONLY ? 1 : NS8];
 #pragma unroll
       for (int s = 0; s < NS8; ++s) {
         float x[8];
@@ -607,7 +618,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) split_pack_bf16(x[2 * jj], x[2 * jj + 1], wh[jj], wl[jj]);
         Bhi[s] = as_bf16x8(make_uint4(wh[0], wh[1], wh[2], wh[3]));
-        Blo[s] = as_bf16x8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
+        if constexpr (!HIONLY) Blo[s] = as_bf16x8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
       }
 #pragma unroll
       for (int st = 0; st < R; ++st, ++e) {
@@ -628,7 +639,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 #pragma unroll
           for (int s = 0; s < NS8; ++s) {
             acc = mfma32(av[s], Bhi[s], acc);
-            acc = mfma32(av[s], Blo[s], acc);
+            if constexpr (!HIONLY) acc = mfma32(av[s], Blo[s], acc);
           }
           const float* ic = a.inv_norm ? icur + 32 * sub : ones;
 #pragma unroll
@@ -684,6 +695,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   flush();
+  if constexpr (HIONLY) {
+    if (tok < a.BM) {
+      unsigned long long* dst = a.ws + (((long long)tok * a.n_splits + ks) * 2 + h) * KL;
+#pragma unroll
+      for (int p = 0; p < KL; ++p) dst[p] = (ldoc[p] >= 0) ? make_key(lsc[p], (uint32_t)ldoc[p]) : 0ull;
+    }
+    return;
+  }
 #pragma unroll
   for (int p = 0; p < KL; ++p)
     mrg[wave * 32 + c][h * KL + p] = (ldoc[p] >= 0) ? make_key(lsc[p], (uint32_t)ldoc[p]) : 0ull;
@@ -729,17 +748,22 @@ __global__ __launch_bounds__(256) void score_filter_select_kernel(const unsigned
                                                                   float* __restrict__ out_score,
                                                                   unsigned long long* __restrict__ out_key, int BM,
                                                                   int Hkv, int n_splits, int KL, int k,
-                                                                  int tokens_per_wg, int n_qblocks, long long tiles) {
+                                                                  int tokens_per_wg, int n_qblocks, long long tiles,
+                                                                  int all_heads) {
   constexpr int PER = kFilterMaxEntries / 64;
   constexpr int D = 128, C = 8;
   __shared__ int32_t cand_s[4][kFilterMaxCand];
   __shared__ unsigned long long keys_s[4][kFilterMaxCand];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
+  // one selection per (token, KV group), or (head mean over every head) per token: then the score of a chunk is the
+  // mean over the groups of the groups' scores, and the bound the mean of the groups' bounds
+  const int S = all_heads ? 1 : Hkv;    // selections per token
+  const int GS = all_heads ? Hkv : 1;   // groups per selection
   const long long pair = (long long)blockIdx.x * 4 + wave;
-  if (pair >= (long long)BM * Hkv) return;  // wave-uniform; no workgroup barrier below
-  const int g = (int)(pair % Hkv);
-  const int tok = (int)(pair / Hkv);
+  if (pair >= (long long)BM * S) return;  // wave-uniform; no workgroup barrier below
+  const int g = (int)(pair % S);
+  const int tok = (int)(pair / S);
   int32_t* cand = cand_s[wave];
   unsigned long long* keys = keys_s[wave];
 
@@ -764,7 +788,10 @@ __global__ __launch_bounds__(256) void score_filter_select_kernel(const unsigned
     if (ge >= k) prefix = cnd;  // wave-uniform
   }
   // fewer than k entries in all (prefix == 0): every entry is a candidate
-  const float band = prefix ? unorderable(prefix) - 2.0f * eps[(long long)tok * Hkv + g] : -INFINITY;
+  float e_sel = 0.f;
+  for (int gg = 0; gg < GS; ++gg) e_sel += eps[(long long)tok * Hkv + g + gg];
+  e_sel /= (float)GS;
+  const float band = prefix ? unorderable(prefix) - 2.0f * e_sel : -INFINITY;
   int total = 0;
   bool overflow = false;
 #pragma unroll
@@ -780,52 +807,62 @@ __global__ __launch_bounds__(256) void score_filter_select_kernel(const unsigned
     }
   }
   overflow = __any(overflow) || total > kFilterMaxCand;
-  if (lane == 0 && overflow) flags[g * n_qblocks + tok / tokens_per_wg] = 1;
+  if (lane == 0 && overflow) flags[g * n_qblocks + tok / tokens_per_wg] = 1;  // (all heads: g = 0)
   const int n = total < kFilterMaxCand ? total : kFilterMaxCand;
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
 
   // ---- exact scores ------------------------------------------------------------------------------------
   const int ch = lane >> 3, part = lane & 7;  // chunk of the document, 16-dim part of the key
-  float q[16];
-  {
-    const float4* qs = reinterpret_cast<const float4*>(qf + ((long long)tok * Hkv + g) * D + 16 * part);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float4 v = qs[i];
-      q[4 * i] = v.x; q[4 * i + 1] = v.y; q[4 * i + 2] = v.z; q[4 * i + 3] = v.w;
-    }
-  }
-  const uint16_t* KRg = KR + (long long)g * tiles * (16 * D);
-  const float* ing = inv_norm + (long long)g * tiles * 16;
+  const float inv_gs = 1.0f / (float)GS;
   for (int j0 = 0; j0 < n; j0 += 4) {  // wave-uniform; four candidates at a time, all their loads in flight together
     long long doc[4];
-    uint4 a0[4], a1[4];
-    float kinv[4];
+    float tot[4] = {0.f, 0.f, 0.f, 0.f};  // the chunk's score, summed over the groups of the selection
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      doc[u] = cand[j0 + u < n ? j0 + u : n - 1];  // past the end: the last candidate again (not stored)
-      const long long key = doc[u] * C + ch;       // routing key of this lane's chunk
-      const long long tile = key >> 4;
-      const int slot = (int)(key & 15);
-      // tile layout [d / 8][16 keys][8 dims]: dims 16 part .. + 15 are pieces 2 part and 2 part + 1 of the key
-      const uint16_t* kp = KRg + tile * (16 * D) + (2 * part * 16 + slot) * 8;
-      a0[u] = *reinterpret_cast<const uint4*>(kp);
-      a1[u] = *reinterpret_cast<const uint4*>(kp + 16 * 8);
-      kinv[u] = ing[key];
+    for (int u = 0; u < 4; ++u) doc[u] = cand[j0 + u < n ? j0 + u : n - 1];  // past the end: the last one again
+    for (int gg = 0; gg < GS; ++gg) {
+      const int gk = g + gg;  // KV group whose keys and folded query are multiplied
+      float q[16];
+      {
+        const float4* qs = reinterpret_cast<const float4*>(qf + ((long long)tok * Hkv + gk) * D + 16 * part);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float4 v = qs[i];
+          q[4 * i] = v.x; q[4 * i + 1] = v.y; q[4 * i + 2] = v.z; q[4 * i + 3] = v.w;
+        }
+      }
+      const uint16_t* KRg = KR + (long long)gk * tiles * (16 * D);
+      const float* ing = inv_norm + (long long)gk * tiles * 16;
+      uint4 a0[4], a1[4];
+      float kinv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const long long key = doc[u] * C + ch;       // routing key of this lane's chunk
+        const long long tile = key >> 4;
+        const int slot = (int)(key & 15);
+        // tile layout [d / 8][16 keys][8 dims]: dims 16 part .. + 15 are pieces 2 part and 2 part + 1 of the key
+        const uint16_t* kp = KRg + tile * (16 * D) + (2 * part * 16 + slot) * 8;
+        a0[u] = *reinterpret_cast<const uint4*>(kp);
+        a1[u] = *reinterpret_cast<const uint4*>(kp + 16 * 8);
+        kinv[u] = ing[key];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t w[8] = {a0[u].x, a0[u].y, a0[u].z, a0[u].w, a1[u].x, a1[u].y, a1[u].z, a1[u].w};
+        float acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          acc = fmaf(q[2 * i], bf16_lo(w[i]), acc);
+          acc = fmaf(q[2 * i + 1], bf16_hi(w[i]), acc);
+        }
+        acc = gsum<8>(acc);                          // the chunk's dot product, in its eight lanes
+        tot[u] += acc * kinv[u];
+      }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const uint32_t w[8] = {a0[u].x, a0[u].y, a0[u].z, a0[u].w, a1[u].x, a1[u].y, a1[u].z, a1[u].w};
-      float acc = 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        acc = fmaf(q[2 * i], bf16_lo(w[i]), acc);
-        acc = fmaf(q[2 * i + 1], bf16_hi(w[i]), acc);
-      }
-      acc = gsum<8>(acc);                           // the chunk's dot product, in its eight lanes
-      float sc = acc * kinv[u];
-      sc = fmaxf(sc, __shfl_xor(sc, 8, 64));        // document max over the eight chunks
+      float sc = tot[u] * inv_gs;
+      sc = fmaxf(sc, __shfl_xor(sc, 8, 64));         // document max over the eight chunks
       sc = fmaxf(sc, __shfl_xor(sc, 16, 64));
       sc = fmaxf(sc, __shfl_xor(sc, 32, 64));
       if (lane == 0 && j0 + u < n) keys[j0 + u] = make_key(sc, (uint32_t)doc[u]);
@@ -833,7 +870,7 @@ __global__ __launch_bounds__(256) void score_filter_select_kernel(const unsigned
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
-  const long long o_base = ((long long)tok * Hkv + g) * k;
+  const long long o_base = ((long long)tok * S + g) * k;
   if (lane < n) {
     const unsigned long long mine = keys[lane];
     int rank = 0;
@@ -882,9 +919,19 @@ GemmPlan plan_score_gemm(const Dims& dm, int BM, int k) {
     p.n_splits = (int)((n_range + p.stages_per_split - 1) / p.stages_per_split);
     p.off_lists = round_up256((size_t)BM * dm.Hkv * dm.d * sizeof(float));
     p.ws_bytes = p.off_lists + round_up256((size_t)BM * p.n_splits * k * sizeof(unsigned long long));
-    p.filter = 0;
-    p.list_len = p.tokens_per_wg = 0;
+    p.list_len = (k <= 8) ? 8 : 16;
+    p.tokens_per_wg = 128;
+    p.filter = (dm.cos && dm.d == 128 && dm.C == 8 && 2 * p.n_splits * p.list_len <= kFilterMaxEntries) ? 1 : 0;
     p.off_eps = p.off_flags = p.off_flists = 0;
+    if (p.filter) {  // as below, with one selection per token
+      p.off_flists = p.off_lists;
+      size_t end = p.off_flists + round_up256((size_t)BM * p.n_splits * 2 * p.list_len * sizeof(unsigned long long));
+      p.off_eps = end;
+      end += round_up256((size_t)BM * dm.Hkv * sizeof(float));
+      p.off_flags = end;
+      end += round_up256((size_t)p.n_qblocks * sizeof(int));
+      p.ws_bytes = end;
+    }
     return p;
   }
   const int tokens_per_wg = (k <= 8) ? 256 : 128;
@@ -926,7 +973,7 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
   float* qf = (float*)ws;
   float* eps = pl.filter ? (float*)((char*)ws + pl.off_eps) : nullptr;
   int* flags = pl.filter ? (int*)((char*)ws + pl.off_flags) : nullptr;
-  const int n_flags = pl.filter ? dm.Hkv * pl.n_qblocks : 0;
+  const int n_flags = pl.filter ? (pl.all_heads ? 1 : dm.Hkv) * pl.n_qblocks : 0;
   *gate_flags = flags;
   if (dm.d == 128)
     hipLaunchKernelGGL(fold_queries_kernel<128>, dim3((unsigned)(BM * dm.Hkv)), dim3(64), 0, st,
@@ -952,17 +999,40 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
   a.stages_per_split = pl.stages_per_split;
   if (pl.all_heads) {
     const unsigned nb = (unsigned)(pl.n_qblocks * pl.n_splits);
-    profile_mark(dm, false, st);
-#define MSA_GEMM_ALL(DD, HH) \
+#define MSA_GEMM_ALL(DD, HH, ONE) \
   do { \
-    if (k <= 8) hipLaunchKernelGGL((score_gemm_all_kernel<DD, 8, HH>), dim3(nb), dim3(256), 0, st, a); \
-    else hipLaunchKernelGGL((score_gemm_all_kernel<DD, 16, HH>), dim3(nb), dim3(256), 0, st, a); \
+    if (k <= 8) hipLaunchKernelGGL((score_gemm_all_kernel<DD, 8, HH, ONE>), dim3(nb), dim3(256), 0, st, a); \
+    else hipLaunchKernelGGL((score_gemm_all_kernel<DD, 16, HH, ONE>), dim3(nb), dim3(256), 0, st, a); \
   } while (0)
-    if (dm.d == 128) {
-      if (dm.Hkv == 2) MSA_GEMM_ALL(128, 2); else if (dm.Hkv == 4) MSA_GEMM_ALL(128, 4); else MSA_GEMM_ALL(128, 8);
-    } else {
-      if (dm.Hkv == 2) MSA_GEMM_ALL(64, 2); else if (dm.Hkv == 4) MSA_GEMM_ALL(64, 4); else MSA_GEMM_ALL(64, 8);
+#define MSA_GEMM_ALL128(ONE) \
+  do { \
+    if (dm.Hkv == 2) MSA_GEMM_ALL(128, 2, ONE); else if (dm.Hkv == 4) MSA_GEMM_ALL(128, 4, ONE); \
+    else MSA_GEMM_ALL(128, 8, ONE); \
+  } while (0)
+    if (pl.filter) {  // d = 128: one-pass product -> candidates -> exact scores -> two-pass kernel where flagged
+      a.ws = (unsigned long long*)((char*)ws + pl.off_flists);
+      profile_mark(dm, false, st);
+      MSA_GEMM_ALL128(true);
+      profile_mark(dm, true, st);
+      if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+      hipLaunchKernelGGL(score_filter_select_kernel, dim3((unsigned)((BM + 3) / 4)), dim3(256), 0, st,
+                         (const unsigned long long*)a.ws, (const float*)eps, (const float*)qf, (const uint16_t*)KR,
+                         inv_norm, flags, out_idx, out_score, out_key, BM, dm.Hkv, pl.n_splits, pl.list_len, k,
+                         pl.tokens_per_wg, pl.n_qblocks, dm.tiles, 1);
+      if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
+      a.ws = (unsigned long long*)((char*)ws + pl.off_lists);
+      a.flags = flags;
+      MSA_GEMM_ALL128(false);
+      return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
     }
+    profile_mark(dm, false, st);
+    if (dm.d == 128) {
+      MSA_GEMM_ALL128(false);
+    } else {
+      if (dm.Hkv == 2) MSA_GEMM_ALL(64, 2, false); else if (dm.Hkv == 4) MSA_GEMM_ALL(64, 4, false);
+      else MSA_GEMM_ALL(64, 8, false);
+    }
+#undef MSA_GEMM_ALL128
 #undef MSA_GEMM_ALL
     profile_mark(dm, true, st);
     return hipGetLastError() == hipSuccess ? MSA_OK : MSA_ERR_HIP;
@@ -979,7 +1049,7 @@ int launch_score_gemm_scan(const Dims& dm, const GemmPlan& pl, const void* q_rou
     hipLaunchKernelGGL(score_filter_select_kernel, dim3((unsigned)((BM * dm.Hkv + 3) / 4)), dim3(256), 0, st,
                        (const unsigned long long*)a.ws, (const float*)eps, (const float*)qf, (const uint16_t*)KR,
                        inv_norm, flags, out_idx, out_score, out_key, BM, dm.Hkv, pl.n_splits, pl.list_len, k,
-                       pl.tokens_per_wg, pl.n_qblocks, dm.tiles);
+                       pl.tokens_per_wg, pl.n_qblocks, dm.tiles, 0);
     if (hipGetLastError() != hipSuccess) return MSA_ERR_HIP;
     a.ws = (unsigned long long*)((char*)ws + pl.off_lists);
     a.flags = flags;

@@ -747,13 +747,17 @@ def test_prefill_scoring_one_pass_filter(k):
     say(f"   token-pooled top-k ok ({nb} inside the tie band)")
 
 
-def test_prefill_one_pass_filter_overflow_is_redone_exactly():
+@pytest.mark.parametrize("scope", ["group", "all"])
+def test_prefill_one_pass_filter_overflow_is_redone_exactly(scope):
     """Ties that no per-lane list can hold: 400 copies of one document, then a bank of identical documents.  The
     one-pass lists overflow inside the error band, the token blocks are flagged and redone by the two-pass kernel, and
-    the exact tie-break (lowest index first) decides."""
+    the exact tie-break (lowest index first) decides.  Per KV group, and with the head mean over every head."""
     N, C, d, Hkv, r, B, M, k = 700, 8, 128, 2, 4, 1, 300, 8
-    say(f"case prefill scoring, one-pass filter overflowing: N={N} docs, 400 of them copies of document 7, M={M}")
-    cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e6)
+    say(f"case prefill scoring, one-pass filter overflowing (scope {scope}): N={N} docs, 400 of them copies of "
+        f"document 7, M={M}")
+    cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e6,
+                        select_scope=msa.MSA_SCOPE_ALL if scope == "all" else msa.MSA_SCOPE_GROUP)
+    S_ = 1 if scope == "all" else Hkv
     _, KRb = S.normal_bf16(43000, (Hkv, N * C, d))
     qb, q = S.normal_bf16(43001, (B, M, Hkv * r, d))
     for i in range(300, 700):
@@ -762,10 +766,11 @@ def test_prefill_one_pass_filter_overflow_is_redone_exactly():
     dKR, dinv = upload_oracle_index(cfg, KRb, inv)
     idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
     torch.cuda.synchronize()
-    oi, n_band = check_topk_generic(q, KRb, C, N, idx, val, k, "cos", "group", False)
+    assert tuple(idx.shape) == (B, M, S_, k)
+    oi, n_band = check_topk_generic(q, KRb, C, N, idx, val, k, "cos", scope, False)
     gi = idx.cpu().numpy()
     n_tied = 0
-    for b, m, g in np.ndindex(B, M, Hkv):
+    for b, m, g in np.ndindex(B, M, S_):
         got = gi[b, m, g].tolist()
         if 7 in got:                       # the copies follow document 7 at once, lowest index first
             j = got.index(7)
@@ -778,7 +783,7 @@ def test_prefill_one_pass_filter_overflow_is_redone_exactly():
     dKR, dinv = upload_oracle_index(cfg, KRb, inv)
     idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
     torch.cuda.synchronize()
-    assert np.array_equal(idx.cpu().numpy(), np.broadcast_to(np.arange(k), (B, M, Hkv, k)))
+    assert np.array_equal(idx.cpu().numpy(), np.broadcast_to(np.arange(k), (B, M, S_, k)))
     say("   a bank of identical documents: documents 0 .. k-1 for every token")
 
 
