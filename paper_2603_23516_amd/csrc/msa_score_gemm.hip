@@ -504,7 +504,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   if (r1 > n_range) r1 = n_range;
   if (tid < 64) ones[tid] = 1.0f;
   const int tok = qb * 128 + wave * 32 + c;
-  const long long n_entries = (r1 > r0) ? (r1 - r0) * HKV * R : 0;
+  const int n_rg = (r1 > r0) ? (int)(r1 - r0) : 0;  // ranges of this workgroup
 
   float lsc[KL];
   int ldoc[KL];
@@ -545,17 +545,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   constexpr int TPC = 4096 / TILE_BYTES;
   const uint32_t goff_full = tid * 16;
   const uint32_t goff_wrap = (tid * 16) % TILE_BYTES;
-  // entry e of this workgroup's stream -> (group, stage); past the end the last entry is fetched again
-  auto entry_at = [&](long long e, int& g, long long& sg) __attribute__((always_inline)) {
-    if (e >= n_entries) e = n_entries - 1;
-    const long long rg = r0 + e / (HKV * R);
-    g = (int)((e / R) % HKV);
-    sg = rg * R + e % R;  // may lie past the last stage of the index: fetched clamped, its documents masked
-  };
-  auto fetch = [&](long long e, unsigned char* kdst, float* idst) __attribute__((always_inline)) {
-    int g;
-    long long sg;
-    entry_at(e, g, sg);
+  // The workgroup's stream of stages, in the order it multiplies them: range (local number rl), group, stage of the
+  // range.  All of it is kept in small 32-bit counters: no division in the loop (64-bit divisions by HKV * R and a
+  // 64-bit modulus per stage were 14 scalar instructions per MFMA).  Past the end the last entry is fetched again.
+  auto fetch = [&](int rl, int g, int st, unsigned char* kdst, float* idst) __attribute__((always_inline)) {
+    if (rl >= n_rg) {
+      rl = n_rg - 1;
+      g = HKV - 1;
+      st = R - 1;
+    }
+    const long long sg = (r0 + rl) * R + st;  // may lie past the last stage of the index: fetched clamped, its documents masked
     const unsigned char* KRg = reinterpret_cast<const unsigned char*>(a.KR) + (long long)g * a.tiles * TILE_BYTES;
     const float* ing = a.inv_norm ? a.inv_norm + (long long)g * a.tiles * 16 : nullptr;
 #pragma unroll
@@ -581,18 +580,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
     else
       asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
   };
-  auto ring_k = [&](long long e) -> unsigned char* { return smem + (e % 3) * STAGE_BYTES; };
-  auto ring_i = [&](long long e) -> float* { return ibuf[e % 3]; };
+  // ring slot of a stage: (number of the stage in the stream) mod 3 = (slot of its group's first stage + st) mod 3
+  auto mod3 = [](int x) -> int { return x >= 6 ? x - 6 : (x >= 3 ? x - 3 : x); };
+  auto ring_k = [&](int slot) -> unsigned char* { return smem + slot * STAGE_BYTES; };
+  auto ring_i = [&](int slot) -> float* { return ibuf[slot]; };
 
-  if (n_entries > 0) {
-    fetch(0, ring_k(0), ring_i(0));
-    fetch(1, ring_k(1), ring_i(1));
+  if (n_rg > 0) {
+    fetch(0, 0, 0, ring_k(0), ring_i(0));
+    fetch(0, 0, 1, ring_k(1), ring_i(1));
     wait_oldest_copy();
   }
   __syncthreads();
   const float inv_groups = 1.0f / (float)HKV;
-  long long e = 0;
-  for (long long rg = r0; rg < r1; ++rg) {  // block-uniform
+  int slot0 = 0;  // ring slot of the current group's first stage (always 0 when R == 3)
+  for (int rl = 0; rl < n_rg; ++rl) {  // block-uniform
+    const long long rg = r0 + rl;
     f32x16_t tot[2 * R];
 #pragma unroll
     for (int t = 0; t < 2 * R; ++t)
@@ -621,10 +623,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
         if constexpr (!HIONLY) Blo[s] = as_bf16x8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
       }
 #pragma unroll
-      for (int st = 0; st < R; ++st, ++e) {
-        fetch(e + 2, ring_k(e + 2), ring_i(e + 2));  // always issued (past the end: the last entry again)
-        const unsigned char* kcur = ring_k(e);
-        const float* icur = a.inv_norm ? ring_i(e) : ones;
+      for (int st = 0; st < R; ++st) {
+        {  // the stage two ahead in the stream: always issued (past the end: the last entry again)
+          constexpr int RR = R;
+          const int fst = (st + 2 < RR) ? st + 2 : st + 2 - RR;
+          int fg = g, frl = rl;
+          if (st + 2 >= RR) {
+            fg = g + 1;
+            if (fg == HKV) {
+              fg = 0;
+              frl = rl + 1;
+            }
+          }
+          const int fslot = mod3(slot0 + st + 2);
+          fetch(frl, fg, fst, ring_k(fslot), ring_i(fslot));
+        }
+        const int cslot = mod3(slot0 + st);
+        const unsigned char* kcur = ring_k(cslot);
+        const float* icur = a.inv_norm ? ring_i(cslot) : ones;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
           const unsigned char* kc = kcur + sub * SUB_BYTES;
@@ -654,6 +670,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
         wait_oldest_copy();
         __syncthreads();
       }
+      if constexpr (R != 3) slot0 = mod3(slot0 + R);
     }
     // ---- the range's totals are complete: head mean, document max, per-lane lists ----------------------
 #pragma unroll
