@@ -37,10 +37,11 @@ __device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// max(x[l], x[l ^ 32]) in every lane.
-__device__ __forceinline__ float max_with_other_half(float x) {
-  const uint32_t u = __float_as_uint(x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+// Lower half of the wave: max(x[l], x[l + 32]); upper half: max(y[l - 32], y[l]).  One swap serves two values: the
+// swap exchanges the upper half of its first operand with the lower half of its second, which leaves {x.lo, y.lo} and
+// {x.hi, y.hi}.
+__device__ __forceinline__ float max_across_halves_pair(float x, float y) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
@@ -332,7 +333,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 #pragma unroll
     for (int cb = 0; cb < TB; ++cb) {
       // a candidate document of this lane: onto the pending buffer (documents arrive in increasing order)
-      auto push = [&](float sc, long long doc) __attribute__((always_inline)) {
+      auto push = [&](float sc, int doc) __attribute__((always_inline)) {
         const bool ok = doc < a.N && sc > lsc[cb][kGemmK - 1];
         if (__any(ok)) {
 #pragma unroll
@@ -341,7 +342,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
             pdoc[cb][q] = ok ? pdoc[cb][q - 1] : pdoc[cb][q];
           }
           psc[cb][0] = ok ? sc : psc[cb][0];
-          pdoc[cb][0] = ok ? (int)doc : pdoc[cb][0];
+          pdoc[cb][0] = ok ? doc : pdoc[cb][0];
           pcnt[cb] += ok ? 1 : 0;
           if (__any(pcnt[cb] == kPend)) flush(cb);
         }
@@ -357,21 +358,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
       if (C8 || a.C == 8) {
         // a document = rows 8j .. 8j + 7: the lane's four and the other half's four; the lower half of the wave
         // takes documents 0, 1 of the sub-tile, the upper half documents 2, 3
-        float m[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) m[j] = max_with_other_half(m4[j]);
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) push(h ? (jj ? m[3] : m[2]) : (jj ? m[1] : m[0]), st * 4 + 2 * h + jj);
+        const int doc0 = (int)st * 4 + 2 * h;
+        push(max_across_halves_pair(m4[0], m4[2]), doc0);
+        push(max_across_halves_pair(m4[1], m4[3]), doc0 + 1);
       } else if constexpr (!C8) {
         if (a.C == 4) {
           // a document = the lane's four rows: document 2j + h of the sub-tile's eight, no exchange
 #pragma unroll
-          for (int j = 0; j < 4; ++j) push(m4[j], st * 8 + 2 * j + h);
+          for (int j = 0; j < 4; ++j) push(m4[j], (int)st * 8 + 2 * j + h);
         } else {
           // C == 16: a document = half of the sub-tile (rows 0..15 / 16..31, both halves of the wave); half h takes
           // document h
-          const float d0 = max_with_other_half(fmaxf(m4[0], m4[1])), d1 = max_with_other_half(fmaxf(m4[2], m4[3]));
-          push(h ? d1 : d0, st * 2 + h);
+          push(max_across_halves_pair(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3])), (int)st * 2 + h);
         }
       }
     }
@@ -676,7 +674,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 #pragma unroll
     for (int t = 0; t < 2 * R; ++t) {
       const long long sub_tile = (rg * R + t / 2) * 2 + (t & 1);  // 32 keys
-      auto push = [&](float sc, long long doc) __attribute__((always_inline)) {
+      auto push = [&](float sc, int doc) __attribute__((always_inline)) {
         const bool ok = doc < a.N && sc > lsc[KL - 1];
         if (__any(ok)) {
 #pragma unroll
@@ -685,7 +683,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
             pdoc[q] = ok ? pdoc[q - 1] : pdoc[q];
           }
           psc[0] = ok ? sc : psc[0];
-          pdoc[0] = ok ? (int)doc : pdoc[0];
+          pdoc[0] = ok ? doc : pdoc[0];
           pcnt += ok ? 1 : 0;
           if (__any(pcnt == kPend)) flush();
         }
@@ -695,17 +693,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
       for (int j = 0; j < 4; ++j)
         m4[j] = fmaxf(fmaxf(tot[t][4 * j], tot[t][4 * j + 1]), fmaxf(tot[t][4 * j + 2], tot[t][4 * j + 3])) * inv_groups;
       if (a.C == 8) {
-        float m[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) m[j] = max_with_other_half(m4[j]);
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) push(h ? (jj ? m[3] : m[2]) : (jj ? m[1] : m[0]), sub_tile * 4 + 2 * h + jj);
+        const int doc0 = (int)sub_tile * 4 + 2 * h;
+        push(max_across_halves_pair(m4[0], m4[2]), doc0);
+        push(max_across_halves_pair(m4[1], m4[3]), doc0 + 1);
       } else if (a.C == 4) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) push(m4[j], sub_tile * 8 + 2 * j + h);
+        for (int j = 0; j < 4; ++j) push(m4[j], (int)sub_tile * 8 + 2 * j + h);
       } else {  // C == 16
-        const float d0 = max_with_other_half(fmaxf(m4[0], m4[1])), d1 = max_with_other_half(fmaxf(m4[2], m4[3]));
-        push(h ? d1 : d0, sub_tile * 2 + h);
+        push(max_across_halves_pair(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3])), (int)sub_tile * 2 + h);
       }
     }
   }
