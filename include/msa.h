@@ -186,7 +186,9 @@ int msa_pool_kv(const msa_config_t* cfg, const void* K, const void* V, int32_t d
  * Scores are accumulated in fp32; each query is carried as a bf16 (hi, lo) pair, so a score differs
  * from exact arithmetic by a few 1e-6 relative.  (With many query tokens, cosine, d = 128 and eight chunks per
  * document the matrix product runs on the hi parts alone as a filter, and the reported scores of the winners are
- * recomputed in fp32 from the fp32 folded query: the selection is the same as with exact scores.)
+ * recomputed in fp32 from the fp32 folded query: the selection is the same as with exact scores.  The filter's
+ * error band assumes |KR row| * inv_norm <= 1.01, which holds for what msa_build_routing_keys writes; an index
+ * from elsewhere must keep to it.)
  */
 int msa_score_topk(const msa_config_t* cfg, const void* q_route, int32_t B, int32_t M,
                    const void* KR, const float* inv_norm, int32_t k, int32_t* out_idx,
