@@ -254,6 +254,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
     }
     pcnt[cb] = 0;
   };
+  // One round of the same: every lane that has pending candidates inserts its OLDEST one.  Called when some lane's
+  // buffer is full, which makes room in it; the other lanes use the round too.  (Emptying the buffers whenever one
+  // of them is full takes kPend rounds for a lane or two that need them: about 1.8 times the rounds in all.)
+  auto insert_oldest = [&](int cb) __attribute__((always_inline)) {
+    const int pc = pcnt[cb];
+    // The oldest pending candidate sits at index pc - 1.  The values pass through empty asm statements so that the
+    // chain of selects stays one: as selects between loads of the arrays the compiler turns it into an indexed
+    // load, which puts the arrays into scratch memory.
+    float sc = psc[cb][0];
+    int doc = pdoc[cb][0];
+    asm volatile("" : "+v"(sc), "+v"(doc));
+#pragma unroll
+    for (int q = 1; q < kPend; ++q) {
+      float t = psc[cb][q];
+      int td = pdoc[cb][q];
+      asm volatile("" : "+v"(t), "+v"(td));
+      sc = (pc > q) ? t : sc;
+      doc = (pc > q) ? td : doc;
+    }
+    const bool ok = pc > 0 && sc > lsc[cb][kGemmK - 1];
+#pragma unroll
+    for (int p = kGemmK - 1; p >= 0; --p) {
+      const float above = (p > 0) ? lsc[cb][p - 1] : INFINITY;
+      const int above_d = (p > 0) ? ldoc[cb][p - 1] : -1;
+      const bool shift = ok && sc > above;
+      const bool here = ok && !shift && sc > lsc[cb][p];
+      lsc[cb][p] = shift ? above : (here ? sc : lsc[cb][p]);
+      ldoc[cb][p] = shift ? above_d : (here ? doc : ldoc[cb][p]);
+    }
+    pcnt[cb] = pc - (pc > 0 ? 1 : 0);
+  };
 
   // ---- staging of key stages: global -> LDS directly (no registers), two stages ahead ---------
   // A 64-lane global_load_lds_dwordx4 lands at LDS base + 16 * lane, and a stage is contiguous in
@@ -344,7 +375,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
           psc[cb][0] = ok ? sc : psc[cb][0];
           pdoc[cb][0] = ok ? doc : pdoc[cb][0];
           pcnt[cb] += ok ? 1 : 0;
-          if (__any(pcnt[cb] == kPend)) flush(cb);
+          if (__any(pcnt[cb] == kPend)) insert_oldest(cb);
         }
       };
       // m4[j]: max over the lane's four rows 8j + 4h .. + 3 of the sub-tile
