@@ -42,7 +42,11 @@ __device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
 // {x.hi, y.hi}.
 __device__ __forceinline__ float max_across_halves_pair(float x, float y) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  // the maximum as one instruction: fmaxf() first passes both halves of the swap through a canonicalising
+  // v_max_f32 x, x, x, because it cannot tell that they are the (already canonical) products of the epilogue
+  float m;
+  asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(r[0]), "v"(r[1]));
+  return m;
 }
 
 template <int W>
