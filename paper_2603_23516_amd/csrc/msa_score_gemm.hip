@@ -168,10 +168,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   const int qb = rest % a.n_qblocks;
   const int ks = rest / a.n_qblocks;
   if (!HIONLY && a.flags != nullptr && a.flags[g * a.n_qblocks + qb] == 0) return;  // block-uniform, ahead of any barrier
-  const long long n_sub = (a.tiles + 1) / 2;
-  const long long n_stage = (n_sub + 1) / 2;
-  const long long s0 = (long long)ks * a.stages_per_split;
-  long long s1 = s0 + a.stages_per_split;
+  // Tiles and stages are counted in 32 bits: a head has at most N tiles (C <= 16), N an int.
+  const int tiles = (int)a.tiles;
+  const int n_stage = (tiles + 3) / 4;
+  const int s0 = ks * a.stages_per_split;
+  int s1 = s0 + a.stages_per_split;
   if (s1 > n_stage) s1 = n_stage;
   if (tid < 64) ones[tid] = 1.0f;
 
@@ -303,23 +304,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   constexpr int TPC = 4096 / TILE_BYTES;
   const uint32_t goff_full = tid * 16;                 // all TPC tiles of the copy exist
   const uint32_t goff_wrap = (tid * 16) % TILE_BYTES;  // only the first does: the others repeat it (masked)
-  auto fetch = [&](long long sg, unsigned char* kdst, float* idst) __attribute__((always_inline)) {
+  auto fetch = [&](int sg, unsigned char* kdst, float* idst) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      long long tile = 4 * sg + TPC * i;
-      if (tile >= a.tiles) tile = a.tiles - 1;         // past the end: repeat the last tile (masked)
+      int tile = 4 * sg + TPC * i;
+      if (tile >= tiles) tile = tiles - 1;             // past the end: repeat the last tile (masked)
       uint32_t goff = goff_full;
-      if constexpr (TPC > 1) goff = (tile + TPC <= a.tiles) ? goff_full : goff_wrap;
-      copy16_to_lds_async(reinterpret_cast<const unsigned char*>(KRg) + tile * TILE_BYTES, goff,
+      if constexpr (TPC > 1) goff = (tile + TPC <= tiles) ? goff_full : goff_wrap;
+      copy16_to_lds_async(reinterpret_cast<const unsigned char*>(KRg) + (long long)tile * TILE_BYTES, goff,
                           kdst + (i * 256 + wave * 64) * 16);
     }
     {
       // dot product: no norms; the copy still runs (from the index itself) to keep the counts equal,
       // and the multiply below reads the constant ones instead
-      long long key0 = sg * 64;
-      const long long last = a.tiles * 16 - 1;
-      if (key0 > last) key0 = last;
-      const int room = (int)(last - key0 < 63 ? last - key0 : 63);  // lanes beyond it repeat the last key
+      const int left = tiles - 4 * sg;  // tiles from this stage's first one to the end (>= 1: sg < n_stage)
+      const long long key0 = (long long)sg * 64;
+      const int room = left >= 4 ? 63 : 16 * left - 1;  // lanes beyond it repeat the last key
       const float* src = ing ? ing + key0 : reinterpret_cast<const float*>(KRg);
       copy4_to_lds_async(src, (uint32_t)((ing && lane > room) ? room : lane) * 4, idst);
     }
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   };
 
   // 32 keys x 64 tokens, contraction over [hi | lo], then the epilogue for these four documents
-  auto sub_tile = [&](long long st, const unsigned char* kcur, const float* icur) __attribute__((always_inline)) {
+  auto sub_tile = [&](int st, const unsigned char* kcur, const float* icur) __attribute__((always_inline)) {
     f32x16_t acc[TB];
 #pragma unroll
     for (int cb = 0; cb < TB; ++cb)
@@ -393,24 +393,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
       if (C8 || a.C == 8) {
         // a document = rows 8j .. 8j + 7: the lane's four and the other half's four; the lower half of the wave
         // takes documents 0, 1 of the sub-tile, the upper half documents 2, 3
-        const int doc0 = (int)st * 4 + 2 * h;
+        const int doc0 = st * 4 + 2 * h;
         push(max_across_halves_pair(m4[0], m4[2]), doc0);
         push(max_across_halves_pair(m4[1], m4[3]), doc0 + 1);
       } else if constexpr (!C8) {
         if (a.C == 4) {
           // a document = the lane's four rows: document 2j + h of the sub-tile's eight, no exchange
 #pragma unroll
-          for (int j = 0; j < 4; ++j) push(m4[j], (int)st * 8 + 2 * j + h);
+          for (int j = 0; j < 4; ++j) push(m4[j], st * 8 + 2 * j + h);
         } else {
           // C == 16: a document = half of the sub-tile (rows 0..15 / 16..31, both halves of the wave); half h takes
           // document h
-          push(max_across_halves_pair(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3])), (int)st * 2 + h);
+          push(max_across_halves_pair(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3])), st * 2 + h);
         }
       }
     }
   };
 
-  auto body = [&](long long sg, const unsigned char* kcur, const float* icur, unsigned char* knxt,
+  auto body = [&](int sg, const unsigned char* kcur, const float* icur, unsigned char* knxt,
                   float* inxt) __attribute__((always_inline)) {
     // always issued (past the end it re-reads the last stage into a buffer nobody reads again)
     fetch((sg + 2 < s1) ? sg + 2 : s1 - 1, knxt, inxt);
@@ -427,7 +427,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
     wait_oldest_copy();
   }
   __syncthreads();
-  for (long long sg = s0; sg < s1; sg += 3) {  // the conditions are block-uniform
+  for (int sg = s0; sg < s1; sg += 3) {  // the conditions are block-uniform
     body(sg, kbuf0, ibuf[0], kbuf2, ibuf[2]);
     if (sg + 1 < s1) body(sg + 1, kbuf1, ibuf[1], kbuf0, ibuf[0]);
     if (sg + 2 < s1) body(sg + 2, kbuf2, ibuf[2], kbuf1, ibuf[1]);
