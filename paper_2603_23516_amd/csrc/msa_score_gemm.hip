@@ -655,6 +655,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
         Bhi[s] = as_bf16x8(make_uint4(wh[0], wh[1], wh[2], wh[3]));
         if constexpr (!HIONLY) Blo[s] = as_bf16x8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
       }
+      // The operands are complete HERE, ahead of the first ring copy of the group.  The compiler waits for its own
+      // loads with vmcnt(0) where they are first used; left to itself it places that use (and the wait) behind the
+      // copy request of the first stage, and the wait then also covers the copies that were requested a moment ago.
+#pragma unroll
+      for (int s = 0; s < NS8; ++s) {
+        asm volatile("" : "+v"(Bhi[s]));
+        if constexpr (!HIONLY) asm volatile("" : "+v"(Blo[s]));
+      }
 #pragma unroll
       for (int st = 0; st < R; ++st) {
         {  // the stage two ahead in the stream: always issued (past the end: the last entry again)
