@@ -717,13 +717,13 @@ def test_prefill_scoring_long_splits():
     say(f"   top-k ok ({n_band} inside the tie band)")
 
 
-@pytest.mark.parametrize("k", [8, 16])
-def test_prefill_scoring_one_pass_filter(k):
+@pytest.mark.parametrize("k,B,M", [(8, 1, 700), (16, 1, 700), (1, 1, 300), (3, 3, 150)])
+def test_prefill_scoring_one_pass_filter(k, B, M):
     """d = 128, eight chunks per document, cosine: the scoring GEMM multiplies the hi parts of the queries only and
     the candidates inside the error band are scored again exactly.  Long key-range splits, token blocks with a
-    ragged tail, r = 2 heads folded per group, an exact tie between two documents; the oracle scores 100 tokens
-    at a time."""
-    N, C, d, Hkv, r, B, M = 6144, 8, 128, 4, 2, 1, 700
+    ragged tail, r = 2 heads folded per group, an exact tie between two documents; k from 1 (the band around the
+    single best score) to 16, one and several batch rows; the oracle scores 100 tokens at a time."""
+    N, C, d, Hkv, r = 6144, 8, 128, 4, 2
     say(f"case prefill scoring, one-pass filter: N={N} docs, C={C}, d={d}, Hkv={Hkv}, r={r}, M={M}, k={k}")
     cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e6)
     _, KRb = S.normal_bf16(42000, (Hkv, N * C, d))
