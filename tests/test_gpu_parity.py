@@ -638,17 +638,19 @@ EQ2_CASES = {
 }
 
 
-@pytest.mark.parametrize("k", [8, 16])
-def test_prefill_scoring_all_heads_long_splits(k):
+@pytest.mark.parametrize("k,N", [(8, 5000), (16, 5000), (16, 2000)])
+def test_prefill_scoring_all_heads_long_splits(k, N):
     """select_scope = ALL with many query tokens: the all-heads scoring GEMM over key ranges long enough for many
     ring rotations, several key-range splits and token blocks with a ragged tail (M = 300), Hkv = 8, with an exact
-    tie between two documents planted in every head; the oracle scores 100 tokens at a time."""
-    N, C, d, Hkv, r, B, M = 5000, 8, 128, 8, 1, 1, 300
+    tie between two documents planted in every head; the oracle scores 100 tokens at a time.  (With k = 16 the
+    5000-document index is cut into more splits than the one-pass filter takes: the two-pass kernel alone; the
+    2000-document bank goes through the filter with 16-entry lists, 1024 list entries per token: its limit.)"""
+    C, d, Hkv, r, B, M = 8, 128, 8, 1, 1, 300
     say(f"case all-heads prefill scoring: N={N} docs, C={C}, d={d}, Hkv={Hkv}, M={M}, k={k}")
     cfg = msa.MsaConfig(N, 64, 8, Hkv * r, Hkv, d, 1e6, select_scope=msa.MSA_SCOPE_ALL)
     _, KRb = S.normal_bf16(42000, (Hkv, N * C, d))
     qb, q = S.normal_bf16(42001, (B, M, Hkv * r, d))
-    KRb[:, 7 * C + 1] = KRb[:, 4500 * C + 6]                      # documents 7 and 4500 tie wherever that chunk is their best
+    KRb[:, 7 * C + 1] = KRb[:, (N - 500) * C + 6]                 # documents 7 and N - 500 tie wherever that chunk is their best
     inv = 1.0 / np.maximum(np.linalg.norm(KRb, axis=-1), O.EPS_NORM)
     dKR, dinv = upload_oracle_index(cfg, KRb, inv)
     idx, val = msa.msa_score_topk(cfg, dev(qb), dKR, dinv, k)
