@@ -32,13 +32,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # WRITE_SIZE runs of this file, each counter scaled by its reading for a plain copy of known size; the summaries, with
 # the kernel signatures and the commit they were measured at, are profiles/pmc_traffic_<workload>.txt.  Only with the
 # default flags (un-pooled bank, per-group selection); None where no such run exists.
-MEASURED_TRAFFIC = {     # measured at commit 106b232
-    "cfg5_decode_50m": {"score": 1642.0e6, "attend": 621.7e6},     # algorithmic 1625.0 / 604.0 MB: x1.010 / x1.029
-    "cfg3_batch32_4m": {"score": 156.0e6, "attend": 1359.2e6},     # 136.3 / 1342.2 MB: x1.144 (score matrix round trip) / x1.013
-    "cfg2_decode_1m": {"score": 34.8e6, "attend": 53.2e6},         # 34.1 / 41.9 MB: x1.021 / x1.268 (split partials)
-    # score: fold 25.7 + one-pass GEMM 571.3 (index 536.9 MB read once) + exact scores of the candidates 363.1 MB;
+MEASURED_TRAFFIC = {     # measured at commit f514938
+    "cfg5_decode_50m": {"score": 1642.2e6, "attend": 621.7e6},     # algorithmic 1625.0 / 604.0 MB: x1.011 / x1.029
+    "cfg3_batch32_4m": {"score": 156.0e6, "attend": 1359.3e6},     # 136.3 / 1342.2 MB: x1.144 (score matrix round trip) / x1.013
+    "cfg2_decode_1m": {"score": 34.8e6, "attend": 52.5e6},         # 34.1 / 41.9 MB: x1.021 / x1.252 (split partials)
+    # score: fold 25.7 + one-pass GEMM 570.9 (index 536.9 MB read once) + exact scores of the candidates 363.1 MB;
     # attend: gather 34368.1 MB: x1.021
-    "cfg4_prefill_16m": {"score": 960.1e6, "attend": 35074.2e6},
+    "cfg4_prefill_16m": {"score": 959.7e6, "attend": 35073.3e6},
 }
 
 
